@@ -1,0 +1,62 @@
+"""L1 tile cache oracle (test infrastructure only).
+
+Section 3.4: a tile already present in the GPU's own memory (the L1 tile
+cache) is used directly; a tile absent from it is fetched from host memory.
+Algorithm 1 looks up A[i,k] then B[k,j] for every k-step of a task.  The
+paper does not name the eviction rule; the reading taken is strict LRU with
+a touch on every lookup.  On one GPU there is no second-level (peer) cache.
+"""
+from collections import OrderedDict
+
+from .plan import _ceil_div
+
+
+def task_order(n_i, n_j, order):
+    """Task ids in issue order.  'row_major': i then j ascending.  'serpentine':
+    j ascends on even tile rows and descends on odd ones."""
+    if order not in ("row_major", "serpentine"):
+        raise ValueError(order)
+    ids = []
+    for i in range(n_i):
+        js = range(n_j)
+        if order == "serpentine" and i % 2 == 1:
+            js = range(n_j - 1, -1, -1)
+        ids.extend(i * n_j + j for j in js)
+    return ids
+
+
+def tgemm_access_sequence(M, N, K, T, order="serpentine"):
+    """Tile lookups of one tiled GEMM in issue order: for every task, k ascending,
+    the A tile then the B tile.  Each entry is (matrix, tile row, tile col, task id, k)."""
+    n_i, n_j, n_k = _ceil_div(M, T), _ceil_div(N, T), _ceil_div(K, T)
+    seq = []
+    for tid in task_order(n_i, n_j, order):
+        i, j = tid // n_j, tid % n_j
+        for k in range(n_k):
+            seq.append(("A", i, k, tid, k))
+            seq.append(("B", k, j, tid, k))
+    return seq
+
+
+def lru_simulate(keys, n_slots):
+    """Runs strict LRU over hashable keys.  Returns (events, stats); events[t] =
+    (hit, evicted_key_or_None)."""
+    if n_slots < 1:
+        raise ValueError("need at least one slot")
+    cache = OrderedDict()
+    events = []
+    hits = misses = evictions = 0
+    for key in keys:
+        if key in cache:
+            cache.move_to_end(key)
+            hits += 1
+            events.append((True, None))
+            continue
+        misses += 1
+        victim = None
+        if len(cache) >= n_slots:
+            victim, _ = cache.popitem(last=False)
+            evictions += 1
+        cache[key] = True
+        events.append((False, victim))
+    return events, dict(hits=hits, misses=misses, evictions=evictions)

@@ -1,0 +1,104 @@
+"""Pins of the MLP oracle: finite differences, closed forms for zero weights and for the
+single-layer (softmax regression) case, invariants, first-order descent."""
+import math
+
+import numpy as np
+
+
+def _net(seed, dims, B):
+    r = np.random.default_rng(seed)
+    X = r.normal(0, 1, (B, dims[0])).astype(np.float32)
+    Ws = [r.normal(0, 0.5, (a, b)).astype(np.float32) for a, b in zip(dims[:-1], dims[1:])]
+    y = r.integers(0, dims[-1], B)
+    return X, Ws, y
+
+
+def test_finite_differences_every_weight(oracle):
+    X, Ws, y = _net(0, [5, 7, 6, 4], 3)
+    loss, dWs, _ = oracle.mlp_backward(X, Ws, y)
+    assert abs(loss - oracle.mlp_loss(X, Ws, y)) < 1e-15
+    h = 1e-5
+    W64 = [w.astype(np.float64) for w in Ws]
+    for l, W in enumerate(W64):
+        num = np.zeros_like(W)
+        for idx in np.ndindex(*W.shape):
+            old = W[idx]
+            W[idx] = old + h
+            lp = oracle.mlp_loss(X, W64, y)
+            W[idx] = old - h
+            lm = oracle.mlp_loss(X, W64, y)
+            W[idx] = old
+            num[idx] = (lp - lm) / (2 * h)
+        err = np.linalg.norm(num - dWs[l]) / np.linalg.norm(dWs[l])
+        assert err < 1e-6, (l, err)
+
+
+def test_zero_weights_closed_form(oracle):
+    dims = [6, 8, 5, 10]
+    X, Ws, y = _net(1, dims, 4)
+    Ws = [np.zeros_like(w) for w in Ws]
+    acts, z, P = oracle.mlp_forward(X, Ws)
+    assert np.array_equal(acts[1], np.full((4, 8), 0.5)) and np.array_equal(acts[2], np.full((4, 5), 0.5))
+    assert np.allclose(P, 0.1, rtol=0, atol=1e-16)
+    assert abs(oracle.mlp_loss(X, Ws, y) - math.log(10)) < 1e-15
+    # the benchmark output widths
+    assert abs(math.log(10000) - 9.210340371976184) < 1e-12
+    loss, dWs, _ = oracle.mlp_backward(X, Ws, y)
+    # with zero weights no error reaches the earlier layers
+    assert np.array_equal(dWs[0], np.zeros_like(dWs[0])) and np.array_equal(dWs[1], np.zeros_like(dWs[1]))
+    # last layer: 0.5 * column sums of (P - Y)/B
+    D = np.full((4, 10), 0.1)
+    D[np.arange(4), y] -= 1
+    assert np.allclose(dWs[2], 0.5 * np.ones((5, 1)) * D.sum(0, keepdims=True) / 4, atol=1e-16)
+
+
+def test_single_layer_is_softmax_regression(oracle):
+    X, Ws, y = _net(2, [9, 6], 7)
+    loss, dWs, deltas = oracle.mlp_backward(X, Ws, y)
+    X64, W64 = X.astype(np.float64), Ws[0].astype(np.float64)
+    z = X64 @ W64
+    P = np.exp(z) / np.exp(z).sum(1, keepdims=True)   # no max shift: small logits
+    Y = np.eye(6)[y]
+    assert np.allclose(dWs[0], X64.T @ (P - Y) / 7, atol=1e-14)
+    assert abs(loss + np.mean(np.log(P[np.arange(7), y]))) < 1e-14
+
+
+def test_invariants_and_orientation(oracle):
+    dims = [5, 9, 4]
+    X, Ws, y = _net(3, dims, 6)
+    acts, z, P = oracle.mlp_forward(X, Ws)
+    assert [a.shape for a in acts] == [(6, 5), (6, 9)] and z.shape == (6, 4)
+    assert np.allclose(P.sum(1), 1, atol=1e-15)
+    loss, dWs, deltas = oracle.mlp_backward(X, Ws, y)
+    assert [g.shape for g in dWs] == [w.shape for w in Ws]
+    assert np.allclose(deltas[-1].sum(1), 0, atol=1e-16)
+    assert loss > 0
+    # softmax is shift invariant: a huge common offset on the logits must not overflow
+    big = [Ws[0], Ws[1] * 0]
+    acts2, z2, P2 = oracle.mlp_forward(X, big)
+    assert np.allclose(P2, 0.25)
+
+
+def test_step_descends_first_order(oracle):
+    X, Ws, y = _net(4, [6, 8, 5], 8)
+    lr = 1e-4
+    loss, newW, dWs = oracle.mlp_step(X, Ws, y, lr)
+    g2 = sum(float((g * g).sum()) for g in dWs)
+    loss_after = oracle.mlp_loss(X, newW, y)
+    assert abs((loss_after - loss) + lr * g2) < 50 * lr * lr * g2 + 1e-12
+    # all updates use the pre-update weights: W_new - W == -lr * dW exactly in fp64
+    for w, nw, g in zip(Ws, newW, dWs):
+        assert np.array_equal(nw, w.astype(np.float64) - lr * g)
+
+
+def test_bf16_inputs_widen_exactly(oracle):
+    X, Ws, y = _net(5, [4, 5, 3], 2)
+    def bits(a):
+        u = a.view(np.uint32).astype(np.uint64)
+        return ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)
+    Xb, Wb = bits(X), [bits(w) for w in Ws]
+    Xf = oracle.bf16_to_f64(Xb).reshape(X.shape).astype(np.float32)
+    Wf = [oracle.bf16_to_f64(w).reshape(w.shape).astype(np.float32) for w in Wb]
+    l1 = oracle.mlp_backward(Xb, Wb, y)
+    l2 = oracle.mlp_backward(Xf, Wf, y)
+    assert l1[0] == l2[0] and all(np.array_equal(a, b) for a, b in zip(l1[1], l2[1]))

@@ -1,0 +1,124 @@
+"""Pins of the plan and tile-cache oracles: the tile counts of section 3.1, partition
+invariants, closed forms of LRU behaviour, an independent brute-force LRU."""
+import os
+
+import pytest
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden", "tile_counts.txt")
+
+
+def _golden_rows():
+    rows = []
+    for line in open(GOLD):
+        line = line.strip()
+        if line and not line.startswith("#"):
+            rows.append(tuple(int(x) for x in line.split()))
+    return rows
+
+
+def test_paper_tile_counts(oracle):
+    rows = _golden_rows()
+    assert len(rows) == 3
+    for n, t, full, edge, ksteps in rows:
+        assert oracle.tile_counts(n, t) == (full, edge)
+        tasks = oracle.plan_tiles(n, n, n, t)
+        assert len(tasks) == full + edge
+        n_full = sum(1 for x in tasks if x["r1"] - x["r0"] == t and x["c1"] - x["c0"] == t)
+        assert n_full == full
+        assert all(x["n_k"] == ksteps for x in tasks)
+        assert len(oracle.kstep_ranges(n, t)) == ksteps
+
+
+@pytest.mark.parametrize("M,N,K,T", [(1000, 1000, 1000, 256), (7, 13, 5, 3), (5, 5, 5, 8), (64, 32, 16, 16),
+                                     (1, 1, 1, 1), (10, 3, 7, 1)])
+def test_plan_partitions_output(oracle, M, N, K, T):
+    tasks = oracle.plan_tiles(M, N, K, T)
+    seen = set()
+    n_j = -(-N // T)
+    for idx, t in enumerate(tasks):
+        assert t["id"] == idx == t["i"] * n_j + t["j"]
+        assert oracle.decode_task(t["id"], n_j) == (t["i"], t["j"])
+        assert 0 < t["r1"] - t["r0"] <= T and 0 < t["c1"] - t["c0"] <= T
+        for r in range(t["r0"], t["r1"]):
+            for c in range(t["c0"], t["c1"]):
+                assert (r, c) not in seen
+                seen.add((r, c))
+    assert len(seen) == M * N
+    ks = oracle.kstep_ranges(K, T)
+    assert ks[0][0] == 0 and ks[-1][1] == K
+    assert all(a[1] == b[0] for a, b in zip(ks, ks[1:]))
+
+
+def test_edge_extents_config1(oracle):
+    tasks = oracle.plan_tiles(1000, 1000, 1000, 256)
+    assert tasks[3]["c1"] - tasks[3]["c0"] == 232 and tasks[15]["r1"] - tasks[15]["r0"] == 232
+    assert oracle.kstep_ranges(1000, 256)[-1] == (768, 1000)
+
+
+def _brute_lru(keys, n):
+    order = []  # least recent first
+    out = []
+    for k in keys:
+        if k in order:
+            order.remove(k)
+            order.append(k)
+            out.append((True, None))
+        else:
+            victim = None
+            if len(order) == n:
+                victim = order.pop(0)
+            order.append(k)
+            out.append((False, victim))
+    return out
+
+
+def test_lru_closed_forms(oracle):
+    n = 5
+    # cyclic sweep over n+1 keys: LRU never hits
+    ev, st = oracle.lru_simulate([i % (n + 1) for i in range(60)], n)
+    assert st["hits"] == 0 and st["misses"] == 60 and st["evictions"] == 60 - n
+    # n keys in n slots: only the compulsory misses
+    ev, st = oracle.lru_simulate([i % n for i in range(60)], n)
+    assert st == dict(hits=60 - n, misses=n, evictions=0)
+    # victim is the least recently *used*, not the first inserted
+    ev, _ = oracle.lru_simulate(["a", "b", "c", "a", "d"], 3)
+    assert ev[-1] == (False, "b")
+
+
+def test_lru_vs_brute_force(oracle):
+    import random
+    rnd = random.Random(11)
+    for n in (1, 2, 3, 7):
+        keys = [rnd.randrange(10) for _ in range(400)]
+        ev, st = oracle.lru_simulate(keys, n)
+        assert ev == _brute_lru(keys, n)
+        assert st["hits"] + st["misses"] == len(keys)
+
+
+def test_access_sequence_structure(oracle):
+    seq = oracle.tgemm_access_sequence(5, 7, 9, 2, order="row_major")
+    n_i, n_j, n_k = 3, 4, 5
+    assert len(seq) == 2 * n_i * n_j * n_k
+    assert seq[0] == ("A", 0, 0, 0, 0) and seq[1] == ("B", 0, 0, 0, 0)
+    assert seq[2 * n_k] == ("A", 0, 0, 1, 0) and seq[2 * n_k + 1] == ("B", 0, 1, 1, 0)
+    serp = oracle.tgemm_access_sequence(5, 7, 9, 2, order="serpentine")
+    tids = [s[3] for s in serp[::2 * n_k]]
+    assert tids == [0, 1, 2, 3, 7, 6, 5, 4, 8, 9, 10, 11]
+    assert sorted(s[:3] for s in serp) == sorted(s[:3] for s in seq)
+
+
+def test_row_major_reuse_closed_form(oracle):
+    """Row-major order, cache smaller than one sweep of B: every B lookup misses, A misses
+    once per (i, k) -- the redundant-transfer pattern section 3.4 describes."""
+    n_i = n_j = n_k = 6
+    T = 4
+    seq = oracle.tgemm_access_sequence(n_i * T, n_j * T, n_k * T, T, order="row_major")
+    slots = 2 * n_k + 3          # holds a row panel of A and a bit more, far less than all of B
+    ev, st = oracle.lru_simulate([s[:3] for s in seq], slots)
+    a_miss = sum(1 for s, e in zip(seq, ev) if s[0] == "A" and not e[0])
+    b_miss = sum(1 for s, e in zip(seq, ev) if s[0] == "B" and not e[0])
+    assert a_miss == n_i * n_k
+    assert b_miss == n_i * n_j * n_k
+    # everything fits: compulsory misses only
+    ev, st = oracle.lru_simulate([s[:3] for s in seq], n_i * n_k + n_k * n_j)
+    assert st["misses"] == n_i * n_k + n_k * n_j and st["evictions"] == 0
