@@ -1,0 +1,196 @@
+/*
+ * tgemm -- tiled in-core / out-of-core matrix multiplication and the MLP
+ * training passes reduced to it, for one MI355X (gfx950).
+ *
+ * C ABI.  Plain pointers and sizes only.  Every function returns an int
+ * status (TGEMM_OK == 0, negative == error) and never throws; the text of the
+ * last error on the calling thread is available from tgemm_last_error().
+ *
+ * Conventions shared by all entry points
+ *   - Matrices are dense, row-major, contiguous (leading dimension == number
+ *     of columns).
+ *   - dtype TGEMM_F32: A, B are float.  dtype TGEMM_BF16: A, B are uint16_t
+ *     holding bfloat16 bit patterns.  C and every accumulation are float.
+ *   - "device pointer" = memory of the context's GPU (hipMalloc, torch cuda
+ *     tensor).  "pinned host pointer" = page-locked host memory
+ *     (hipHostMalloc, torch pin_memory).  Pageable host memory is rejected
+ *     with TGEMM_EUNPINNED.
+ *   - The caller owns every matrix, weight, input and label buffer and keeps
+ *     it alive and unmodified for the duration of a call.  The library owns
+ *     contexts, its tile cache, workspaces and any stream it created itself.
+ *   - Calls are synchronous: on return the result is complete and visible
+ *     (unless tgemm_opts.async_incore is set, see tgemm_sync).  After an
+ *     error the context stays usable; outputs are unspecified only for
+ *     TGEMM_EHIP, which is reported after work has started.
+ *   - The library's streams do not synchronise with any other stream: work that produces an input
+ *     on another stream (including the null stream) must have completed before a call.
+ *   - A context is used by one caller thread at a time.
+ */
+#ifndef TGEMM_H
+#define TGEMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct tgemm_ctx tgemm_ctx;
+typedef struct tgemm_mlp tgemm_mlp;
+
+enum { TGEMM_F32 = 0, TGEMM_BF16 = 1 };
+
+enum {
+    TGEMM_OK = 0,
+    TGEMM_EARG = -1,      /* null / aliasing / non-positive size / unknown enum / mixed pointer kinds */
+    TGEMM_ENOMEM = -2,    /* host or device allocation failed */
+    TGEMM_EUNPINNED = -3, /* a host pointer is not page-locked */
+    TGEMM_EBUDGET = -4,   /* hbm_budget below the minimum working set */
+    TGEMM_EHIP = -5,      /* a HIP call failed after work started */
+    TGEMM_ESTATE = -6     /* call order violated (e.g. backward before forward) */
+};
+
+/* Order in which output-tile tasks are issued (the result does not depend on it). */
+enum { TGEMM_ORDER_SERPENTINE = 0, TGEMM_ORDER_ROW_MAJOR = 1 };
+
+typedef struct tgemm_opts {
+    int32_t trace;         /* 1: record one tgemm_trace_rec per tile product of out-of-core runs */
+    int32_t order;         /* TGEMM_ORDER_* */
+    int32_t affinity_core; /* >= 0: bind the submit thread to this CPU core (section 3.2, "GPU
+                              computation thread"); -1: leave it to the OS */
+    int32_t async_incore;  /* 1: in-core tgemm_run returns after enqueueing; see tgemm_sync */
+    int32_t kernel_config; /* 0: automatic; 1..3 force a macro-tile shape (small, medium, large) */
+    int32_t reserved[3];
+} tgemm_opts;
+
+/* One output tile C_ij = one task (section 3.1; Algorithm 1, "decode").
+ * id = i * n_j + j.  Row range [r0, r1), column range [c0, c1); n_k = number of k-steps. */
+typedef struct tgemm_task {
+    int64_t id, i, j, r0, r1, c0, c1, n_k;
+} tgemm_task;
+
+typedef struct tgemm_stats {
+    double wall_ms;        /* host wall clock of the last tgemm_run / mlp_* call                  */
+    double kernel_ms;      /* HIP-event time on the launch stream around the GEMM kernel(s) of the
+                              last in-core tgemm_run (0 for out-of-core runs)                       */
+    int64_t in_core;       /* 1 if the last run was in-core                                       */
+    int64_t n_tasks;       /* output tiles                                                        */
+    int64_t n_tile_gemms;  /* tile products C_ij += A_ik B_kj                                      */
+    int64_t n_slots;       /* A/B tile-cache slots the budget allowed (out-of-core)               */
+    int64_t hits, misses, evictions; /* tile-cache lookups (out-of-core)                          */
+    int64_t h2d_bytes, d2h_bytes;    /* bytes moved over the host link (out-of-core)              */
+    int64_t kernel_launches;
+} tgemm_stats;
+
+/* One tile product of an out-of-core run, in issue order (Algorithm 1, the k loop). */
+typedef struct tgemm_trace_rec {
+    int64_t task_id;
+    int32_t i, j, k;       /* C tile (i,j), step k: uses A tile (i,k) and B tile (k,j)            */
+    int32_t stream;        /* 0..3: the stream / reservation-station slot the task ran on         */
+    int32_t a_hit, b_hit;  /* 1: tile was in the cache, 0: fetched from host memory               */
+    int32_t a_slot, b_slot;
+    int32_t a_evicted, b_evicted; /* 1: the fetch displaced another tile                          */
+} tgemm_trace_rec;
+
+const char* tgemm_strerror(int code);
+const char* tgemm_last_error(void);
+
+/* Section 3.5, Algorithm 1 lines 1-4: creates the runtime of one GPU -- 4 streams (section 3.2:
+ * four concurrent tasks per GPU, one per stream), the task queue, the tile cache directory and the
+ * submit thread.
+ *   device   HIP device ordinal.
+ *   streams  NULL, or 4 hipStream_t values (as void*) borrowed from the caller for the lifetime of
+ *            the context; entries that are NULL are created (and later destroyed) by the library.
+ *            All streams must have default priority.
+ *   opts     NULL for defaults (no trace, serpentine order, no core binding, synchronous).
+ * Errors: TGEMM_EARG (out == NULL, bad device, bad enum), TGEMM_EHIP, TGEMM_ENOMEM. */
+int tgemm_create(tgemm_ctx** out, int device, void* const* streams, const tgemm_opts* opts);
+
+/* Frees everything the context owns.  NULL is accepted.  All work has completed on return. */
+int tgemm_destroy(tgemm_ctx* ctx);
+
+/* Section 3.1 + Algorithm 1: C <- C + A B computed tile by tile.
+ *   A  M x K, B  K x N (dtype elements), C  M x N float, all row-major contiguous; C is read and
+ *      written; A, B, C must not overlap.
+ *   T  tile size (> 0).  Output tile (i,j) is one task; it accumulates A_ik B_kj for k ascending;
+ *      edge tiles are clamped to the matrix.
+ *   All three pointers device pointers  -> in-core: one kernel launch covers every task, hbm_budget
+ *      is ignored.
+ *   All three pointers pinned host      -> out-of-core: A/B tiles are staged into an HBM tile cache
+ *      (LRU, section 3.4) and C tiles are uploaded, accumulated and harvested on 4 streams.  Every
+ *      device byte allocated for the call (A/B slots + 4 C slots) stays within hbm_budget bytes;
+ *      the minimum is 4 C slots + 8 A/B slots (TGEMM_EBUDGET otherwise, before any work).
+ *   M, N or K == 0 is legal (C unchanged).
+ * Errors: TGEMM_EARG, TGEMM_EUNPINNED, TGEMM_EBUDGET, TGEMM_ENOMEM, TGEMM_EHIP. */
+int tgemm_run(tgemm_ctx* ctx, const void* A, const void* B, void* C,
+              int64_t M, int64_t N, int64_t K, int32_t T, int32_t dtype, size_t hbm_budget);
+
+/* Waits for everything enqueued on the context's streams (only needed with opts.async_incore). */
+int tgemm_sync(tgemm_ctx* ctx);
+
+/* Section 3.1 / Algorithm 1 "decode": the task list of an M x N x K product with tile size T, in id
+ * order.  Pure host code, no context needed.  Writes min(cap, n) records to out (out may be NULL
+ * when cap == 0) and the total number of tasks to *n_tasks. */
+int tgemm_plan(int64_t M, int64_t N, int64_t K, int32_t T, tgemm_task* out, int64_t cap, int64_t* n_tasks);
+
+/* Issue order of the task ids for an n_i x n_j task grid under `order`; writes n_i * n_j ids. */
+int tgemm_task_order(int64_t n_i, int64_t n_j, int32_t order, int64_t* out_ids);
+
+/* Statistics of the last tgemm_run / mlp_* call on the context. */
+int tgemm_last_stats(tgemm_ctx* ctx, tgemm_stats* out);
+
+/* Trace of the last out-of-core run (requires opts.trace).  Copies min(cap, n) records. */
+int tgemm_trace(tgemm_ctx* ctx, tgemm_trace_rec* out, int64_t cap, int64_t* n);
+
+/* Section 3.2, non-blocking task queue: pushes n ids from `producers` threads and pops them from
+ * `consumers` threads through the library's lock-free queue; writes to popped_count[id] how many
+ * times each id came out.  Host-only self test used by the CPU test-suite. */
+int tgemm_queue_selftest(int64_t n, int32_t producers, int32_t consumers, int32_t* popped_count);
+
+/* ---- MLP passes (section 2: forward pass = equation 1, backward pass = equations 3 and 4) ----
+ *
+ * Network: n_layers weight matrices W_l of shape dims[l] x dims[l+1], no bias; sigmoid after every
+ * layer but the last; softmax + mean cross-entropy on the last.
+ *   W        n_layers caller-owned matrices (dtype elements).  All device pointers: the products run
+ *            in-core.  (Pinned host weights, i.e. the out-of-core MLP, are not implemented yet and
+ *            are rejected with TGEMM_EARG.)
+ *   T        tile size of every product.
+ *   hbm_budget  upper bound on device bytes the object may allocate for activations and errors
+ *            (0 = no bound).
+ * The object allocates its activation / error workspaces on the first forward for a batch size and
+ * reuses them while the batch size does not grow. */
+int mlp_create(tgemm_ctx* ctx, tgemm_mlp** out, int32_t n_layers, const int64_t* dims,
+               void* const* W, int32_t dtype, int32_t T, size_t hbm_budget);
+int mlp_destroy(tgemm_mlp* mlp);
+
+/* Equation 1 for every layer: Z_l = A_{l-1} W_l, A_l = sigmoid(Z_l); last layer: logits.
+ *   X      device pointer, batch x dims[0], dtype elements.
+ *   probs  NULL, or device pointer to batch x dims[n_layers] floats receiving softmax(logits). */
+int mlp_forward(tgemm_mlp* mlp, const void* X, int64_t batch, float* probs);
+
+/* Equations 3 and 4 for every layer, from the activations of the preceding mlp_forward:
+ *   D_L = (softmax(Z_L) - onehot(labels)) / batch;  dW_l = A_{l-1}^T D_l;
+ *   D_{l-1} = (D_l W_l^T) * A_{l-1} * (1 - A_{l-1}).
+ *   labels  device pointer, batch int32 values in [0, dims[n_layers]).
+ *   dW      NULL, or n_layers device pointers (dims[l] x dims[l+1] floats) receiving dW_l.
+ *   loss    host pointer receiving the mean cross-entropy (may be NULL).
+ * The weights are not changed.  TGEMM_ESTATE if no forward preceded. */
+int mlp_backward(tgemm_mlp* mlp, const int32_t* labels, void* const* dW, float* loss);
+
+/* One training step: forward, backward and W_l <- W_l - lr * dW_l fused into the dW product's
+ * epilogue (dW is never stored); every error D_{l-1} is formed from the pre-update W_l.
+ *   loss  host pointer receiving the loss before the update (may be NULL). */
+int mlp_step(tgemm_mlp* mlp, const void* X, const int32_t* labels, int64_t batch, float lr, float* loss);
+
+/* Test access to the object's device workspaces after a forward / backward:
+ *   what 0: activation A_l (l = 1..n_layers-1; batch x dims[l], dtype elements)
+ *        1: logits Z_L (batch x dims[n_layers] floats; layer ignored)
+ *        2: error D_l  (l = 1..n_layers; batch x dims[l]; float for l == n_layers, else dtype)
+ * Copies `bytes` bytes to the host buffer dst.  TGEMM_EARG if bytes exceeds the matrix. */
+int mlp_read(tgemm_mlp* mlp, int32_t what, int32_t layer, void* dst, size_t bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TGEMM_H */

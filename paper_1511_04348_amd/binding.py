@@ -1,0 +1,214 @@
+"""ctypes binding of libtgemm.so: argument marshalling only, same names as include/tgemm.h.
+
+Pointers are passed as integers (``tensor.data_ptr()``) or anything with a ``data_ptr()`` method.
+Every error code raises ``TgemmError`` carrying the code and the library's message.  The library
+must have been built (``python -m paper_1511_04348_amd.build``); there is no fallback.
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtgemm.so")
+
+TGEMM_F32, TGEMM_BF16 = 0, 1
+TGEMM_OK, TGEMM_EARG, TGEMM_ENOMEM, TGEMM_EUNPINNED, TGEMM_EBUDGET, TGEMM_EHIP, TGEMM_ESTATE = 0, -1, -2, -3, -4, -5, -6
+TGEMM_ORDER_SERPENTINE, TGEMM_ORDER_ROW_MAJOR = 0, 1
+
+EXPORTS = [
+    "tgemm_strerror", "tgemm_last_error", "tgemm_create", "tgemm_destroy", "tgemm_run", "tgemm_sync",
+    "tgemm_plan", "tgemm_task_order", "tgemm_last_stats", "tgemm_trace", "tgemm_queue_selftest",
+    "mlp_create", "mlp_destroy", "mlp_forward", "mlp_backward", "mlp_step", "mlp_read",
+]
+
+
+class tgemm_opts(ctypes.Structure):
+    _fields_ = [("trace", ctypes.c_int32), ("order", ctypes.c_int32), ("affinity_core", ctypes.c_int32),
+                ("async_incore", ctypes.c_int32), ("kernel_config", ctypes.c_int32),
+                ("reserved", ctypes.c_int32 * 3)]
+
+
+class tgemm_task(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int64) for n in ("id", "i", "j", "r0", "r1", "c0", "c1", "n_k")]
+
+
+class tgemm_stats(ctypes.Structure):
+    _fields_ = [("wall_ms", ctypes.c_double), ("kernel_ms", ctypes.c_double)] + \
+               [(n, ctypes.c_int64) for n in ("in_core", "n_tasks", "n_tile_gemms", "n_slots", "hits", "misses",
+                                              "evictions", "h2d_bytes", "d2h_bytes", "kernel_launches")]
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+class tgemm_trace_rec(ctypes.Structure):
+    _fields_ = [("task_id", ctypes.c_int64)] + \
+               [(n, ctypes.c_int32) for n in ("i", "j", "k", "stream", "a_hit", "b_hit", "a_slot", "b_slot",
+                                              "a_evicted", "b_evicted")]
+
+
+class TgemmError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__("tgemm error %d: %s" % (code, msg))
+        self.code = code
+
+
+_lib = None
+
+
+def load():
+    """Loads libtgemm.so (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("libtgemm.so is missing at %s: run `python -m paper_1511_04348_amd.build` "
+                           "(there is no CPU fallback)" % LIB_PATH)
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+    P = ctypes.POINTER
+    lib.tgemm_strerror.argtypes, lib.tgemm_strerror.restype = [ctypes.c_int], ctypes.c_char_p
+    lib.tgemm_last_error.argtypes, lib.tgemm_last_error.restype = [], ctypes.c_char_p
+    lib.tgemm_create.argtypes = [P(vp), ctypes.c_int, P(vp), P(tgemm_opts)]
+    lib.tgemm_destroy.argtypes = [vp]
+    lib.tgemm_run.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, i32, sz]
+    lib.tgemm_sync.argtypes = [vp]
+    lib.tgemm_plan.argtypes = [i64, i64, i64, i32, P(tgemm_task), i64, P(i64)]
+    lib.tgemm_task_order.argtypes = [i64, i64, i32, P(i64)]
+    lib.tgemm_last_stats.argtypes = [vp, P(tgemm_stats)]
+    lib.tgemm_trace.argtypes = [vp, P(tgemm_trace_rec), i64, P(i64)]
+    lib.tgemm_queue_selftest.argtypes = [i64, i32, i32, P(i32)]
+    lib.mlp_create.argtypes = [vp, P(vp), i32, P(i64), P(vp), i32, i32, sz]
+    lib.mlp_destroy.argtypes = [vp]
+    lib.mlp_forward.argtypes = [vp, vp, i64, vp]
+    lib.mlp_backward.argtypes = [vp, vp, P(vp), P(ctypes.c_float)]
+    lib.mlp_step.argtypes = [vp, vp, vp, i64, ctypes.c_float, P(ctypes.c_float)]
+    lib.mlp_read.argtypes = [vp, i32, i32, vp, sz]
+    for name in EXPORTS:
+        if name not in ("tgemm_strerror", "tgemm_last_error"):
+            getattr(lib, name).restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def _check(rc):
+    if rc != 0:
+        raise TgemmError(rc, load().tgemm_last_error().decode("utf-8", "replace"))
+
+
+def _p(x):
+    if x is None:
+        return None
+    if hasattr(x, "data_ptr"):
+        return x.data_ptr()
+    if hasattr(x, "cuda_stream"):
+        return x.cuda_stream
+    return int(x)
+
+
+def tgemm_strerror(code):
+    return load().tgemm_strerror(code).decode()
+
+
+def tgemm_last_error():
+    return load().tgemm_last_error().decode("utf-8", "replace")
+
+
+def tgemm_create(device=0, streams=None, trace=0, order=TGEMM_ORDER_SERPENTINE, affinity_core=-1,
+                 async_incore=0, kernel_config=0):
+    lib = load()
+    o = tgemm_opts(trace=trace, order=order, affinity_core=affinity_core, async_incore=async_incore,
+                   kernel_config=kernel_config)
+    arr = None
+    if streams is not None:
+        if len(streams) != 4:
+            raise ValueError("streams must have 4 entries")
+        arr = (ctypes.c_void_p * 4)(*[_p(s) for s in streams])
+    out = ctypes.c_void_p()
+    _check(lib.tgemm_create(ctypes.byref(out), device, arr, ctypes.byref(o)))
+    return out
+
+
+def tgemm_destroy(ctx):
+    _check(load().tgemm_destroy(ctx))
+
+
+def tgemm_run(ctx, A, B, C, M, N, K, T, dtype=TGEMM_F32, hbm_budget=0):
+    _check(load().tgemm_run(ctx, _p(A), _p(B), _p(C), M, N, K, T, dtype, hbm_budget))
+
+
+def tgemm_sync(ctx):
+    _check(load().tgemm_sync(ctx))
+
+
+def tgemm_plan(M, N, K, T):
+    lib = load()
+    n = ctypes.c_int64()
+    _check(lib.tgemm_plan(M, N, K, T, None, 0, ctypes.byref(n)))
+    buf = (tgemm_task * max(1, n.value))()
+    _check(lib.tgemm_plan(M, N, K, T, buf, n.value, ctypes.byref(n)))
+    return [{f: getattr(buf[t], f) for f, _ in tgemm_task._fields_} for t in range(n.value)]
+
+
+def tgemm_task_order(n_i, n_j, order):
+    buf = (ctypes.c_int64 * max(1, n_i * n_j))()
+    _check(load().tgemm_task_order(n_i, n_j, order, buf))
+    return list(buf[: n_i * n_j])
+
+
+def tgemm_last_stats(ctx):
+    s = tgemm_stats()
+    _check(load().tgemm_last_stats(ctx, ctypes.byref(s)))
+    return s.as_dict()
+
+
+def tgemm_trace(ctx):
+    lib = load()
+    n = ctypes.c_int64()
+    _check(lib.tgemm_trace(ctx, None, 0, ctypes.byref(n)))
+    buf = (tgemm_trace_rec * max(1, n.value))()
+    _check(lib.tgemm_trace(ctx, buf, n.value, ctypes.byref(n)))
+    return [{f: getattr(buf[t], f) for f, _ in tgemm_trace_rec._fields_} for t in range(n.value)]
+
+
+def tgemm_queue_selftest(n, producers, consumers):
+    buf = (ctypes.c_int32 * max(1, n))()
+    _check(load().tgemm_queue_selftest(n, producers, consumers, buf))
+    return list(buf[:n])
+
+
+def mlp_create(ctx, dims, weights, dtype=TGEMM_F32, T=1024, hbm_budget=0):
+    n_layers = len(weights)
+    if len(dims) != n_layers + 1:
+        raise ValueError("dims must have n_layers + 1 entries")
+    d = (ctypes.c_int64 * len(dims))(*dims)
+    w = (ctypes.c_void_p * n_layers)(*[_p(x) for x in weights])
+    out = ctypes.c_void_p()
+    _check(load().mlp_create(ctx, ctypes.byref(out), n_layers, d, w, dtype, T, hbm_budget))
+    return out
+
+
+def mlp_destroy(mlp):
+    _check(load().mlp_destroy(mlp))
+
+
+def mlp_forward(mlp, X, batch, probs=None):
+    _check(load().mlp_forward(mlp, _p(X), batch, _p(probs)))
+
+
+def mlp_backward(mlp, labels, dW=None):
+    loss = ctypes.c_float()
+    arr = None
+    if dW is not None:
+        arr = (ctypes.c_void_p * len(dW))(*[_p(x) for x in dW])
+    _check(load().mlp_backward(mlp, _p(labels), arr, ctypes.byref(loss)))
+    return loss.value
+
+
+def mlp_step(mlp, X, labels, batch, lr):
+    loss = ctypes.c_float()
+    _check(load().mlp_step(mlp, _p(X), _p(labels), batch, lr, ctypes.byref(loss)))
+    return loss.value
+
+
+def mlp_read(mlp, what, layer, dst, nbytes):
+    _check(load().mlp_read(mlp, what, layer, _p(dst), nbytes))

@@ -1,0 +1,48 @@
+// Shared internals of the tgemm library: error reporting and the context object.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdarg.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "../../include/tgemm.h"
+
+namespace tg {
+
+// Records the message for tgemm_last_error() on this thread and returns `code`.
+int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+
+#define TG_HIP(call)                                                                         \
+    do {                                                                                     \
+        hipError_t e_ = (call);                                                              \
+        if (e_ != hipSuccess)                                                                \
+            return tg::fail(TGEMM_EHIP, "%s failed: %s (%s:%d)", #call, hipGetErrorString(e_), \
+                            __FILE__, __LINE__);                                             \
+    } while (0)
+
+enum PtrKind { PTR_DEVICE = 0, PTR_PINNED = 1, PTR_PAGEABLE = 2 };
+PtrKind classify_pointer(const void* p, int device);
+
+class Engine;   // out-of-core tile engine (engine.cpp)
+
+}  // namespace tg
+
+struct tgemm_ctx {
+    int device = 0;
+    hipStream_t streams[4] = {nullptr, nullptr, nullptr, nullptr};
+    bool own_stream[4] = {false, false, false, false};
+    tgemm_opts opts{};
+    tgemm_stats stats{};
+    hipEvent_t ev_start = nullptr, ev_stop = nullptr;
+    bool kernel_timing_pending = false;
+    std::vector<tgemm_trace_rec> trace;
+    tg::Engine* engine = nullptr;
+};
+
+namespace tg {
+// Device-side staging + scheduling of one out-of-core product (engine.cpp).
+int run_out_of_core(tgemm_ctx* ctx, const void* A, const void* B, float* C, int64_t M, int64_t N,
+                    int64_t K, int32_t T, int32_t dtype, size_t hbm_budget);
+void destroy_engine(tgemm_ctx* ctx);
+}  // namespace tg

@@ -1,0 +1,389 @@
+// fp32 tile GEMM kernel for gfx950 (CDNA4): the "Asynchronous GEMM(A[i,k], B[k,j])" of
+// Algorithm 1 of the paper, for every k-step of every output tile C_ij (section 3.1).
+//
+// One launch covers a whole tiled product.  A workgroup owns one macro tile (BM x BN) of one
+// task's output tile and walks that task's k-steps in ascending order, so the summation order of
+// every C element is fixed.  Workgroups are numbered task by task, which makes the T x T task
+// grid the L2 blocking: the workgroups resident on one XCD at a time belong to one or two tasks
+// and share their A row panel and B column panel.
+//
+// Data path: global -> registers (prefetch of chunk c+1 while chunk c is multiplied) -> LDS
+// (double buffered, [k][m] and [k][n] layouts, row padded by 4 floats) -> v_mfma_f32_32x32x2_f32.
+// A wave reads RA consecutive rows (RB consecutive columns) per lane with one wide LDS read, so the
+// 32x32 MFMA block r of a wave covers rows {RA*i + r}: a permutation of the wave tile that costs
+// nothing and gives each lane RB contiguous output columns for vector stores.
+//
+// Operand storage: A is "k-contiguous" (row-major M x K) or "m-contiguous" (stored K x M, the
+// transposed-A product of the backward pass); likewise B.  Edge tiles and ragged k-steps are
+// zero-filled on the way into LDS and masked on the way out.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "gemm_kernel.h"
+
+namespace tg {
+
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int BK = 16;       // k extent of one LDS stage
+constexpr int PAD = 4;       // floats of row padding in LDS
+
+template <int R> struct Vec;
+template <> struct Vec<1> { typedef float type; };
+template <> struct Vec<2> { typedef f32x2 type; };
+template <> struct Vec<4> { typedef f32x4 type; };
+
+template <int R> __device__ inline float vget(const typename Vec<R>::type& v, int i) { return v[i]; }
+template <> __device__ inline float vget<1>(const float& v, int) { return v; }
+
+// ---- global -> register staging of one operand tile chunk -------------------------------------
+// KC = true : source rows are mn, BK contiguous k each.   unit u -> (mn = u / 4, kq = u % 4)
+// KC = false: source rows are k, BMN contiguous mn each.  unit u -> (k = u / (BMN/4), q = u % (BMN/4))
+template <int BMN, int NT, bool KC>
+struct TileLoader {
+    static constexpr int UNITS = BMN * BK / 4;
+    static constexpr int UP = (UNITS + NT - 1) / NT;   // units per thread
+    static_assert(UNITS % NT == 0, "tile must divide evenly over the threads");
+
+    __device__ static inline void load(f32x4 (&reg)[UP], const float* __restrict__ X, int64_t ld,
+                                       int mn0, int mn_end, int kk, int klim, bool vec_ok, int tid)
+    {
+#pragma unroll
+        for (int p = 0; p < UP; ++p) {
+            const int u = tid + p * NT;
+            f32x4 v = {0.f, 0.f, 0.f, 0.f};
+            if (KC) {
+                const int mn = mn0 + (u >> 2);
+                const int k = kk + ((u & 3) << 2);
+                if (mn < mn_end) {
+                    const float* src = X + (int64_t)mn * ld + k;
+                    if (vec_ok && k + 3 < klim) {
+                        v = *reinterpret_cast<const f32x4*>(src);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (k + e < klim) v[e] = src[e];
+                    }
+                }
+            } else {
+                constexpr int Q = BMN / 4;
+                const int k = kk + u / Q;
+                const int mn = mn0 + ((u % Q) << 2);
+                if (k < klim) {
+                    const float* src = X + (int64_t)k * ld + mn;
+                    if (vec_ok && mn + 3 < mn_end) {
+                        v = *reinterpret_cast<const f32x4*>(src);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (mn + e < mn_end) v[e] = src[e];
+                    }
+                }
+            }
+            reg[p] = v;
+        }
+    }
+
+    // registers -> LDS stage (layout [BK][BMN + PAD])
+    __device__ static inline void store(const f32x4 (&reg)[UP], float* __restrict__ S, int tid)
+    {
+        constexpr int LD = BMN + PAD;
+#pragma unroll
+        for (int p = 0; p < UP; ++p) {
+            const int u = tid + p * NT;
+            if (KC) {
+                const int mn = u >> 2;
+                const int k = (u & 3) << 2;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) S[(k + e) * LD + mn] = reg[p][e];
+            } else {
+                constexpr int Q = BMN / 4;
+                const int k = u / Q;
+                const int mn = (u % Q) << 2;
+                *reinterpret_cast<f32x4*>(&S[k * LD + mn]) = reg[p];
+            }
+        }
+    }
+};
+
+// ---- the kernel ---------------------------------------------------------------------------------
+template <int RA, int RB, int WM, int WN, bool A_KC, bool B_KC, int EPI>
+__global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p)
+{
+    constexpr int WTM = 32 * RA, WTN = 32 * RB;
+    constexpr int BM = WM * WTM, BN = WN * WTN;
+    constexpr int NT = WM * WN * 64;
+    constexpr int LDA_S = BM + PAD, LDB_S = BN + PAD;
+    constexpr int STAGE_A = BK * LDA_S, STAGE_B = BK * LDB_S;
+    typedef TileLoader<BM, NT, A_KC> LA;
+    typedef TileLoader<BN, NT, B_KC> LB;
+    typedef typename Vec<RA>::type VA;
+    typedef typename Vec<RB>::type VB;
+
+    extern __shared__ __attribute__((aligned(16))) float smem[];
+    float* As = smem;                    // [2][BK][LDA_S]
+    float* Bs = smem + 2 * STAGE_A;      // [2][BK][LDB_S]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int li = lane & 31, lh = lane >> 5;
+
+    // -- workgroup -> (task i,j ; macro tile si,sj).  Consecutive logical ids stay on one XCD.
+    int lid;
+    {
+        const int n = gridDim.x, b = blockIdx.x;
+        const int q = n >> 3, r = n & 7, xcd = b & 7, local = b >> 3;
+        lid = xcd * q + (xcd < r ? xcd : r) + local;
+    }
+    const int band = p.tpm * p.macro_cols;            // macro tiles in a full band of tasks
+    int ti = lid / band;
+    const int in_band = lid - ti * band;
+    const int h = (ti == p.n_i - 1) ? p.tpm_last : p.tpm;
+    int tj = in_band / (h * p.tpn);
+    if (tj > p.n_j - 1) tj = p.n_j - 1;
+    const int in_task = in_band - tj * h * p.tpn;
+    const int wcols = (tj == p.n_j - 1) ? p.tpn_last : p.tpn;
+    const int si = in_task / wcols, sj = in_task - si * wcols;
+
+    const int row0 = ti * p.T + si * BM;
+    const int col0 = tj * p.T + sj * BN;
+    const int row_end = min(p.M, (ti + 1) * p.T);
+    const int col_end = min(p.N, (tj + 1) * p.T);
+
+    const float* __restrict__ A = reinterpret_cast<const float*>(p.A);
+    const float* __restrict__ B = reinterpret_cast<const float*>(p.B);
+
+    f32x16 acc[RA][RB];
+#pragma unroll
+    for (int r = 0; r < RA; ++r)
+#pragma unroll
+        for (int c = 0; c < RB; ++c)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[r][c][v] = 0.f;
+
+    f32x4 ra[LA::UP], rb[LB::UP];
+
+    const int n_chunks = p.n_chunks;
+    const int cps = p.chunks_per_step;
+
+    auto chunk_range = [&](int c, int& kk, int& klim) {
+        const int step = c / cps;
+        kk = step * p.T + (c - step * cps) * BK;
+        klim = min(p.K, (step + 1) * p.T);
+    };
+
+    if (n_chunks > 0) {
+        int kk, klim;
+        chunk_range(0, kk, klim);
+        LA::load(ra, A, p.lda, row0, row_end, kk, klim, p.vec_a, tid);
+        LB::load(rb, B, p.ldb, col0, col_end, kk, klim, p.vec_b, tid);
+        LA::store(ra, As, tid);
+        LB::store(rb, Bs, tid);
+    }
+    __syncthreads();
+
+    const int a_off = wm * WTM + RA * li;
+    const int b_off = wn * WTN + RB * li;
+
+    for (int c = 0; c < n_chunks; ++c) {
+        const int st = c & 1;
+        const bool more = (c + 1 < n_chunks);
+        if (more) {
+            int kk, klim;
+            chunk_range(c + 1, kk, klim);
+            LA::load(ra, A, p.lda, row0, row_end, kk, klim, p.vec_a, tid);
+            LB::load(rb, B, p.ldb, col0, col_end, kk, klim, p.vec_b, tid);
+        }
+        const float* as = As + st * STAGE_A + lh * LDA_S + a_off;
+        const float* bs = Bs + st * STAGE_B + lh * LDB_S + b_off;
+#pragma unroll
+        for (int kp = 0; kp < BK / 2; ++kp) {
+            const VA a = *reinterpret_cast<const VA*>(as + (2 * kp) * LDA_S);
+            const VB b = *reinterpret_cast<const VB*>(bs + (2 * kp) * LDB_S);
+#pragma unroll
+            for (int r = 0; r < RA; ++r)
+#pragma unroll
+                for (int cc = 0; cc < RB; ++cc)
+                    acc[r][cc] = __builtin_amdgcn_mfma_f32_32x32x2f32(vget<RA>(a, r), vget<RB>(b, cc),
+                                                                      acc[r][cc], 0, 0, 0);
+        }
+        if (more) {
+            LA::store(ra, As + (st ^ 1) * STAGE_A, tid);
+            LB::store(rb, Bs + (st ^ 1) * STAGE_B, tid);
+        }
+        __syncthreads();
+    }
+
+    // -- epilogue.  acc[r][cc][v] is element (row, col) of the wave tile with
+    //    row = RA * (8*(v/4) + 4*lh + v%4) + r,  col = RB * li + cc.
+    float* __restrict__ C = p.C;
+    const float* __restrict__ aux = reinterpret_cast<const float*>(p.aux);
+    const float alpha = p.alpha, beta = p.beta;
+    const int colb = col0 + wn * WTN + RB * li;
+    const bool cvec = p.vec_c && (RB == 4) && (colb + 3 < col_end);
+#pragma unroll
+    for (int r = 0; r < RA; ++r) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = row0 + wm * WTM + RA * (8 * (v >> 2) + 4 * lh + (v & 3)) + r;
+            if (row >= row_end) continue;
+            float o[RB];
+#pragma unroll
+            for (int cc = 0; cc < RB; ++cc) o[cc] = acc[r][cc][v];
+            float* dst = C + (int64_t)row * p.ldc + colb;
+            if (EPI == EPI_AXPBY) {
+                if (beta != 0.f) {
+                    if (cvec) {
+                        const f32x4 cin = *reinterpret_cast<const f32x4*>(dst);
+#pragma unroll
+                        for (int cc = 0; cc < RB; ++cc) o[cc] = fmaf(alpha, o[cc], beta * cin[cc]);
+                    } else {
+#pragma unroll
+                        for (int cc = 0; cc < RB; ++cc)
+                            if (colb + cc < col_end) o[cc] = fmaf(alpha, o[cc], beta * dst[cc]);
+                    }
+                } else {
+#pragma unroll
+                    for (int cc = 0; cc < RB; ++cc) o[cc] = alpha * o[cc];
+                }
+            } else if (EPI == EPI_SIGMOID) {
+#pragma unroll
+                for (int cc = 0; cc < RB; ++cc) o[cc] = 1.f / (1.f + __expf(-o[cc]));
+            } else if (EPI == EPI_DSIGMOID) {
+                const float* ax = aux + (int64_t)row * p.ldaux + colb;
+#pragma unroll
+                for (int cc = 0; cc < RB; ++cc)
+                    if (colb + cc < col_end) {
+                        const float a = ax[cc];
+                        o[cc] = o[cc] * a * (1.f - a);
+                    }
+            }
+            if (cvec) {
+                f32x4 ov;
+#pragma unroll
+                for (int cc = 0; cc < RB; ++cc) ov[cc & 3] = o[cc];
+                *reinterpret_cast<f32x4*>(dst) = ov;
+            } else {
+#pragma unroll
+                for (int cc = 0; cc < RB; ++cc)
+                    if (colb + cc < col_end) dst[cc] = o[cc];
+            }
+        }
+    }
+}
+
+// ---- host-side launcher -------------------------------------------------------------------------
+template <int RA, int RB, int WM, int WN>
+struct Cfg {
+    static constexpr int BM = WM * 32 * RA, BN = WN * 32 * RB, NT = WM * WN * 64;
+    static constexpr size_t LDS = 2 * (size_t)BK * ((BM + PAD) + (BN + PAD)) * sizeof(float);
+};
+
+template <int RA, int RB, int WM, int WN, bool A_KC, bool B_KC, int EPI>
+static hipError_t launch_one(const GemmParams& p, int grid, hipStream_t stream)
+{
+    typedef Cfg<RA, RB, WM, WN> C;
+    auto kern = tile_gemm_f32<RA, RB, WM, WN, A_KC, B_KC, EPI>;
+    static bool attr_set = false;   // per instantiation; the attribute is per function, idempotent
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(C::NT), C::LDS, stream, p);
+    return hipGetLastError();
+}
+
+template <int RA, int RB, int WM, int WN>
+static hipError_t launch_cfg(GemmParams& p, const GemmDesc& d, hipStream_t stream)
+{
+    typedef Cfg<RA, RB, WM, WN> C;
+    const int64_t T = d.T;
+    p.n_i = (int)((d.M + T - 1) / T);
+    p.n_j = (int)((d.N + T - 1) / T);
+    const int64_t n_k = (d.K + T - 1) / T;
+    const int64_t last_m = d.M - (int64_t)(p.n_i - 1) * T;
+    const int64_t last_n = d.N - (int64_t)(p.n_j - 1) * T;
+    const int64_t full_m = p.n_i > 1 ? T : last_m, full_n = p.n_j > 1 ? T : last_n;
+    p.tpm = (int)((full_m + C::BM - 1) / C::BM);
+    p.tpn = (int)((full_n + C::BN - 1) / C::BN);
+    p.tpm_last = (int)((last_m + C::BM - 1) / C::BM);
+    p.tpn_last = (int)((last_n + C::BN - 1) / C::BN);
+    p.macro_cols = (p.n_j - 1) * p.tpn + p.tpn_last;
+    const int64_t macro_rows = (int64_t)(p.n_i - 1) * p.tpm + p.tpm_last;
+    const int64_t grid = macro_rows * p.macro_cols;
+    if (grid <= 0 || grid > 0x7fffffff) return hipErrorInvalidValue;
+    const int64_t full_k = n_k > 1 ? T : d.K;
+    p.chunks_per_step = (int)((full_k + BK - 1) / BK);
+    const int64_t last_k = d.K - (n_k - 1) * T;
+    p.n_chunks = (int)((n_k - 1) * p.chunks_per_step + (last_k + BK - 1) / BK);
+
+#define TG_LAUNCH(AK, BKC, E) return launch_one<RA, RB, WM, WN, AK, BKC, E>(p, (int)grid, stream)
+#define TG_EPI(AK, BKC)                                            \
+    switch (d.epilogue) {                                          \
+        case EPI_AXPBY: TG_LAUNCH(AK, BKC, EPI_AXPBY);             \
+        case EPI_SIGMOID: TG_LAUNCH(AK, BKC, EPI_SIGMOID);         \
+        case EPI_DSIGMOID: TG_LAUNCH(AK, BKC, EPI_DSIGMOID);       \
+        default: return hipErrorInvalidValue;                      \
+    }
+    if (d.a_kcontig && !d.b_kcontig) { TG_EPI(true, false) }
+    if (!d.a_kcontig && !d.b_kcontig) { TG_EPI(false, false) }
+    if (d.a_kcontig && d.b_kcontig) { TG_EPI(true, true) }
+    return hipErrorInvalidValue;   // (m-contiguous A) x (k-contiguous B) is not used by any pass
+#undef TG_EPI
+#undef TG_LAUNCH
+}
+
+int pick_config(const GemmDesc& d)
+{
+    if (d.config >= 1 && d.config <= 3) return d.config;
+    // Enough macro tiles to give every CU at least ~2 workgroups of the large shape; otherwise
+    // shrink the macro tile so that small products still spread over the 256 CUs.
+    auto tiles = [&](int64_t bm, int64_t bn) {
+        const int64_t T = d.T;
+        const int64_t n_i = (d.M + T - 1) / T, n_j = (d.N + T - 1) / T;
+        const int64_t lm = d.M - (n_i - 1) * T, ln = d.N - (n_j - 1) * T;
+        const int64_t fm = n_i > 1 ? T : lm, fn = n_j > 1 ? T : ln;
+        return ((n_i - 1) * ((fm + bm - 1) / bm) + (lm + bm - 1) / bm) *
+               ((n_j - 1) * ((fn + bn - 1) / bn) + (ln + bn - 1) / bn);
+    };
+    if (tiles(256, 256) >= 384) return 3;
+    if (tiles(128, 128) >= 384) return 2;
+    return 1;
+}
+
+hipError_t launch_tile_gemm_f32(const GemmDesc& d, hipStream_t stream)
+{
+    if (d.M <= 0 || d.N <= 0 || d.K < 0 || d.T <= 0) return hipErrorInvalidValue;
+    if (d.M > 0x7fffffff || d.N > 0x7fffffff || d.K > 0x7fffffff) return hipErrorInvalidValue;
+    GemmParams p;
+    p.A = d.A; p.B = d.B; p.C = d.C; p.aux = d.aux;
+    p.lda = d.lda; p.ldb = d.ldb; p.ldc = d.ldc; p.ldaux = d.ldaux;
+    p.M = (int)d.M; p.N = (int)d.N; p.K = (int)d.K;
+    // a tile size beyond every dimension means "one task, one k-step"; clamp so that the index
+    // arithmetic in the kernel stays inside int
+    int64_t T = d.T;
+    const int64_t big = (d.M > d.N ? d.M : d.N) > d.K ? (d.M > d.N ? d.M : d.N) : d.K;
+    if (T > big) T = big > 0 ? big : 1;
+    p.T = (int)T;
+    p.alpha = d.alpha; p.beta = d.beta;
+    const bool t4 = (T % 4 == 0);
+    auto al16 = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15) == 0; };
+    p.vec_a = t4 && al16(d.A) && (d.lda % 4 == 0);
+    p.vec_b = t4 && al16(d.B) && (d.ldb % 4 == 0);
+    p.vec_c = t4 && al16(d.C) && (d.ldc % 4 == 0);
+    GemmDesc dd = d;
+    dd.T = (int32_t)T;
+    switch (pick_config(dd)) {
+        case 3: return launch_cfg<2, 4, 4, 2>(p, dd, stream);   // 256 x 256, 512 threads
+        case 2: return launch_cfg<2, 2, 2, 2>(p, dd, stream);   // 128 x 128, 256 threads
+        default: return launch_cfg<1, 1, 2, 2>(p, dd, stream);  //  64 x  64, 256 threads
+    }
+}
+
+}  // namespace tg

@@ -1,0 +1,51 @@
+// Internal interface between the runtime (engine, MLP passes) and the tile GEMM kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace tg {
+
+enum { EPI_AXPBY = 0, EPI_SIGMOID = 1, EPI_DSIGMOID = 2 };
+
+// What a caller asks for: out = epilogue(op(A) op(B)), tiled by T (section 3.1 of the paper).
+//   EPI_AXPBY    C = alpha * (A B) + beta * C       (beta == 0: C is not read)
+//   EPI_SIGMOID  C = sigmoid(A B)
+//   EPI_DSIGMOID C = (A B) * aux * (1 - aux)         (aux: M x N, leading dimension ldaux)
+// a_kcontig: A stored M x K row-major (k contiguous); otherwise stored K x M (m contiguous).
+// b_kcontig: B stored N x K row-major (k contiguous); otherwise stored K x N (n contiguous).
+struct GemmDesc {
+    const void* A;
+    const void* B;
+    float* C;
+    const void* aux;
+    int64_t lda, ldb, ldc, ldaux;
+    int64_t M, N, K;
+    int32_t T;
+    int32_t a_kcontig, b_kcontig;
+    int32_t epilogue;
+    float alpha, beta;
+    int32_t config;   // 0 = automatic, 1..3 = small / medium / large macro tile
+};
+
+// Kernel argument block (filled by the launcher).
+struct GemmParams {
+    const void* A;
+    const void* B;
+    float* C;
+    const void* aux;
+    int64_t lda, ldb, ldc, ldaux;
+    int M, N, K, T;
+    int n_i, n_j;               // task grid
+    int tpm, tpn;               // macro tiles per full task, rows / cols
+    int tpm_last, tpn_last;     // macro tiles of the last (possibly ragged) task row / col
+    int macro_cols;             // macro-tile columns of the whole matrix
+    int chunks_per_step;        // BK-chunks in a full k-step
+    int n_chunks;               // BK-chunks over all k-steps
+    float alpha, beta;
+    bool vec_a, vec_b, vec_c;   // 16-byte vector access is legal for this operand
+};
+
+int pick_config(const GemmDesc& d);
+hipError_t launch_tile_gemm_f32(const GemmDesc& d, hipStream_t stream);
+
+}  // namespace tg

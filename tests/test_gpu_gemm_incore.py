@@ -1,0 +1,162 @@
+"""GPU parity of the in-core tiled GEMM against the CPU oracle, through the C ABI.
+
+Bars: integer-valued inputs bit-exact; uniform[-1,1) fp32 inputs relative Frobenius error <= 1e-5
+(the fp32 chain of length K contributes about 2^-24 * sqrt(K) / sqrt(6), i.e. 2e-6 at K = 8000)."""
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import announce, rel_fro, run_incore
+from paper_1511_04348_amd import binding as tg
+from paper_1511_04348_amd import inputs
+
+pytestmark = pytest.mark.gpu
+TOL_F32 = 1e-5
+
+
+@pytest.fixture(scope="module")
+def ctxs():
+    made = {cfg: tg.tgemm_create(0, kernel_config=cfg) for cfg in (0, 1, 2, 3)}
+    yield made
+    for c in made.values():
+        tg.tgemm_destroy(c)
+
+
+INT_CASES = [
+    # M, N, K, T
+    (1, 1, 1, 1), (3, 5, 7, 2), (37, 53, 29, 16), (64, 64, 16, 1024), (257, 131, 77, 64),
+    (300, 300, 300, 100), (513, 259, 1025, 256), (1000, 1000, 1000, 256), (130, 1030, 40, 512),
+    (700, 36, 2050, 1024),
+]
+
+
+@pytest.mark.parametrize("cfg", [0, 1, 2, 3])
+@pytest.mark.parametrize("M,N,K,T", INT_CASES)
+def test_integer_inputs_bit_exact(ctxs, oracle, M, N, K, T, cfg):
+    announce("int", M, N, K, T, "cfg", cfg)
+    A = inputs.int_matrix(11, M, K)
+    B = inputs.int_matrix(12, K, N)
+    C0 = inputs.int_matrix(13, M, N, lo=-7, hi=7)
+    ref = oracle.gemm(A.numpy(), B.numpy(), c_in=C0.numpy())
+    C = C0.cuda()
+    run_incore(ctxs[cfg], A.cuda(), B.cuda(), C, T)
+    assert np.array_equal(C.cpu().numpy().astype(np.float64), ref)
+
+
+def test_config1_full_parity(ctxs, oracle):
+    """fp32 1000^3, T = 256 (232-wide edge tiles), uniform[-1,1), C = 0."""
+    n, T = 1000, 256
+    A = inputs.uniform_matrix(1, n, n)
+    B = inputs.uniform_matrix(2, n, n)
+    ref = oracle.gemm(A.numpy(), B.numpy())
+    for cfg in (0, 1, 2, 3):
+        announce("config1 cfg", cfg)
+        C = torch.zeros(n, n, device="cuda")
+        run_incore(ctxs[cfg], A.cuda(), B.cuda(), C, T)
+        err = rel_fro(C.cpu().numpy(), ref)
+        print("config1 cfg", cfg, "rel fro", err)
+        assert err <= TOL_F32
+    st = tg.tgemm_last_stats(ctxs[0])
+    assert st["in_core"] == 1 and st["n_tasks"] == 16 and st["n_tile_gemms"] == 64 and st["kernel_ms"] > 0
+
+
+def test_accumulates_into_c_and_unaligned_pointers(ctxs, oracle):
+    """C <- C + A B with non-zero C; odd leading dimensions and a 4-byte-aligned base pointer
+    force the scalar load/store paths."""
+    M, N, K, T = 203, 157, 301, 64
+    A = inputs.uniform_matrix(3, M, K)
+    B = inputs.uniform_matrix(4, K, N)
+    C0 = inputs.uniform_matrix(5, M, N)
+    ref = oracle.gemm(A.numpy(), B.numpy(), c_in=C0.numpy())
+    for cfg in (1, 2, 3):
+        announce("unaligned cfg", cfg)
+        bufA = torch.empty(M * K + 1, device="cuda")
+        bufB = torch.empty(K * N + 1, device="cuda")
+        bufC = torch.empty(M * N + 1, device="cuda")
+        a, b, c = bufA[1:].view(M, K), bufB[1:].view(K, N), bufC[1:].view(M, N)
+        a.copy_(A); b.copy_(B); c.copy_(C0)
+        run_incore(ctxs[cfg], a, b, c, T)
+        assert rel_fro(c.cpu().numpy(), ref) <= TOL_F32
+
+
+def test_tile_size_does_not_change_integer_result(ctxs, oracle):
+    M, N, K = 390, 270, 530
+    A = inputs.int_matrix(21, M, K)
+    B = inputs.int_matrix(22, K, N)
+    ref = oracle.gemm(A.numpy(), B.numpy())
+    for T in (1000, 256, 128, 100, 52, 17):
+        announce("tile size", T)
+        C = torch.zeros(M, N, device="cuda")
+        run_incore(ctxs[0], A.cuda(), B.cuda(), C, T)
+        assert np.array_equal(C.cpu().numpy().astype(np.float64), ref), T
+
+
+def test_empty_dimensions(ctxs):
+    C = torch.full((4, 5), 3.0, device="cuda")
+    A = torch.zeros(4, 1, device="cuda")
+    B = torch.zeros(1, 5, device="cuda")
+    tg.tgemm_run(ctxs[0], A, B, C, 4, 5, 0, 16)        # K = 0: C unchanged
+    tg.tgemm_run(ctxs[0], A, B, C, 0, 5, 1, 16)        # M = 0: nothing to do
+    torch.cuda.synchronize()
+    assert torch.equal(C.cpu(), torch.full((4, 5), 3.0))
+
+
+def test_error_paths(ctxs):
+    ctx = ctxs[0]
+    A = torch.zeros(8, 8, device="cuda")
+    host = torch.zeros(8, 8)                      # pageable
+    pinned = torch.zeros(8, 8).pin_memory()
+    with pytest.raises(tg.TgemmError) as e:
+        tg.tgemm_run(ctx, host, A, A.clone(), 8, 8, 8, 4)
+    assert e.value.code == tg.TGEMM_EUNPINNED
+    with pytest.raises(tg.TgemmError) as e:
+        tg.tgemm_run(ctx, pinned, A, A.clone(), 8, 8, 8, 4)
+    assert e.value.code == tg.TGEMM_EARG          # mixed kinds
+    with pytest.raises(tg.TgemmError) as e:
+        tg.tgemm_run(ctx, A, A.clone(), A, 8, 8, 8, 4)
+    assert e.value.code == tg.TGEMM_EARG          # C aliases A
+    with pytest.raises(tg.TgemmError) as e:
+        tg.tgemm_run(ctx, A, A.clone(), A.clone(), 8, 8, 8, 0)
+    assert e.value.code == tg.TGEMM_EARG
+    with pytest.raises(tg.TgemmError) as e:
+        tg.tgemm_run(ctx, A, A.clone(), A.clone(), 8, 8, 8, 4, dtype=7)
+    assert e.value.code == tg.TGEMM_EARG
+    # the context is still usable
+    C = torch.zeros(8, 8, device="cuda")
+    tg.tgemm_run(ctx, torch.eye(8, device="cuda"), torch.ones(8, 8, device="cuda"), C, 8, 8, 8, 4)
+    assert torch.equal(C.cpu(), torch.ones(8, 8))
+
+
+def test_config2_sampled_parity_full_size(ctxs, oracle):
+    """fp32 8000^3, T = 1024 (832-wide edge tiles): every tile-corner entry and 4096 random
+    entries against fp64 dot products; an integer-valued run checked the same way, bit-exact."""
+    n, T = 8000, 1024
+    A = inputs.uniform_matrix(1, n, n, device="cuda")
+    B = inputs.uniform_matrix(2, n, n, device="cuda")
+    C = torch.zeros(n, n, device="cuda")
+    announce("config2 uniform")
+    run_incore(ctxs[0], A, B, C, T)
+    edges = sorted(set([0, n - 1] + [t * T for t in range(1, 8)] + [t * T - 1 for t in range(1, 8)]))
+    rr, cc = np.meshgrid(edges, edges, indexing="ij")
+    rnd = np.random.default_rng(0)
+    rows = np.concatenate([rr.ravel(), rnd.integers(0, n, 4096)])
+    cols = np.concatenate([cc.ravel(), rnd.integers(0, n, 4096)])
+    An, Bn = A.cpu().numpy(), B.cpu().numpy()
+    ref = oracle.gemm_samples(An, Bn, rows, cols)
+    got = C.cpu().numpy()[rows, cols]
+    err = rel_fro(got, ref)
+    print("config2 sampled rel fro", err, "kernel ms", tg.tgemm_last_stats(ctxs[0])["kernel_ms"])
+    assert err <= TOL_F32
+    # column / row sums: C 1 = A (B 1) and 1^T C = (1^T A) B touch every entry of C
+    ones = np.ones(n)
+    assert rel_fro(C.double().sum(1).cpu().numpy(), An.astype(np.float64) @ (Bn.astype(np.float64) @ ones)) <= TOL_F32
+    assert rel_fro(C.double().sum(0).cpu().numpy(), (ones @ An.astype(np.float64)) @ Bn.astype(np.float64)) <= TOL_F32
+    announce("config2 integer")
+    Ai = inputs.int_matrix(31, n, n, device="cuda")
+    Bi = inputs.int_matrix(32, n, n, device="cuda")
+    Ci = torch.zeros(n, n, device="cuda")
+    run_incore(ctxs[0], Ai, Bi, Ci, T)
+    Ain, Bin = Ai.cpu().numpy(), Bi.cpu().numpy()
+    refi = oracle.gemm_samples(Ain, Bin, rows, cols)
+    assert np.array_equal(Ci.cpu().numpy()[rows, cols].astype(np.float64), refi)
+    assert np.array_equal(Ci.double().sum(1).cpu().numpy(), Ain.astype(np.float64) @ (Bin.astype(np.float64) @ ones))
