@@ -17,13 +17,16 @@ if ROOT not in sys.path:
 
 METRIC = "tiled GEMM TFLOP/s (in-core, out-of-core) + MLP train samples/s, 1 GPU"
 PEAK_F32_MFMA_TFLOPS = 157.3   # MI355X dense fp32 matrix peak
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (summaries under
+# profiles/); keyed by (size, tile).  None where no counter run exists.
+MEASURED_TRAFFIC_BYTES = {(8000, 1024): 1.926e9}
 
 
 def cpu_baseline_gemm(A_host, B_host, budget_s=12.0):
     """Times the oracle (as it stands) on a row slab of the same product, sized to ~budget_s."""
     import oracle
     K, N = B_host.shape
-    rows = 8
+    rows = 64
     t0 = time.perf_counter()
     oracle.gemm(A_host[:rows], B_host)
     t = time.perf_counter() - t0
@@ -44,6 +47,8 @@ def main():
     ap.add_argument("--tile", type=int, default=1024)
     ap.add_argument("--kernel-config", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run 5 plain device copies of 256 MiB (a known-size reference for HBM counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
@@ -75,6 +80,13 @@ def main():
     wall = time.perf_counter() - t0
     tg.tgemm_destroy(ctx)
 
+    if args.copy_probe:
+        src = torch.ones(64 * 1024 * 1024, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+
     ms_per_step = wall * 1e3 / args.steps
     avg_kernel_ms = kernel_ms / args.steps
     achieved = flops / (avg_kernel_ms * 1e-3) / 1e12
@@ -85,7 +97,8 @@ def main():
         "config": {"workload": "fp32 tiled GEMM M=N=K=%d, T=%d, in-core (A, B, C resident in HBM), C += A B" % (n, T),
                    "tile": T, "tasks": ((n + T - 1) // T) ** 2},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_F32_MFMA_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_F32_MFMA_TFLOPS, "traffic": None,
+                     "frac": achieved / PEAK_F32_MFMA_TFLOPS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((n, T)) if args.kernel_config == 0 else None,
                      "kernel": "tile_gemm_f32", "avg_kernel_ms": avg_kernel_ms,
                      "flops_per_launch": flops},
     }
