@@ -1,13 +1,387 @@
-// Out-of-core tile engine (placeholder until the engine lands).
+// Out-of-core tile engine: the one-GPU form of the paper's scheduling runtime and tile cache.
+//
+//   section 3.2  GPU computation thread  -> one submit thread per run (optionally bound to a core)
+//                4 concurrent tasks      -> 4 HIP streams; a stream = one reservation-station slot
+//                non-blocking task queue -> TaskQueue (ms_queue.h), filled by the caller thread
+//   section 3.4  L1 tile cache           -> slots in one HBM pool, directory keyed (matrix, ti, tj),
+//                                           strict LRU; there is no second-level (peer) cache on
+//                                           one GPU, a miss goes to host memory
+//   Algorithm 1  lines 5-17              -> submit_loop(): dequeue, decode, k loop {lookup A_ik,
+//                                           lookup B_kj, fetch on miss, asynchronous tile GEMM},
+//                                           asynchronous harvest of C_ij
+//
+// What differs from Algorithm 1: there is no per-round "synchronize all streams" (line 8).  A
+// stream takes the next task as soon as its previous one has finished, and every cross-stream
+// hazard is an event edge instead of a host-side wait:
+//   - a tile fetched on stream s and hit from stream s' : s' waits for the slot's `ready` event;
+//   - a slot evicted on stream s while kernels on other streams may still read the old tile:
+//     s waits for the slot's per-stream `read` events before the new copy is enqueued.
+// Cache decisions are taken in issue order on the host, so hits, misses and evictions are a pure
+// function of (sizes, T, slot count, task order), independent of timing.
+#include <pthread.h>
+#include <string.h>
+
+#include <algorithm>
+#include <atomic>
+#include <chrono>
+#include <thread>
+#include <unordered_map>
+#include <vector>
+
 #include "common.h"
+#include "gemm_kernel.h"
+#include "ms_queue.h"
 
 namespace tg {
 
-int run_out_of_core(tgemm_ctx*, const void*, const void*, float*, int64_t, int64_t, int64_t, int32_t, int32_t, size_t)
+namespace {
+
+struct Slot {
+    int64_t key = -1;
+    hipEvent_t ready = nullptr;
+    int ready_stream = -1;
+    hipEvent_t read_ev[4] = {nullptr, nullptr, nullptr, nullptr};
+    bool read_pending[4] = {false, false, false, false};
+    int prev = -1, next = -1;
+};
+
+inline int64_t tile_key(int mat, int64_t ti, int64_t tj) { return ((int64_t)mat << 62) | (ti << 31) | tj; }
+
+}  // namespace
+
+class Engine {
+public:
+    char* pool = nullptr;
+    size_t pool_bytes = 0;
+    std::vector<Slot> slots;
+    hipEvent_t task_done[4] = {nullptr, nullptr, nullptr, nullptr};
+    bool task_pending[4] = {false, false, false, false};
+    // directory + LRU list (head = least recently used)
+    std::unordered_map<int64_t, int> dir;
+    int lru_head = -1, lru_tail = -1;
+    int n_used = 0;
+
+    ~Engine()
+    {
+        for (auto& s : slots) {
+            if (s.ready) (void)hipEventDestroy(s.ready);
+            for (auto& e : s.read_ev)
+                if (e) (void)hipEventDestroy(e);
+        }
+        for (auto& e : task_done)
+            if (e) (void)hipEventDestroy(e);
+        if (pool) (void)hipFree(pool);
+    }
+
+    int ensure_pool(size_t bytes)
+    {
+        if (pool && pool_bytes >= bytes) return TGEMM_OK;
+        if (pool) {
+            (void)hipFree(pool);
+            pool = nullptr;
+            pool_bytes = 0;
+        }
+        hipError_t e = hipMalloc((void**)&pool, bytes);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            pool = nullptr;
+            return fail(TGEMM_ENOMEM, "tile cache: hipMalloc of %zu bytes failed: %s", bytes, hipGetErrorString(e));
+        }
+        pool_bytes = bytes;
+        return TGEMM_OK;
+    }
+
+    int ensure_events(int n_slots)
+    {
+        for (auto& e : task_done)
+            if (!e) TG_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        const size_t old = slots.size();
+        if ((size_t)n_slots > old) slots.resize(n_slots);
+        for (size_t i = old; i < slots.size(); ++i) {
+            TG_HIP(hipEventCreateWithFlags(&slots[i].ready, hipEventDisableTiming));
+            for (auto& e : slots[i].read_ev) TG_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        }
+        return TGEMM_OK;
+    }
+
+    void reset_directory()
+    {
+        dir.clear();
+        lru_head = lru_tail = -1;
+        n_used = 0;
+        for (auto& s : slots) {
+            s.key = -1;
+            s.ready_stream = -1;
+            s.prev = s.next = -1;
+            for (auto& p : s.read_pending) p = false;
+        }
+        for (auto& p : task_pending) p = false;
+    }
+
+    void lru_unlink(int i)
+    {
+        Slot& s = slots[i];
+        if (s.prev >= 0) slots[s.prev].next = s.next; else lru_head = s.next;
+        if (s.next >= 0) slots[s.next].prev = s.prev; else lru_tail = s.prev;
+        s.prev = s.next = -1;
+    }
+    void lru_push_mru(int i)
+    {
+        Slot& s = slots[i];
+        s.prev = lru_tail;
+        s.next = -1;
+        if (lru_tail >= 0) slots[lru_tail].next = i; else lru_head = i;
+        lru_tail = i;
+    }
+};
+
+void destroy_engine(tgemm_ctx* ctx)
 {
-    return fail(TGEMM_EARG, "out-of-core runs are not implemented yet");
+    delete ctx->engine;
+    ctx->engine = nullptr;
 }
 
-void destroy_engine(tgemm_ctx*) {}
+namespace {
+
+struct Run {
+    tgemm_ctx* ctx;
+    Engine* eng;
+    const char* A;
+    const char* B;
+    float* C;
+    int64_t M, N, K, T;
+    int64_t n_i, n_j, n_k;
+    int64_t tm, tn, tk;        // slot extents (rows of A/C tiles, cols of B/C tiles, k extent)
+    size_t es;                 // bytes per A/B element
+    size_t slot_ab, slot_c;    // bytes per slot
+    int n_ab;                  // A/B slots available
+    TaskQueue* queue;
+    std::atomic<bool> producer_done{false};
+    std::atomic<bool> failed{false};
+    int rc = TGEMM_OK;
+    char err[256] = "";
+    int rr = 0;                // round-robin start of the stream search
+
+    char* ab_slot_ptr(int slot) const { return eng->pool + 4 * slot_c + (size_t)slot * slot_ab; }
+    float* c_slot_ptr(int s) const { return (float*)(eng->pool + (size_t)s * slot_c); }
+
+    bool check(hipError_t e, const char* what)
+    {
+        if (e == hipSuccess) return true;
+        if (rc == TGEMM_OK) {
+            rc = TGEMM_EHIP;
+            snprintf(err, sizeof err, "%s failed: %s", what, hipGetErrorString(e));
+            failed.store(true, std::memory_order_release);
+        }
+        return false;
+    }
+
+    // Algorithm 1 lines 6-7: the next free reservation-station slot (= stream).
+    int pick_stream()
+    {
+        for (;;) {
+            for (int t = 0; t < 4; ++t) {
+                const int s = (rr + t) & 3;
+                if (!eng->task_pending[s]) { rr = s + 1; return s; }
+                const hipError_t q = hipEventQuery(eng->task_done[s]);
+                if (q == hipSuccess) {
+                    eng->task_pending[s] = false;
+                    rr = s + 1;
+                    return s;
+                }
+                if (q != hipErrorNotReady) {
+                    check(q, "hipEventQuery");
+                    return -1;
+                }
+                (void)hipGetLastError();
+            }
+            std::this_thread::sleep_for(std::chrono::microseconds(20));
+        }
+    }
+
+    // Algorithm 1 lines 12-15: look the tile up in the L1 tile cache; on a miss take a free slot
+    // or evict the least recently used one and fetch the tile from host memory.
+    int acquire(int mat, int64_t ti, int64_t tj, int s, const char* src, size_t src_pitch,
+                size_t width_bytes, size_t height, size_t slot_pitch, int* hit, int* evicted)
+    {
+        Engine& e = *eng;
+        hipStream_t st = ctx->streams[s];
+        const int64_t key = tile_key(mat, ti, tj);
+        auto it = e.dir.find(key);
+        *evicted = 0;
+        if (it != e.dir.end()) {
+            const int slot = it->second;
+            e.lru_unlink(slot);
+            e.lru_push_mru(slot);
+            *hit = 1;
+            ctx->stats.hits++;
+            if (e.slots[slot].ready_stream != s)
+                check(hipStreamWaitEvent(st, e.slots[slot].ready, 0), "hipStreamWaitEvent(ready)");
+            return slot;
+        }
+        *hit = 0;
+        ctx->stats.misses++;
+        int slot;
+        if (e.n_used < n_ab) {
+            slot = e.n_used++;
+        } else {
+            slot = e.lru_head;
+            e.lru_unlink(slot);
+            e.dir.erase(e.slots[slot].key);
+            *evicted = 1;
+            ctx->stats.evictions++;
+            Slot& sl = e.slots[slot];
+            for (int s2 = 0; s2 < 4; ++s2) {
+                if (sl.read_pending[s2] && s2 != s)
+                    check(hipStreamWaitEvent(st, sl.read_ev[s2], 0), "hipStreamWaitEvent(read)");
+                sl.read_pending[s2] = false;
+            }
+        }
+        Slot& sl = e.slots[slot];
+        sl.key = key;
+        e.dir[key] = slot;
+        e.lru_push_mru(slot);
+        check(hipMemcpy2DAsync(ab_slot_ptr(slot), slot_pitch, src, src_pitch, width_bytes, height,
+                               hipMemcpyHostToDevice, st), "hipMemcpy2DAsync(H2D tile)");
+        ctx->stats.h2d_bytes += (int64_t)(width_bytes * height);
+        check(hipEventRecord(sl.ready, st), "hipEventRecord(ready)");
+        sl.ready_stream = s;
+        return slot;
+    }
+
+    // Algorithm 1 lines 9-17 for one task on stream s.
+    void issue_task(int64_t id, int s)
+    {
+        hipStream_t st = ctx->streams[s];
+        const int64_t i = id / n_j, j = id % n_j;              // decode
+        const int64_t r0 = i * T, rows = std::min(T, M - r0);
+        const int64_t c0 = j * T, cols = std::min(T, N - c0);
+        float* cs = c_slot_ptr(s);
+        // C_ij enters with its current value: the product accumulates into C
+        check(hipMemcpy2DAsync(cs, tn * 4, C + r0 * N + c0, N * 4, cols * 4, rows, hipMemcpyHostToDevice, st),
+              "hipMemcpy2DAsync(H2D C tile)");
+        ctx->stats.h2d_bytes += rows * cols * 4;
+        for (int64_t k = 0; k < n_k && rc == TGEMM_OK; ++k) {
+            const int64_t k0 = k * T, klen = std::min(T, K - k0);
+            int a_hit, b_hit, a_ev, b_ev;
+            const int sa = acquire(0, i, k, s, A + (r0 * K + k0) * es, K * es, klen * es, rows, tk * es, &a_hit, &a_ev);
+            const int sb = acquire(1, k, j, s, B + (k0 * N + c0) * es, N * es, cols * es, klen, tn * es, &b_hit, &b_ev);
+            GemmDesc d;
+            memset(&d, 0, sizeof d);
+            d.A = ab_slot_ptr(sa); d.B = ab_slot_ptr(sb); d.C = cs;
+            d.lda = tk; d.ldb = tn; d.ldc = tn;
+            d.M = rows; d.N = cols; d.K = klen;
+            d.T = (int32_t)std::max(std::max(rows, cols), klen);   // the tile product is one task, one step
+            d.a_kcontig = 1; d.b_kcontig = 0;
+            d.epilogue = EPI_AXPBY; d.alpha = 1.f; d.beta = 1.f;
+            d.config = ctx->opts.kernel_config;
+            check(launch_tile_gemm_f32(d, st), "tile GEMM launch");
+            ctx->stats.kernel_launches++;
+            Slot& la = eng->slots[sa];
+            Slot& lb = eng->slots[sb];
+            check(hipEventRecord(la.read_ev[s], st), "hipEventRecord(read A)");
+            la.read_pending[s] = true;
+            check(hipEventRecord(lb.read_ev[s], st), "hipEventRecord(read B)");
+            lb.read_pending[s] = true;
+            if (ctx->opts.trace) {
+                tgemm_trace_rec r;
+                r.task_id = id; r.i = (int32_t)i; r.j = (int32_t)j; r.k = (int32_t)k; r.stream = s;
+                r.a_hit = a_hit; r.b_hit = b_hit; r.a_slot = sa; r.b_slot = sb; r.a_evicted = a_ev; r.b_evicted = b_ev;
+                ctx->trace.push_back(r);
+            }
+        }
+        // harvest
+        check(hipMemcpy2DAsync(C + r0 * N + c0, N * 4, cs, tn * 4, cols * 4, rows, hipMemcpyDeviceToHost, st),
+              "hipMemcpy2DAsync(D2H C tile)");
+        ctx->stats.d2h_bytes += rows * cols * 4;
+        check(hipEventRecord(eng->task_done[s], st), "hipEventRecord(task done)");
+        eng->task_pending[s] = true;
+    }
+
+    void submit_loop()
+    {
+        if (!check(hipSetDevice(ctx->device), "hipSetDevice")) return;
+        if (ctx->opts.affinity_core >= 0) {
+            cpu_set_t set;
+            CPU_ZERO(&set);
+            CPU_SET(ctx->opts.affinity_core, &set);
+            (void)pthread_setaffinity_np(pthread_self(), sizeof set, &set);   // best effort
+        }
+        // Algorithm 1 line 5: run until the task queue has drained (and the producer has finished)
+        int64_t id;
+        while (rc == TGEMM_OK) {
+            if (!queue->dequeue(&id)) {
+                if (!producer_done.load(std::memory_order_acquire)) {
+                    std::this_thread::yield();
+                    continue;
+                }
+                if (!queue->dequeue(&id)) break;
+            }
+            const int s = pick_stream();
+            if (s < 0) break;
+            issue_task(id, s);
+        }
+        for (int s = 0; s < 4; ++s) check(hipStreamSynchronize(ctx->streams[s]), "hipStreamSynchronize");
+        for (auto& p : eng->task_pending) p = false;
+    }
+};
+
+inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+}  // namespace
+
+int run_out_of_core(tgemm_ctx* ctx, const void* A, const void* B, float* C, int64_t M, int64_t N,
+                    int64_t K, int32_t T, int32_t dtype, size_t hbm_budget)
+{
+    if (dtype != TGEMM_F32) return fail(TGEMM_EARG, "tgemm_run: the bf16 out-of-core path is not built yet");
+    Run r;
+    r.ctx = ctx;
+    r.A = (const char*)A; r.B = (const char*)B; r.C = C;
+    r.M = M; r.N = N; r.K = K; r.T = T;
+    r.n_i = (M + T - 1) / T; r.n_j = (N + T - 1) / T; r.n_k = (K + T - 1) / T;
+    r.tm = std::min<int64_t>(T, M); r.tn = std::min<int64_t>(T, N); r.tk = std::min<int64_t>(T, K);
+    r.es = 4;
+    r.slot_ab = round_up(std::max(r.tm * r.tk, r.tk * r.tn) * r.es, 256);
+    r.slot_c = round_up((size_t)(r.tm * r.tn) * 4, 256);
+    const size_t min_bytes = 4 * r.slot_c + 8 * r.slot_ab;
+    if (hbm_budget < min_bytes)
+        return fail(TGEMM_EBUDGET, "tgemm_run: hbm_budget %zu is below the minimum working set %zu "
+                    "(4 C slots of %zu bytes + 8 A/B slots of %zu bytes)", hbm_budget, min_bytes, r.slot_c, r.slot_ab);
+    int64_t n_ab = (int64_t)((hbm_budget - 4 * r.slot_c) / r.slot_ab);
+    n_ab = std::min<int64_t>(n_ab, r.n_i * r.n_k + r.n_k * r.n_j);   // never more than the distinct tiles
+    n_ab = std::max<int64_t>(n_ab, 8);
+    r.n_ab = (int)n_ab;
+
+    if (!ctx->engine) {
+        ctx->engine = new (std::nothrow) Engine();
+        if (!ctx->engine) return fail(TGEMM_ENOMEM, "tgemm_run: host allocation failed");
+    }
+    r.eng = ctx->engine;
+    int rc = r.eng->ensure_pool(4 * r.slot_c + (size_t)r.n_ab * r.slot_ab);
+    if (rc != TGEMM_OK) return rc;
+    rc = r.eng->ensure_events(r.n_ab);
+    if (rc != TGEMM_OK) return rc;
+    r.eng->reset_directory();
+    ctx->stats.n_slots = r.n_ab;
+
+    // Algorithm 1 line 1: the task queue receives every task id in issue order
+    const int64_t n_tasks = r.n_i * r.n_j;
+    std::vector<int64_t> order((size_t)n_tasks);
+    rc = tgemm_task_order(r.n_i, r.n_j, ctx->opts.order, order.data());
+    if (rc != TGEMM_OK) return rc;
+    TaskQueue queue((uint32_t)std::min<int64_t>(n_tasks, 1 << 20));
+    r.queue = &queue;
+    if (ctx->opts.trace) ctx->trace.reserve((size_t)(n_tasks * r.n_k));
+
+    // Algorithm 1 lines 3-4: the GPU computation thread; the caller thread is the producer
+    std::thread submit([&r] { r.submit_loop(); });
+    for (int64_t t = 0; t < n_tasks && !r.failed.load(std::memory_order_acquire); ++t)
+        while (!queue.enqueue(order[(size_t)t]) && !r.failed.load(std::memory_order_acquire))
+            std::this_thread::yield();   // pool full: the consumer is behind
+    r.producer_done.store(true, std::memory_order_release);
+    submit.join();
+    if (r.rc != TGEMM_OK) return fail(r.rc, "%s", r.err);
+    return TGEMM_OK;
+}
 
 }  // namespace tg
