@@ -87,7 +87,7 @@ typedef struct tgemm_stats {
 typedef struct tgemm_trace_rec {
     int64_t task_id;
     int32_t i, j, k;       /* C tile (i,j), step k: uses A tile (i,k) and B tile (k,j)            */
-    int32_t stream;        /* 0..3: the stream / reservation-station slot the task ran on         */
+    int32_t stream;        /* 0..3: the reservation-station slot (C tile buffer) the task used    */
     int32_t a_hit, b_hit;  /* 1: tile was in the cache, 0: fetched from host memory               */
     int32_t a_slot, b_slot;
     int32_t a_evicted, b_evicted; /* 1: the fetch displaced another tile                          */
@@ -96,9 +96,11 @@ typedef struct tgemm_trace_rec {
 const char* tgemm_strerror(int code);
 const char* tgemm_last_error(void);
 
-/* Section 3.5, Algorithm 1 lines 1-4: creates the runtime of one GPU -- 4 streams (section 3.2:
- * four concurrent tasks per GPU, one per stream), the task queue, the tile cache directory and the
- * submit thread.
+/* Section 3.5, Algorithm 1 lines 1-4: creates the runtime of one GPU -- 4 streams and 4 task slots
+ * (section 3.2: four concurrent tasks per GPU), the task queue, the tile cache directory and the
+ * submit thread.  Out-of-core runs use the streams as a pipeline: streams[0] fetches tiles from host
+ * memory, streams[1] and streams[2] run the tile products, streams[3] harvests finished C tiles;
+ * in-core runs and the MLP passes launch on streams[0].
  *   device   HIP device ordinal.
  *   streams  NULL, or 4 hipStream_t values (as void*) borrowed from the caller for the lifetime of
  *            the context; entries that are NULL are created (and later destroyed) by the library.
@@ -118,7 +120,8 @@ int tgemm_destroy(tgemm_ctx* ctx);
  *   All three pointers device pointers  -> in-core: one kernel launch covers every task, hbm_budget
  *      is ignored.
  *   All three pointers pinned host      -> out-of-core: A/B tiles are staged into an HBM tile cache
- *      (LRU, section 3.4) and C tiles are uploaded, accumulated and harvested on 4 streams.  Every
+ *      (LRU, section 3.4); C tiles are uploaded, accumulated and harvested; fetch, products and
+ *      harvest overlap on the 4 streams with 4 tasks in flight.  Every
  *      device byte allocated for the call (A/B slots + 4 C slots) stays within hbm_budget bytes;
  *      the minimum is 4 C slots + 8 A/B slots (TGEMM_EBUDGET otherwise, before any work).
  *   M, N or K == 0 is legal (C unchanged).

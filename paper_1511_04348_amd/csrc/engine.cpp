@@ -1,7 +1,8 @@
 // Out-of-core tile engine: the one-GPU form of the paper's scheduling runtime and tile cache.
 //
 //   section 3.2  GPU computation thread  -> one submit thread per run (optionally bound to a core)
-//                4 concurrent tasks      -> 4 HIP streams; a stream = one reservation-station slot
+//                4 concurrent tasks      -> 4 reservation-station slots (each owns a C tile buffer);
+//                                           4 HIP streams with fixed roles, see below
 //                non-blocking task queue -> TaskQueue (ms_queue.h), filled by the caller thread
 //   section 3.4  L1 tile cache           -> slots in one HBM pool, directory keyed (matrix, ti, tj),
 //                                           strict LRU; there is no second-level (peer) cache on
@@ -10,15 +11,24 @@
 //                                           lookup B_kj, fetch on miss, asynchronous tile GEMM},
 //                                           asynchronous harvest of C_ij
 //
-// What differs from Algorithm 1: there is no per-round "synchronize all streams" (line 8).  A
-// stream takes the next task as soon as its previous one has finished, and every cross-stream
-// hazard is an event edge instead of a host-side wait:
-//   - a tile fetched on stream s and hit from stream s' : s' waits for the slot's `ready` event;
-//   - a slot evicted on stream s while kernels on other streams may still read the old tile:
-//     s waits for the slot's per-stream `read` events before the new copy is enqueued.
+// What differs from Algorithm 1:
+//   - No per-round "synchronize all streams" (line 8): a reservation-station slot takes the next
+//     task as soon as its previous one has been harvested.
+//   - Stream roles.  The paper runs each task's fetches, products and harvest on the task's own
+//     stream and relies on four such chains to overlap.  On this GPU concurrent kernels share the
+//     CUs evenly, so four copy->product chains fall into lock step (all fetch, then all multiply)
+//     and the host link and the MFMA pipes take turns instead of overlapping.  The four streams
+//     therefore form a pipeline: stream 0 fetches (every A/B tile and C_ij upload, in issue order,
+//     running ahead of the products as far as the cache allows), streams 1 and 2 multiply (tasks
+//     alternate between them), stream 3 harvests.  Four tasks are still in flight at a time.
+//   - Every cross-stream hazard is an event edge, never a host-side wait: a product waits for
+//     the `ready` events of its two tiles and of its C buffer; a fetch into an evicted slot waits
+//     for the `read` events of the products that still use the old tile; the harvest waits for
+//     the task's last product; the next upload into a C buffer waits for its harvest.
 // Cache decisions are taken in issue order on the host, so hits, misses and evictions are a pure
 // function of (sizes, T, slot count, task order), independent of timing.
 #include <pthread.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <algorithm>
@@ -29,6 +39,7 @@
 #include <vector>
 
 #include "common.h"
+#include "copy_kernel.h"
 #include "gemm_kernel.h"
 #include "ms_queue.h"
 
@@ -39,9 +50,8 @@ namespace {
 struct Slot {
     int64_t key = -1;
     hipEvent_t ready = nullptr;
-    int ready_stream = -1;
-    hipEvent_t read_ev[4] = {nullptr, nullptr, nullptr, nullptr};
-    bool read_pending[4] = {false, false, false, false};
+    hipEvent_t read_ev[2] = {nullptr, nullptr};     // last product on compute stream 0 / 1 that read the slot
+    bool read_pending[2] = {false, false};
     int prev = -1, next = -1;
 };
 
@@ -54,7 +64,10 @@ public:
     char* pool = nullptr;
     size_t pool_bytes = 0;
     std::vector<Slot> slots;
-    hipEvent_t task_done[4] = {nullptr, nullptr, nullptr, nullptr};
+    // per reservation-station slot
+    hipEvent_t c_ready[4] = {nullptr, nullptr, nullptr, nullptr};       // C_ij uploaded
+    hipEvent_t products_done[4] = {nullptr, nullptr, nullptr, nullptr}; // last k-step finished
+    hipEvent_t task_done[4] = {nullptr, nullptr, nullptr, nullptr};     // C_ij harvested
     bool task_pending[4] = {false, false, false, false};
     // directory + LRU list (head = least recently used)
     std::unordered_map<int64_t, int> dir;
@@ -68,8 +81,11 @@ public:
             for (auto& e : s.read_ev)
                 if (e) (void)hipEventDestroy(e);
         }
-        for (auto& e : task_done)
-            if (e) (void)hipEventDestroy(e);
+        for (int i = 0; i < 4; ++i) {
+            if (task_done[i]) (void)hipEventDestroy(task_done[i]);
+            if (c_ready[i]) (void)hipEventDestroy(c_ready[i]);
+            if (products_done[i]) (void)hipEventDestroy(products_done[i]);
+        }
         if (pool) (void)hipFree(pool);
     }
 
@@ -93,8 +109,11 @@ public:
 
     int ensure_events(int n_slots)
     {
-        for (auto& e : task_done)
-            if (!e) TG_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        for (int i = 0; i < 4; ++i) {
+            if (!task_done[i]) TG_HIP(hipEventCreateWithFlags(&task_done[i], hipEventDisableTiming));
+            if (!c_ready[i]) TG_HIP(hipEventCreateWithFlags(&c_ready[i], hipEventDisableTiming));
+            if (!products_done[i]) TG_HIP(hipEventCreateWithFlags(&products_done[i], hipEventDisableTiming));
+        }
         const size_t old = slots.size();
         if ((size_t)n_slots > old) slots.resize(n_slots);
         for (size_t i = old; i < slots.size(); ++i) {
@@ -111,7 +130,6 @@ public:
         n_used = 0;
         for (auto& s : slots) {
             s.key = -1;
-            s.ready_stream = -1;
             s.prev = s.next = -1;
             for (auto& p : s.read_pending) p = false;
         }
@@ -160,7 +178,9 @@ struct Run {
     std::atomic<bool> failed{false};
     int rc = TGEMM_OK;
     char err[256] = "";
-    int rr = 0;                // round-robin start of the stream search
+    int rr = 0;                // round-robin start of the slot search
+    int64_t n_issued = 0;      // tasks issued so far (alternates the compute stream)
+    int copy_mode = 1;
 
     char* ab_slot_ptr(int slot) const { return eng->pool + 4 * slot_c + (size_t)slot * slot_ab; }
     float* c_slot_ptr(int s) const { return (float*)(eng->pool + (size_t)s * slot_c); }
@@ -176,8 +196,20 @@ struct Run {
         return false;
     }
 
-    // Algorithm 1 lines 6-7: the next free reservation-station slot (= stream).
-    int pick_stream()
+    // One tile transfer.  copy_mode 1 (default): hipMemcpy2DAsync, i.e. the DMA engines -- they take
+    // no CU resources, so tile products running meanwhile keep their speed.  copy_mode 0
+    // (TGEMM_COPY=kernel): the library's strided copy kernel reading page-locked host memory
+    // directly; measured slower end to end because its long-latency host reads share the CUs'
+    // memory pipelines with the products.
+    hipError_t copy2d(void* dst, size_t dpitch, const void* src, size_t spitch, size_t width, size_t height,
+                      hipMemcpyKind kind, hipStream_t st)
+    {
+        if (copy_mode == 1) return hipMemcpy2DAsync(dst, dpitch, src, spitch, width, height, kind, st);
+        return launch_copy_2d(dst, dpitch, src, spitch, width, height, st);
+    }
+
+    // Algorithm 1 lines 6-7: the next free reservation-station slot.
+    int pick_slot()
     {
         for (;;) {
             for (int t = 0; t < 4; ++t) {
@@ -200,12 +232,12 @@ struct Run {
     }
 
     // Algorithm 1 lines 12-15: look the tile up in the L1 tile cache; on a miss take a free slot
-    // or evict the least recently used one and fetch the tile from host memory.
-    int acquire(int mat, int64_t ti, int64_t tj, int s, const char* src, size_t src_pitch,
+    // or evict the least recently used one and fetch the tile from host memory (fetch stream).
+    int acquire(int mat, int64_t ti, int64_t tj, const char* src, size_t src_pitch,
                 size_t width_bytes, size_t height, size_t slot_pitch, int* hit, int* evicted)
     {
         Engine& e = *eng;
-        hipStream_t st = ctx->streams[s];
+        hipStream_t fetch = ctx->streams[0];
         const int64_t key = tile_key(mat, ti, tj);
         auto it = e.dir.find(key);
         *evicted = 0;
@@ -215,8 +247,6 @@ struct Run {
             e.lru_push_mru(slot);
             *hit = 1;
             ctx->stats.hits++;
-            if (e.slots[slot].ready_stream != s)
-                check(hipStreamWaitEvent(st, e.slots[slot].ready, 0), "hipStreamWaitEvent(ready)");
             return slot;
         }
         *hit = 0;
@@ -231,41 +261,49 @@ struct Run {
             *evicted = 1;
             ctx->stats.evictions++;
             Slot& sl = e.slots[slot];
-            for (int s2 = 0; s2 < 4; ++s2) {
-                if (sl.read_pending[s2] && s2 != s)
-                    check(hipStreamWaitEvent(st, sl.read_ev[s2], 0), "hipStreamWaitEvent(read)");
-                sl.read_pending[s2] = false;
+            for (int c = 0; c < 2; ++c) {
+                if (sl.read_pending[c])
+                    check(hipStreamWaitEvent(fetch, sl.read_ev[c], 0), "hipStreamWaitEvent(read)");
+                sl.read_pending[c] = false;
             }
         }
         Slot& sl = e.slots[slot];
         sl.key = key;
         e.dir[key] = slot;
         e.lru_push_mru(slot);
-        check(hipMemcpy2DAsync(ab_slot_ptr(slot), slot_pitch, src, src_pitch, width_bytes, height,
-                               hipMemcpyHostToDevice, st), "hipMemcpy2DAsync(H2D tile)");
+        check(copy2d(ab_slot_ptr(slot), slot_pitch, src, src_pitch, width_bytes, height,
+                     hipMemcpyHostToDevice, fetch), "H2D tile copy");
         ctx->stats.h2d_bytes += (int64_t)(width_bytes * height);
-        check(hipEventRecord(sl.ready, st), "hipEventRecord(ready)");
-        sl.ready_stream = s;
+        check(hipEventRecord(sl.ready, fetch), "hipEventRecord(ready)");
         return slot;
     }
 
-    // Algorithm 1 lines 9-17 for one task on stream s.
+    // Algorithm 1 lines 9-17 for one task in reservation-station slot s.
     void issue_task(int64_t id, int s)
     {
-        hipStream_t st = ctx->streams[s];
+        hipStream_t fetch = ctx->streams[0], harvest = ctx->streams[3];
+        const int cs_idx = (int)(n_issued++ & 1);
+        hipStream_t comp = ctx->streams[1 + cs_idx];
         const int64_t i = id / n_j, j = id % n_j;              // decode
         const int64_t r0 = i * T, rows = std::min(T, M - r0);
         const int64_t c0 = j * T, cols = std::min(T, N - c0);
         float* cs = c_slot_ptr(s);
-        // C_ij enters with its current value: the product accumulates into C
-        check(hipMemcpy2DAsync(cs, tn * 4, C + r0 * N + c0, N * 4, cols * 4, rows, hipMemcpyHostToDevice, st),
-              "hipMemcpy2DAsync(H2D C tile)");
+        // C_ij enters with its current value: the product accumulates into C.  The buffer is free:
+        // pick_slot() saw the harvest of its previous task complete.
+        check(copy2d(cs, tn * 4, C + r0 * N + c0, N * 4, cols * 4, rows, hipMemcpyHostToDevice, fetch),
+              "H2D C tile copy");
         ctx->stats.h2d_bytes += rows * cols * 4;
+        check(hipEventRecord(eng->c_ready[s], fetch), "hipEventRecord(C ready)");
+        check(hipStreamWaitEvent(comp, eng->c_ready[s], 0), "hipStreamWaitEvent(C ready)");
         for (int64_t k = 0; k < n_k && rc == TGEMM_OK; ++k) {
             const int64_t k0 = k * T, klen = std::min(T, K - k0);
             int a_hit, b_hit, a_ev, b_ev;
-            const int sa = acquire(0, i, k, s, A + (r0 * K + k0) * es, K * es, klen * es, rows, tk * es, &a_hit, &a_ev);
-            const int sb = acquire(1, k, j, s, B + (k0 * N + c0) * es, N * es, cols * es, klen, tn * es, &b_hit, &b_ev);
+            const int sa = acquire(0, i, k, A + (r0 * K + k0) * es, K * es, klen * es, rows, tk * es, &a_hit, &a_ev);
+            const int sb = acquire(1, k, j, B + (k0 * N + c0) * es, N * es, cols * es, klen, tn * es, &b_hit, &b_ev);
+            Slot& la = eng->slots[sa];
+            Slot& lb = eng->slots[sb];
+            check(hipStreamWaitEvent(comp, la.ready, 0), "hipStreamWaitEvent(A ready)");
+            check(hipStreamWaitEvent(comp, lb.ready, 0), "hipStreamWaitEvent(B ready)");
             GemmDesc d;
             memset(&d, 0, sizeof d);
             d.A = ab_slot_ptr(sa); d.B = ab_slot_ptr(sb); d.C = cs;
@@ -275,14 +313,12 @@ struct Run {
             d.a_kcontig = 1; d.b_kcontig = 0;
             d.epilogue = EPI_AXPBY; d.alpha = 1.f; d.beta = 1.f;
             d.config = ctx->opts.kernel_config;
-            check(launch_tile_gemm_f32(d, st), "tile GEMM launch");
+            check(launch_tile_gemm_f32(d, comp), "tile GEMM launch");
             ctx->stats.kernel_launches++;
-            Slot& la = eng->slots[sa];
-            Slot& lb = eng->slots[sb];
-            check(hipEventRecord(la.read_ev[s], st), "hipEventRecord(read A)");
-            la.read_pending[s] = true;
-            check(hipEventRecord(lb.read_ev[s], st), "hipEventRecord(read B)");
-            lb.read_pending[s] = true;
+            check(hipEventRecord(la.read_ev[cs_idx], comp), "hipEventRecord(read A)");
+            la.read_pending[cs_idx] = true;
+            check(hipEventRecord(lb.read_ev[cs_idx], comp), "hipEventRecord(read B)");
+            lb.read_pending[cs_idx] = true;
             if (ctx->opts.trace) {
                 tgemm_trace_rec r;
                 r.task_id = id; r.i = (int32_t)i; r.j = (int32_t)j; r.k = (int32_t)k; r.stream = s;
@@ -291,10 +327,12 @@ struct Run {
             }
         }
         // harvest
-        check(hipMemcpy2DAsync(C + r0 * N + c0, N * 4, cs, tn * 4, cols * 4, rows, hipMemcpyDeviceToHost, st),
-              "hipMemcpy2DAsync(D2H C tile)");
+        check(hipEventRecord(eng->products_done[s], comp), "hipEventRecord(products done)");
+        check(hipStreamWaitEvent(harvest, eng->products_done[s], 0), "hipStreamWaitEvent(products done)");
+        check(copy2d(C + r0 * N + c0, N * 4, cs, tn * 4, cols * 4, rows, hipMemcpyDeviceToHost, harvest),
+              "D2H C tile copy");
         ctx->stats.d2h_bytes += rows * cols * 4;
-        check(hipEventRecord(eng->task_done[s], st), "hipEventRecord(task done)");
+        check(hipEventRecord(eng->task_done[s], harvest), "hipEventRecord(task done)");
         eng->task_pending[s] = true;
     }
 
@@ -317,7 +355,7 @@ struct Run {
                 }
                 if (!queue->dequeue(&id)) break;
             }
-            const int s = pick_stream();
+            const int s = pick_slot();
             if (s < 0) break;
             issue_task(id, s);
         }
@@ -341,6 +379,7 @@ int run_out_of_core(tgemm_ctx* ctx, const void* A, const void* B, float* C, int6
     r.n_i = (M + T - 1) / T; r.n_j = (N + T - 1) / T; r.n_k = (K + T - 1) / T;
     r.tm = std::min<int64_t>(T, M); r.tn = std::min<int64_t>(T, N); r.tk = std::min<int64_t>(T, K);
     r.es = 4;
+    if (const char* cm = getenv("TGEMM_COPY")) r.copy_mode = (strcmp(cm, "kernel") == 0) ? 0 : 1;
     r.slot_ab = round_up(std::max(r.tm * r.tk, r.tk * r.tn) * r.es, 256);
     r.slot_c = round_up((size_t)(r.tm * r.tn) * 4, 256);
     const size_t min_bytes = 4 * r.slot_c + 8 * r.slot_ab;

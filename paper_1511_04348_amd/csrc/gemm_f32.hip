@@ -342,8 +342,8 @@ static hipError_t launch_cfg(GemmParams& p, const GemmDesc& d, hipStream_t strea
 int pick_config(const GemmDesc& d)
 {
     if (d.config >= 1 && d.config <= 3) return d.config;
-    // Enough macro tiles to give every CU at least ~2 workgroups of the large shape; otherwise
-    // shrink the macro tile so that small products still spread over the 256 CUs.
+    // Large macro tiles are the most efficient per flop; smaller ones spread small products over
+    // the 256 CUs.  Pick the shape with the least estimated time.
     auto tiles = [&](int64_t bm, int64_t bn) {
         const int64_t T = d.T;
         const int64_t n_i = (d.M + T - 1) / T, n_j = (d.N + T - 1) / T;
@@ -352,9 +352,16 @@ int pick_config(const GemmDesc& d)
         return ((n_i - 1) * ((fm + bm - 1) / bm) + (lm + bm - 1) / bm) *
                ((n_j - 1) * ((fn + bn - 1) / bn) + (ln + bn - 1) / bn);
     };
-    if (tiles(256, 256) >= 384) return 3;
-    if (tiles(128, 128) >= 384) return 2;
-    return 1;
+    // cost model: rounds of 256 CUs (one large or two medium/small workgroups per CU) times the
+    // relative time of one round
+    auto cost = [&](int64_t n_tiles, int64_t per_round, double round_time) {
+        return (double)((n_tiles + per_round - 1) / per_round) * round_time;
+    };
+    const double c3 = cost(tiles(256, 256), 256, 1.0);
+    const double c2 = cost(tiles(128, 128), 512, 0.54);
+    const double c1 = cost(tiles(64, 64), 512, 0.14);
+    if (c3 <= c2 && c3 <= c1) return 3;
+    return c2 <= c1 ? 2 : 1;
 }
 
 hipError_t launch_tile_gemm_f32(const GemmDesc& d, hipStream_t stream)
