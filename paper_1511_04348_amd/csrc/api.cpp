@@ -188,7 +188,6 @@ int tgemm_run(tgemm_ctx* ctx, const void* A, const void* B, void* C,
     }
 
     // ---- in-core: one launch covers every task (Algorithm 1 with every tile an L1 hit)
-    if (dtype != TGEMM_F32) return fail(TGEMM_EARG, "tgemm_run: the bf16 kernel is not built yet");
     GemmDesc d;
     memset(&d, 0, sizeof d);
     d.A = A; d.B = B; d.C = (float*)C;
@@ -199,7 +198,7 @@ int tgemm_run(tgemm_ctx* ctx, const void* A, const void* B, void* C,
     d.config = ctx->opts.kernel_config;
     hipStream_t st = ctx->streams[0];
     TG_HIP(hipEventRecord(ctx->ev_start, st));
-    hipError_t e = launch_tile_gemm_f32(d, st);
+    hipError_t e = launch_tile_gemm(d, dtype == TGEMM_BF16, st);
     if (e != hipSuccess) return fail(TGEMM_EHIP, "tile GEMM launch failed: %s", hipGetErrorString(e));
     TG_HIP(hipEventRecord(ctx->ev_stop, st));
     ctx->kernel_timing_pending = true;

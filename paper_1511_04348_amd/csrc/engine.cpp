@@ -181,6 +181,7 @@ struct Run {
     int rr = 0;                // round-robin start of the slot search
     int64_t n_issued = 0;      // tasks issued so far (alternates the compute stream)
     int copy_mode = 1;
+    bool bf16 = false;
 
     char* ab_slot_ptr(int slot) const { return eng->pool + 4 * slot_c + (size_t)slot * slot_ab; }
     float* c_slot_ptr(int s) const { return (float*)(eng->pool + (size_t)s * slot_c); }
@@ -313,7 +314,7 @@ struct Run {
             d.a_kcontig = 1; d.b_kcontig = 0;
             d.epilogue = EPI_AXPBY; d.alpha = 1.f; d.beta = 1.f;
             d.config = ctx->opts.kernel_config;
-            check(launch_tile_gemm_f32(d, comp), "tile GEMM launch");
+            check(launch_tile_gemm(d, bf16, comp), "tile GEMM launch");
             ctx->stats.kernel_launches++;
             check(hipEventRecord(la.read_ev[cs_idx], comp), "hipEventRecord(read A)");
             la.read_pending[cs_idx] = true;
@@ -371,14 +372,14 @@ inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 int run_out_of_core(tgemm_ctx* ctx, const void* A, const void* B, float* C, int64_t M, int64_t N,
                     int64_t K, int32_t T, int32_t dtype, size_t hbm_budget)
 {
-    if (dtype != TGEMM_F32) return fail(TGEMM_EARG, "tgemm_run: the bf16 out-of-core path is not built yet");
     Run r;
     r.ctx = ctx;
     r.A = (const char*)A; r.B = (const char*)B; r.C = C;
     r.M = M; r.N = N; r.K = K; r.T = T;
     r.n_i = (M + T - 1) / T; r.n_j = (N + T - 1) / T; r.n_k = (K + T - 1) / T;
     r.tm = std::min<int64_t>(T, M); r.tn = std::min<int64_t>(T, N); r.tk = std::min<int64_t>(T, K);
-    r.es = 4;
+    r.es = dtype == TGEMM_BF16 ? 2 : 4;
+    r.bf16 = dtype == TGEMM_BF16;
     if (const char* cm = getenv("TGEMM_COPY")) r.copy_mode = (strcmp(cm, "kernel") == 0) ? 0 : 1;
     r.slot_ab = round_up(std::max(r.tm * r.tk, r.tk * r.tn) * r.es, 256);
     r.slot_c = round_up((size_t)(r.tm * r.tn) * 4, 256);

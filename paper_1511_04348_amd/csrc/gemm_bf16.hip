@@ -1,0 +1,396 @@
+// bf16 -> fp32 tile GEMM kernel for gfx950 (CDNA4): the tile product of Algorithm 1 of the paper
+// for bf16 operands with fp32 accumulation (v_mfma_f32_32x32x16_bf16).
+//
+// Same structure as the fp32 kernel: one launch covers a whole tiled product, a workgroup owns one
+// macro tile of one task's output tile and walks the k-steps in ascending order; workgroups are
+// numbered task by task and XCD by XCD.
+//
+// The MFMA wants, per lane, 8 consecutive-k elements of one row of A and of one column of B, so
+// both operands sit in LDS k-contiguous: As[m][k], Bs[n][k], 64 k per stage, rows padded to 144 B
+// (conflict-free 16-byte reads).  A k-contiguous source (row-major A; W in the D W^T product) is
+// copied with 16-byte loads and 16-byte LDS writes.  An m/n-contiguous source (row-major B; A^T
+// and D in the A^T D product) is transposed in registers on the way: a thread loads 8 k-rows x 4
+// columns (eight 8-byte loads), regroups the 16-bit halves into four 8-k vectors and writes four
+// 16-byte LDS rows.  Which k lands in which MFMA slot is irrelevant as long as A and B agree.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "gemm_kernel.h"
+
+namespace tg {
+namespace bf {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+constexpr int BK = 64;            // k per LDS stage
+constexpr int ROW_W = 36;         // LDS row stride in 32-bit words: 128 B of data + 16 B pad
+
+__device__ inline float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+__device__ inline uint16_t f32_to_bf16_rne(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);   // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// ---- k-contiguous source: rows are mn, 64 contiguous k per stage -------------------------------
+// unit u -> (mn = u / 8, kq = u % 8): 16 bytes = 8 k.
+template <int BMN, int NT>
+struct LoaderKC {
+    static constexpr int UP = BMN * 8 / NT;
+    static_assert((BMN * 8) % NT == 0, "tile must divide evenly over the threads");
+    u32x4 reg[UP];
+
+    __device__ inline void load(const uint16_t* __restrict__ X, int64_t ld, int mn0, int mn_end, int kk,
+                                int klim, bool vec_ok, int tid)
+    {
+#pragma unroll
+        for (int p = 0; p < UP; ++p) {
+            const int u = tid + p * NT;
+            const int mn = mn0 + (u >> 3);
+            const int k = kk + ((u & 7) << 3);
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (mn < mn_end && k < klim) {
+                const uint16_t* src = X + (int64_t)mn * ld + k;
+                if (vec_ok && k + 7 < klim) {
+                    v = *reinterpret_cast<const u32x4*>(src);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (k + e < klim) v[e >> 1] |= (uint32_t)src[e] << ((e & 1) * 16);
+                }
+            }
+            reg[p] = v;
+        }
+    }
+    __device__ inline void store(uint32_t* __restrict__ S, int tid) const
+    {
+#pragma unroll
+        for (int p = 0; p < UP; ++p) {
+            const int u = tid + p * NT;
+            *reinterpret_cast<u32x4*>(&S[(u >> 3) * ROW_W + ((u & 7) << 2)]) = reg[p];
+        }
+    }
+};
+
+// ---- mn-contiguous source: rows are k, BMN contiguous mn ---------------------------------------
+// unit u -> (q = u % (BMN/4), kg = u / (BMN/4)): 8 k-rows (8 kg .. 8 kg + 7) x 4 mn (4 q .. 4 q + 3).
+template <int BMN, int NT>
+struct LoaderMC {
+    static constexpr int Q = BMN / 4;
+    static constexpr int UP = Q * 8 / NT;
+    static_assert((Q * 8) % NT == 0 && UP >= 1, "tile must divide evenly over the threads");
+    u32x2 reg[UP][8];
+
+    __device__ inline void load(const uint16_t* __restrict__ X, int64_t ld, int mn0, int mn_end, int kk,
+                                int klim, bool vec_ok, int tid)
+    {
+#pragma unroll
+        for (int p = 0; p < UP; ++p) {
+            const int u = tid + p * NT;
+            const int mn = mn0 + ((u % Q) << 2);
+            const int kb = kk + ((u / Q) << 3);
+            const bool full = vec_ok && (mn + 3 < mn_end);
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+                u32x2 v = {0u, 0u};
+                const int k = kb + r;
+                if (k < klim && mn < mn_end) {
+                    const uint16_t* src = X + (int64_t)k * ld + mn;
+                    if (full) {
+                        v = *reinterpret_cast<const u32x2*>(src);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (mn + e < mn_end) v[e >> 1] |= (uint32_t)src[e] << ((e & 1) * 16);
+                    }
+                }
+                reg[p][r] = v;
+            }
+        }
+    }
+    // 8 x 4 block of 16-bit elements -> four rows of 8 k
+    __device__ inline void store(uint32_t* __restrict__ S, int tid) const
+    {
+#pragma unroll
+        for (int p = 0; p < UP; ++p) {
+            const int u = tid + p * NT;
+            const int mn = (u % Q) << 2;
+            const int kg = u / Q;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                u32x4 o;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const uint32_t x = reg[p][2 * q][e >> 1], y = reg[p][2 * q + 1][e >> 1];
+                    o[q] = (e & 1) ? ((x >> 16) | (y & 0xffff0000u)) : ((x & 0xffffu) | (y << 16));
+                }
+                *reinterpret_cast<u32x4*>(&S[(mn + e) * ROW_W + (kg << 2)]) = o;
+            }
+        }
+    }
+};
+
+template <int BMN, int NT, bool KC> struct PickLoader { typedef LoaderKC<BMN, NT> type; };
+template <int BMN, int NT> struct PickLoader<BMN, NT, false> { typedef LoaderMC<BMN, NT> type; };
+
+// ---- the kernel ---------------------------------------------------------------------------------
+template <int RA, int RB, int WM, int WN, bool A_KC, bool B_KC, int EPI, bool OUT_BF16>
+__global__ __launch_bounds__(WM * WN * 64) void tile_gemm_bf16(const GemmParams p)
+{
+    constexpr int WTM = 32 * RA, WTN = 32 * RB;
+    constexpr int BM = WM * WTM, BN = WN * WTN;
+    constexpr int NT = WM * WN * 64;
+    constexpr int STAGE_A = BM * ROW_W, STAGE_B = BN * ROW_W;   // words
+    typedef typename PickLoader<BM, NT, A_KC>::type LA;
+    typedef typename PickLoader<BN, NT, B_KC>::type LB;
+
+    extern __shared__ __attribute__((aligned(16))) uint32_t smem_w[];
+    uint32_t* As = smem_w;                    // [2][BM][ROW_W]
+    uint32_t* Bs = smem_w + 2 * STAGE_A;      // [2][BN][ROW_W]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int li = lane & 31, lh = lane >> 5;
+
+    int lid;
+    {
+        const int n = gridDim.x, b = blockIdx.x;
+        const int q = n >> 3, r = n & 7, xcd = b & 7, local = b >> 3;
+        lid = xcd * q + (xcd < r ? xcd : r) + local;
+    }
+    const int band = p.tpm * p.macro_cols;
+    int ti = lid / band;
+    const int in_band = lid - ti * band;
+    const int h = (ti == p.n_i - 1) ? p.tpm_last : p.tpm;
+    int tj = in_band / (h * p.tpn);
+    if (tj > p.n_j - 1) tj = p.n_j - 1;
+    const int in_task = in_band - tj * h * p.tpn;
+    const int wcols = (tj == p.n_j - 1) ? p.tpn_last : p.tpn;
+    const int si = in_task / wcols, sj = in_task - si * wcols;
+
+    const int row0 = ti * p.T + si * BM;
+    const int col0 = tj * p.T + sj * BN;
+    const int row_end = min(p.M, (ti + 1) * p.T);
+    const int col_end = min(p.N, (tj + 1) * p.T);
+
+    const uint16_t* __restrict__ A = reinterpret_cast<const uint16_t*>(p.A);
+    const uint16_t* __restrict__ B = reinterpret_cast<const uint16_t*>(p.B);
+
+    f32x16 acc[RA][RB];
+#pragma unroll
+    for (int r = 0; r < RA; ++r)
+#pragma unroll
+        for (int c = 0; c < RB; ++c)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[r][c][v] = 0.f;
+
+    LA la;
+    LB lb;
+    const int n_chunks = p.n_chunks;
+    const int cps = p.chunks_per_step;
+    auto chunk_range = [&](int c, int& kk, int& klim) {
+        const int step = c / cps;
+        kk = step * p.T + (c - step * cps) * BK;
+        klim = min(p.K, (step + 1) * p.T);
+    };
+
+    if (n_chunks > 0) {
+        int kk, klim;
+        chunk_range(0, kk, klim);
+        la.load(A, p.lda, row0, row_end, kk, klim, p.vec_a, tid);
+        lb.load(B, p.ldb, col0, col_end, kk, klim, p.vec_b, tid);
+        la.store(As, tid);
+        lb.store(Bs, tid);
+    }
+    __syncthreads();
+
+    // lane's LDS read base: row (wave tile row / col + li), k offset 8 * lh elements = 4 * lh words
+    const int a_off = (wm * WTM + li) * ROW_W + lh * 4;
+    const int b_off = (wn * WTN + li) * ROW_W + lh * 4;
+
+    for (int c = 0; c < n_chunks; ++c) {
+        const int st = c & 1;
+        const bool more = (c + 1 < n_chunks);
+        if (more) {
+            int kk, klim;
+            chunk_range(c + 1, kk, klim);
+            la.load(A, p.lda, row0, row_end, kk, klim, p.vec_a, tid);
+            lb.load(B, p.ldb, col0, col_end, kk, klim, p.vec_b, tid);
+        }
+        const uint32_t* as = As + st * STAGE_A + a_off;
+        const uint32_t* bs = Bs + st * STAGE_B + b_off;
+#pragma unroll
+        for (int s = 0; s < BK / 16; ++s) {
+            bf16x8 af[RA], bfr[RB];
+#pragma unroll
+            for (int r = 0; r < RA; ++r)
+                af[r] = *reinterpret_cast<const bf16x8*>(as + r * 32 * ROW_W + s * 8);
+#pragma unroll
+            for (int cc = 0; cc < RB; ++cc)
+                bfr[cc] = *reinterpret_cast<const bf16x8*>(bs + cc * 32 * ROW_W + s * 8);
+#pragma unroll
+            for (int r = 0; r < RA; ++r)
+#pragma unroll
+                for (int cc = 0; cc < RB; ++cc)
+                    acc[r][cc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[r], bfr[cc], acc[r][cc], 0, 0, 0);
+        }
+        if (more) {
+            la.store(As + (st ^ 1) * STAGE_A, tid);
+            lb.store(Bs + (st ^ 1) * STAGE_B, tid);
+        }
+        __syncthreads();
+    }
+
+    // -- epilogue.  acc[r][cc][v] is element (row, col) of the wave tile with
+    //    row = 32 r + 8 (v / 4) + 4 lh + v % 4,  col = 32 cc + li.
+    const float alpha = p.alpha, beta = p.beta;
+    float* __restrict__ Cf = p.C;
+    uint16_t* __restrict__ Cb = reinterpret_cast<uint16_t*>(p.C);
+    const uint16_t* __restrict__ aux = reinterpret_cast<const uint16_t*>(p.aux);
+#pragma unroll
+    for (int r = 0; r < RA; ++r) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = row0 + wm * WTM + 32 * r + 8 * (v >> 2) + 4 * lh + (v & 3);
+            if (row >= row_end) continue;
+#pragma unroll
+            for (int cc = 0; cc < RB; ++cc) {
+                const int col = col0 + wn * WTN + 32 * cc + li;
+                if (col >= col_end) continue;
+                const int64_t idx = (int64_t)row * p.ldc + col;
+                float o = acc[r][cc][v];
+                if (EPI == EPI_AXPBY) {
+                    if (beta != 0.f) {
+                        const float cin = OUT_BF16 ? bf16_to_f32(Cb[idx]) : Cf[idx];
+                        o = fmaf(alpha, o, beta * cin);
+                    } else {
+                        o = alpha * o;
+                    }
+                } else if (EPI == EPI_SIGMOID) {
+                    o = 1.f / (1.f + __expf(-o));
+                } else if (EPI == EPI_DSIGMOID) {
+                    const float a = bf16_to_f32(aux[(int64_t)row * p.ldaux + col]);
+                    o = o * a * (1.f - a);
+                }
+                if (OUT_BF16) Cb[idx] = f32_to_bf16_rne(o);
+                else Cf[idx] = o;
+            }
+        }
+    }
+}
+
+// ---- host-side launcher -------------------------------------------------------------------------
+template <int RA, int RB, int WM, int WN>
+struct Cfg {
+    static constexpr int BM = WM * 32 * RA, BN = WN * 32 * RB, NT = WM * WN * 64;
+    static constexpr size_t LDS = 2 * (size_t)(BM + BN) * ROW_W * 4;
+};
+
+template <int RA, int RB, int WM, int WN, bool A_KC, bool B_KC, int EPI, bool OB>
+static hipError_t launch_one(const GemmParams& p, int grid, hipStream_t stream)
+{
+    typedef Cfg<RA, RB, WM, WN> C;
+    auto kern = tile_gemm_bf16<RA, RB, WM, WN, A_KC, B_KC, EPI, OB>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(C::NT), C::LDS, stream, p);
+    return hipGetLastError();
+}
+
+template <int RA, int RB, int WM, int WN>
+static hipError_t launch_cfg(GemmParams& p, const GemmDesc& d, hipStream_t stream)
+{
+    typedef Cfg<RA, RB, WM, WN> C;
+    const int64_t T = d.T;
+    p.n_i = (int)((d.M + T - 1) / T);
+    p.n_j = (int)((d.N + T - 1) / T);
+    const int64_t n_k = (d.K + T - 1) / T;
+    const int64_t last_m = d.M - (int64_t)(p.n_i - 1) * T;
+    const int64_t last_n = d.N - (int64_t)(p.n_j - 1) * T;
+    const int64_t full_m = p.n_i > 1 ? T : last_m, full_n = p.n_j > 1 ? T : last_n;
+    p.tpm = (int)((full_m + C::BM - 1) / C::BM);
+    p.tpn = (int)((full_n + C::BN - 1) / C::BN);
+    p.tpm_last = (int)((last_m + C::BM - 1) / C::BM);
+    p.tpn_last = (int)((last_n + C::BN - 1) / C::BN);
+    p.macro_cols = (p.n_j - 1) * p.tpn + p.tpn_last;
+    const int64_t macro_rows = (int64_t)(p.n_i - 1) * p.tpm + p.tpm_last;
+    const int64_t grid = macro_rows * p.macro_cols;
+    if (grid <= 0 || grid > 0x7fffffff) return hipErrorInvalidValue;
+    const int64_t full_k = n_k > 1 ? T : d.K;
+    p.chunks_per_step = (int)((full_k + BK - 1) / BK);
+    const int64_t last_k = d.K - (n_k - 1) * T;
+    p.n_chunks = (int)((n_k - 1) * p.chunks_per_step + (last_k + BK - 1) / BK);
+
+#define TGB_LAUNCH(AK, BKC, E, OB) return launch_one<RA, RB, WM, WN, AK, BKC, E, OB>(p, (int)grid, stream)
+#define TGB_EPI(AK, BKC)                                                            \
+    if (d.epilogue == EPI_AXPBY && !d.out_bf16) { TGB_LAUNCH(AK, BKC, EPI_AXPBY, false); }    \
+    if (d.epilogue == EPI_AXPBY && d.out_bf16) { TGB_LAUNCH(AK, BKC, EPI_AXPBY, true); }      \
+    if (d.epilogue == EPI_SIGMOID && d.out_bf16) { TGB_LAUNCH(AK, BKC, EPI_SIGMOID, true); }  \
+    if (d.epilogue == EPI_DSIGMOID && d.out_bf16) { TGB_LAUNCH(AK, BKC, EPI_DSIGMOID, true); } \
+    return hipErrorInvalidValue;
+    if (d.a_kcontig && !d.b_kcontig) { TGB_EPI(true, false) }
+    if (!d.a_kcontig && !d.b_kcontig) { TGB_EPI(false, false) }
+    if (d.a_kcontig && d.b_kcontig) { TGB_EPI(true, true) }
+    return hipErrorInvalidValue;
+#undef TGB_EPI
+#undef TGB_LAUNCH
+}
+
+}  // namespace bf
+
+hipError_t launch_tile_gemm_bf16(const GemmDesc& d, hipStream_t stream)
+{
+    if (d.M <= 0 || d.N <= 0 || d.K < 0 || d.T <= 0) return hipErrorInvalidValue;
+    if (d.M > 0x3fffffff || d.N > 0x3fffffff || d.K > 0x3fffffff) return hipErrorInvalidValue;
+    GemmParams p;
+    p.A = d.A; p.B = d.B; p.C = d.C; p.aux = d.aux;
+    p.lda = d.lda; p.ldb = d.ldb; p.ldc = d.ldc; p.ldaux = d.ldaux;
+    p.M = (int)d.M; p.N = (int)d.N; p.K = (int)d.K;
+    int64_t T = d.T;
+    const int64_t big = (d.M > d.N ? d.M : d.N) > d.K ? (d.M > d.N ? d.M : d.N) : d.K;
+    if (T > big) T = big > 0 ? big : 1;
+    p.T = (int)T;
+    p.alpha = d.alpha; p.beta = d.beta;
+    // k-contiguous operands use 16-byte loads (8 elements), m/n-contiguous ones 8-byte loads (4)
+    auto ok = [&](const void* q, int64_t ld, bool kc) {
+        const int e = kc ? 8 : 4;
+        return (T % e == 0) && ((reinterpret_cast<uintptr_t>(q) & (uintptr_t)(2 * e - 1)) == 0) && (ld % e == 0);
+    };
+    p.vec_a = ok(d.A, d.lda, d.a_kcontig != 0);
+    p.vec_b = ok(d.B, d.ldb, d.b_kcontig != 0);
+    p.vec_c = false;
+    GemmDesc dd = d;
+    dd.T = (int32_t)T;
+    int cfg = d.config;
+    if (cfg < 1 || cfg > 3) {
+        auto tiles = [&](int64_t bm, int64_t bn) {
+            const int64_t n_i = (d.M + T - 1) / T, n_j = (d.N + T - 1) / T;
+            const int64_t lm = d.M - (n_i - 1) * T, ln = d.N - (n_j - 1) * T;
+            const int64_t fm = n_i > 1 ? T : lm, fn = n_j > 1 ? T : ln;
+            return ((n_i - 1) * ((fm + bm - 1) / bm) + (lm + bm - 1) / bm) *
+                   ((n_j - 1) * ((fn + bn - 1) / bn) + (ln + bn - 1) / bn);
+        };
+        auto cost = [&](int64_t n_tiles, int64_t per_round, double round_time) {
+            return (double)((n_tiles + per_round - 1) / per_round) * round_time;
+        };
+        const double c3 = cost(tiles(256, 256), 256, 1.0);
+        const double c2 = cost(tiles(128, 128), 512, 0.6);
+        cfg = c3 <= c2 ? 3 : 2;
+    }
+    if (cfg == 3) return bf::launch_cfg<2, 4, 4, 2>(p, dd, stream);   // 256 x 256, 512 threads
+    return bf::launch_cfg<2, 2, 2, 2>(p, dd, stream);                  // 128 x 128, 256 threads
+}
+
+}  // namespace tg

@@ -25,6 +25,7 @@ struct GemmDesc {
     int32_t epilogue;
     float alpha, beta;
     int32_t config;   // 0 = automatic, 1..3 = small / medium / large macro tile
+    int32_t out_bf16; // bf16 kernel only: C (and aux) hold bf16 bit patterns instead of float
 };
 
 // Kernel argument block (filled by the launcher).
@@ -47,5 +48,12 @@ struct GemmParams {
 
 int pick_config(const GemmDesc& d);
 hipError_t launch_tile_gemm_f32(const GemmDesc& d, hipStream_t stream);
+// A, B are bf16 bit patterns; accumulation is fp32.  With out_bf16 the result is rounded to nearest
+// even into bf16 and aux is read as bf16; otherwise C is float (aux unused).
+hipError_t launch_tile_gemm_bf16(const GemmDesc& d, hipStream_t stream);
+inline hipError_t launch_tile_gemm(const GemmDesc& d, int dtype_bf16, hipStream_t stream)
+{
+    return dtype_bf16 ? launch_tile_gemm_bf16(d, stream) : launch_tile_gemm_f32(d, stream);
+}
 
 }  // namespace tg
