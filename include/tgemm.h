@@ -155,14 +155,23 @@ int tgemm_queue_selftest(int64_t n, int32_t producers, int32_t consumers, int32_
  *
  * Network: n_layers weight matrices W_l of shape dims[l] x dims[l+1], no bias; sigmoid after every
  * layer but the last; softmax + mean cross-entropy on the last.
- *   W        n_layers caller-owned matrices (dtype elements).  All device pointers: the products run
- *            in-core.  (Pinned host weights, i.e. the out-of-core MLP, are not implemented yet and
- *            are rejected with TGEMM_EARG.)
+ *   W        n_layers caller-owned matrices (dtype elements), all of one kind.
+ *            Device pointers: in-core, every product is one launch.
+ *            Pinned host pointers: out-of-core.  T x T weight tiles are staged through an HBM tile
+ *            cache (LRU, section 3.4); the forward pass fetches each tile once, the backward pass
+ *            uses a tile for D W^T, updates it and writes it back.  On return of every call the
+ *            host weights are complete and no modified tile remains only on the device.
+ *   dtype    TGEMM_F32, or TGEMM_BF16: weights, X, activations and errors are bf16, logits,
+ *            probabilities, dW outputs and all accumulation float; the updated weights are
+ *            bf16_round_to_nearest_even(float(W) - lr * dW).
  *   T        tile size of every product.
- *   hbm_budget  upper bound on device bytes the object may allocate for activations and errors
- *            (0 = no bound).
- * The object allocates its activation / error workspaces on the first forward for a batch size and
- * reuses them while the batch size does not grow. */
+ *   hbm_budget  upper bound on device bytes the object may allocate: activations, errors, logits and
+ *            (out-of-core) the weight-tile cache, which takes what the workspaces leave.  0 = no
+ *            bound (in-core only; out-of-core needs a budget).  TGEMM_EBUDGET is reported by the
+ *            first forward / step whose batch makes the workspaces plus the minimum cache
+ *            (2 * max_l ceil(dims[l] / T) + 2 tiles) exceed it.
+ * The object allocates its workspaces on the first forward for a batch size and reuses them while
+ * the batch size does not grow. */
 int mlp_create(tgemm_ctx* ctx, tgemm_mlp** out, int32_t n_layers, const int64_t* dims,
                void* const* W, int32_t dtype, int32_t T, size_t hbm_budget);
 int mlp_destroy(tgemm_mlp* mlp);
@@ -176,7 +185,8 @@ int mlp_forward(tgemm_mlp* mlp, const void* X, int64_t batch, float* probs);
  *   D_L = (softmax(Z_L) - onehot(labels)) / batch;  dW_l = A_{l-1}^T D_l;
  *   D_{l-1} = (D_l W_l^T) * A_{l-1} * (1 - A_{l-1}).
  *   labels  device pointer, batch int32 values in [0, dims[n_layers]).
- *   dW      NULL, or n_layers device pointers (dims[l] x dims[l+1] floats) receiving dW_l.
+ *   dW      NULL, or n_layers device pointers (dims[l] x dims[l+1] floats, also for TGEMM_BF16)
+ *           receiving dW_l; single entries may be NULL.
  *   loss    host pointer receiving the mean cross-entropy (may be NULL).
  * The weights are not changed.  TGEMM_ESTATE if no forward preceded. */
 int mlp_backward(tgemm_mlp* mlp, const int32_t* labels, void* const* dW, float* loss);
@@ -189,7 +199,7 @@ int mlp_step(tgemm_mlp* mlp, const void* X, const int32_t* labels, int64_t batch
 /* Test access to the object's device workspaces after a forward / backward:
  *   what 0: activation A_l (l = 1..n_layers-1; batch x dims[l], dtype elements)
  *        1: logits Z_L (batch x dims[n_layers] floats; layer ignored)
- *        2: error D_l  (l = 1..n_layers; batch x dims[l]; float for l == n_layers, else dtype)
+ *        2: error D_l  (l = 1..n_layers; batch x dims[l], dtype elements)
  * Copies `bytes` bytes to the host buffer dst.  TGEMM_EARG if bytes exceeds the matrix. */
 int mlp_read(tgemm_mlp* mlp, int32_t what, int32_t layer, void* dst, size_t bytes);
 

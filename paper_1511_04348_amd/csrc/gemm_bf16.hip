@@ -199,13 +199,27 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_bf16(const GemmParams 
         const int step = c / cps;
         kk = step * p.T + (c - step * cps) * BK;
         klim = min(p.K, (step + 1) * p.T);
+        return step;
+    };
+    // B chunk source: the dense matrix, or the tile of (k-step, task column) from the tile table,
+    // addressed with coordinates local to that tile
+    auto b_source = [&](int step, int kk, int klim, const uint16_t*& base, int& mn0, int& mn_end, int& k0, int& k1) {
+        if (p.b_tiles) {
+            base = reinterpret_cast<const uint16_t*>(p.b_tiles[(int64_t)step * p.n_j + tj]);
+            mn0 = col0 - tj * p.T; mn_end = col_end - tj * p.T;
+            k0 = kk - step * p.T; k1 = klim - step * p.T;
+        } else {
+            base = B; mn0 = col0; mn_end = col_end; k0 = kk; k1 = klim;
+        }
     };
 
     if (n_chunks > 0) {
-        int kk, klim;
-        chunk_range(0, kk, klim);
+        int kk, klim, bm0, bm1, bk0, bk1;
+        const uint16_t* bsrc;
+        const int step = chunk_range(0, kk, klim);
+        b_source(step, kk, klim, bsrc, bm0, bm1, bk0, bk1);
         la.load(A, p.lda, row0, row_end, kk, klim, p.vec_a, tid);
-        lb.load(B, p.ldb, col0, col_end, kk, klim, p.vec_b, tid);
+        lb.load(bsrc, p.ldb, bm0, bm1, bk0, bk1, p.vec_b, tid);
         la.store(As, tid);
         lb.store(Bs, tid);
     }
@@ -219,10 +233,12 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_bf16(const GemmParams 
         const int st = c & 1;
         const bool more = (c + 1 < n_chunks);
         if (more) {
-            int kk, klim;
-            chunk_range(c + 1, kk, klim);
+            int kk, klim, bm0, bm1, bk0, bk1;
+            const uint16_t* bsrc;
+            const int step = chunk_range(c + 1, kk, klim);
+            b_source(step, kk, klim, bsrc, bm0, bm1, bk0, bk1);
             la.load(A, p.lda, row0, row_end, kk, klim, p.vec_a, tid);
-            lb.load(B, p.ldb, col0, col_end, kk, klim, p.vec_b, tid);
+            lb.load(bsrc, p.ldb, bm0, bm1, bk0, bk1, p.vec_b, tid);
         }
         const uint32_t* as = As + st * STAGE_A + a_off;
         const uint32_t* bs = Bs + st * STAGE_B + b_off;
@@ -251,8 +267,11 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_bf16(const GemmParams 
     // -- epilogue.  acc[r][cc][v] is element (row, col) of the wave tile with
     //    row = 32 r + 8 (v / 4) + 4 lh + v % 4,  col = 32 cc + li.
     const float alpha = p.alpha, beta = p.beta;
-    float* __restrict__ Cf = p.C;
-    uint16_t* __restrict__ Cb = reinterpret_cast<uint16_t*>(p.C);
+    // C: the dense matrix, or this task's tile from the tile table (tile-local coordinates)
+    const int64_t c_shift = p.c_tiles ? ((int64_t)(ti * p.T) * p.ldc + tj * p.T) : 0;
+    void* c_base = p.c_tiles ? p.c_tiles[(int64_t)ti * p.n_j + tj] : (void*)p.C;
+    float* __restrict__ Cf = reinterpret_cast<float*>(c_base) - c_shift;
+    uint16_t* __restrict__ Cb = reinterpret_cast<uint16_t*>(c_base) - c_shift;
     const uint16_t* __restrict__ aux = reinterpret_cast<const uint16_t*>(p.aux);
 #pragma unroll
     for (int r = 0; r < RA; ++r) {
@@ -363,6 +382,7 @@ hipError_t launch_tile_gemm_bf16(const GemmDesc& d, hipStream_t stream)
     if (T > big) T = big > 0 ? big : 1;
     p.T = (int)T;
     p.alpha = d.alpha; p.beta = d.beta;
+    p.b_tiles = d.b_tiles; p.c_tiles = d.c_tiles;
     // k-contiguous operands use 16-byte loads (8 elements), m/n-contiguous ones 8-byte loads (4)
     auto ok = [&](const void* q, int64_t ld, bool kc) {
         const int e = kc ? 8 : 4;

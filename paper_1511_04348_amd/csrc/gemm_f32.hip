@@ -174,13 +174,27 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
         const int step = c / cps;
         kk = step * p.T + (c - step * cps) * BK;
         klim = min(p.K, (step + 1) * p.T);
+        return step;
+    };
+    // B chunk source: the dense matrix, or the tile of (k-step, task column) from the tile table,
+    // addressed with coordinates local to that tile
+    auto b_source = [&](int step, int kk, int klim, const float*& base, int& mn0, int& mn_end, int& k0, int& k1) {
+        if (p.b_tiles) {
+            base = reinterpret_cast<const float*>(p.b_tiles[(int64_t)step * p.n_j + tj]);
+            mn0 = col0 - tj * p.T; mn_end = col_end - tj * p.T;
+            k0 = kk - step * p.T; k1 = klim - step * p.T;
+        } else {
+            base = B; mn0 = col0; mn_end = col_end; k0 = kk; k1 = klim;
+        }
     };
 
     if (n_chunks > 0) {
-        int kk, klim;
-        chunk_range(0, kk, klim);
+        int kk, klim, bm0, bm1, bk0, bk1;
+        const float* bsrc;
+        const int step = chunk_range(0, kk, klim);
+        b_source(step, kk, klim, bsrc, bm0, bm1, bk0, bk1);
         LA::load(ra, A, p.lda, row0, row_end, kk, klim, p.vec_a, tid);
-        LB::load(rb, B, p.ldb, col0, col_end, kk, klim, p.vec_b, tid);
+        LB::load(rb, bsrc, p.ldb, bm0, bm1, bk0, bk1, p.vec_b, tid);
         LA::store(ra, As, tid);
         LB::store(rb, Bs, tid);
     }
@@ -193,10 +207,12 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
         const int st = c & 1;
         const bool more = (c + 1 < n_chunks);
         if (more) {
-            int kk, klim;
-            chunk_range(c + 1, kk, klim);
+            int kk, klim, bm0, bm1, bk0, bk1;
+            const float* bsrc;
+            const int step = chunk_range(c + 1, kk, klim);
+            b_source(step, kk, klim, bsrc, bm0, bm1, bk0, bk1);
             LA::load(ra, A, p.lda, row0, row_end, kk, klim, p.vec_a, tid);
-            LB::load(rb, B, p.ldb, col0, col_end, kk, klim, p.vec_b, tid);
+            LB::load(rb, bsrc, p.ldb, bm0, bm1, bk0, bk1, p.vec_b, tid);
         }
         const float* as = As + st * STAGE_A + lh * LDA_S + a_off;
         const float* bs = Bs + st * STAGE_B + lh * LDB_S + b_off;
@@ -220,7 +236,10 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
 
     // -- epilogue.  acc[r][cc][v] is element (row, col) of the wave tile with
     //    row = RA * (8*(v/4) + 4*lh + v%4) + r,  col = RB * li + cc.
-    float* __restrict__ C = p.C;
+    // C: the dense matrix, or this task's tile from the tile table (tile-local coordinates)
+    float* __restrict__ C = p.c_tiles ? reinterpret_cast<float*>(p.c_tiles[(int64_t)ti * p.n_j + tj]) -
+                                            ((int64_t)(ti * p.T) * p.ldc + tj * p.T)
+                                      : p.C;
     const float* __restrict__ aux = reinterpret_cast<const float*>(p.aux);
     const float alpha = p.alpha, beta = p.beta;
     const int colb = col0 + wn * WTN + RB * li;
@@ -379,6 +398,7 @@ hipError_t launch_tile_gemm_f32(const GemmDesc& d, hipStream_t stream)
     if (T > big) T = big > 0 ? big : 1;
     p.T = (int)T;
     p.alpha = d.alpha; p.beta = d.beta;
+    p.b_tiles = d.b_tiles; p.c_tiles = d.c_tiles;
     const bool t4 = (T % 4 == 0);
     auto al16 = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15) == 0; };
     p.vec_a = t4 && al16(d.A) && (d.lda % 4 == 0);

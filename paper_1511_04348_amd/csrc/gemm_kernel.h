@@ -26,6 +26,12 @@ struct GemmDesc {
     float alpha, beta;
     int32_t config;   // 0 = automatic, 1..3 = small / medium / large macro tile
     int32_t out_bf16; // bf16 kernel only: C (and aux) hold bf16 bit patterns instead of float
+    // Optional tile tables (device arrays of device pointers) for operands that live as separate
+    // T x T tiles in cache slots instead of one dense matrix.  Entry [step * n_j + tj] of b_tiles
+    // is the B tile of k-step `step` and task column tj; entry [ti * n_j + tj] of c_tiles is the C
+    // tile of task (ti, tj).  Inside a tile the pitch is ldb / ldc.  NULL = dense operand.
+    const void* const* b_tiles;
+    void* const* c_tiles;
 };
 
 // Kernel argument block (filled by the launcher).
@@ -44,6 +50,8 @@ struct GemmParams {
     int n_chunks;               // BK-chunks over all k-steps
     float alpha, beta;
     bool vec_a, vec_b, vec_c;   // 16-byte vector access is legal for this operand
+    const void* const* b_tiles; // see GemmDesc
+    void* const* c_tiles;
 };
 
 int pick_config(const GemmDesc& d);

@@ -4,31 +4,118 @@
 //            (equation 3)  dW_l = A_{l-1}^T D_l
 //   update                 W_l <- W_l - lr dW_l   (the dW product's epilogue writes straight into W_l)
 // plus one row-wise kernel for softmax, cross-entropy and the output error D_L.
-// Every product goes through the same tile GEMM kernel as tgemm_run, with tile size T.
+// Every product goes through the same tile GEMM kernels as tgemm_run, with tile size T.
+//
+// Two residency modes.  In-core: the weights are device matrices and every product is one launch
+// on stream 0.  Out-of-core: the weights stay in pinned host memory and are staged, T x T tile by
+// tile, through an HBM tile cache (strict LRU; section 3.4 of the paper) -- the kernels then take
+// the weight operand as a table of tile pointers.  Streams form the same pipeline as in
+// tgemm_run: stream 0 fetches weight tiles (running ahead of the products), stream 1 computes,
+// stream 3 writes updated tiles back.  The forward pass walks W_l by tile columns (a column of
+// tiles is one launch over the whole batch, so every weight tile is fetched once per pass); the
+// backward pass walks W_l by tile rows (the row's tiles serve the D W^T product, then receive the
+// update, then are written back), so each tile crosses the link at most twice per step in each
+// direction.
 #include <math.h>
 #include <string.h>
 
+#include <algorithm>
 #include <chrono>
+#include <unordered_map>
 #include <vector>
 
 #include "common.h"
 #include "gemm_kernel.h"
 
+namespace tg {
+namespace {
+
+// ---- weight tile cache (out-of-core mode) -------------------------------------------------------
+struct WSlot {
+    int64_t key = -1;
+    hipEvent_t ready = nullptr;      // fetch finished (stream 0)
+    hipEvent_t read = nullptr;       // last product using the tile finished (stream 1)
+    hipEvent_t flushed = nullptr;    // write-back finished (stream 3)
+    bool read_pending = false, flush_pending = false;
+    int prev = -1, next = -1;
+};
+
+struct WeightCache {
+    char* pool = nullptr;
+    size_t slot_bytes = 0;
+    int n_slots = 0, n_used = 0;
+    std::vector<WSlot> slots;
+    std::unordered_map<int64_t, int> dir;
+    int lru_head = -1, lru_tail = -1;
+
+    ~WeightCache() { release(); }
+    void release()
+    {
+        for (auto& s : slots) {
+            if (s.ready) (void)hipEventDestroy(s.ready);
+            if (s.read) (void)hipEventDestroy(s.read);
+            if (s.flushed) (void)hipEventDestroy(s.flushed);
+        }
+        slots.clear();
+        if (pool) (void)hipFree(pool);
+        pool = nullptr;
+        dir.clear();
+        n_slots = n_used = 0;
+        lru_head = lru_tail = -1;
+    }
+    char* ptr(int slot) const { return pool + (size_t)slot * slot_bytes; }
+    void unlink(int i)
+    {
+        WSlot& s = slots[i];
+        if (s.prev >= 0) slots[s.prev].next = s.next; else lru_head = s.next;
+        if (s.next >= 0) slots[s.next].prev = s.prev; else lru_tail = s.prev;
+        s.prev = s.next = -1;
+    }
+    void push_mru(int i)
+    {
+        WSlot& s = slots[i];
+        s.prev = lru_tail;
+        s.next = -1;
+        if (lru_tail >= 0) slots[lru_tail].next = i; else lru_head = i;
+        lru_tail = i;
+    }
+};
+
+struct TableRing {
+    static constexpr int N = 32;
+    void** dev[N] = {};
+    void** host[N] = {};
+    hipEvent_t done[N] = {};
+    bool used[N] = {};
+    int next = 0;
+    int cap = 0;   // pointers per entry
+};
+
+inline int64_t wkey(int layer, int64_t r, int64_t c) { return ((int64_t)layer << 56) | (r << 28) | c; }
+
+}  // namespace
+}  // namespace tg
+
 struct tgemm_mlp {
     tgemm_ctx* ctx = nullptr;
     int n_layers = 0;
     std::vector<int64_t> dims;
-    std::vector<float*> W;
+    std::vector<char*> W;         // caller-owned weights (device or pinned host)
+    int32_t dtype = TGEMM_F32;
+    size_t es = 4;                // bytes per weight / activation / error element
     int32_t T = 0;
     size_t budget = 0;
+    bool ooc = false;
     int64_t cap_batch = 0;        // batch the workspaces were sized for
     int64_t batch = 0;            // batch of the last forward (0: none yet)
-    const float* X = nullptr;     // input of the last forward (caller owned)
-    std::vector<float*> act;      // act[l], l = 1..L-1 : batch x dims[l]
-    std::vector<float*> delta;    // delta[l], l = 1..L : batch x dims[l]
-    float* logits = nullptr;      // batch x dims[L]
+    const char* X = nullptr;      // input of the last forward (caller owned)
+    std::vector<char*> act;       // act[l], l = 1..L-1 : batch x dims[l], dtype
+    std::vector<char*> delta;     // delta[l], l = 1..L : batch x dims[l], dtype
+    float* logits = nullptr;      // batch x dims[L], float
     float* row_loss = nullptr;    // batch
     bool have_delta = false;
+    tg::WeightCache cache;
+    tg::TableRing ring;
 };
 
 namespace tg {
@@ -44,12 +131,21 @@ __device__ inline float wave_sum(float v)
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
     return v;
 }
+__device__ inline uint16_t to_bf16_rne(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
 
 // One workgroup per row of the logits.  P = softmax(z) with the row maximum subtracted;
-// row_loss = -log P[label]; delta = (P - onehot(label)) * inv_batch.  probs / delta may be NULL.
+// row_loss = -log P[label]; delta = (P - onehot(label)) * inv_batch (float, or bf16 rounded to
+// nearest even).  probs / delta / labels may be NULL (no labels: no loss, no delta).
+template <bool DELTA_BF16>
 __global__ __launch_bounds__(256) void softmax_xent_rows(const float* __restrict__ logits, int64_t ld, int n,
                                                          const int32_t* __restrict__ labels, float inv_batch,
-                                                         float* __restrict__ delta, float* __restrict__ probs,
+                                                         void* __restrict__ delta, float* __restrict__ probs,
                                                          float* __restrict__ row_loss)
 {
     __shared__ float red[4];
@@ -68,20 +164,28 @@ __global__ __launch_bounds__(256) void softmax_xent_rows(const float* __restrict
     if (lane == 0) red[wave] = s;
     __syncthreads();
     s = (red[0] + red[1]) + (red[2] + red[3]);
-    const int y = labels[row];
+    const int y = labels ? labels[row] : -1;
     const float inv = 1.f / s;
-    for (int c = tid; c < n; c += 256) {
-        const float p = expf(z[c] - m) * inv;
-        if (probs) probs[(int64_t)row * ld + c] = p;
-        if (delta) delta[(int64_t)row * ld + c] = (p - (c == y ? 1.f : 0.f)) * inv_batch;
+    if (probs || delta) {
+        for (int c = tid; c < n; c += 256) {
+            const float p = expf(z[c] - m) * inv;
+            if (probs) probs[(int64_t)row * ld + c] = p;
+            if (delta) {
+                const float d = (p - (c == y ? 1.f : 0.f)) * inv_batch;
+                if (DELTA_BF16) reinterpret_cast<uint16_t*>(delta)[(int64_t)row * ld + c] = to_bf16_rne(d);
+                else reinterpret_cast<float*>(delta)[(int64_t)row * ld + c] = d;
+            }
+        }
     }
-    if (tid == 0) row_loss[row] = (y >= 0 && y < n) ? (logf(s) + m - z[y]) : NAN;
+    if (tid == 0 && labels) row_loss[row] = (y >= 0 && y < n) ? (logf(s) + m - z[y]) : NAN;
 }
 
 double now_ms()
 {
     return std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now().time_since_epoch()).count();
 }
+
+inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 void free_workspaces(tgemm_mlp* m)
 {
@@ -91,6 +195,22 @@ void free_workspaces(tgemm_mlp* m)
     if (m->row_loss) (void)hipFree(m->row_loss);
     m->logits = nullptr; m->row_loss = nullptr;
     m->cap_batch = 0; m->batch = 0; m->have_delta = false;
+    m->cache.release();
+    TableRing& r = m->ring;
+    for (int i = 0; i < TableRing::N; ++i) {
+        if (r.dev[i]) (void)hipFree(r.dev[i]);
+        if (r.host[i]) (void)hipHostFree(r.host[i]);
+        if (r.done[i]) (void)hipEventDestroy(r.done[i]);
+        r.dev[i] = nullptr; r.host[i] = nullptr; r.done[i] = nullptr; r.used[i] = false;
+    }
+    r.next = 0; r.cap = 0;
+}
+
+int64_t total_tiles(const tgemm_mlp* m)
+{
+    int64_t n = 0;
+    for (int l = 1; l <= m->n_layers; ++l) n += cdiv(m->dims[l - 1], m->T) * cdiv(m->dims[l], m->T);
+    return n;
 }
 
 int ensure_workspaces(tgemm_mlp* m, int64_t batch)
@@ -98,21 +218,58 @@ int ensure_workspaces(tgemm_mlp* m, int64_t batch)
     if (batch <= m->cap_batch) return TGEMM_OK;
     free_workspaces(m);
     const int L = m->n_layers;
-    size_t total = (size_t)batch * 4;
-    for (int l = 1; l <= L; ++l) total += (size_t)batch * m->dims[l] * 4 * 2;
-    if (m->budget && total > m->budget)
+    size_t total = (size_t)batch * 4 + (size_t)batch * m->dims[L] * 4;
+    for (int l = 1; l <= L; ++l) total += (size_t)batch * m->dims[l] * m->es * (l < L ? 2 : 1);
+    // out-of-core: the rest of the budget is the weight tile cache
+    int64_t max_tiles = 0, n_slots = 0;
+    const size_t slot_bytes = (size_t)m->T * m->T * m->es;
+    if (m->ooc) {
+        for (int l = 0; l <= L; ++l) max_tiles = std::max(max_tiles, cdiv(m->dims[l], m->T));
+        const size_t ring_bytes = (size_t)TableRing::N * max_tiles * sizeof(void*);
+        const size_t need = total + ring_bytes + (size_t)(2 * max_tiles + 2) * slot_bytes;
+        if (m->budget < need)
+            return fail(TGEMM_EBUDGET, "mlp: batch %lld needs %zu bytes of activations and at least %lld weight-tile "
+                        "slots of %zu bytes; hbm_budget is %zu", (long long)batch, total, (long long)(2 * max_tiles + 2),
+                        slot_bytes, m->budget);
+        n_slots = (int64_t)((m->budget - total - ring_bytes) / slot_bytes);
+        n_slots = std::min(n_slots, total_tiles(m));
+        total += ring_bytes;
+    } else if (m->budget && total > m->budget) {
         return fail(TGEMM_EBUDGET, "mlp: activations and errors for batch %lld need %zu bytes, hbm_budget is %zu",
                     (long long)batch, total, m->budget);
-    auto alloc = [&](float** p, size_t bytes) -> bool {
-        if (hipMalloc((void**)p, bytes) != hipSuccess) { (void)hipGetLastError(); *p = nullptr; return false; }
+    }
+    auto alloc = [&](void** p, size_t bytes) -> bool {
+        if (hipMalloc(p, bytes) != hipSuccess) { (void)hipGetLastError(); *p = nullptr; return false; }
         return true;
     };
-    bool ok = alloc(&m->row_loss, (size_t)batch * 4) && alloc(&m->logits, (size_t)batch * m->dims[L] * 4);
+    bool ok = alloc((void**)&m->row_loss, (size_t)batch * 4) && alloc((void**)&m->logits, (size_t)batch * m->dims[L] * 4);
     for (int l = 1; l <= L && ok; ++l) {
-        if (l < L) ok = ok && alloc(&m->act[l], (size_t)batch * m->dims[l] * 4);
-        ok = ok && alloc(&m->delta[l], (size_t)batch * m->dims[l] * 4);
+        if (l < L) ok = ok && alloc((void**)&m->act[l], (size_t)batch * m->dims[l] * m->es);
+        ok = ok && alloc((void**)&m->delta[l], (size_t)batch * m->dims[l] * m->es);
+    }
+    if (ok && m->ooc) {
+        WeightCache& c = m->cache;
+        c.slot_bytes = slot_bytes;
+        ok = alloc((void**)&c.pool, (size_t)n_slots * slot_bytes);
+        if (ok) {
+            c.n_slots = (int)n_slots;
+            c.slots.resize((size_t)n_slots);
+            for (auto& s : c.slots) {
+                ok = ok && hipEventCreateWithFlags(&s.ready, hipEventDisableTiming) == hipSuccess &&
+                     hipEventCreateWithFlags(&s.read, hipEventDisableTiming) == hipSuccess &&
+                     hipEventCreateWithFlags(&s.flushed, hipEventDisableTiming) == hipSuccess;
+            }
+        }
+        TableRing& r = m->ring;
+        r.cap = (int)max_tiles;
+        for (int i = 0; i < TableRing::N && ok; ++i) {
+            ok = alloc((void**)&r.dev[i], (size_t)max_tiles * sizeof(void*)) &&
+                 hipHostMalloc((void**)&r.host[i], (size_t)max_tiles * sizeof(void*), hipHostMallocDefault) == hipSuccess &&
+                 hipEventCreateWithFlags(&r.done[i], hipEventDisableTiming) == hipSuccess;
+        }
     }
     if (!ok) {
+        (void)hipGetLastError();
         free_workspaces(m);
         return fail(TGEMM_ENOMEM, "mlp: device allocation of %zu workspace bytes failed", total);
     }
@@ -120,34 +277,153 @@ int ensure_workspaces(tgemm_mlp* m, int64_t batch)
     return TGEMM_OK;
 }
 
-int launch(tgemm_mlp* m, GemmDesc& d)
+// ---- out-of-core helpers ------------------------------------------------------------------------
+
+// Tile (r, c) of W_l into the cache (section 3.4: hit -> use it, miss -> fetch from host memory).
+int acquire_tile(tgemm_mlp* m, int l, int64_t r, int64_t c, int* slot_out)
 {
-    d.T = m->T;
-    d.config = m->ctx->opts.kernel_config;
-    hipError_t e = launch_tile_gemm_f32(d, m->ctx->streams[0]);
-    if (e != hipSuccess) return fail(TGEMM_EHIP, "mlp: tile GEMM launch failed: %s", hipGetErrorString(e));
-    m->ctx->stats.kernel_launches++;
-    m->ctx->stats.n_tile_gemms += ((d.M + d.T - 1) / d.T) * ((d.N + d.T - 1) / d.T) * ((d.K + d.T - 1) / d.T);
+    WeightCache& wc = m->cache;
+    tgemm_ctx* ctx = m->ctx;
+    hipStream_t fetch = ctx->streams[0];
+    const int64_t key = wkey(l, r, c);
+    auto it = wc.dir.find(key);
+    if (it != wc.dir.end()) {
+        wc.unlink(it->second);
+        wc.push_mru(it->second);
+        ctx->stats.hits++;
+        *slot_out = it->second;
+        return TGEMM_OK;
+    }
+    ctx->stats.misses++;
+    int slot;
+    if (wc.n_used < wc.n_slots) {
+        slot = wc.n_used++;
+    } else {
+        slot = wc.lru_head;
+        wc.unlink(slot);
+        wc.dir.erase(wc.slots[slot].key);
+        ctx->stats.evictions++;
+        WSlot& s = wc.slots[slot];
+        if (s.read_pending) TG_HIP(hipStreamWaitEvent(fetch, s.read, 0));
+        if (s.flush_pending) TG_HIP(hipStreamWaitEvent(fetch, s.flushed, 0));
+        s.read_pending = s.flush_pending = false;
+    }
+    WSlot& s = wc.slots[slot];
+    s.key = key;
+    wc.dir[key] = slot;
+    wc.push_mru(slot);
+    const int64_t T = m->T, nc = m->dims[l];
+    const int64_t rows = std::min(T, m->dims[l - 1] - r * T), cols = std::min(T, nc - c * T);
+    const char* src = m->W[l - 1] + ((size_t)(r * T) * nc + (size_t)c * T) * m->es;
+    TG_HIP(hipMemcpy2DAsync(wc.ptr(slot), (size_t)T * m->es, src, (size_t)nc * m->es, (size_t)cols * m->es, (size_t)rows,
+                            hipMemcpyHostToDevice, fetch));
+    ctx->stats.h2d_bytes += rows * cols * (int64_t)m->es;
+    TG_HIP(hipEventRecord(s.ready, fetch));
+    *slot_out = slot;
     return TGEMM_OK;
 }
 
-// equation 1 for every layer
-int forward(tgemm_mlp* m, const float* X, int64_t batch)
+// Claims the next table-ring entry (waits on the host until the launch that last used it is done,
+// which also bounds how far the host runs ahead of the GPU).
+int ring_claim(tgemm_mlp* m, int* entry)
+{
+    TableRing& r = m->ring;
+    const int e = r.next;
+    r.next = (r.next + 1) % TableRing::N;
+    if (r.used[e]) TG_HIP(hipEventSynchronize(r.done[e]));
+    r.used[e] = false;
+    *entry = e;
+    return TGEMM_OK;
+}
+
+// Uploads the table of `n` slot pointers for the next launch on the compute stream and makes that
+// stream wait for the tiles' fetches.
+int ring_publish(tgemm_mlp* m, int entry, const int* tile_slots, int n)
+{
+    TableRing& r = m->ring;
+    hipStream_t comp = m->ctx->streams[1];
+    for (int i = 0; i < n; ++i) {
+        r.host[entry][i] = m->cache.ptr(tile_slots[i]);
+        TG_HIP(hipStreamWaitEvent(comp, m->cache.slots[tile_slots[i]].ready, 0));
+    }
+    TG_HIP(hipMemcpyAsync(r.dev[entry], r.host[entry], (size_t)n * sizeof(void*), hipMemcpyHostToDevice, comp));
+    return TGEMM_OK;
+}
+
+int ring_finish(tgemm_mlp* m, int entry, const int* tile_slots, int n)
+{
+    TableRing& r = m->ring;
+    hipStream_t comp = m->ctx->streams[1];
+    TG_HIP(hipEventRecord(r.done[entry], comp));
+    r.used[entry] = true;
+    for (int i = 0; i < n; ++i) {
+        WSlot& s = m->cache.slots[tile_slots[i]];
+        TG_HIP(hipEventRecord(s.read, comp));
+        s.read_pending = true;
+    }
+    return TGEMM_OK;
+}
+
+int launch(tgemm_mlp* m, GemmDesc& d, hipStream_t st)
+{
+    d.T = m->T;
+    d.config = m->ctx->opts.kernel_config;
+    hipError_t e = launch_tile_gemm(d, m->dtype == TGEMM_BF16, st);
+    if (e != hipSuccess) return fail(TGEMM_EHIP, "mlp: tile GEMM launch failed: %s", hipGetErrorString(e));
+    m->ctx->stats.kernel_launches++;
+    m->ctx->stats.n_tile_gemms += cdiv(d.M, d.T) * cdiv(d.N, d.T) * cdiv(d.K, d.T);
+    return TGEMM_OK;
+}
+
+hipStream_t compute_stream(tgemm_mlp* m) { return m->ctx->streams[m->ooc ? 1 : 0]; }
+
+// equation 1 for layer l: out = epilogue(A_{l-1} W_l)
+int forward_layer(tgemm_mlp* m, int l, const char* in, int64_t batch)
 {
     const int L = m->n_layers;
-    const float* in = X;
-    for (int l = 1; l <= L; ++l) {
-        GemmDesc d;
-        memset(&d, 0, sizeof d);
-        d.A = in; d.lda = m->dims[l - 1]; d.a_kcontig = 1;              // A_{l-1}: batch x n_{l-1}
-        d.B = m->W[l - 1]; d.ldb = m->dims[l]; d.b_kcontig = 0;          // W_l: n_{l-1} x n_l
-        d.C = (l < L) ? m->act[l] : m->logits; d.ldc = m->dims[l];
-        d.M = batch; d.N = m->dims[l]; d.K = m->dims[l - 1];
-        d.epilogue = (l < L) ? EPI_SIGMOID : EPI_AXPBY;
-        d.alpha = 1.f; d.beta = 0.f;
-        const int rc = launch(m, d);
+    const bool bf = m->dtype == TGEMM_BF16;
+    GemmDesc d;
+    memset(&d, 0, sizeof d);
+    d.A = in; d.lda = m->dims[l - 1]; d.a_kcontig = 1;                  // A_{l-1}: batch x n_{l-1}
+    d.b_kcontig = 0;                                                     // W_l: n_{l-1} x n_l
+    d.M = batch; d.K = m->dims[l - 1];
+    d.epilogue = (l < L) ? EPI_SIGMOID : EPI_AXPBY;
+    d.alpha = 1.f; d.beta = 0.f;
+    d.out_bf16 = (bf && l < L) ? 1 : 0;                                  // logits stay float
+    char* out = (l < L) ? m->act[l] : (char*)m->logits;
+    const size_t out_es = (l < L) ? m->es : 4;
+    d.ldc = m->dims[l];
+    if (!m->ooc) {
+        d.B = m->W[l - 1]; d.ldb = m->dims[l];
+        d.C = (float*)out; d.N = m->dims[l];
+        return launch(m, d, compute_stream(m));
+    }
+    // out-of-core: one launch per tile column j of W_l, over the whole batch and all k-steps
+    const int64_t T = m->T, n_k = cdiv(m->dims[l - 1], T), n_j = cdiv(m->dims[l], T);
+    std::vector<int> tiles((size_t)n_k);
+    for (int64_t j = 0; j < n_j; ++j) {
+        int entry, rc;
+        if ((rc = ring_claim(m, &entry)) != TGEMM_OK) return rc;
+        for (int64_t k = 0; k < n_k; ++k)
+            if ((rc = acquire_tile(m, l, k, j, &tiles[(size_t)k])) != TGEMM_OK) return rc;
+        if ((rc = ring_publish(m, entry, tiles.data(), (int)n_k)) != TGEMM_OK) return rc;
+        d.b_tiles = (const void* const*)m->ring.dev[entry];
+        d.B = m->cache.ptr(tiles[0]); d.ldb = T;
+        d.C = (float*)(out + (size_t)(j * T) * out_es);
+        d.N = std::min(T, m->dims[l] - j * T);
+        if ((rc = launch(m, d, compute_stream(m))) != TGEMM_OK) return rc;
+        if ((rc = ring_finish(m, entry, tiles.data(), (int)n_k)) != TGEMM_OK) return rc;
+    }
+    return TGEMM_OK;
+}
+
+int forward(tgemm_mlp* m, const char* X, int64_t batch)
+{
+    const char* in = X;
+    for (int l = 1; l <= m->n_layers; ++l) {
+        const int rc = forward_layer(m, l, in, batch);
         if (rc != TGEMM_OK) return rc;
-        in = d.C;
+        in = (l < m->n_layers) ? m->act[l] : nullptr;
     }
     m->X = X;
     m->batch = batch;
@@ -159,17 +435,29 @@ int softmax(tgemm_mlp* m, const int32_t* labels, float* probs, bool want_delta)
 {
     const int L = m->n_layers;
     const int64_t n = m->dims[L];
-    hipLaunchKernelGGL(softmax_xent_rows, dim3((unsigned)m->batch), dim3(256), 0, m->ctx->streams[0],
-                       m->logits, n, (int)n, labels, 1.f / (float)m->batch,
-                       want_delta ? m->delta[L] : nullptr, probs, m->row_loss);
+    void* delta = want_delta ? (void*)m->delta[L] : nullptr;
+    if (m->dtype == TGEMM_BF16)
+        hipLaunchKernelGGL(softmax_xent_rows<true>, dim3((unsigned)m->batch), dim3(256), 0, compute_stream(m),
+                           m->logits, n, (int)n, labels, 1.f / (float)m->batch, delta, probs, m->row_loss);
+    else
+        hipLaunchKernelGGL(softmax_xent_rows<false>, dim3((unsigned)m->batch), dim3(256), 0, compute_stream(m),
+                           m->logits, n, (int)n, labels, 1.f / (float)m->batch, delta, probs, m->row_loss);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(TGEMM_EHIP, "mlp: softmax launch failed: %s", hipGetErrorString(e));
     return TGEMM_OK;
 }
 
+int sync_all(tgemm_mlp* m)
+{
+    for (int s = 0; s < 4; ++s) TG_HIP(hipStreamSynchronize(m->ctx->streams[s]));
+    for (auto& s : m->cache.slots) s.read_pending = s.flush_pending = false;
+    for (auto& u : m->ring.used) u = false;
+    return TGEMM_OK;
+}
+
 int read_loss(tgemm_mlp* m, float* loss)
 {
-    hipStream_t st = m->ctx->streams[0];
+    hipStream_t st = compute_stream(m);
     std::vector<float> rows((size_t)m->batch);
     TG_HIP(hipMemcpyAsync(rows.data(), m->row_loss, (size_t)m->batch * 4, hipMemcpyDeviceToHost, st));
     TG_HIP(hipStreamSynchronize(st));
@@ -179,41 +467,109 @@ int read_loss(tgemm_mlp* m, float* loss)
     return TGEMM_OK;
 }
 
-// equations 4 and 3 for every layer, last to first.  update: W_l <- W_l - lr dW_l in place of
-// storing dW_l; dW: optional destinations for the plain gradients.
+// equations 4 and 3 for layer l.  update: W_l <- W_l - lr dW_l in place of storing dW_l; dW_out:
+// optional dense float destination for the plain gradient.
+int backward_layer(tgemm_mlp* m, int l, float* dW_out, bool update, float lr)
+{
+    const bool bf = m->dtype == TGEMM_BF16;
+    const int64_t batch = m->batch, T = m->T;
+    const char* a_prev = (l == 1) ? m->X : m->act[l - 1];
+    hipStream_t comp = compute_stream(m);
+
+    GemmDesc da;   // D_{l-1} = (D_l W_l^T) * A_{l-1} * (1 - A_{l-1})
+    memset(&da, 0, sizeof da);
+    da.A = m->delta[l]; da.lda = m->dims[l]; da.a_kcontig = 1;             // D_l: batch x n_l
+    da.b_kcontig = 1;                                                      // W_l stored n_{l-1} x n_l = N x K
+    da.M = batch; da.K = m->dims[l];
+    da.ldc = m->dims[l - 1]; da.ldaux = m->dims[l - 1];
+    da.epilogue = EPI_DSIGMOID; da.alpha = 1.f; da.beta = 0.f;
+    da.out_bf16 = bf ? 1 : 0;
+
+    GemmDesc dw;   // dW_l = A_{l-1}^T D_l
+    memset(&dw, 0, sizeof dw);
+    dw.lda = m->dims[l - 1]; dw.a_kcontig = 0;                             // A_{l-1} stored K x M (batch x n_{l-1})
+    dw.B = m->delta[l]; dw.ldb = m->dims[l]; dw.b_kcontig = 0;             // D_l: batch x n_l
+    dw.N = m->dims[l]; dw.K = batch;
+    dw.epilogue = EPI_AXPBY;
+
+    if (!m->ooc) {
+        if (l > 1) {   // reads W_l before it is updated below
+            da.B = m->W[l - 1]; da.ldb = m->dims[l];
+            da.C = (float*)m->delta[l - 1]; da.aux = a_prev; da.N = m->dims[l - 1];
+            const int rc = launch(m, da, comp);
+            if (rc != TGEMM_OK) return rc;
+        }
+        if (update || dW_out) {
+            dw.A = a_prev; dw.M = m->dims[l - 1]; dw.ldc = m->dims[l];
+            if (update) { dw.C = (float*)m->W[l - 1]; dw.alpha = -lr; dw.beta = 1.f; dw.out_bf16 = bf ? 1 : 0; }
+            else { dw.C = dW_out; dw.alpha = 1.f; dw.beta = 0.f; dw.out_bf16 = 0; }
+            const int rc = launch(m, dw, comp);
+            if (rc != TGEMM_OK) return rc;
+        }
+        return TGEMM_OK;
+    }
+
+    // out-of-core: walk W_l by tile rows r.  The row's tiles serve D W^T (pre-update values), then
+    // take the update, then are written back to the host weights.
+    if (l == 1 && !update && !dW_out) return TGEMM_OK;   // nothing needs W_1
+    const int64_t n_r = cdiv(m->dims[l - 1], T), n_c = cdiv(m->dims[l], T);
+    hipStream_t flush = m->ctx->streams[3];
+    std::vector<int> tiles((size_t)n_c);
+    for (int64_t r = 0; r < n_r; ++r) {
+        const int64_t rows = std::min(T, m->dims[l - 1] - r * T);
+        int rc, entry;
+        const bool need_tiles = (l > 1) || update;
+        if (need_tiles)
+            for (int64_t c = 0; c < n_c; ++c)
+                if ((rc = acquire_tile(m, l, r, c, &tiles[(size_t)c])) != TGEMM_OK) return rc;
+        if (l > 1) {
+            if ((rc = ring_claim(m, &entry)) != TGEMM_OK) return rc;
+            if ((rc = ring_publish(m, entry, tiles.data(), (int)n_c)) != TGEMM_OK) return rc;
+            da.b_tiles = (const void* const*)m->ring.dev[entry];
+            da.B = m->cache.ptr(tiles[0]); da.ldb = T;
+            da.C = (float*)(m->delta[l - 1] + (size_t)(r * T) * m->es);
+            da.aux = a_prev + (size_t)(r * T) * m->es;
+            da.N = rows;
+            if ((rc = launch(m, da, comp)) != TGEMM_OK) return rc;
+            if ((rc = ring_finish(m, entry, tiles.data(), (int)n_c)) != TGEMM_OK) return rc;
+        }
+        dw.A = a_prev + (size_t)(r * T) * m->es;
+        dw.M = rows;
+        if (update) {
+            if ((rc = ring_claim(m, &entry)) != TGEMM_OK) return rc;
+            if ((rc = ring_publish(m, entry, tiles.data(), (int)n_c)) != TGEMM_OK) return rc;
+            dw.c_tiles = (void* const*)m->ring.dev[entry];
+            dw.C = (float*)m->cache.ptr(tiles[0]); dw.ldc = T;
+            dw.alpha = -lr; dw.beta = 1.f; dw.out_bf16 = bf ? 1 : 0;
+            if ((rc = launch(m, dw, comp)) != TGEMM_OK) return rc;
+            if ((rc = ring_finish(m, entry, tiles.data(), (int)n_c)) != TGEMM_OK) return rc;
+            // write the updated row of tiles back (stream 3) once the launch has finished
+            TG_HIP(hipStreamWaitEvent(flush, m->ring.done[entry], 0));
+            for (int64_t c = 0; c < n_c; ++c) {
+                const int64_t cols = std::min(T, m->dims[l] - c * T);
+                char* dst = m->W[l - 1] + ((size_t)(r * T) * m->dims[l] + (size_t)c * T) * m->es;
+                TG_HIP(hipMemcpy2DAsync(dst, (size_t)m->dims[l] * m->es, m->cache.ptr(tiles[(size_t)c]), (size_t)T * m->es,
+                                        (size_t)cols * m->es, (size_t)rows, hipMemcpyDeviceToHost, flush));
+                m->ctx->stats.d2h_bytes += rows * cols * (int64_t)m->es;
+                WSlot& s = m->cache.slots[tiles[(size_t)c]];
+                TG_HIP(hipEventRecord(s.flushed, flush));
+                s.flush_pending = true;
+            }
+        } else if (dW_out) {
+            dw.c_tiles = nullptr;
+            dw.C = dW_out + (size_t)(r * T) * m->dims[l]; dw.ldc = m->dims[l];
+            dw.alpha = 1.f; dw.beta = 0.f; dw.out_bf16 = 0;
+            if ((rc = launch(m, dw, comp)) != TGEMM_OK) return rc;
+        }
+    }
+    return TGEMM_OK;
+}
+
 int backward(tgemm_mlp* m, void* const* dW, bool update, float lr)
 {
-    const int L = m->n_layers;
-    const int64_t batch = m->batch;
-    for (int l = L; l >= 1; --l) {
-        const float* a_prev = (l == 1) ? m->X : m->act[l - 1];
-        if (l > 1) {
-            // D_{l-1} = (D_l W_l^T) * A_{l-1} * (1 - A_{l-1}); reads W_l before it is updated below
-            GemmDesc d;
-            memset(&d, 0, sizeof d);
-            d.A = m->delta[l]; d.lda = m->dims[l]; d.a_kcontig = 1;          // D_l: batch x n_l
-            d.B = m->W[l - 1]; d.ldb = m->dims[l]; d.b_kcontig = 1;          // W_l stored n_{l-1} x n_l = N x K
-            d.C = m->delta[l - 1]; d.ldc = m->dims[l - 1];
-            d.aux = a_prev; d.ldaux = m->dims[l - 1];
-            d.M = batch; d.N = m->dims[l - 1]; d.K = m->dims[l];
-            d.epilogue = EPI_DSIGMOID; d.alpha = 1.f; d.beta = 0.f;
-            const int rc = launch(m, d);
-            if (rc != TGEMM_OK) return rc;
-        }
-        if (update || (dW && dW[l - 1])) {
-            // dW_l = A_{l-1}^T D_l
-            GemmDesc d;
-            memset(&d, 0, sizeof d);
-            d.A = a_prev; d.lda = m->dims[l - 1]; d.a_kcontig = 0;           // stored K x M (batch x n_{l-1})
-            d.B = m->delta[l]; d.ldb = m->dims[l]; d.b_kcontig = 0;          // batch x n_l
-            d.M = m->dims[l - 1]; d.N = m->dims[l]; d.K = batch;
-            d.ldc = m->dims[l];
-            d.epilogue = EPI_AXPBY;
-            if (update) { d.C = m->W[l - 1]; d.alpha = -lr; d.beta = 1.f; }
-            else { d.C = (float*)dW[l - 1]; d.alpha = 1.f; d.beta = 0.f; }
-            const int rc = launch(m, d);
-            if (rc != TGEMM_OK) return rc;
-        }
+    for (int l = m->n_layers; l >= 1; --l) {
+        const int rc = backward_layer(m, l, dW ? (float*)dW[l - 1] : nullptr, update, lr);
+        if (rc != TGEMM_OK) return rc;
     }
     return TGEMM_OK;
 }
@@ -221,9 +577,16 @@ int backward(tgemm_mlp* m, void* const* dW, bool update, float lr)
 int check_batch(tgemm_mlp* m, const void* X, int64_t batch)
 {
     if (!m) return fail(TGEMM_EARG, "mlp: object is NULL");
-    if (!X || batch <= 0 || batch > ((int64_t)1 << 30)) return fail(TGEMM_EARG, "mlp: bad input or batch %lld", (long long)batch);
+    if (!X || batch <= 0 || batch > ((int64_t)1 << 28)) return fail(TGEMM_EARG, "mlp: bad input or batch %lld", (long long)batch);
     if (classify_pointer(X, m->ctx->device) != PTR_DEVICE) return fail(TGEMM_EARG, "mlp: X must be a device pointer");
     return TGEMM_OK;
+}
+
+void begin_call(tgemm_mlp* m)
+{
+    memset(&m->ctx->stats, 0, sizeof m->ctx->stats);
+    m->ctx->stats.in_core = m->ooc ? 0 : 1;
+    m->ctx->stats.n_slots = m->cache.n_slots;
 }
 
 }  // namespace
@@ -240,24 +603,30 @@ int mlp_create(tgemm_ctx* ctx, tgemm_mlp** out, int32_t n_layers, const int64_t*
     *out = nullptr;
     if (!ctx || !dims || !W || n_layers < 1 || n_layers > 64 || T <= 0)
         return fail(TGEMM_EARG, "mlp_create: bad argument");
-    if (dtype != TGEMM_F32) return fail(TGEMM_EARG, "mlp_create: only TGEMM_F32 is built so far");
+    if (dtype != TGEMM_F32 && dtype != TGEMM_BF16) return fail(TGEMM_EARG, "mlp_create: unknown dtype %d", dtype);
     for (int l = 0; l <= n_layers; ++l)
-        if (dims[l] <= 0 || dims[l] > ((int64_t)1 << 30)) return fail(TGEMM_EARG, "mlp_create: dims[%d] = %lld", l, (long long)dims[l]);
+        if (dims[l] <= 0 || dims[l] > ((int64_t)1 << 28)) return fail(TGEMM_EARG, "mlp_create: dims[%d] = %lld", l, (long long)dims[l]);
     TG_HIP(hipSetDevice(ctx->device));
+    int n_dev = 0, n_host = 0;
     for (int l = 0; l < n_layers; ++l) {
         if (!W[l]) return fail(TGEMM_EARG, "mlp_create: W[%d] is NULL", l);
         const PtrKind k = classify_pointer(W[l], ctx->device);
         if (k == PTR_PAGEABLE) return fail(TGEMM_EUNPINNED, "mlp_create: W[%d] is pageable host memory", l);
-        if (k != PTR_DEVICE) return fail(TGEMM_EARG, "mlp_create: host-resident weights (out-of-core MLP) are not built yet");
+        if (k == PTR_DEVICE) ++n_dev; else ++n_host;
     }
+    if (n_dev && n_host) return fail(TGEMM_EARG, "mlp_create: weights must be all device or all pinned host pointers");
+    if (n_host && hbm_budget == 0) return fail(TGEMM_EBUDGET, "mlp_create: host-resident weights need an hbm_budget");
     tgemm_mlp* m = new (std::nothrow) tgemm_mlp();
     if (!m) return fail(TGEMM_ENOMEM, "mlp_create: host allocation failed");
     m->ctx = ctx;
     m->n_layers = n_layers;
     m->dims.assign(dims, dims + n_layers + 1);
-    for (int l = 0; l < n_layers; ++l) m->W.push_back((float*)W[l]);
+    for (int l = 0; l < n_layers; ++l) m->W.push_back((char*)W[l]);
+    m->dtype = dtype;
+    m->es = dtype == TGEMM_BF16 ? 2 : 4;
     m->T = T;
     m->budget = hbm_budget;
+    m->ooc = n_host > 0;
     m->act.assign(n_layers + 1, nullptr);
     m->delta.assign(n_layers + 1, nullptr);
     *out = m;
@@ -268,7 +637,7 @@ int mlp_destroy(tgemm_mlp* m)
 {
     if (!m) return TGEMM_OK;
     (void)hipSetDevice(m->ctx->device);
-    (void)hipStreamSynchronize(m->ctx->streams[0]);
+    for (int s = 0; s < 4; ++s) (void)hipStreamSynchronize(m->ctx->streams[s]);
     free_workspaces(m);
     delete m;
     return TGEMM_OK;
@@ -279,18 +648,12 @@ int mlp_forward(tgemm_mlp* m, const void* X, int64_t batch, float* probs)
     int rc = check_batch(m, X, batch);
     if (rc != TGEMM_OK) return rc;
     const double t0 = now_ms();
-    memset(&m->ctx->stats, 0, sizeof m->ctx->stats);
     TG_HIP(hipSetDevice(m->ctx->device));
     if ((rc = ensure_workspaces(m, batch)) != TGEMM_OK) return rc;
-    if ((rc = forward(m, (const float*)X, batch)) != TGEMM_OK) return rc;
-    if (probs) {
-        // softmax needs labels only for the loss; a zero label vector is not available here, so
-        // the probabilities are produced by the same kernel with the row-loss output ignored
-        TG_HIP(hipMemsetAsync(m->row_loss, 0, (size_t)batch * 4, m->ctx->streams[0]));
-        if ((rc = softmax(m, (const int32_t*)m->row_loss, probs, false)) != TGEMM_OK) return rc;
-    }
-    TG_HIP(hipStreamSynchronize(m->ctx->streams[0]));
-    m->ctx->stats.in_core = 1;
+    begin_call(m);
+    if ((rc = forward(m, (const char*)X, batch)) != TGEMM_OK) return rc;
+    if (probs && (rc = softmax(m, nullptr, probs, false)) != TGEMM_OK) return rc;
+    if ((rc = sync_all(m)) != TGEMM_OK) return rc;
     m->ctx->stats.wall_ms = now_ms() - t0;
     return TGEMM_OK;
 }
@@ -300,14 +663,14 @@ int mlp_backward(tgemm_mlp* m, const int32_t* labels, void* const* dW, float* lo
     if (!m || !labels) return fail(TGEMM_EARG, "mlp_backward: NULL argument");
     if (m->batch <= 0) return fail(TGEMM_ESTATE, "mlp_backward: no forward pass precedes");
     const double t0 = now_ms();
-    memset(&m->ctx->stats, 0, sizeof m->ctx->stats);
     TG_HIP(hipSetDevice(m->ctx->device));
+    begin_call(m);
     int rc;
     if ((rc = softmax(m, labels, nullptr, true)) != TGEMM_OK) return rc;
     if ((rc = backward(m, dW, false, 0.f)) != TGEMM_OK) return rc;
     if ((rc = read_loss(m, loss)) != TGEMM_OK) return rc;
+    if ((rc = sync_all(m)) != TGEMM_OK) return rc;
     m->have_delta = true;
-    m->ctx->stats.in_core = 1;
     m->ctx->stats.wall_ms = now_ms() - t0;
     return TGEMM_OK;
 }
@@ -318,15 +681,15 @@ int mlp_step(tgemm_mlp* m, const void* X, const int32_t* labels, int64_t batch, 
     if (rc != TGEMM_OK) return rc;
     if (!labels) return fail(TGEMM_EARG, "mlp_step: labels is NULL");
     const double t0 = now_ms();
-    memset(&m->ctx->stats, 0, sizeof m->ctx->stats);
     TG_HIP(hipSetDevice(m->ctx->device));
     if ((rc = ensure_workspaces(m, batch)) != TGEMM_OK) return rc;
-    if ((rc = forward(m, (const float*)X, batch)) != TGEMM_OK) return rc;
+    begin_call(m);
+    if ((rc = forward(m, (const char*)X, batch)) != TGEMM_OK) return rc;
     if ((rc = softmax(m, labels, nullptr, true)) != TGEMM_OK) return rc;
     if ((rc = backward(m, nullptr, true, lr)) != TGEMM_OK) return rc;
     if ((rc = read_loss(m, loss)) != TGEMM_OK) return rc;
+    if ((rc = sync_all(m)) != TGEMM_OK) return rc;
     m->have_delta = true;
-    m->ctx->stats.in_core = 1;
     m->ctx->stats.wall_ms = now_ms() - t0;
     return TGEMM_OK;
 }
@@ -336,13 +699,13 @@ int mlp_read(tgemm_mlp* m, int32_t what, int32_t layer, void* dst, size_t bytes)
     if (!m || !dst) return fail(TGEMM_EARG, "mlp_read: NULL argument");
     if (m->batch <= 0) return fail(TGEMM_ESTATE, "mlp_read: no forward pass precedes");
     const int L = m->n_layers;
-    const float* src = nullptr;
+    const void* src = nullptr;
     size_t have = 0;
-    if (what == 0 && layer >= 1 && layer < L) { src = m->act[layer]; have = (size_t)m->batch * m->dims[layer] * 4; }
+    if (what == 0 && layer >= 1 && layer < L) { src = m->act[layer]; have = (size_t)m->batch * m->dims[layer] * m->es; }
     else if (what == 1) { src = m->logits; have = (size_t)m->batch * m->dims[L] * 4; }
     else if (what == 2 && layer >= 1 && layer <= L) {
         if (!m->have_delta) return fail(TGEMM_ESTATE, "mlp_read: no backward pass precedes");
-        src = m->delta[layer]; have = (size_t)m->batch * m->dims[layer] * 4;
+        src = m->delta[layer]; have = (size_t)m->batch * m->dims[layer] * m->es;
     }
     if (!src) return fail(TGEMM_EARG, "mlp_read: what=%d layer=%d", what, layer);
     if (bytes > have) return fail(TGEMM_EARG, "mlp_read: %zu bytes requested, matrix has %zu", bytes, have);
