@@ -57,11 +57,11 @@ struct LoaderKC {
             if (mn < mn_end && k < klim) {
                 const uint16_t* src = X + (int64_t)mn * ld + k;
                 if (vec_ok && k + 7 < klim) {
-                    v = *reinterpret_cast<const u32x4*>(src);
+                    v = gload<u32x4>(src);
                 } else {
 #pragma unroll
                     for (int e = 0; e < 8; ++e)
-                        if (k + e < klim) v[e >> 1] |= (uint32_t)src[e] << ((e & 1) * 16);
+                        if (k + e < klim) v[e >> 1] |= (uint32_t)gload<uint16_t>(src + e) << ((e & 1) * 16);
                 }
             }
             reg[p] = v;
@@ -102,11 +102,11 @@ struct LoaderMC {
                 if (k < klim && mn < mn_end) {
                     const uint16_t* src = X + (int64_t)k * ld + mn;
                     if (full) {
-                        v = *reinterpret_cast<const u32x2*>(src);
+                        v = gload<u32x2>(src);
                     } else {
 #pragma unroll
                         for (int e = 0; e < 4; ++e)
-                            if (mn + e < mn_end) v[e >> 1] |= (uint32_t)src[e] << ((e & 1) * 16);
+                            if (mn + e < mn_end) v[e >> 1] |= (uint32_t)gload<uint16_t>(src + e) << ((e & 1) * 16);
                     }
                 }
                 reg[p][r] = v;
@@ -287,7 +287,7 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_bf16(const GemmParams 
                 float o = acc[r][cc][v];
                 if (EPI == EPI_AXPBY) {
                     if (beta != 0.f) {
-                        const float cin = OUT_BF16 ? bf16_to_f32(Cb[idx]) : Cf[idx];
+                        const float cin = OUT_BF16 ? bf16_to_f32(gload<uint16_t>(Cb + idx)) : gload<float>(Cf + idx);
                         o = fmaf(alpha, o, beta * cin);
                     } else {
                         o = alpha * o;
@@ -295,11 +295,11 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_bf16(const GemmParams 
                 } else if (EPI == EPI_SIGMOID) {
                     o = 1.f / (1.f + __expf(-o));
                 } else if (EPI == EPI_DSIGMOID) {
-                    const float a = bf16_to_f32(aux[(int64_t)row * p.ldaux + col]);
+                    const float a = bf16_to_f32(gload<uint16_t>(aux + (int64_t)row * p.ldaux + col));
                     o = o * a * (1.f - a);
                 }
-                if (OUT_BF16) Cb[idx] = f32_to_bf16_rne(o);
-                else Cf[idx] = o;
+                if (OUT_BF16) gstore<uint16_t>(Cb + idx, f32_to_bf16_rne(o));
+                else gstore<float>(Cf + idx, o);
             }
         }
     }

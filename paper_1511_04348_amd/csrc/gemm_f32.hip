@@ -60,11 +60,11 @@ struct TileLoader {
                 if (mn < mn_end) {
                     const float* src = X + (int64_t)mn * ld + k;
                     if (vec_ok && k + 3 < klim) {
-                        v = *reinterpret_cast<const f32x4*>(src);
+                        v = gload<f32x4>(src);
                     } else {
 #pragma unroll
                         for (int e = 0; e < 4; ++e)
-                            if (k + e < klim) v[e] = src[e];
+                            if (k + e < klim) v[e] = gload<float>(src + e);
                     }
                 }
             } else {
@@ -74,11 +74,11 @@ struct TileLoader {
                 if (k < klim) {
                     const float* src = X + (int64_t)k * ld + mn;
                     if (vec_ok && mn + 3 < mn_end) {
-                        v = *reinterpret_cast<const f32x4*>(src);
+                        v = gload<f32x4>(src);
                     } else {
 #pragma unroll
                         for (int e = 0; e < 4; ++e)
-                            if (mn + e < mn_end) v[e] = src[e];
+                            if (mn + e < mn_end) v[e] = gload<float>(src + e);
                     }
                 }
             }
@@ -257,13 +257,13 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
             if (EPI == EPI_AXPBY) {
                 if (beta != 0.f) {
                     if (cvec) {
-                        const f32x4 cin = *reinterpret_cast<const f32x4*>(dst);
+                        const f32x4 cin = gload<f32x4>(dst);
 #pragma unroll
                         for (int cc = 0; cc < RB; ++cc) o[cc] = fmaf(alpha, o[cc], beta * cin[cc]);
                     } else {
 #pragma unroll
                         for (int cc = 0; cc < RB; ++cc)
-                            if (colb + cc < col_end) o[cc] = fmaf(alpha, o[cc], beta * dst[cc]);
+                            if (colb + cc < col_end) o[cc] = fmaf(alpha, o[cc], beta * gload<float>(dst + cc));
                     }
                 } else {
 #pragma unroll
@@ -277,7 +277,7 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
 #pragma unroll
                 for (int cc = 0; cc < RB; ++cc)
                     if (colb + cc < col_end) {
-                        const float a = ax[cc];
+                        const float a = gload<float>(ax + cc);
                         o[cc] = o[cc] * a * (1.f - a);
                     }
             }
@@ -285,11 +285,11 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
                 f32x4 ov;
 #pragma unroll
                 for (int cc = 0; cc < RB; ++cc) ov[cc & 3] = o[cc];
-                *reinterpret_cast<f32x4*>(dst) = ov;
+                gstore<f32x4>(dst, ov);
             } else {
 #pragma unroll
                 for (int cc = 0; cc < RB; ++cc)
-                    if (colb + cc < col_end) dst[cc] = o[cc];
+                    if (colb + cc < col_end) gstore<float>(dst + cc, o[cc]);
             }
         }
     }

@@ -64,4 +64,22 @@ inline hipError_t launch_tile_gemm(const GemmDesc& d, int dtype_bf16, hipStream_
     return dtype_bf16 ? launch_tile_gemm_bf16(d, stream) : launch_tile_gemm_f32(d, stream);
 }
 
+#ifdef __HIPCC__
+// Loads / stores through explicitly global (address space 1) pointers.  Operand pointers that come
+// out of a tile table are "generic" to the compiler, which would otherwise emit flat memory
+// instructions; those count against the LDS wait counter and stall the LDS reads behind every
+// outstanding prefetch.
+#define TG_GLOBAL __attribute__((address_space(1)))
+template <typename V, typename E>
+__device__ inline V gload(const E* p)
+{
+    return *reinterpret_cast<const TG_GLOBAL V*>((const TG_GLOBAL E*)p);
+}
+template <typename V, typename E>
+__device__ inline void gstore(E* p, const V& v)
+{
+    *reinterpret_cast<TG_GLOBAL V*>((TG_GLOBAL E*)p) = v;
+}
+#endif
+
 }  // namespace tg
