@@ -15,6 +15,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "gemm_kernel.h"
 
 namespace tg {
@@ -44,6 +46,23 @@ struct LoaderKC {
     static constexpr int UP = BMN * 8 / NT;
     static_assert((BMN * 8) % NT == 0, "tile must divide evenly over the threads");
     u32x4 reg[UP];
+    uint32_t off[UP];     // byte offset of unit p from the chunk origin (interior fast path)
+
+    __device__ inline void init(int64_t ld, int tid)
+    {
+#pragma unroll
+        for (int p = 0; p < UP; ++p) {
+            const int u = tid + p * NT;
+            off[p] = (uint32_t)(((int64_t)(u >> 3) * ld + ((u & 7) << 3)) * 2);
+        }
+    }
+    // interior tile, full chunk: no predicates, origin = element (mn0, kk)
+    __device__ inline void load_fast(const uint16_t* __restrict__ origin)
+    {
+        const char* base = reinterpret_cast<const char*>(origin);
+#pragma unroll
+        for (int p = 0; p < UP; ++p) reg[p] = gload<u32x4>(base + off[p]);
+    }
 
     __device__ inline void load(const uint16_t* __restrict__ X, int64_t ld, int mn0, int mn_end, int kk,
                                 int klim, bool vec_ok, int tid)
@@ -78,23 +97,47 @@ struct LoaderKC {
 };
 
 // ---- mn-contiguous source: rows are k, BMN contiguous mn ---------------------------------------
-// unit u -> (q = u % (BMN/4), kg = u / (BMN/4)): 8 k-rows (8 kg .. 8 kg + 7) x 4 mn (4 q .. 4 q + 3).
+// A unit is 8 k-rows (8 kg .. 8 kg + 7) x 4 mn (4 q .. 4 q + 3); a thread owns UP units that differ
+// in kg.  Thread bits 0-1 and 4.. select q, bits 2-3 (then the bits above q, then the unit index)
+// select kg: any 16 consecutive lanes hold 4 values of q and 4 of kg, which makes the four 16-byte
+// LDS row stores below bank-conflict free (row stride 9 bank quads), while the lanes of a wave
+// still cover 128 contiguous bytes of each k-row.
 template <int BMN, int NT>
 struct LoaderMC {
     static constexpr int Q = BMN / 4;
-    static constexpr int UP = Q * 8 / NT;
-    static_assert((Q * 8) % NT == 0 && UP >= 1, "tile must divide evenly over the threads");
+    static constexpr int QH = Q / 4;          // values of the high part of q
+    static constexpr int UP = Q * 8 / NT;     // units per thread
+    static constexpr int KG_T = 8 / UP;       // kg values covered by the thread index
+    static_assert(Q * 8 % NT == 0 && UP >= 1 && KG_T >= 4 && NT == 16 * QH * (KG_T / 4), "thread/unit mapping");
     u32x2 reg[UP][8];
+    uint32_t off0;        // byte offset of unit 0's first row from the chunk origin
+    int q, kg0;
+
+    __device__ inline void init(int64_t ld, int tid)
+    {
+        q = (tid & 3) | (((tid >> 4) & (QH - 1)) << 2);
+        kg0 = ((tid >> 2) & 3) | ((tid / (16 * QH)) << 2);
+        off0 = (uint32_t)(((int64_t)(kg0 << 3) * ld + (q << 2)) * 2);
+    }
+    // interior tile, full chunk: origin = element (k = kk, mn = mn0)
+    __device__ inline void load_fast(const uint16_t* __restrict__ origin, int64_t ld)
+    {
+        const char* base = reinterpret_cast<const char*>(origin);
+#pragma unroll
+        for (int p = 0; p < UP; ++p)
+#pragma unroll
+            for (int r = 0; r < 8; ++r)
+                reg[p][r] = gload<u32x2>(base + (size_t)(p * KG_T * 8 + r) * (size_t)ld * 2 + off0);
+    }
 
     __device__ inline void load(const uint16_t* __restrict__ X, int64_t ld, int mn0, int mn_end, int kk,
                                 int klim, bool vec_ok, int tid)
     {
+        const int mn = mn0 + (q << 2);
+        const bool full = vec_ok && (mn + 3 < mn_end);
 #pragma unroll
         for (int p = 0; p < UP; ++p) {
-            const int u = tid + p * NT;
-            const int mn = mn0 + ((u % Q) << 2);
-            const int kb = kk + ((u / Q) << 3);
-            const bool full = vec_ok && (mn + 3 < mn_end);
+            const int kb = kk + ((kg0 + p * KG_T) << 3);
 #pragma unroll
             for (int r = 0; r < 8; ++r) {
                 u32x2 v = {0u, 0u};
@@ -116,18 +159,17 @@ struct LoaderMC {
     // 8 x 4 block of 16-bit elements -> four rows of 8 k
     __device__ inline void store(uint32_t* __restrict__ S, int tid) const
     {
+        const int mn = q << 2;
 #pragma unroll
         for (int p = 0; p < UP; ++p) {
-            const int u = tid + p * NT;
-            const int mn = (u % Q) << 2;
-            const int kg = u / Q;
+            const int kg = kg0 + p * KG_T;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 u32x4 o;
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const uint32_t x = reg[p][2 * q][e >> 1], y = reg[p][2 * q + 1][e >> 1];
-                    o[q] = (e & 1) ? ((x >> 16) | (y & 0xffff0000u)) : ((x & 0xffffu) | (y << 16));
+                for (int w = 0; w < 4; ++w) {
+                    const uint32_t x = reg[p][2 * w][e >> 1], y = reg[p][2 * w + 1][e >> 1];
+                    o[w] = (e & 1) ? ((x >> 16) | (y & 0xffff0000u)) : ((x & 0xffffu) | (y << 16));
                 }
                 *reinterpret_cast<u32x4*>(&S[(mn + e) * ROW_W + (kg << 2)]) = o;
             }
@@ -135,11 +177,23 @@ struct LoaderMC {
     }
 };
 
+template <int BMN, int NT>
+__device__ inline void fast_load(LoaderKC<BMN, NT>& l, const uint16_t* X, int64_t ld, int mn0, int kk)
+{
+    l.load_fast(X + (int64_t)mn0 * ld + kk);
+}
+template <int BMN, int NT>
+__device__ inline void fast_load(LoaderMC<BMN, NT>& l, const uint16_t* X, int64_t ld, int mn0, int kk)
+{
+    l.load_fast(X + (int64_t)kk * ld + mn0, ld);
+}
+
 template <int BMN, int NT, bool KC> struct PickLoader { typedef LoaderKC<BMN, NT> type; };
 template <int BMN, int NT> struct PickLoader<BMN, NT, false> { typedef LoaderMC<BMN, NT> type; };
 
 // ---- the kernel ---------------------------------------------------------------------------------
-template <int RA, int RB, int WM, int WN, bool A_KC, bool B_KC, int EPI, bool OUT_BF16>
+// DEPTH = chunks in flight in registers in the interior (fast) k loop.
+template <int RA, int RB, int WM, int WN, int DEPTH, bool A_KC, bool B_KC, int EPI, bool OUT_BF16>
 __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_bf16(const GemmParams p)
 {
     constexpr int WTM = 32 * RA, WTN = 32 * RB;
@@ -191,55 +245,22 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_bf16(const GemmParams 
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[r][c][v] = 0.f;
 
-    LA la;
-    LB lb;
+    LA la[DEPTH];
+    LB lb[DEPTH];
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) {
+        la[d].init(p.lda, tid);
+        lb[d].init(p.ldb, tid);
+    }
     const int n_chunks = p.n_chunks;
     const int cps = p.chunks_per_step;
-    auto chunk_range = [&](int c, int& kk, int& klim) {
-        const int step = c / cps;
-        kk = step * p.T + (c - step * cps) * BK;
-        klim = min(p.K, (step + 1) * p.T);
-        return step;
-    };
-    // B chunk source: the dense matrix, or the tile of (k-step, task column) from the tile table,
-    // addressed with coordinates local to that tile
-    auto b_source = [&](int step, int kk, int klim, const uint16_t*& base, int& mn0, int& mn_end, int& k0, int& k1) {
-        if (p.b_tiles) {
-            base = reinterpret_cast<const uint16_t*>(p.b_tiles[(int64_t)step * p.n_j + tj]);
-            mn0 = col0 - tj * p.T; mn_end = col_end - tj * p.T;
-            k0 = kk - step * p.T; k1 = klim - step * p.T;
-        } else {
-            base = B; mn0 = col0; mn_end = col_end; k0 = kk; k1 = klim;
-        }
-    };
-
-    if (n_chunks > 0) {
-        int kk, klim, bm0, bm1, bk0, bk1;
-        const uint16_t* bsrc;
-        const int step = chunk_range(0, kk, klim);
-        b_source(step, kk, klim, bsrc, bm0, bm1, bk0, bk1);
-        la.load(A, p.lda, row0, row_end, kk, klim, p.vec_a, tid);
-        lb.load(bsrc, p.ldb, bm0, bm1, bk0, bk1, p.vec_b, tid);
-        la.store(As, tid);
-        lb.store(Bs, tid);
-    }
-    __syncthreads();
 
     // lane's LDS read base: row (wave tile row / col + li), k offset 8 * lh elements = 4 * lh words
     const int a_off = (wm * WTM + li) * ROW_W + lh * 4;
     const int b_off = (wn * WTN + li) * ROW_W + lh * 4;
 
-    for (int c = 0; c < n_chunks; ++c) {
-        const int st = c & 1;
-        const bool more = (c + 1 < n_chunks);
-        if (more) {
-            int kk, klim, bm0, bm1, bk0, bk1;
-            const uint16_t* bsrc;
-            const int step = chunk_range(c + 1, kk, klim);
-            b_source(step, kk, klim, bsrc, bm0, bm1, bk0, bk1);
-            la.load(A, p.lda, row0, row_end, kk, klim, p.vec_a, tid);
-            lb.load(bsrc, p.ldb, bm0, bm1, bk0, bk1, p.vec_b, tid);
-        }
+    // one 64-k chunk from LDS stage st
+    auto compute = [&](int st) {
         const uint32_t* as = As + st * STAGE_A + a_off;
         const uint32_t* bs = Bs + st * STAGE_B + b_off;
 #pragma unroll
@@ -257,11 +278,122 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_bf16(const GemmParams 
                 for (int cc = 0; cc < RB; ++cc)
                     acc[r][cc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[r], bfr[cc], acc[r][cc], 0, 0, 0);
         }
-        if (more) {
-            la.store(As + (st ^ 1) * STAGE_A, tid);
-            lb.store(Bs + (st ^ 1) * STAGE_B, tid);
+    };
+
+    int ld_step = 0, ld_within = 0;      // chunk the next issue fetches
+    const int bcol = col0 - tj * p.T;    // column inside the task's tile column (tile tables)
+
+    if (p.fast_a && p.fast_b && p.fast_k && (row0 + BM <= row_end) && (col0 + BN <= col_end)) {
+        // ---- interior macro tile, every chunk a full 64 k: unpredicated loads from a running
+        // origin plus fixed per-thread offsets; DEPTH chunks in flight in registers.
+        const uint16_t* a_org = A + (A_KC ? (int64_t)row0 * p.lda : (int64_t)row0);
+        const uint16_t* b_org = B + (B_KC ? (int64_t)col0 * p.ldb : (int64_t)col0);
+        const int64_t a_adv = A_KC ? (int64_t)BK : (int64_t)BK * p.lda;
+        const int64_t b_adv = B_KC ? (int64_t)BK : (int64_t)BK * p.ldb;
+        auto issue = [&](LA& sa, LB& sb) {
+            fast_load(sa, a_org, p.lda, 0, 0);
+            a_org += a_adv;
+            if (p.b_tiles && ld_within == 0) {
+                const uint16_t* t = reinterpret_cast<const uint16_t*>(p.b_tiles[(int64_t)ld_step * p.n_j + tj]);
+                b_org = t + (B_KC ? (int64_t)bcol * p.ldb : (int64_t)bcol);
+            }
+            fast_load(sb, b_org, p.ldb, 0, 0);
+            b_org += b_adv;
+            if (++ld_within == cps) { ld_within = 0; ++ld_step; }
+        };
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d)
+            if (d < n_chunks) issue(la[d], lb[d]);
+        if (n_chunks > 0) {
+            la[0].store(As, tid);
+            lb[0].store(Bs, tid);
         }
         __syncthreads();
+        // L2 prefetch.  The workgroups that run side by side on an XCD share this tile's A row
+        // panel (8 of them) and B column panel (4), and they reach each new chunk together, so
+        // every chunk would start with a burst of first-touch misses that all of them wait for.
+        // Each workgroup therefore touches, two chunks ahead, its slice of the lines of the
+        // shared panels (one 4-byte load per line, 96 threads): the fill then overlaps two
+        // multiply phases and the real loads find their lines in L2.  The value is never used;
+        // the empty asm keeps the load alive and is placed where its data has long arrived.
+        // A chunk of either layout is BM (BN) cache lines of 128 bytes: one per row when k is
+        // contiguous, BM / 64 per k-row otherwise.  Of the A lines this workgroup takes those
+        // congruent to its tile column modulo 8, of the B lines those congruent to its tile row
+        // modulo 4; every address lies inside the chunk after the one just issued, which the
+        // caller has checked to exist.
+        uint32_t pf[2] = {0u, 0u};
+        constexpr int PF_A = BM / 8, PF_B = BN / 4;
+        static_assert(PF_A + PF_B <= NT, "prefetch threads");
+        auto prefetch = [&](uint32_t& dst) {
+            // a_org / b_org already point at the chunk after the one just issued
+            if (tid < PF_A) {
+                const int l = 8 * tid + (sj & 7);                       // < BM
+                constexpr int SEG = BM / 64;                            // lines per k-row (m-contiguous)
+                const uint16_t* q = A_KC ? a_org + (int64_t)l * p.lda
+                                         : a_org + (int64_t)(l / SEG) * p.lda + (l % SEG) * 64;
+                dst = gload<uint32_t>(q);
+            } else if (tid < PF_A + PF_B && !(p.b_tiles && ld_within == 0)) {
+                const int l = 4 * (tid - PF_A) + (si & 3);              // < BN
+                constexpr int SEG = BN / 64;
+                const uint16_t* q = B_KC ? b_org + (int64_t)l * p.ldb
+                                         : b_org + (int64_t)(l / SEG) * p.ldb + (l % SEG) * 64;
+                dst = gload<uint32_t>(q);
+            }
+        };
+        // iteration c: refill the register set that held chunk c with chunk c + DEPTH, multiply
+        // chunk c, move chunk c + 1 (issued DEPTH - 1 iterations ago) into the other LDS stage
+        constexpr int UNROLL = DEPTH > 2 ? DEPTH : 2;
+        for (int c0 = 0; c0 < n_chunks; c0 += UNROLL) {
+#pragma unroll
+            for (int d = 0; d < UNROLL; ++d) {
+                const int c = c0 + d;
+                if (c < n_chunks) {
+                    if (c + DEPTH < n_chunks) issue(la[d % DEPTH], lb[d % DEPTH]);
+                    if (DEPTH == 1 && c + 2 < n_chunks) prefetch(pf[d & 1]);
+                    compute(c & 1);
+                    if (c + 1 < n_chunks) {
+                        la[(d + 1) % DEPTH].store(As + ((c + 1) & 1) * STAGE_A, tid);
+                        lb[(d + 1) % DEPTH].store(Bs + ((c + 1) & 1) * STAGE_B, tid);
+                    }
+                    __syncthreads();
+                    if (DEPTH == 1) asm volatile("" ::"v"(pf[(d + 1) & 1]));
+                }
+            }
+        }
+    } else {
+        // ---- edge tiles and ragged k-steps: predicated, zero-filling loaders, one chunk in flight
+        LA& sa = la[0];
+        LB& sb = lb[0];
+        auto issue = [&]() {
+            const int kk = ld_step * p.T + ld_within * BK;
+            const int klim = min(p.K, (ld_step + 1) * p.T);
+            sa.load(A, p.lda, row0, row_end, kk, klim, p.vec_a, tid);
+            const uint16_t* bsrc = B;
+            int bm0 = col0, bm1 = col_end, bk0 = kk, bk1 = klim;
+            if (p.b_tiles) {
+                bsrc = reinterpret_cast<const uint16_t*>(p.b_tiles[(int64_t)ld_step * p.n_j + tj]);
+                bm0 = bcol; bm1 = col_end - tj * p.T;
+                bk0 = kk - ld_step * p.T; bk1 = klim - ld_step * p.T;
+            }
+            sb.load(bsrc, p.ldb, bm0, bm1, bk0, bk1, p.vec_b, tid);
+            if (++ld_within == cps) { ld_within = 0; ++ld_step; }
+        };
+        if (n_chunks > 0) {
+            issue();
+            sa.store(As, tid);
+            sb.store(Bs, tid);
+        }
+        __syncthreads();
+        for (int c = 0; c < n_chunks; ++c) {
+            const bool more = (c + 1 < n_chunks);
+            if (more) issue();
+            compute(c & 1);
+            if (more) {
+                sa.store(As + ((c + 1) & 1) * STAGE_A, tid);
+                sb.store(Bs + ((c + 1) & 1) * STAGE_B, tid);
+            }
+            __syncthreads();
+        }
     }
 
     // -- epilogue.  acc[r][cc][v] is element (row, col) of the wave tile with
@@ -312,11 +444,11 @@ struct Cfg {
     static constexpr size_t LDS = 2 * (size_t)(BM + BN) * ROW_W * 4;
 };
 
-template <int RA, int RB, int WM, int WN, bool A_KC, bool B_KC, int EPI, bool OB>
+template <int RA, int RB, int WM, int WN, int DEPTH, bool A_KC, bool B_KC, int EPI, bool OB>
 static hipError_t launch_one(const GemmParams& p, int grid, hipStream_t stream)
 {
     typedef Cfg<RA, RB, WM, WN> C;
-    auto kern = tile_gemm_bf16<RA, RB, WM, WN, A_KC, B_KC, EPI, OB>;
+    auto kern = tile_gemm_bf16<RA, RB, WM, WN, DEPTH, A_KC, B_KC, EPI, OB>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -328,7 +460,7 @@ static hipError_t launch_one(const GemmParams& p, int grid, hipStream_t stream)
     return hipGetLastError();
 }
 
-template <int RA, int RB, int WM, int WN>
+template <int RA, int RB, int WM, int WN, int DEPTH>
 static hipError_t launch_cfg(GemmParams& p, const GemmDesc& d, hipStream_t stream)
 {
     typedef Cfg<RA, RB, WM, WN> C;
@@ -352,7 +484,7 @@ static hipError_t launch_cfg(GemmParams& p, const GemmDesc& d, hipStream_t strea
     const int64_t last_k = d.K - (n_k - 1) * T;
     p.n_chunks = (int)((n_k - 1) * p.chunks_per_step + (last_k + BK - 1) / BK);
 
-#define TGB_LAUNCH(AK, BKC, E, OB) return launch_one<RA, RB, WM, WN, AK, BKC, E, OB>(p, (int)grid, stream)
+#define TGB_LAUNCH(AK, BKC, E, OB) return launch_one<RA, RB, WM, WN, DEPTH, AK, BKC, E, OB>(p, (int)grid, stream)
 #define TGB_EPI(AK, BKC)                                                            \
     if (d.epilogue == EPI_AXPBY && !d.out_bf16) { TGB_LAUNCH(AK, BKC, EPI_AXPBY, false); }    \
     if (d.epilogue == EPI_AXPBY && d.out_bf16) { TGB_LAUNCH(AK, BKC, EPI_AXPBY, true); }      \
@@ -391,6 +523,11 @@ hipError_t launch_tile_gemm_bf16(const GemmDesc& d, hipStream_t stream)
     p.vec_a = ok(d.A, d.lda, d.a_kcontig != 0);
     p.vec_b = ok(d.B, d.ldb, d.b_kcontig != 0);
     p.vec_c = false;
+    // the unpredicated load path keeps per-thread byte offsets in 32 bits
+    auto off32 = [](int64_t ld) { return 256 * ld * 2 + 4096 < ((int64_t)1 << 31); };
+    p.fast_a = p.vec_a && off32(d.lda);
+    p.fast_b = p.vec_b && off32(d.ldb);
+    p.fast_k = (d.K % bf::BK == 0) && (T % bf::BK == 0 || T >= d.K);   // every chunk is a full 64 k
     GemmDesc dd = d;
     dd.T = (int32_t)T;
     int cfg = d.config;
@@ -409,8 +546,8 @@ hipError_t launch_tile_gemm_bf16(const GemmDesc& d, hipStream_t stream)
         const double c2 = cost(tiles(128, 128), 512, 0.6);
         cfg = c3 <= c2 ? 3 : 2;
     }
-    if (cfg == 3) return bf::launch_cfg<2, 4, 4, 2>(p, dd, stream);   // 256 x 256, 512 threads
-    return bf::launch_cfg<2, 2, 2, 2>(p, dd, stream);                  // 128 x 128, 256 threads
+    if (cfg == 3) return bf::launch_cfg<2, 4, 4, 2, 1>(p, dd, stream);   // 256 x 256, 8 waves of 64 x 128
+    return bf::launch_cfg<2, 2, 2, 2, 1>(p, dd, stream);                  // 128 x 128, 4 waves of 64 x 64
 }
 
 }  // namespace tg

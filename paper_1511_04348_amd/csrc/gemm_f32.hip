@@ -19,6 +19,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "gemm_kernel.h"
 
 namespace tg {
@@ -84,6 +86,27 @@ struct TileLoader {
             }
             reg[p] = v;
         }
+    }
+
+    // Full-chunk fast path: per-thread byte offsets from the chunk origin (element (mn0, kk)),
+    // computed once, and unpredicated 16-byte loads.  On an edge tile only `valid` (>= 4) of the
+    // BMN rows / columns exist: units beyond them are clamped onto the last valid ones, so every
+    // address stays inside the matrix.  What they load lands in rows / columns of the product
+    // that the epilogue never stores, and cannot reach any other element.
+    __device__ static inline void init_offsets(uint32_t (&off)[UP], int64_t ld, int valid, int tid)
+    {
+#pragma unroll
+        for (int p = 0; p < UP; ++p) {
+            const int u = tid + p * NT;
+            if (KC) off[p] = (uint32_t)(((int64_t)min(u >> 2, valid - 1) * ld + ((u & 3) << 2)) * 4);
+            else off[p] = (uint32_t)(((int64_t)(u / (BMN / 4)) * ld + min((u % (BMN / 4)) << 2, valid - 4)) * 4);
+        }
+    }
+    __device__ static inline void load_fast(f32x4 (&reg)[UP], const uint32_t (&off)[UP], const float* __restrict__ origin)
+    {
+        const char* base = reinterpret_cast<const char*>(origin);
+#pragma unroll
+        for (int p = 0; p < UP; ++p) reg[p] = gload<f32x4>(base + off[p]);
     }
 
     // registers -> LDS stage (layout [BK][BMN + PAD])
@@ -166,54 +189,13 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
             for (int v = 0; v < 16; ++v) acc[r][c][v] = 0.f;
 
     f32x4 ra[LA::UP], rb[LB::UP];
-
     const int n_chunks = p.n_chunks;
     const int cps = p.chunks_per_step;
-
-    auto chunk_range = [&](int c, int& kk, int& klim) {
-        const int step = c / cps;
-        kk = step * p.T + (c - step * cps) * BK;
-        klim = min(p.K, (step + 1) * p.T);
-        return step;
-    };
-    // B chunk source: the dense matrix, or the tile of (k-step, task column) from the tile table,
-    // addressed with coordinates local to that tile
-    auto b_source = [&](int step, int kk, int klim, const float*& base, int& mn0, int& mn_end, int& k0, int& k1) {
-        if (p.b_tiles) {
-            base = reinterpret_cast<const float*>(p.b_tiles[(int64_t)step * p.n_j + tj]);
-            mn0 = col0 - tj * p.T; mn_end = col_end - tj * p.T;
-            k0 = kk - step * p.T; k1 = klim - step * p.T;
-        } else {
-            base = B; mn0 = col0; mn_end = col_end; k0 = kk; k1 = klim;
-        }
-    };
-
-    if (n_chunks > 0) {
-        int kk, klim, bm0, bm1, bk0, bk1;
-        const float* bsrc;
-        const int step = chunk_range(0, kk, klim);
-        b_source(step, kk, klim, bsrc, bm0, bm1, bk0, bk1);
-        LA::load(ra, A, p.lda, row0, row_end, kk, klim, p.vec_a, tid);
-        LB::load(rb, bsrc, p.ldb, bm0, bm1, bk0, bk1, p.vec_b, tid);
-        LA::store(ra, As, tid);
-        LB::store(rb, Bs, tid);
-    }
-    __syncthreads();
-
     const int a_off = wm * WTM + RA * li;
     const int b_off = wn * WTN + RB * li;
 
-    for (int c = 0; c < n_chunks; ++c) {
-        const int st = c & 1;
-        const bool more = (c + 1 < n_chunks);
-        if (more) {
-            int kk, klim, bm0, bm1, bk0, bk1;
-            const float* bsrc;
-            const int step = chunk_range(c + 1, kk, klim);
-            b_source(step, kk, klim, bsrc, bm0, bm1, bk0, bk1);
-            LA::load(ra, A, p.lda, row0, row_end, kk, klim, p.vec_a, tid);
-            LB::load(rb, bsrc, p.ldb, bm0, bm1, bk0, bk1, p.vec_b, tid);
-        }
+    // one 16-k chunk from LDS stage st
+    auto compute = [&](int st) {
         const float* as = As + st * STAGE_A + lh * LDA_S + a_off;
         const float* bs = Bs + st * STAGE_B + lh * LDB_S + b_off;
 #pragma unroll
@@ -227,11 +209,82 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
                     acc[r][cc] = __builtin_amdgcn_mfma_f32_32x32x2f32(vget<RA>(a, r), vget<RB>(b, cc),
                                                                       acc[r][cc], 0, 0, 0);
         }
-        if (more) {
-            LA::store(ra, As + (st ^ 1) * STAGE_A, tid);
-            LB::store(rb, Bs + (st ^ 1) * STAGE_B, tid);
+    };
+
+    int ld_step = 0, ld_within = 0;      // chunk the next issue fetches
+    const int bcol = col0 - tj * p.T;    // column inside the task's tile column (tile tables)
+
+    const int a_valid = min(BM, row_end - row0), b_valid = min(BN, col_end - col0);
+    if (p.fast_a && p.fast_b && p.fast_k && a_valid >= 4 && b_valid >= 4 && (A_KC || a_valid % 4 == 0) &&
+        (B_KC || b_valid % 4 == 0)) {
+        // ---- every chunk a full 16 k: unpredicated loads from a running origin plus fixed
+        // per-thread offsets (clamped into the tile's valid extent on edge tiles)
+        uint32_t offa[LA::UP], offb[LB::UP];
+        LA::init_offsets(offa, p.lda, a_valid, tid);
+        LB::init_offsets(offb, p.ldb, b_valid, tid);
+        const float* a_org = A + (A_KC ? (int64_t)row0 * p.lda : (int64_t)row0);
+        const float* b_org = B + (B_KC ? (int64_t)col0 * p.ldb : (int64_t)col0);
+        const int64_t a_adv = A_KC ? (int64_t)BK : (int64_t)BK * p.lda;
+        const int64_t b_adv = B_KC ? (int64_t)BK : (int64_t)BK * p.ldb;
+        auto issue = [&]() {
+            LA::load_fast(ra, offa, a_org);
+            a_org += a_adv;
+            if (p.b_tiles && ld_within == 0) {
+                const float* t = reinterpret_cast<const float*>(p.b_tiles[(int64_t)ld_step * p.n_j + tj]);
+                b_org = t + (B_KC ? (int64_t)bcol * p.ldb : (int64_t)bcol);
+            }
+            LB::load_fast(rb, offb, b_org);
+            b_org += b_adv;
+            if (++ld_within == cps) { ld_within = 0; ++ld_step; }
+        };
+        if (n_chunks > 0) {
+            issue();
+            LA::store(ra, As, tid);
+            LB::store(rb, Bs, tid);
         }
         __syncthreads();
+        for (int c = 0; c < n_chunks; ++c) {
+            const bool more = (c + 1 < n_chunks);
+            if (more) issue();
+            compute(c & 1);
+            if (more) {
+                LA::store(ra, As + ((c + 1) & 1) * STAGE_A, tid);
+                LB::store(rb, Bs + ((c + 1) & 1) * STAGE_B, tid);
+            }
+            __syncthreads();
+        }
+    } else {
+        // ---- edge tiles and ragged k-steps: predicated, zero-filling loaders
+        auto issue = [&]() {
+            const int kk = ld_step * p.T + ld_within * BK;
+            const int klim = min(p.K, (ld_step + 1) * p.T);
+            LA::load(ra, A, p.lda, row0, row_end, kk, klim, p.vec_a, tid);
+            const float* bsrc = B;
+            int bm0 = col0, bm1 = col_end, bk0 = kk, bk1 = klim;
+            if (p.b_tiles) {
+                bsrc = reinterpret_cast<const float*>(p.b_tiles[(int64_t)ld_step * p.n_j + tj]);
+                bm0 = bcol; bm1 = col_end - tj * p.T;
+                bk0 = kk - ld_step * p.T; bk1 = klim - ld_step * p.T;
+            }
+            LB::load(rb, bsrc, p.ldb, bm0, bm1, bk0, bk1, p.vec_b, tid);
+            if (++ld_within == cps) { ld_within = 0; ++ld_step; }
+        };
+        if (n_chunks > 0) {
+            issue();
+            LA::store(ra, As, tid);
+            LB::store(rb, Bs, tid);
+        }
+        __syncthreads();
+        for (int c = 0; c < n_chunks; ++c) {
+            const bool more = (c + 1 < n_chunks);
+            if (more) issue();
+            compute(c & 1);
+            if (more) {
+                LA::store(ra, As + ((c + 1) & 1) * STAGE_A, tid);
+                LB::store(rb, Bs + ((c + 1) & 1) * STAGE_B, tid);
+            }
+            __syncthreads();
+        }
     }
 
     // -- epilogue.  acc[r][cc][v] is element (row, col) of the wave tile with
@@ -404,6 +457,11 @@ hipError_t launch_tile_gemm_f32(const GemmDesc& d, hipStream_t stream)
     p.vec_a = t4 && al16(d.A) && (d.lda % 4 == 0);
     p.vec_b = t4 && al16(d.B) && (d.ldb % 4 == 0);
     p.vec_c = t4 && al16(d.C) && (d.ldc % 4 == 0);
+    // the unpredicated load path keeps per-thread byte offsets in 32 bits and needs full chunks
+    auto off32 = [](int64_t ld) { return 256 * ld * 4 + 4096 < ((int64_t)1 << 31); };
+    p.fast_a = p.vec_a && off32(d.lda);
+    p.fast_b = p.vec_b && off32(d.ldb);
+    p.fast_k = (d.K % BK == 0) && (T % BK == 0 || T >= d.K);
     GemmDesc dd = d;
     dd.T = (int32_t)T;
     switch (pick_config(dd)) {

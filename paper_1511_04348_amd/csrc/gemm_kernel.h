@@ -50,6 +50,8 @@ struct GemmParams {
     int n_chunks;               // BK-chunks over all k-steps
     float alpha, beta;
     bool vec_a, vec_b, vec_c;   // 16-byte vector access is legal for this operand
+    bool fast_a, fast_b;        // interior tiles may use the unpredicated, 32-bit-offset load path
+    bool fast_k;                // every k chunk is full (no ragged k-step tails)
     const void* const* b_tiles; // see GemmDesc
     void* const* c_tiles;
 };
