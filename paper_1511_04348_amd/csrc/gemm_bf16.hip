@@ -48,15 +48,18 @@ struct LoaderKC {
     u32x4 reg[UP];
     uint32_t off[UP];     // byte offset of unit p from the chunk origin (interior fast path)
 
-    __device__ inline void init(int64_t ld, int tid)
+    // `valid` (>= 4) of the BMN rows exist on an edge tile: rows beyond them are clamped onto the
+    // last valid one, so every address stays inside the matrix; what they load only reaches rows /
+    // columns of the product that the epilogue never stores.
+    __device__ inline void init(int64_t ld, int valid, int tid)
     {
 #pragma unroll
         for (int p = 0; p < UP; ++p) {
             const int u = tid + p * NT;
-            off[p] = (uint32_t)(((int64_t)(u >> 3) * ld + ((u & 7) << 3)) * 2);
+            off[p] = (uint32_t)(((int64_t)min(u >> 3, valid - 1) * ld + ((u & 7) << 3)) * 2);
         }
     }
-    // interior tile, full chunk: no predicates, origin = element (mn0, kk)
+    // full chunk: no predicates, origin = element (mn0, kk)
     __device__ inline void load_fast(const uint16_t* __restrict__ origin)
     {
         const char* base = reinterpret_cast<const char*>(origin);
@@ -113,13 +116,15 @@ struct LoaderMC {
     uint32_t off0;        // byte offset of unit 0's first row from the chunk origin
     int q, kg0;
 
-    __device__ inline void init(int64_t ld, int tid)
+    // `valid` (>= 4, a multiple of 4) of the BMN columns exist on an edge tile: units beyond them
+    // are clamped onto the last valid four.
+    __device__ inline void init(int64_t ld, int valid, int tid)
     {
         q = (tid & 3) | (((tid >> 4) & (QH - 1)) << 2);
         kg0 = ((tid >> 2) & 3) | ((tid / (16 * QH)) << 2);
-        off0 = (uint32_t)(((int64_t)(kg0 << 3) * ld + (q << 2)) * 2);
+        off0 = (uint32_t)(((int64_t)(kg0 << 3) * ld + min(q << 2, valid - 4)) * 2);
     }
-    // interior tile, full chunk: origin = element (k = kk, mn = mn0)
+    // full chunk: origin = element (k = kk, mn = mn0)
     __device__ inline void load_fast(const uint16_t* __restrict__ origin, int64_t ld)
     {
         const char* base = reinterpret_cast<const char*>(origin);
@@ -247,10 +252,11 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_bf16(const GemmParams 
 
     LA la[DEPTH];
     LB lb[DEPTH];
+    const int a_valid = min(BM, row_end - row0), b_valid = min(BN, col_end - col0);
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d) {
-        la[d].init(p.lda, tid);
-        lb[d].init(p.ldb, tid);
+        la[d].init(p.lda, max(a_valid, 4), tid);
+        lb[d].init(p.ldb, max(b_valid, 4), tid);
     }
     const int n_chunks = p.n_chunks;
     const int cps = p.chunks_per_step;
@@ -283,9 +289,11 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_bf16(const GemmParams 
     int ld_step = 0, ld_within = 0;      // chunk the next issue fetches
     const int bcol = col0 - tj * p.T;    // column inside the task's tile column (tile tables)
 
-    if (p.fast_a && p.fast_b && p.fast_k && (row0 + BM <= row_end) && (col0 + BN <= col_end)) {
-        // ---- interior macro tile, every chunk a full 64 k: unpredicated loads from a running
-        // origin plus fixed per-thread offsets; DEPTH chunks in flight in registers.
+    if (p.fast_a && p.fast_b && p.fast_k && a_valid >= 4 && b_valid >= 4 && (A_KC || a_valid % 4 == 0) &&
+        (B_KC || b_valid % 4 == 0)) {
+        // ---- every chunk a full 64 k: unpredicated loads from a running origin plus fixed
+        // per-thread offsets (clamped into the tile's valid extent on edge tiles); DEPTH chunks in
+        // flight in registers.
         const uint16_t* a_org = A + (A_KC ? (int64_t)row0 * p.lda : (int64_t)row0);
         const uint16_t* b_org = B + (B_KC ? (int64_t)col0 * p.ldb : (int64_t)col0);
         const int64_t a_adv = A_KC ? (int64_t)BK : (int64_t)BK * p.lda;
@@ -309,54 +317,20 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_bf16(const GemmParams 
             lb[0].store(Bs, tid);
         }
         __syncthreads();
-        // L2 prefetch.  The workgroups that run side by side on an XCD share this tile's A row
-        // panel (8 of them) and B column panel (4), and they reach each new chunk together, so
-        // every chunk would start with a burst of first-touch misses that all of them wait for.
-        // Each workgroup therefore touches, two chunks ahead, its slice of the lines of the
-        // shared panels (one 4-byte load per line, 96 threads): the fill then overlaps two
-        // multiply phases and the real loads find their lines in L2.  The value is never used;
-        // the empty asm keeps the load alive and is placed where its data has long arrived.
-        // A chunk of either layout is BM (BN) cache lines of 128 bytes: one per row when k is
-        // contiguous, BM / 64 per k-row otherwise.  Of the A lines this workgroup takes those
-        // congruent to its tile column modulo 8, of the B lines those congruent to its tile row
-        // modulo 4; every address lies inside the chunk after the one just issued, which the
-        // caller has checked to exist.
-        uint32_t pf[2] = {0u, 0u};
-        constexpr int PF_A = BM / 8, PF_B = BN / 4;
-        static_assert(PF_A + PF_B <= NT, "prefetch threads");
-        auto prefetch = [&](uint32_t& dst) {
-            // a_org / b_org already point at the chunk after the one just issued
-            if (tid < PF_A) {
-                const int l = 8 * tid + (sj & 7);                       // < BM
-                constexpr int SEG = BM / 64;                            // lines per k-row (m-contiguous)
-                const uint16_t* q = A_KC ? a_org + (int64_t)l * p.lda
-                                         : a_org + (int64_t)(l / SEG) * p.lda + (l % SEG) * 64;
-                dst = gload<uint32_t>(q);
-            } else if (tid < PF_A + PF_B && !(p.b_tiles && ld_within == 0)) {
-                const int l = 4 * (tid - PF_A) + (si & 3);              // < BN
-                constexpr int SEG = BN / 64;
-                const uint16_t* q = B_KC ? b_org + (int64_t)l * p.ldb
-                                         : b_org + (int64_t)(l / SEG) * p.ldb + (l % SEG) * 64;
-                dst = gload<uint32_t>(q);
-            }
-        };
         // iteration c: refill the register set that held chunk c with chunk c + DEPTH, multiply
         // chunk c, move chunk c + 1 (issued DEPTH - 1 iterations ago) into the other LDS stage
-        constexpr int UNROLL = DEPTH > 2 ? DEPTH : 2;
-        for (int c0 = 0; c0 < n_chunks; c0 += UNROLL) {
+        for (int c0 = 0; c0 < n_chunks; c0 += DEPTH) {
 #pragma unroll
-            for (int d = 0; d < UNROLL; ++d) {
+            for (int d = 0; d < DEPTH; ++d) {
                 const int c = c0 + d;
                 if (c < n_chunks) {
-                    if (c + DEPTH < n_chunks) issue(la[d % DEPTH], lb[d % DEPTH]);
-                    if (DEPTH == 1 && c + 2 < n_chunks) prefetch(pf[d & 1]);
+                    if (c + DEPTH < n_chunks) issue(la[d], lb[d]);
                     compute(c & 1);
                     if (c + 1 < n_chunks) {
                         la[(d + 1) % DEPTH].store(As + ((c + 1) & 1) * STAGE_A, tid);
                         lb[(d + 1) % DEPTH].store(Bs + ((c + 1) & 1) * STAGE_B, tid);
                     }
                     __syncthreads();
-                    if (DEPTH == 1) asm volatile("" ::"v"(pf[(d + 1) & 1]));
                 }
             }
         }
