@@ -19,7 +19,7 @@ METRIC = "tiled GEMM TFLOP/s (in-core, out-of-core) + MLP train samples/s, 1 GPU
 PEAK_F32_MFMA_TFLOPS = 157.3   # MI355X dense fp32 matrix peak
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (summaries under
 # profiles/); keyed by (size, tile).  None where no counter run exists.
-MEASURED_TRAFFIC_BYTES = {(8000, 1024): 1.926e9}
+MEASURED_TRAFFIC_BYTES = {(8000, 1024): 1.920e9}
 
 
 def cpu_baseline_gemm(A_host, B_host, budget_s=12.0):
