@@ -200,8 +200,9 @@ int mlp_step(tgemm_mlp* mlp, const void* X, const int32_t* labels, int64_t batch
  *   what 0: activation A_l (l = 1..n_layers-1; batch x dims[l], dtype elements)
  *        1: logits Z_L (batch x dims[n_layers] floats; layer ignored)
  *        2: error D_l  (l = 1..n_layers; batch x dims[l], dtype elements)
- * Copies `bytes` bytes to the host buffer dst.  TGEMM_EARG if bytes exceeds the matrix. */
-int mlp_read(tgemm_mlp* mlp, int32_t what, int32_t layer, void* dst, size_t bytes);
+ * Copies `bytes` bytes starting `offset` bytes into the matrix to the host buffer dst.  TGEMM_EARG
+ * if offset + bytes exceeds the matrix. */
+int mlp_read(tgemm_mlp* mlp, int32_t what, int32_t layer, void* dst, size_t offset, size_t bytes);
 
 #ifdef __cplusplus
 }

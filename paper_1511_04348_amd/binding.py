@@ -82,7 +82,7 @@ def load():
     lib.mlp_forward.argtypes = [vp, vp, i64, vp]
     lib.mlp_backward.argtypes = [vp, vp, P(vp), P(ctypes.c_float)]
     lib.mlp_step.argtypes = [vp, vp, vp, i64, ctypes.c_float, P(ctypes.c_float)]
-    lib.mlp_read.argtypes = [vp, i32, i32, vp, sz]
+    lib.mlp_read.argtypes = [vp, i32, i32, vp, sz, sz]
     for name in EXPORTS:
         if name not in ("tgemm_strerror", "tgemm_last_error"):
             getattr(lib, name).restype = ctypes.c_int
@@ -210,5 +210,5 @@ def mlp_step(mlp, X, labels, batch, lr):
     return loss.value
 
 
-def mlp_read(mlp, what, layer, dst, nbytes):
-    _check(load().mlp_read(mlp, what, layer, _p(dst), nbytes))
+def mlp_read(mlp, what, layer, dst, nbytes, offset=0):
+    _check(load().mlp_read(mlp, what, layer, _p(dst), offset, nbytes))

@@ -694,7 +694,7 @@ int mlp_step(tgemm_mlp* m, const void* X, const int32_t* labels, int64_t batch, 
     return TGEMM_OK;
 }
 
-int mlp_read(tgemm_mlp* m, int32_t what, int32_t layer, void* dst, size_t bytes)
+int mlp_read(tgemm_mlp* m, int32_t what, int32_t layer, void* dst, size_t offset, size_t bytes)
 {
     if (!m || !dst) return fail(TGEMM_EARG, "mlp_read: NULL argument");
     if (m->batch <= 0) return fail(TGEMM_ESTATE, "mlp_read: no forward pass precedes");
@@ -708,9 +708,10 @@ int mlp_read(tgemm_mlp* m, int32_t what, int32_t layer, void* dst, size_t bytes)
         src = m->delta[layer]; have = (size_t)m->batch * m->dims[layer] * m->es;
     }
     if (!src) return fail(TGEMM_EARG, "mlp_read: what=%d layer=%d", what, layer);
-    if (bytes > have) return fail(TGEMM_EARG, "mlp_read: %zu bytes requested, matrix has %zu", bytes, have);
+    if (offset > have || bytes > have - offset)
+        return fail(TGEMM_EARG, "mlp_read: %zu bytes at offset %zu requested, matrix has %zu", bytes, offset, have);
     TG_HIP(hipSetDevice(m->ctx->device));
-    TG_HIP(hipMemcpy(dst, src, bytes, hipMemcpyDeviceToHost));
+    TG_HIP(hipMemcpy(dst, (const char*)src + offset, bytes, hipMemcpyDeviceToHost));
     return TGEMM_OK;
 }
 
