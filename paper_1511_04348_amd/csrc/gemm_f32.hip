@@ -30,6 +30,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int BK = 16;       // k extent of one LDS stage
+constexpr int KQ = BK / 4;   // 16-byte units per k-contiguous row of a stage
 constexpr int PAD = 4;       // floats of row padding in LDS
 
 template <int R> struct Vec;
@@ -41,7 +42,7 @@ template <int R> __device__ inline float vget(const typename Vec<R>::type& v, in
 template <> __device__ inline float vget<1>(const float& v, int) { return v; }
 
 // ---- global -> register staging of one operand tile chunk -------------------------------------
-// KC = true : source rows are mn, BK contiguous k each.   unit u -> (mn = u / 4, kq = u % 4)
+// KC = true : source rows are mn, BK contiguous k each.   unit u -> (mn = u / KQ, kq = u % KQ)
 // KC = false: source rows are k, BMN contiguous mn each.  unit u -> (k = u / (BMN/4), q = u % (BMN/4))
 template <int BMN, int NT, bool KC>
 struct TileLoader {
@@ -57,8 +58,8 @@ struct TileLoader {
             const int u = tid + p * NT;
             f32x4 v = {0.f, 0.f, 0.f, 0.f};
             if (KC) {
-                const int mn = mn0 + (u >> 2);
-                const int k = kk + ((u & 3) << 2);
+                const int mn = mn0 + (u / KQ);
+                const int k = kk + ((u % KQ) << 2);
                 if (mn < mn_end) {
                     const float* src = X + (int64_t)mn * ld + k;
                     if (vec_ok && k + 3 < klim) {
@@ -98,7 +99,7 @@ struct TileLoader {
 #pragma unroll
         for (int p = 0; p < UP; ++p) {
             const int u = tid + p * NT;
-            if (KC) off[p] = (uint32_t)(((int64_t)min(u >> 2, valid - 1) * ld + ((u & 3) << 2)) * 4);
+            if (KC) off[p] = (uint32_t)(((int64_t)min(u / KQ, valid - 1) * ld + ((u % KQ) << 2)) * 4);
             else off[p] = (uint32_t)(((int64_t)(u / (BMN / 4)) * ld + min((u % (BMN / 4)) << 2, valid - 4)) * 4);
         }
     }
@@ -117,8 +118,8 @@ struct TileLoader {
         for (int p = 0; p < UP; ++p) {
             const int u = tid + p * NT;
             if (KC) {
-                const int mn = u >> 2;
-                const int k = (u & 3) << 2;
+                const int mn = u / KQ;
+                const int k = (u % KQ) << 2;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) S[(k + e) * LD + mn] = reg[p][e];
             } else {
