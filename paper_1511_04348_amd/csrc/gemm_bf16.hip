@@ -44,6 +44,7 @@ __device__ inline uint16_t f32_to_bf16_rne(float f)
 template <int BMN, int NT>
 struct LoaderKC {
     static constexpr int UP = BMN * 8 / NT;
+    static constexpr int N_LOADS = UP;        // global load instructions per chunk (fast path)
     static_assert((BMN * 8) % NT == 0, "tile must divide evenly over the threads");
     u32x4 reg[UP];
     uint32_t off[UP];     // byte offset of unit p from the chunk origin (interior fast path)
@@ -111,6 +112,7 @@ struct LoaderMC {
     static constexpr int QH = Q / 4;          // values of the high part of q
     static constexpr int UP = Q * 8 / NT;     // units per thread
     static constexpr int KG_T = 8 / UP;       // kg values covered by the thread index
+    static constexpr int N_LOADS = UP * 8;    // global load instructions per chunk (fast path)
     static_assert(Q * 8 % NT == 0 && UP >= 1 && KG_T >= 4 && NT == 16 * QH * (KG_T / 4), "thread/unit mapping");
     u32x2 reg[UP][8];
     uint32_t off0;        // byte offset of unit 0's first row from the chunk origin
@@ -298,33 +300,72 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_bf16(const GemmParams 
         const uint16_t* b_org = B + (B_KC ? (int64_t)col0 * p.ldb : (int64_t)col0);
         const int64_t a_adv = A_KC ? (int64_t)BK : (int64_t)BK * p.lda;
         const int64_t b_adv = B_KC ? (int64_t)BK : (int64_t)BK * p.ldb;
-        auto issue = [&](LA& sa, LB& sb) {
-            fast_load(sa, a_org, p.lda, 0, 0);
-            a_org += a_adv;
+        // The origin of the next B chunk changes tile at a k-step boundary when B is a tile table;
+        // that (uniform) branch is kept apart from the loads so that loads, MFMAs and LDS traffic
+        // of one iteration form a single scheduling region.
+        auto next_b_origin = [&]() {
             if (p.b_tiles && ld_within == 0) {
                 const uint16_t* t = reinterpret_cast<const uint16_t*>(p.b_tiles[(int64_t)ld_step * p.n_j + tj]);
                 b_org = t + (B_KC ? (int64_t)bcol * p.ldb : (int64_t)bcol);
             }
+        };
+        auto issue = [&](LA& sa, LB& sb) {
+            fast_load(sa, a_org, p.lda, 0, 0);
+            a_org += a_adv;
             fast_load(sb, b_org, p.ldb, 0, 0);
             b_org += b_adv;
-            if (++ld_within == cps) { ld_within = 0; ++ld_step; }
+            ld_within = (ld_within + 1 == cps) ? 0 : ld_within + 1;
+            ld_step += (ld_within == 0);
         };
+        constexpr int N_VMEM = LA::N_LOADS + LB::N_LOADS;     // global load instructions per chunk
+        constexpr int N_MFMA = RA * RB * (BK / 16);
+        constexpr bool SPREAD_LOADS = (NT == 512);            // measured: helps the 8-wave shape only
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d)
-            if (d < n_chunks) issue(la[d], lb[d]);
+            if (d < n_chunks) {
+                next_b_origin();
+                issue(la[d], lb[d]);
+            }
         if (n_chunks > 0) {
             la[0].store(As, tid);
             lb[0].store(Bs, tid);
         }
         __syncthreads();
-        // iteration c: refill the register set that held chunk c with chunk c + DEPTH, multiply
-        // chunk c, move chunk c + 1 (issued DEPTH - 1 iterations ago) into the other LDS stage
-        for (int c0 = 0; c0 < n_chunks; c0 += DEPTH) {
+        // Steady state: iteration c refills the register set that held chunk c with chunk c + DEPTH,
+        // multiplies chunk c, and moves chunk c + 1 (issued DEPTH - 1 iterations ago) into the other
+        // LDS stage.  Nothing in the body is conditional, and the global loads are spread between
+        // the MFMAs: the vector-memory unit takes a wave's loads at a limited rate, and a wave that
+        // issues all of them up front sits in that queue while its MFMAs wait behind them.
+        int c0 = 0;
+        for (; c0 + 2 * DEPTH <= n_chunks; c0 += DEPTH) {
+#pragma unroll
+            for (int d = 0; d < DEPTH; ++d) {
+                const int c = c0 + d;
+                next_b_origin();
+                issue(la[d], lb[d]);
+                compute(c & 1);
+                la[(d + 1) % DEPTH].store(As + ((c + 1) & 1) * STAGE_A, tid);
+                lb[(d + 1) % DEPTH].store(Bs + ((c + 1) & 1) * STAGE_B, tid);
+                if (SPREAD_LOADS) {
+#pragma unroll
+                    for (int i = 0; i < N_VMEM; ++i) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, N_MFMA / N_VMEM, 0);   // MFMA
+                        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                 // one global load
+                    }
+                }
+                __syncthreads();
+            }
+        }
+        // the last chunks: nothing left to issue
+        for (; c0 < n_chunks; c0 += DEPTH) {
 #pragma unroll
             for (int d = 0; d < DEPTH; ++d) {
                 const int c = c0 + d;
                 if (c < n_chunks) {
-                    if (c + DEPTH < n_chunks) issue(la[d], lb[d]);
+                    if (c + DEPTH < n_chunks) {
+                        next_b_origin();
+                        issue(la[d], lb[d]);
+                    }
                     compute(c & 1);
                     if (c + 1 < n_chunks) {
                         la[(d + 1) % DEPTH].store(As + ((c + 1) & 1) * STAGE_A, tid);
