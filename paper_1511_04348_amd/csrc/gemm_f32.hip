@@ -227,31 +227,53 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
         const float* b_org = B + (B_KC ? (int64_t)col0 * p.ldb : (int64_t)col0);
         const int64_t a_adv = A_KC ? (int64_t)BK : (int64_t)BK * p.lda;
         const int64_t b_adv = B_KC ? (int64_t)BK : (int64_t)BK * p.ldb;
-        auto issue = [&]() {
-            LA::load_fast(ra, offa, a_org);
-            a_org += a_adv;
+        // The origin of the next B chunk changes tile at a k-step boundary when B is a tile table;
+        // that (uniform) branch is kept apart from the loads so that loads, MFMAs and LDS traffic
+        // of one iteration form a single scheduling region.
+        auto next_b_origin = [&]() {
             if (p.b_tiles && ld_within == 0) {
                 const float* t = reinterpret_cast<const float*>(p.b_tiles[(int64_t)ld_step * p.n_j + tj]);
                 b_org = t + (B_KC ? (int64_t)bcol * p.ldb : (int64_t)bcol);
             }
+        };
+        auto issue = [&]() {
+            LA::load_fast(ra, offa, a_org);
+            a_org += a_adv;
             LB::load_fast(rb, offb, b_org);
             b_org += b_adv;
-            if (++ld_within == cps) { ld_within = 0; ++ld_step; }
+            ld_within = (ld_within + 1 == cps) ? 0 : ld_within + 1;
+            ld_step += (ld_within == 0);
         };
+        constexpr int N_VMEM = LA::UP + LB::UP;               // global load instructions per chunk
+        constexpr int N_MFMA = RA * RB * (BK / 2);
+        constexpr int GAP = (N_MFMA / 2) / N_VMEM > 0 ? (N_MFMA / 2) / N_VMEM : 1;
         if (n_chunks > 0) {
+            next_b_origin();
             issue();
             LA::store(ra, As, tid);
             LB::store(rb, Bs, tid);
         }
         __syncthreads();
-        for (int c = 0; c < n_chunks; ++c) {
-            const bool more = (c + 1 < n_chunks);
-            if (more) issue();
+        // Steady state: nothing in the body is conditional, and the global loads of the next chunk
+        // are spread over the first half of this chunk's MFMAs -- the vector-memory unit takes a
+        // wave's loads at a limited rate, and a wave that issues them all up front sits in that
+        // queue while its MFMAs wait behind them.
+        int c = 0;
+        for (; c + 1 < n_chunks; ++c) {
+            next_b_origin();
+            issue();
             compute(c & 1);
-            if (more) {
-                LA::store(ra, As + ((c + 1) & 1) * STAGE_A, tid);
-                LB::store(rb, Bs + ((c + 1) & 1) * STAGE_B, tid);
+            LA::store(ra, As + ((c + 1) & 1) * STAGE_A, tid);
+            LB::store(rb, Bs + ((c + 1) & 1) * STAGE_B, tid);
+#pragma unroll
+            for (int i = 0; i < N_VMEM; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, GAP, 0);   // MFMA
+                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);     // one global load
             }
+            __syncthreads();
+        }
+        if (c < n_chunks) {
+            compute(c & 1);
             __syncthreads();
         }
     } else {
