@@ -453,8 +453,8 @@ int pick_config(const GemmDesc& d)
         return (double)((n_tiles + per_round - 1) / per_round) * round_time;
     };
     const double c3 = cost(tiles(256, 256), 256, 1.0);
-    const double c2 = cost(tiles(128, 128), 512, 0.54);
-    const double c1 = cost(tiles(64, 64), 512, 0.14);
+    const double c2 = cost(tiles(128, 128), 512, 0.52);
+    const double c1 = cost(tiles(64, 64), 512, 0.15);
     if (c3 <= c2 && c3 <= c1) return 3;
     return c2 <= c1 ? 2 : 1;
 }
