@@ -51,8 +51,16 @@ enum {
     TGEMM_ESTATE = -6     /* call order violated (e.g. backward before forward) */
 };
 
-/* Order in which output-tile tasks are issued (the result does not depend on it). */
-enum { TGEMM_ORDER_SERPENTINE = 0, TGEMM_ORDER_ROW_MAJOR = 1 };
+/* Order in which output-tile tasks are issued (the result does not depend on it, the tile-cache
+ * traffic does).
+ *   ROW_MAJOR   tile rows top to bottom, columns left to right.
+ *   SERPENTINE  as ROW_MAJOR, but odd tile rows run right to left.
+ *   STRIPS      column strips of `strip` tile columns, left to right; inside a strip the tile rows
+ *               ascend (even strips) or descend (odd strips), and inside a tile row the strip's
+ *               columns ascend.  With strip = slots / k-steps - 2 the strip's B tiles and two row
+ *               panels of A fit in the cache together, so under strict LRU B is fetched once and
+ *               A once per strip; that is the automatic width. */
+enum { TGEMM_ORDER_SERPENTINE = 0, TGEMM_ORDER_ROW_MAJOR = 1, TGEMM_ORDER_STRIPS = 2 };
 
 typedef struct tgemm_opts {
     int32_t trace;         /* 1: record one tgemm_trace_rec per tile product of out-of-core runs */
@@ -61,7 +69,8 @@ typedef struct tgemm_opts {
                               computation thread"); -1: leave it to the OS */
     int32_t async_incore;  /* 1: in-core tgemm_run returns after enqueueing; see tgemm_sync */
     int32_t kernel_config; /* 0: automatic; 1..3 force a macro-tile shape (small, medium, large) */
-    int32_t reserved[3];
+    int32_t strip_width;   /* TGEMM_ORDER_STRIPS: tile columns per strip; 0 = from the slot count */
+    int32_t reserved[2];
 } tgemm_opts;
 
 /* One output tile C_ij = one task (section 3.1; Algorithm 1, "decode").
@@ -105,7 +114,8 @@ const char* tgemm_last_error(void);
  *   streams  NULL, or 4 hipStream_t values (as void*) borrowed from the caller for the lifetime of
  *            the context; entries that are NULL are created (and later destroyed) by the library.
  *            All streams must have default priority.
- *   opts     NULL for defaults (no trace, serpentine order, no core binding, synchronous).
+ *   opts     NULL for defaults (no trace, strips order with automatic width, no core binding,
+ *            synchronous).
  * Errors: TGEMM_EARG (out == NULL, bad device, bad enum), TGEMM_EHIP, TGEMM_ENOMEM. */
 int tgemm_create(tgemm_ctx** out, int device, void* const* streams, const tgemm_opts* opts);
 
@@ -137,8 +147,9 @@ int tgemm_sync(tgemm_ctx* ctx);
  * when cap == 0) and the total number of tasks to *n_tasks. */
 int tgemm_plan(int64_t M, int64_t N, int64_t K, int32_t T, tgemm_task* out, int64_t cap, int64_t* n_tasks);
 
-/* Issue order of the task ids for an n_i x n_j task grid under `order`; writes n_i * n_j ids. */
-int tgemm_task_order(int64_t n_i, int64_t n_j, int32_t order, int64_t* out_ids);
+/* Issue order of the task ids for an n_i x n_j task grid under `order` (`strip` >= 1 is the strip
+ * width of TGEMM_ORDER_STRIPS and ignored otherwise); writes n_i * n_j ids. */
+int tgemm_task_order(int64_t n_i, int64_t n_j, int32_t order, int64_t strip, int64_t* out_ids);
 
 /* Statistics of the last tgemm_run / mlp_* call on the context. */
 int tgemm_last_stats(tgemm_ctx* ctx, tgemm_stats* out);

@@ -11,9 +11,20 @@ from collections import OrderedDict
 from .plan import _ceil_div
 
 
-def task_order(n_i, n_j, order):
-    """Task ids in issue order.  'row_major': i then j ascending.  'serpentine':
-    j ascends on even tile rows and descends on odd ones."""
+def task_order(n_i, n_j, order, strip=None):
+    """Task ids in issue order.  'row_major': i then j ascending.  'serpentine': j ascends on even
+    tile rows and descends on odd ones.  'strips': column strips `strip` tile columns wide, left
+    to right; the tile rows ascend in even strips and descend in odd ones; the strip's columns
+    ascend inside every tile row."""
+    if order == "strips":
+        if strip is None or strip < 1:
+            raise ValueError("strip width")
+        ids = []
+        for s, j0 in enumerate(range(0, n_j, strip)):
+            rows = range(n_i) if s % 2 == 0 else range(n_i - 1, -1, -1)
+            for i in rows:
+                ids.extend(i * n_j + j for j in range(j0, min(n_j, j0 + strip)))
+        return ids
     if order not in ("row_major", "serpentine"):
         raise ValueError(order)
     ids = []
@@ -25,12 +36,19 @@ def task_order(n_i, n_j, order):
     return ids
 
 
-def tgemm_access_sequence(M, N, K, T, order="serpentine"):
+def auto_strip(n_slots, n_k, n_j):
+    """Strip width for the 'strips' order from the slot count: the strip's B tiles and two row
+    panels of A (n_k tiles per tile column / row) fit in the cache together.  Two, because under
+    strict LRU the previous row panel outlives the strip's oldest B column."""
+    return min(n_j, max(1, n_slots // n_k - 2))
+
+
+def tgemm_access_sequence(M, N, K, T, order="serpentine", strip=None):
     """Tile lookups of one tiled GEMM in issue order: for every task, k ascending,
     the A tile then the B tile.  Each entry is (matrix, tile row, tile col, task id, k)."""
     n_i, n_j, n_k = _ceil_div(M, T), _ceil_div(N, T), _ceil_div(K, T)
     seq = []
-    for tid in task_order(n_i, n_j, order):
+    for tid in task_order(n_i, n_j, order, strip):
         i, j = tid // n_j, tid % n_j
         for k in range(n_k):
             seq.append(("A", i, k, tid, k))

@@ -12,7 +12,7 @@ LIB_PATH = os.path.join(_HERE, "libtgemm.so")
 
 TGEMM_F32, TGEMM_BF16 = 0, 1
 TGEMM_OK, TGEMM_EARG, TGEMM_ENOMEM, TGEMM_EUNPINNED, TGEMM_EBUDGET, TGEMM_EHIP, TGEMM_ESTATE = 0, -1, -2, -3, -4, -5, -6
-TGEMM_ORDER_SERPENTINE, TGEMM_ORDER_ROW_MAJOR = 0, 1
+TGEMM_ORDER_SERPENTINE, TGEMM_ORDER_ROW_MAJOR, TGEMM_ORDER_STRIPS = 0, 1, 2
 
 EXPORTS = [
     "tgemm_strerror", "tgemm_last_error", "tgemm_create", "tgemm_destroy", "tgemm_run", "tgemm_sync",
@@ -24,7 +24,7 @@ EXPORTS = [
 class tgemm_opts(ctypes.Structure):
     _fields_ = [("trace", ctypes.c_int32), ("order", ctypes.c_int32), ("affinity_core", ctypes.c_int32),
                 ("async_incore", ctypes.c_int32), ("kernel_config", ctypes.c_int32),
-                ("reserved", ctypes.c_int32 * 3)]
+                ("strip_width", ctypes.c_int32), ("reserved", ctypes.c_int32 * 2)]
 
 
 class tgemm_task(ctypes.Structure):
@@ -73,7 +73,7 @@ def load():
     lib.tgemm_run.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, i32, sz]
     lib.tgemm_sync.argtypes = [vp]
     lib.tgemm_plan.argtypes = [i64, i64, i64, i32, P(tgemm_task), i64, P(i64)]
-    lib.tgemm_task_order.argtypes = [i64, i64, i32, P(i64)]
+    lib.tgemm_task_order.argtypes = [i64, i64, i32, i64, P(i64)]
     lib.tgemm_last_stats.argtypes = [vp, P(tgemm_stats)]
     lib.tgemm_trace.argtypes = [vp, P(tgemm_trace_rec), i64, P(i64)]
     lib.tgemm_queue_selftest.argtypes = [i64, i32, i32, P(i32)]
@@ -113,11 +113,11 @@ def tgemm_last_error():
     return load().tgemm_last_error().decode("utf-8", "replace")
 
 
-def tgemm_create(device=0, streams=None, trace=0, order=TGEMM_ORDER_SERPENTINE, affinity_core=-1,
-                 async_incore=0, kernel_config=0):
+def tgemm_create(device=0, streams=None, trace=0, order=TGEMM_ORDER_STRIPS, affinity_core=-1,
+                 async_incore=0, kernel_config=0, strip_width=0):
     lib = load()
     o = tgemm_opts(trace=trace, order=order, affinity_core=affinity_core, async_incore=async_incore,
-                   kernel_config=kernel_config)
+                   kernel_config=kernel_config, strip_width=strip_width)
     arr = None
     if streams is not None:
         if len(streams) != 4:
@@ -149,9 +149,9 @@ def tgemm_plan(M, N, K, T):
     return [{f: getattr(buf[t], f) for f, _ in tgemm_task._fields_} for t in range(n.value)]
 
 
-def tgemm_task_order(n_i, n_j, order):
+def tgemm_task_order(n_i, n_j, order, strip=1):
     buf = (ctypes.c_int64 * max(1, n_i * n_j))()
-    _check(load().tgemm_task_order(n_i, n_j, order, buf))
+    _check(load().tgemm_task_order(n_i, n_j, order, strip, buf))
     return list(buf[: n_i * n_j])
 
 

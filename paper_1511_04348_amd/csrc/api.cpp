@@ -86,9 +86,11 @@ int tgemm_create(tgemm_ctx** out, int device, void* const* streams, const tgemm_
     tgemm_opts o;
     memset(&o, 0, sizeof o);
     o.affinity_core = -1;
+    o.order = TGEMM_ORDER_STRIPS;
     if (opts) o = *opts;
-    if (o.order != TGEMM_ORDER_SERPENTINE && o.order != TGEMM_ORDER_ROW_MAJOR)
+    if (o.order != TGEMM_ORDER_SERPENTINE && o.order != TGEMM_ORDER_ROW_MAJOR && o.order != TGEMM_ORDER_STRIPS)
         return fail(TGEMM_EARG, "tgemm_create: unknown task order %d", o.order);
+    if (o.strip_width < 0) return fail(TGEMM_EARG, "tgemm_create: strip_width %d", o.strip_width);
     if (o.kernel_config < 0 || o.kernel_config > 3)
         return fail(TGEMM_EARG, "tgemm_create: kernel_config %d", o.kernel_config);
     TG_HIP(hipSetDevice(device));

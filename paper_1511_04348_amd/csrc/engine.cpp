@@ -407,7 +407,12 @@ int run_out_of_core(tgemm_ctx* ctx, const void* A, const void* B, float* C, int6
     // Algorithm 1 line 1: the task queue receives every task id in issue order
     const int64_t n_tasks = r.n_i * r.n_j;
     std::vector<int64_t> order((size_t)n_tasks);
-    rc = tgemm_task_order(r.n_i, r.n_j, ctx->opts.order, order.data());
+    // strips: as many tile columns of B as fit in the cache beside two row panels of A (under
+    // strict LRU the previous row panel is still younger than the strip's first B column when the
+    // next one arrives, so it needs room too or the strip's B tiles get evicted in a cascade)
+    int64_t strip = ctx->opts.strip_width > 0 ? ctx->opts.strip_width : std::max<int64_t>(1, r.n_ab / r.n_k - 2);
+    strip = std::min(strip, r.n_j);
+    rc = tgemm_task_order(r.n_i, r.n_j, ctx->opts.order, strip, order.data());
     if (rc != TGEMM_OK) return rc;
     TaskQueue queue((uint32_t)std::min<int64_t>(n_tasks, 1 << 20));
     r.queue = &queue;

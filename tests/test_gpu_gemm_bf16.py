@@ -78,7 +78,7 @@ def test_out_of_core_bf16(oracle):
     B = _bf16(inputs.uniform_matrix(2, K, N))
     C0 = inputs.uniform_matrix(3, M, N)
     ref = oracle.gemm(inputs.bf16_bits(A), inputs.bf16_bits(B), c_in=C0.numpy())
-    ctx = tg.tgemm_create(0, trace=1)
+    ctx = tg.tgemm_create(0, trace=1, order=tg.TGEMM_ORDER_SERPENTINE)
     try:
         Ap, Bp, Cp = A.pin_memory(), B.pin_memory(), C0.clone().pin_memory()
         budget = 4 * T * T * 4 + n_ab * T * T * 2

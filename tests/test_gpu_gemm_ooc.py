@@ -29,9 +29,9 @@ def _budget(T, n_ab, M, N, K):
     return 4 * up(tm * tn * 4) + n_ab * up(max(tm * tk, tk * tn) * 4)
 
 
-def _check_trace(oracle, ctx, M, N, K, T, order_name, n_slots):
+def _check_trace(oracle, ctx, M, N, K, T, order_name, n_slots, strip=None):
     trace = tg.tgemm_trace(ctx)
-    seq = oracle.tgemm_access_sequence(M, N, K, T, order=order_name)
+    seq = oracle.tgemm_access_sequence(M, N, K, T, order=order_name, strip=strip)
     events, st = oracle.lru_simulate([s[:3] for s in seq], n_slots)
     assert len(trace) * 2 == len(seq)
     n_j = -(-N // T)
@@ -57,17 +57,20 @@ def _tile_bytes(key, M, N, K, T):
     return rows * cols * 4
 
 
-@pytest.mark.parametrize("order,order_name", [(tg.TGEMM_ORDER_SERPENTINE, "serpentine"),
-                                              (tg.TGEMM_ORDER_ROW_MAJOR, "row_major")])
+@pytest.mark.parametrize("order,order_name,strip", [(tg.TGEMM_ORDER_SERPENTINE, "serpentine", 0),
+                                                    (tg.TGEMM_ORDER_ROW_MAJOR, "row_major", 0),
+                                                    (tg.TGEMM_ORDER_STRIPS, "strips", 0),     # automatic width
+                                                    (tg.TGEMM_ORDER_STRIPS, "strips", 3)])
 @pytest.mark.parametrize("M,N,K,T,n_ab", [(1500, 1400, 1300, 256, 20), (640, 640, 640, 128, 8),
-                                          (300, 2000, 700, 256, 11), (1024, 1024, 1024, 256, 64)])
-def test_scaled_down_parity_trace_and_stats(oracle, M, N, K, T, n_ab, order, order_name):
-    announce("ooc", M, N, K, T, n_ab, order_name)
+                                          (300, 2000, 700, 256, 11), (1024, 1024, 1024, 256, 64),
+                                          (1280, 2304, 768, 256, 15)])
+def test_scaled_down_parity_trace_and_stats(oracle, M, N, K, T, n_ab, order, order_name, strip):
+    announce("ooc", M, N, K, T, n_ab, order_name, strip)
     A = inputs.uniform_matrix(1, M, K)
     B = inputs.uniform_matrix(2, K, N)
     C0 = inputs.uniform_matrix(3, M, N)
     ref = oracle.gemm(A.numpy(), B.numpy(), c_in=C0.numpy())
-    ctx = tg.tgemm_create(0, trace=1, order=order)
+    ctx = tg.tgemm_create(0, trace=1, order=order, strip_width=strip)
     try:
         Ap, Bp, Cp = _pinned(A), _pinned(B), _pinned(C0)
         tg.tgemm_run(ctx, Ap, Bp, Cp, M, N, K, T, tg.TGEMM_F32, _budget(T, n_ab, M, N, K))
@@ -80,7 +83,9 @@ def test_scaled_down_parity_trace_and_stats(oracle, M, N, K, T, n_ab, order, ord
         distinct = n_i * n_k + n_k * n_j
         assert stats["n_slots"] == min(n_ab, distinct) and stats["in_core"] == 0
         assert stats["n_tasks"] == n_i * n_j and stats["n_tile_gemms"] == n_i * n_j * n_k == stats["kernel_launches"]
-        seq, events, _ = _check_trace(oracle, ctx, M, N, K, T, order_name, stats["n_slots"])
+        if order_name == "strips" and strip == 0:
+            strip = oracle.auto_strip(stats["n_slots"], n_k, n_j)
+        seq, events, _ = _check_trace(oracle, ctx, M, N, K, T, order_name, stats["n_slots"], strip or None)
         miss_bytes = sum(_tile_bytes(s[:3], M, N, K, T) for s, e in zip(seq, events) if not e[0])
         assert stats["h2d_bytes"] == miss_bytes + M * N * 4          # every miss fetched once + C in
         assert stats["d2h_bytes"] == M * N * 4                       # every C tile harvested once
@@ -114,8 +119,8 @@ def test_uniform_run_is_bitwise_reproducible_across_orders(oracle):
     A = _pinned(inputs.uniform_matrix(1, M, K))
     B = _pinned(inputs.uniform_matrix(2, K, N))
     outs = []
-    for order in (tg.TGEMM_ORDER_SERPENTINE, tg.TGEMM_ORDER_ROW_MAJOR, tg.TGEMM_ORDER_SERPENTINE):
-        ctx = tg.tgemm_create(0, order=order)
+    for order in (tg.TGEMM_ORDER_SERPENTINE, tg.TGEMM_ORDER_ROW_MAJOR, tg.TGEMM_ORDER_STRIPS):
+        ctx = tg.tgemm_create(0, order=order, strip_width=2)
         try:
             C = torch.zeros(M, N).pin_memory()
             tg.tgemm_run(ctx, A, B, C, M, N, K, T, tg.TGEMM_F32, _budget(T, 8, M, N, K))
@@ -174,7 +179,11 @@ def test_config3_full_size(oracle):
         stats = tg.tgemm_last_stats(ctx)
         print("config3 stats", stats, "TFLOP/s", 2.0 * n ** 3 / stats["wall_ms"] / 1e9, flush=True)
         assert stats["n_slots"] == 115 and stats["n_tasks"] == 256 and stats["n_tile_gemms"] == 4096
-        _check_trace(oracle, ctx, n, n, n, T, "serpentine", 115)
+        # default order: strips of 115 / 16 - 2 = 5 tile columns; B comes in once and A once per
+        # strip, less what survives in the cache across a strip boundary
+        assert oracle.auto_strip(115, 16, 16) == 5
+        _check_trace(oracle, ctx, n, n, n, T, "strips", 115, strip=5)
+        assert stats["misses"] == 1232
         assert stats["h2d_bytes"] == (stats["misses"] + 256) * T * T * 4 and stats["d2h_bytes"] == n * n * 4
     finally:
         tg.tgemm_destroy(ctx)

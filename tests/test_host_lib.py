@@ -50,6 +50,10 @@ def test_task_order_matches_oracle(lib, oracle):
     for n_i, n_j in [(1, 1), (3, 4), (16, 16), (5, 1), (1, 7)]:
         assert tg.tgemm_task_order(n_i, n_j, tg.TGEMM_ORDER_ROW_MAJOR) == task_order(n_i, n_j, "row_major")
         assert tg.tgemm_task_order(n_i, n_j, tg.TGEMM_ORDER_SERPENTINE) == task_order(n_i, n_j, "serpentine")
+        for strip in (1, 2, 3, 7, 100):
+            got = tg.tgemm_task_order(n_i, n_j, tg.TGEMM_ORDER_STRIPS, strip)
+            assert got == task_order(n_i, n_j, "strips", strip)
+            assert sorted(got) == list(range(n_i * n_j))
 
 
 @pytest.mark.parametrize("n,p,c", [(0, 1, 1), (1, 1, 1), (1000, 1, 1), (200000, 4, 4), (50000, 1, 6), (50000, 6, 1)])
@@ -66,7 +70,8 @@ def test_argument_errors_without_gpu(lib):
     assert lib.tgemm_run(None, None, None, None, 1, 1, 1, 1, 0, 0) == tg.TGEMM_EARG
     assert lib.tgemm_create(None, 0, None, None) == tg.TGEMM_EARG
     assert lib.tgemm_destroy(None) == tg.TGEMM_OK
-    assert lib.tgemm_task_order(2, 2, 9, (ctypes.c_int64 * 4)()) == tg.TGEMM_EARG
+    assert lib.tgemm_task_order(2, 2, 9, 1, (ctypes.c_int64 * 4)()) == tg.TGEMM_EARG
+    assert lib.tgemm_task_order(2, 2, tg.TGEMM_ORDER_STRIPS, 0, (ctypes.c_int64 * 4)()) == tg.TGEMM_EARG
     assert tg.tgemm_strerror(tg.TGEMM_EBUDGET).startswith("hbm_budget")
 
 

@@ -122,3 +122,38 @@ def test_row_major_reuse_closed_form(oracle):
     # everything fits: compulsory misses only
     ev, st = oracle.lru_simulate([s[:3] for s in seq], n_i * n_k + n_k * n_j)
     assert st["misses"] == n_i * n_k + n_k * n_j and st["evictions"] == 0
+
+
+def test_strips_order_written_out(oracle):
+    """3 x 5 task grid, strips two tile columns wide: the strips go left to right, the rows
+    down, up, down, and the columns of a strip left to right in every row."""
+    got = oracle.task_order(3, 5, "strips", strip=2)
+    assert got == [0, 1, 5, 6, 10, 11,   12, 13, 7, 8, 2, 3,   4, 9, 14]
+    assert oracle.task_order(3, 5, "strips", strip=5) == oracle.task_order(3, 5, "row_major")
+    assert oracle.task_order(4, 1, "strips", strip=1) == [0, 1, 2, 3]
+    for n_i, n_j, w in [(1, 1, 1), (4, 7, 3), (6, 6, 6), (5, 2, 9)]:
+        assert sorted(oracle.task_order(n_i, n_j, "strips", strip=w)) == list(range(n_i * n_j))
+    with pytest.raises(ValueError):
+        oracle.task_order(3, 5, "strips")
+
+
+def test_strips_traffic_closed_form(oracle):
+    """With (w + 2) * n_k slots a strip's B tiles are fetched once and never evicted while the
+    strip runs, and each A row panel once per strip, except the panel shared by two consecutive
+    strips (the last row of one is the first of the next).  One slot fewer per k-step than
+    (w + 1) * n_k and the strip's B tiles are thrown out at every row change."""
+    n_i, n_j, n_k, T, w = 5, 6, 4, 2, 2
+    n_strips = n_j // w
+    seq = oracle.tgemm_access_sequence(n_i * T, n_j * T, n_k * T, T, order="strips", strip=w)
+    assert oracle.auto_strip((w + 2) * n_k, n_k, n_j) == w
+    ev, st = oracle.lru_simulate([s[:3] for s in seq], (w + 2) * n_k)
+    a_miss = sum(1 for s, e in zip(seq, ev) if s[0] == "A" and not e[0])
+    b_miss = sum(1 for s, e in zip(seq, ev) if s[0] == "B" and not e[0])
+    assert b_miss == n_k * n_j
+    assert a_miss == n_strips * n_i * n_k - (n_strips - 1) * n_k
+    ev, tight = oracle.lru_simulate([s[:3] for s in seq], (w + 1) * n_k - 1)
+    assert tight["misses"] > 2 * st["misses"]
+    # serpentine on the same cache refetches far more
+    serp = oracle.tgemm_access_sequence(n_i * T, n_j * T, n_k * T, T, order="serpentine")
+    _, st2 = oracle.lru_simulate([s[:3] for s in serp], (w + 2) * n_k)
+    assert st2["misses"] > st["misses"]
