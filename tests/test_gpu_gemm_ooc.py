@@ -130,6 +130,44 @@ def test_uniform_run_is_bitwise_reproducible_across_orders(oracle):
     assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
 
 
+@pytest.mark.parametrize("dtype,M,N,K,T", [("f32", 1024, 768, 512, 256),      # 16-byte units
+                                          ("f32", 1101, 903, 1303, 256),     # odd pitch: 4-byte units
+                                          ("bf16", 1024, 1024, 512, 256),    # 16-byte units
+                                          ("bf16", 1101, 903, 1303, 256)])   # odd pitch: 2-byte units
+def test_copy_kernel_transfers_match_dma(oracle, monkeypatch, dtype, M, N, K, T):
+    """The optional transfer path (a strided copy kernel that reads and writes the pinned host
+    matrices directly) must give the bits the DMA path gives, and both the oracle's values:
+    integer inputs, so the comparison is exact.  The unit width of the copy follows the
+    alignment of pointers, pitches and row bytes, hence the odd shapes."""
+    announce("ooc copy kernel", dtype, M, N, K, T)
+    A = inputs.int_matrix(21, M, K)
+    B = inputs.int_matrix(22, K, N)
+    C0 = inputs.int_matrix(23, M, N, lo=-7, hi=7)
+    if dtype == "bf16":
+        A, B = A.to(torch.bfloat16), B.to(torch.bfloat16)      # small integers: exact
+        code, esz = tg.TGEMM_BF16, 2
+    else:
+        code, esz = tg.TGEMM_F32, 4
+    ref = oracle.gemm(A.float().numpy(), B.float().numpy(), c_in=C0.numpy())
+    Ap, Bp = _pinned(A), _pinned(B)
+    budget = 4 * T * T * 4 + 9 * T * T * esz
+    outs = {}
+    for mode in ("kernel", "dma"):
+        monkeypatch.setenv("TGEMM_COPY", mode)
+        ctx = tg.tgemm_create(0, order=tg.TGEMM_ORDER_SERPENTINE)
+        try:
+            Cp = _pinned(C0)
+            tg.tgemm_run(ctx, Ap, Bp, Cp, M, N, K, T, code, budget)
+            st = tg.tgemm_last_stats(ctx)
+            assert st["in_core"] == 0 and st["n_slots"] == 9 and st["evictions"] > 0
+            outs[mode] = Cp.clone()
+        finally:
+            tg.tgemm_destroy(ctx)
+    assert np.array_equal(outs["kernel"].numpy().astype(np.float64), ref)
+    assert torch.equal(outs["kernel"], outs["dma"])
+    assert torch.equal(Ap, A) and torch.equal(Bp, B)
+
+
 def test_error_paths():
     ctx = tg.tgemm_create(0)
     try:

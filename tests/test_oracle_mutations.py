@@ -1,0 +1,189 @@
+"""The pins must be able to fail: every planted mistake in a copy of the oracle's source (a
+dropped term, a wrong sign, a wrong index or axis, a transposed operand) has to be caught by at
+least one pin test, and the untouched source has to pass all of them.
+
+Each mutant is built on the CPU from the oracle's own source text with one substitution; the
+oracle package on disk and the GPU library are never touched.  The pin tests are the functions
+of the test_oracle_* modules, called directly with a stand-in for the `oracle` fixture."""
+import os
+import subprocess
+import types
+
+import pytest
+
+import test_oracle_gemm as pins_gemm
+import test_oracle_mlp as pins_mlp
+import test_oracle_plan_lru as pins_plan
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _mutated_module(oracle, fname, old, new, extra_globals=None):
+    """oracle/<fname> with the single occurrence of `old` replaced by `new`, as a module object."""
+    src = open(os.path.join(ROOT, "oracle", fname)).read()
+    assert src.count(old) == 1, "mutation target must occur exactly once: %r" % old
+    src = src.replace(old, new)
+    mod = types.ModuleType("oracle._mutant_" + fname[:-3])
+    mod.__package__ = "oracle"
+    mod.__file__ = os.path.join(ROOT, "oracle", fname)
+    if extra_globals:
+        mod.__dict__.update(extra_globals)
+    exec(compile(src, mod.__file__ + "<mutant>", "exec"), mod.__dict__)
+    return mod
+
+
+def _stand_in(oracle, mod):
+    """A namespace like the oracle package in which the mutant's public functions win."""
+    ns = types.SimpleNamespace(**{k: v for k, v in vars(oracle).items() if not k.startswith("__")})
+    for k, v in vars(mod).items():
+        if callable(v) and not k.startswith("_") and hasattr(oracle, k):
+            setattr(ns, k, v)
+    return ns
+
+
+def _killed_by(ns, pins):
+    """Names of the pin tests that fail on the stand-in."""
+    killers = []
+    for fn, args in pins:
+        try:
+            fn(ns, *args)
+        except Exception as e:                    # an assertion, or a crash from a broken shape
+            killers.append("%s: %s" % (fn.__name__, type(e).__name__))
+    return killers
+
+
+MLP_PINS = [(pins_mlp.test_finite_differences_every_weight, ()), (pins_mlp.test_zero_weights_closed_form, ()),
+            (pins_mlp.test_single_layer_is_softmax_regression, ()), (pins_mlp.test_invariants_and_orientation, ()),
+            (pins_mlp.test_step_descends_first_order, ()), (pins_mlp.test_bf16_inputs_widen_exactly, ())]
+
+MLP_MUTANTS = [
+    ("sigmoid sign", "a = 1.0 / (1.0 + np.exp(-z))", "a = 1.0 / (1.0 + np.exp(z))"),
+    ("softmax axis", "probs = e / e.sum(axis=1, keepdims=True)", "probs = e / e.sum(axis=0, keepdims=True)"),
+    ("loss sum instead of mean", "return float(np.mean(lse - z[np.arange(z.shape[0]), y]))",
+     "return float(np.sum(lse - z[np.arange(z.shape[0]), y]))"),
+    ("one-hot sign", "d[np.arange(B), y] -= 1.0", "d[np.arange(B), y] += 1.0"),
+    ("dropped 1/batch", "    d /= B\n", "    d = d\n"),
+    ("dropped (1 - a) factor", "d = dA * acts[l] * (1.0 - acts[l])", "d = dA * acts[l]"),
+    ("dropped a factor", "d = dA * acts[l] * (1.0 - acts[l])", "d = dA * (1.0 - acts[l])"),
+    ("dW from the wrong activation", "dWs[l] = acts[l].T @ d", "dWs[l] = acts[max(l - 1, 0)].T @ d"),
+    ("delta not propagated", "dA = d @ _f64(Ws[l]).T", "dA = d @ np.abs(_f64(Ws[l])).T"),
+    ("update sign", "new = [_f64(W) - lr * g for W, g in zip(Ws, dWs)]", "new = [_f64(W) + lr * g for W, g in zip(Ws, dWs)]"),
+    ("update without lr", "new = [_f64(W) - lr * g for W, g in zip(Ws, dWs)]", "new = [_f64(W) - g for W, g in zip(Ws, dWs)]"),
+]
+
+
+@pytest.mark.parametrize("name,old,new", MLP_MUTANTS, ids=[m[0] for m in MLP_MUTANTS])
+def test_mlp_mutant_is_caught(oracle, name, old, new):
+    mod = _mutated_module(oracle, "mlp.py", old, new)
+    killers = _killed_by(_stand_in(oracle, mod), MLP_PINS)
+    print(name, "->", killers)
+    assert killers, "no pin notices: " + name
+
+
+PLAN_LRU_PINS = ([(pins_plan.test_paper_tile_counts, ()), (pins_plan.test_edge_extents_config1, ()),
+                  (pins_plan.test_lru_closed_forms, ()), (pins_plan.test_lru_vs_brute_force, ()),
+                  (pins_plan.test_access_sequence_structure, ()), (pins_plan.test_row_major_reuse_closed_form, ()),
+                  (pins_plan.test_strips_order_written_out, ()), (pins_plan.test_strips_traffic_closed_form, ())]
+                 + [(pins_plan.test_plan_partitions_output, a) for a in [(1000, 1000, 1000, 256), (7, 13, 5, 3), (5, 5, 5, 8)]])
+
+LRU_MUTANTS = [
+    ("hit does not refresh (FIFO)", "            cache.move_to_end(key)\n", "            pass\n"),
+    ("evicts the most recent", "victim, _ = cache.popitem(last=False)", "victim, _ = cache.popitem(last=True)"),
+    ("one slot too many", "if len(cache) >= n_slots:", "if len(cache) > n_slots:"),
+    ("serpentine parity", 'if order == "serpentine" and i % 2 == 1:', 'if order == "serpentine" and i % 2 == 0:'),
+    ("strips parity", "rows = range(n_i) if s % 2 == 0 else range(n_i - 1, -1, -1)",
+     "rows = range(n_i) if s % 2 == 1 else range(n_i - 1, -1, -1)"),
+    ("strips never turn round", "rows = range(n_i) if s % 2 == 0 else range(n_i - 1, -1, -1)", "rows = range(n_i)"),
+    ("B tile index transposed", 'seq.append(("B", k, j, tid, k))', 'seq.append(("B", j, k, tid, k))'),
+    ("B looked up before A", 'seq.append(("A", i, k, tid, k))\n            seq.append(("B", k, j, tid, k))',
+     'seq.append(("B", k, j, tid, k))\n            seq.append(("A", i, k, tid, k))'),
+    ("task id decoded column-major", "i, j = tid // n_j, tid % n_j", "i, j = tid % n_i, tid // n_i"),
+    ("automatic strip one too wide", "return min(n_j, max(1, n_slots // n_k - 2))", "return min(n_j, max(1, n_slots // n_k - 1))"),
+]
+
+PLAN_MUTANTS = [
+    ("floor instead of ceil", "    return -(-a // b)", "    return a // b"),
+    ("edge tiles counted as full", "    full = (n // t) ** 2", "    full = _ceil_div(n, t) ** 2"),
+    ("edge not clamped", "r0=i * T, r1=min(M, (i + 1) * T)", "r0=i * T, r1=(i + 1) * T"),
+    ("columns clamped to M", "c0=j * T, c1=min(N, (j + 1) * T)", "c0=j * T, c1=min(M, (j + 1) * T)"),
+    ("id column-major", "id=i * n_j + j", "id=j * n_i + i"),
+    ("k-steps from N", "n_i, n_j, n_k = _ceil_div(M, T), _ceil_div(N, T), _ceil_div(K, T)\n    tasks",
+     "n_i, n_j, n_k = _ceil_div(M, T), _ceil_div(N, T), _ceil_div(N, T)\n    tasks"),
+]
+
+
+@pytest.mark.parametrize("name,old,new", LRU_MUTANTS, ids=[m[0] for m in LRU_MUTANTS])
+def test_lru_mutant_is_caught(oracle, name, old, new):
+    mod = _mutated_module(oracle, "lru.py", old, new)
+    killers = _killed_by(_stand_in(oracle, mod), PLAN_LRU_PINS)
+    print(name, "->", killers)
+    assert killers, "no pin notices: " + name
+
+
+@pytest.mark.parametrize("name,old,new", PLAN_MUTANTS, ids=[m[0] for m in PLAN_MUTANTS])
+def test_plan_mutant_is_caught(oracle, name, old, new):
+    mod = _mutated_module(oracle, "plan.py", old, new)
+    killers = _killed_by(_stand_in(oracle, mod), PLAN_LRU_PINS)
+    print(name, "->", killers)
+    assert killers, "no pin notices: " + name
+
+
+GEMM_PINS = ([(pins_gemm.test_identity_zero_ones, ()), (pins_gemm.test_rank1_closed_form, ()),
+              (pins_gemm.test_brute_force_vs_numpy_all_small_shapes, ("f32",)),
+              (pins_gemm.test_brute_force_vs_numpy_all_small_shapes, ("bf16",)),
+              (pins_gemm.test_bf16_widening_is_exact, ()), (pins_gemm.test_pure_python_triple_loop, ()),
+              (pins_gemm.test_integer_inputs_exact, ()), (pins_gemm.test_tiled_equals_untiled_any_T, ()),
+              (pins_gemm.test_samples_match_full, ()), (pins_gemm.test_empty_dims, ())])
+
+GEMM_C_MUTANTS = [
+    ("A read transposed", "const double a = load_elem(A, m * sam + k * sak, dtype);",
+     "const double a = load_elem(A, m * sak + k * sam, dtype);"),
+    ("B read transposed", "row[n] += a * load_elem(B, k * sbk + n * sbn, dtype);",
+     "row[n] += a * load_elem(B, k * sbn + n * sbk, dtype);"),
+    ("C input dropped", "row[n] = c_in ? (double)c_in[m * ldc_in + n] : 0.0;", "row[n] = 0.0;"),
+    ("last k dropped", "        for (int64_t k = 0; k < K; ++k) {\n            const double a",
+     "        for (int64_t k = 0; k < K - 1; ++k) {\n            const double a"),
+    ("difference instead of sum", "row[n] += a * load_elem(B, k * sbk + n * sbn, dtype);",
+     "row[n] -= a * load_elem(B, k * sbk + n * sbn, dtype);"),
+    ("bf16 widened from the low half", "uint32_t bits = ((uint32_t)((const uint16_t *)base)[idx]) << 16;",
+     "uint32_t bits = ((uint32_t)((const uint16_t *)base)[idx]);"),
+    ("tiled: edge tile not clamped in k", "const int64_t k0 = tk * T, k1 = min64(K, k0 + T);",
+     "const int64_t k0 = tk * T, k1 = (tk + 1 < nK) ? k0 + T : k0 + (K - k0) / 2 * 2;"),
+    ("tiled: k-steps overwrite instead of accumulate", "                    c_out[m * N + n] += s;",
+     "                    c_out[m * N + n] = s;"),
+    ("samples: row and column swapped", "const int64_t m = rows[s], n = cols[s];", "const int64_t m = cols[s], n = rows[s];"),
+    ("samples: C input dropped", "double acc = c_in ? (double)c_in[m * ldc_in + n] : 0.0;", "double acc = 0.0;"),
+]
+
+
+@pytest.fixture(scope="module")
+def mutant_dir(tmp_path_factory):
+    return tmp_path_factory.mktemp("oracle_mutants")
+
+
+@pytest.mark.parametrize("name,old,new", GEMM_C_MUTANTS, ids=[m[0] for m in GEMM_C_MUTANTS])
+def test_gemm_c_mutant_is_caught(oracle, mutant_dir, name, old, new):
+    src = open(os.path.join(ROOT, "oracle", "oracle_gemm.c")).read()
+    assert src.count(old) == 1, "mutation target must occur exactly once: %r" % old
+    tag = "m%d" % [m[0] for m in GEMM_C_MUTANTS].index(name)
+    c_path, so_path = str(mutant_dir / (tag + ".c")), str(mutant_dir / (tag + ".so"))
+    open(c_path, "w").write(src.replace(old, new))
+    subprocess.run(["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-o", so_path, c_path], check=True)
+    # the ctypes front end, unchanged, on top of the mutated library
+    mod = _mutated_module(oracle, "gemm.py", "from .build import build_oracle\n",
+                          "build_oracle = lambda: %r\n" % so_path)
+    killers = _killed_by(_stand_in(oracle, mod), GEMM_PINS)
+    print(name, "->", killers)
+    assert killers, "no pin notices: " + name
+
+
+def test_the_untouched_oracle_passes_every_pin(oracle):
+    """The harness itself: with no substitution nothing is reported."""
+    ident = _mutated_module(oracle, "mlp.py", "import numpy as np\n", "import numpy as np\n")
+    assert _killed_by(_stand_in(oracle, ident), MLP_PINS) == []
+    ident = _mutated_module(oracle, "lru.py", "from collections import OrderedDict\n", "from collections import OrderedDict\n")
+    assert _killed_by(_stand_in(oracle, ident), PLAN_LRU_PINS) == []
+    ident = _mutated_module(oracle, "plan.py", "def _ceil_div(a, b):", "def _ceil_div(a, b):")
+    assert _killed_by(_stand_in(oracle, ident), PLAN_LRU_PINS) == []
+    ident = _mutated_module(oracle, "gemm.py", "from .build import build_oracle\n", "from .build import build_oracle\n")
+    assert _killed_by(_stand_in(oracle, ident), GEMM_PINS) == []

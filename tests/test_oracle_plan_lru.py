@@ -47,6 +47,9 @@ def test_plan_partitions_output(oracle, M, N, K, T):
     ks = oracle.kstep_ranges(K, T)
     assert ks[0][0] == 0 and ks[-1][1] == K
     assert all(a[1] == b[0] for a, b in zip(ks, ks[1:]))
+    assert all(0 < b - a <= T for a, b in ks)
+    # steps per task (section 3.1): one per tile of the shared dimension, counted without ceil
+    assert all(t["n_k"] == len(ks) == sum(1 for k in range(K) if k % T == 0) for t in tasks)
 
 
 def test_edge_extents_config1(oracle):
