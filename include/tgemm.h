@@ -68,7 +68,8 @@ typedef struct tgemm_opts {
     int32_t affinity_core; /* >= 0: bind the submit thread to this CPU core (section 3.2, "GPU
                               computation thread"); -1: leave it to the OS */
     int32_t async_incore;  /* 1: in-core tgemm_run returns after enqueueing; see tgemm_sync */
-    int32_t kernel_config; /* 0: automatic; 1..3 force a macro-tile shape (small, medium, large) */
+    int32_t kernel_config; /* 0: automatic; 1..3 force a macro-tile shape (small, medium, large);
+                              4: large, bf16 register-staged kernel even where the direct-to-LDS one applies */
     int32_t strip_width;   /* TGEMM_ORDER_STRIPS: tile columns per strip; 0 = from the slot count */
     int32_t reserved[2];
 } tgemm_opts;

@@ -91,7 +91,7 @@ int tgemm_create(tgemm_ctx** out, int device, void* const* streams, const tgemm_
     if (o.order != TGEMM_ORDER_SERPENTINE && o.order != TGEMM_ORDER_ROW_MAJOR && o.order != TGEMM_ORDER_STRIPS)
         return fail(TGEMM_EARG, "tgemm_create: unknown task order %d", o.order);
     if (o.strip_width < 0) return fail(TGEMM_EARG, "tgemm_create: strip_width %d", o.strip_width);
-    if (o.kernel_config < 0 || o.kernel_config > 3)
+    if (o.kernel_config < 0 || o.kernel_config > 4)
         return fail(TGEMM_EARG, "tgemm_create: kernel_config %d", o.kernel_config);
     TG_HIP(hipSetDevice(device));
     tgemm_ctx* c = new (std::nothrow) tgemm_ctx();

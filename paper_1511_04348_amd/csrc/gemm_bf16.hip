@@ -17,27 +17,13 @@
 
 #include <type_traits>
 
-#include "gemm_kernel.h"
+#include "gemm_bf16_common.h"
 
 namespace tg {
 namespace bf {
 
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-
 constexpr int BK = 64;            // k per LDS stage
 constexpr int ROW_W = 36;         // LDS row stride in 32-bit words: 128 B of data + 16 B pad
-
-__device__ inline float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
-__device__ inline uint16_t f32_to_bf16_rne(float f)
-{
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);   // NaN stays NaN
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
-}
 
 // ---- k-contiguous source: rows are mn, 64 contiguous k per stage -------------------------------
 // unit u -> (mn = u / 8, kq = u % 8): 16 bytes = 8 k.
@@ -220,26 +206,9 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_bf16(const GemmParams 
     const int wm = wave / WN, wn = wave % WN;
     const int li = lane & 31, lh = lane >> 5;
 
-    int lid;
-    {
-        const int n = gridDim.x, b = blockIdx.x;
-        const int q = n >> 3, r = n & 7, xcd = b & 7, local = b >> 3;
-        lid = xcd * q + (xcd < r ? xcd : r) + local;
-    }
-    const int band = p.tpm * p.macro_cols;
-    int ti = lid / band;
-    const int in_band = lid - ti * band;
-    const int h = (ti == p.n_i - 1) ? p.tpm_last : p.tpm;
-    int tj = in_band / (h * p.tpn);
-    if (tj > p.n_j - 1) tj = p.n_j - 1;
-    const int in_task = in_band - tj * h * p.tpn;
-    const int wcols = (tj == p.n_j - 1) ? p.tpn_last : p.tpn;
-    const int si = in_task / wcols, sj = in_task - si * wcols;
-
-    const int row0 = ti * p.T + si * BM;
-    const int col0 = tj * p.T + sj * BN;
-    const int row_end = min(p.M, (ti + 1) * p.T);
-    const int col_end = min(p.N, (tj + 1) * p.T);
+    const TileCoord tc = decode_tile<BM, BN>(p);
+    const int ti = tc.ti, tj = tc.tj, row0 = tc.row0, col0 = tc.col0, row_end = tc.row_end, col_end = tc.col_end;
+    (void)ti;
 
     const uint16_t* __restrict__ A = reinterpret_cast<const uint16_t*>(p.A);
     const uint16_t* __restrict__ B = reinterpret_cast<const uint16_t*>(p.B);
@@ -284,7 +253,7 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_bf16(const GemmParams 
             for (int r = 0; r < RA; ++r)
 #pragma unroll
                 for (int cc = 0; cc < RB; ++cc)
-                    acc[r][cc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[r], bfr[cc], acc[r][cc], 0, 0, 0);
+                    acc[r][cc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cc], af[r], acc[r][cc], 0, 0, 0);   // transposed block
         }
     };
 
@@ -411,45 +380,7 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_bf16(const GemmParams 
         }
     }
 
-    // -- epilogue.  acc[r][cc][v] is element (row, col) of the wave tile with
-    //    row = 32 r + 8 (v / 4) + 4 lh + v % 4,  col = 32 cc + li.
-    const float alpha = p.alpha, beta = p.beta;
-    // C: the dense matrix, or this task's tile from the tile table (tile-local coordinates)
-    const int64_t c_shift = p.c_tiles ? ((int64_t)(ti * p.T) * p.ldc + tj * p.T) : 0;
-    void* c_base = p.c_tiles ? p.c_tiles[(int64_t)ti * p.n_j + tj] : (void*)p.C;
-    float* __restrict__ Cf = reinterpret_cast<float*>(c_base) - c_shift;
-    uint16_t* __restrict__ Cb = reinterpret_cast<uint16_t*>(c_base) - c_shift;
-    const uint16_t* __restrict__ aux = reinterpret_cast<const uint16_t*>(p.aux);
-#pragma unroll
-    for (int r = 0; r < RA; ++r) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int row = row0 + wm * WTM + 32 * r + 8 * (v >> 2) + 4 * lh + (v & 3);
-            if (row >= row_end) continue;
-#pragma unroll
-            for (int cc = 0; cc < RB; ++cc) {
-                const int col = col0 + wn * WTN + 32 * cc + li;
-                if (col >= col_end) continue;
-                const int64_t idx = (int64_t)row * p.ldc + col;
-                float o = acc[r][cc][v];
-                if (EPI == EPI_AXPBY) {
-                    if (beta != 0.f) {
-                        const float cin = OUT_BF16 ? bf16_to_f32(gload<uint16_t>(Cb + idx)) : gload<float>(Cf + idx);
-                        o = fmaf(alpha, o, beta * cin);
-                    } else {
-                        o = alpha * o;
-                    }
-                } else if (EPI == EPI_SIGMOID) {
-                    o = 1.f / (1.f + __expf(-o));
-                } else if (EPI == EPI_DSIGMOID) {
-                    const float a = bf16_to_f32(gload<uint16_t>(aux + (int64_t)row * p.ldaux + col));
-                    o = o * a * (1.f - a);
-                }
-                if (OUT_BF16) gstore<uint16_t>(Cb + idx, f32_to_bf16_rne(o));
-                else gstore<float>(Cf + idx, o);
-            }
-        }
-    }
+    epilogue<RA, RB, EPI, OUT_BF16>(p, tc, acc, row0 + wm * WTM, col0 + wn * WTN, li, lh);
 }
 
 // ---- host-side launcher -------------------------------------------------------------------------
@@ -479,25 +410,8 @@ template <int RA, int RB, int WM, int WN, int DEPTH>
 static hipError_t launch_cfg(GemmParams& p, const GemmDesc& d, hipStream_t stream)
 {
     typedef Cfg<RA, RB, WM, WN> C;
-    const int64_t T = d.T;
-    p.n_i = (int)((d.M + T - 1) / T);
-    p.n_j = (int)((d.N + T - 1) / T);
-    const int64_t n_k = (d.K + T - 1) / T;
-    const int64_t last_m = d.M - (int64_t)(p.n_i - 1) * T;
-    const int64_t last_n = d.N - (int64_t)(p.n_j - 1) * T;
-    const int64_t full_m = p.n_i > 1 ? T : last_m, full_n = p.n_j > 1 ? T : last_n;
-    p.tpm = (int)((full_m + C::BM - 1) / C::BM);
-    p.tpn = (int)((full_n + C::BN - 1) / C::BN);
-    p.tpm_last = (int)((last_m + C::BM - 1) / C::BM);
-    p.tpn_last = (int)((last_n + C::BN - 1) / C::BN);
-    p.macro_cols = (p.n_j - 1) * p.tpn + p.tpn_last;
-    const int64_t macro_rows = (int64_t)(p.n_i - 1) * p.tpm + p.tpm_last;
-    const int64_t grid = macro_rows * p.macro_cols;
-    if (grid <= 0 || grid > 0x7fffffff) return hipErrorInvalidValue;
-    const int64_t full_k = n_k > 1 ? T : d.K;
-    p.chunks_per_step = (int)((full_k + BK - 1) / BK);
-    const int64_t last_k = d.K - (n_k - 1) * T;
-    p.n_chunks = (int)((n_k - 1) * p.chunks_per_step + (last_k + BK - 1) / BK);
+    const int64_t grid = fill_grid(p, d, C::BM, C::BN, BK);
+    if (grid == 0) return hipErrorInvalidValue;
 
 #define TGB_LAUNCH(AK, BKC, E, OB) return launch_one<RA, RB, WM, WN, DEPTH, AK, BKC, E, OB>(p, (int)grid, stream)
 #define TGB_EPI(AK, BKC)                                                            \
@@ -537,7 +451,13 @@ hipError_t launch_tile_gemm_bf16(const GemmDesc& d, hipStream_t stream)
     };
     p.vec_a = ok(d.A, d.lda, d.a_kcontig != 0);
     p.vec_b = ok(d.B, d.ldb, d.b_kcontig != 0);
-    p.vec_c = false;
+    // epilogue: 4 consecutive columns per access (16 bytes of fp32, 8 bytes of bf16); the tile table's
+    // slots are aligned by the cache
+    {
+        const uintptr_t need = d.out_bf16 ? 7 : 15;
+        p.vec_c = (d.ldc % 4 == 0) && ((reinterpret_cast<uintptr_t>(d.C) & need) == 0) && (T % 4 == 0);
+        p.vec_aux = d.aux && (d.ldaux % 4 == 0) && ((reinterpret_cast<uintptr_t>(d.aux) & 7) == 0) && (T % 4 == 0);
+    }
     // the unpredicated load path keeps per-thread byte offsets in 32 bits
     auto off32 = [](int64_t ld) { return 256 * ld * 2 + 4096 < ((int64_t)1 << 31); };
     p.fast_a = p.vec_a && off32(d.lda);
@@ -545,8 +465,11 @@ hipError_t launch_tile_gemm_bf16(const GemmDesc& d, hipStream_t stream)
     p.fast_k = (d.K % bf::BK == 0) && (T % bf::BK == 0 || T >= d.K);   // every chunk is a full 64 k
     GemmDesc dd = d;
     dd.T = (int32_t)T;
+    // config: 1, 2 = 128 x 128 macro tiles; 3 = 256 x 256 (direct-to-LDS kernel when the operands
+    // allow it, else register-staged); 4 = 256 x 256 register-staged; 0 = pick by a cost model
+    const bool dl_ok = bf::bf16_dl_applicable(dd);
     int cfg = d.config;
-    if (cfg < 1 || cfg > 3) {
+    if (cfg < 1 || cfg > 4) {
         auto tiles = [&](int64_t bm, int64_t bn) {
             const int64_t n_i = (d.M + T - 1) / T, n_j = (d.N + T - 1) / T;
             const int64_t lm = d.M - (n_i - 1) * T, ln = d.N - (n_j - 1) * T;
@@ -557,11 +480,14 @@ hipError_t launch_tile_gemm_bf16(const GemmDesc& d, hipStream_t stream)
         auto cost = [&](int64_t n_tiles, int64_t per_round, double round_time) {
             return (double)((n_tiles + per_round - 1) / per_round) * round_time;
         };
+        // time of one round of workgroups over the chip, relative to a 256 x 256 round of the kernel
+        // that will run (measured)
         const double c3 = cost(tiles(256, 256), 256, 1.0);
-        const double c2 = cost(tiles(128, 128), 512, 0.6);
+        const double c2 = cost(tiles(128, 128), 512, dl_ok ? 0.95 : 0.6);
         cfg = c3 <= c2 ? 3 : 2;
     }
-    if (cfg == 3) return bf::launch_cfg<2, 4, 4, 2, 1>(p, dd, stream);   // 256 x 256, 8 waves of 64 x 128
+    if (cfg == 3 && dl_ok) return bf::launch_tile_gemm_bf16_dl(p, dd, stream);
+    if (cfg >= 3) return bf::launch_cfg<2, 4, 4, 2, 1>(p, dd, stream);   // 256 x 256, 8 waves of 64 x 128
     return bf::launch_cfg<2, 2, 2, 2, 1>(p, dd, stream);                  // 128 x 128, 4 waves of 64 x 64
 }
 

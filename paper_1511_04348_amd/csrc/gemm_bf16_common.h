@@ -1,0 +1,209 @@
+// Pieces shared by the two bf16 tile GEMM kernels (register-staged and direct-to-LDS): the
+// workgroup -> macro tile decode, the epilogue, and the grid arithmetic of the launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "gemm_kernel.h"
+
+namespace tg {
+namespace bf {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+__device__ inline float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+__device__ inline uint16_t f32_to_bf16_rne(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);   // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// Which macro tile a workgroup owns.  Workgroups are numbered XCD by XCD (consecutive logical ids
+// stay on one XCD and share its L2) and task by task (the T x T task grid is the L2 blocking).
+struct TileCoord {
+    int ti, tj;             // task (output tile of section 3.1)
+    int row0, col0;         // first row / column of the macro tile
+    int row_end, col_end;   // end of the task's rows / columns (clamped to the matrix)
+};
+
+template <int BM, int BN>
+__device__ inline TileCoord decode_tile(const GemmParams& p)
+{
+    int lid;
+    {
+        const int n = gridDim.x, b = blockIdx.x;
+        const int q = n >> 3, r = n & 7, xcd = b & 7, local = b >> 3;
+        lid = xcd * q + (xcd < r ? xcd : r) + local;
+    }
+    TileCoord t;
+    const int band = p.tpm * p.macro_cols;
+    t.ti = lid / band;
+    const int in_band = lid - t.ti * band;
+    const int h = (t.ti == p.n_i - 1) ? p.tpm_last : p.tpm;
+    t.tj = in_band / (h * p.tpn);
+    if (t.tj > p.n_j - 1) t.tj = p.n_j - 1;
+    const int in_task = in_band - t.tj * h * p.tpn;
+    const int wcols = (t.tj == p.n_j - 1) ? p.tpn_last : p.tpn;
+    const int si = in_task / wcols, sj = in_task - si * wcols;
+    t.row0 = t.ti * p.T + si * BM;
+    t.col0 = t.tj * p.T + sj * BN;
+    t.row_end = min(p.M, (t.ti + 1) * p.T);
+    t.col_end = min(p.N, (t.tj + 1) * p.T);
+    return t;
+}
+
+// The kernels feed the MFMA with the B fragment as its first and the A fragment as its second
+// operand, i.e. they accumulate the transposed 32 x 32 block: a lane then owns one row of C and
+// four consecutive columns per register quad,
+//    acc[r][cc][v]:  row = 32 r + li,  col = 32 cc + 8 (v / 4) + 4 lh + v % 4     (li = lane % 32, lh = lane / 32),
+// which turns the epilogue's traffic into 16-byte (fp32) or 8-byte (bf16) accesses.  Everything the
+// epilogue reads for one r is requested before the first value is used.
+// wrow0 / wcol0: first row / column of the wave tile in the matrix.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+template <int RA, int RB, int EPI, bool OUT_BF16>
+__device__ inline void epilogue(const GemmParams& p, const TileCoord& t, const f32x16 (&acc)[RA][RB], int wrow0,
+                                int wcol0, int li, int lh)
+{
+    const float alpha = p.alpha, beta = p.beta;
+    // C: the dense matrix, or this task's tile from the tile table (tile-local coordinates)
+    const int64_t c_shift = p.c_tiles ? ((int64_t)(t.ti * p.T) * p.ldc + t.tj * p.T) : 0;
+    void* c_base = p.c_tiles ? p.c_tiles[(int64_t)t.ti * p.n_j + t.tj] : (void*)p.C;
+    float* __restrict__ Cf = reinterpret_cast<float*>(c_base) - c_shift;
+    uint16_t* __restrict__ Cb = reinterpret_cast<uint16_t*>(c_base) - c_shift;
+    const uint16_t* __restrict__ aux = reinterpret_cast<const uint16_t*>(p.aux);
+    const bool read_c = (EPI == EPI_AXPBY) && beta != 0.f;
+    const bool vec_c = p.vec_c, vec_aux = p.vec_aux;
+#pragma unroll
+    for (int r = 0; r < RA; ++r) {
+        const int row = wrow0 + 32 * r + li;
+        if (row >= t.row_end) continue;
+        const int64_t crow = (int64_t)row * p.ldc;
+        f32x4 in[RB][4];     // C (AXPBY) or the activation (DSIGMOID) at this lane's 4 x RB quads
+        if (read_c || EPI == EPI_DSIGMOID) {
+#pragma unroll
+            for (int cc = 0; cc < RB; ++cc)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int col = wcol0 + 32 * cc + 8 * g + 4 * lh;
+                    f32x4 x = {0.f, 0.f, 0.f, 0.f};
+                    if (EPI == EPI_DSIGMOID) {
+                        const uint16_t* src = aux + (int64_t)row * p.ldaux + col;
+                        if (vec_aux && col + 3 < t.col_end) {
+                            const u32x2 w = gload<u32x2>(src);
+                            x[0] = __uint_as_float(w[0] << 16); x[1] = __uint_as_float(w[0] & 0xffff0000u);
+                            x[2] = __uint_as_float(w[1] << 16); x[3] = __uint_as_float(w[1] & 0xffff0000u);
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                if (col + e < t.col_end) x[e] = bf16_to_f32(gload<uint16_t>(src + e));
+                        }
+                    } else if (OUT_BF16) {
+                        const uint16_t* src = Cb + crow + col;
+                        if (vec_c && col + 3 < t.col_end) {
+                            const u32x2 w = gload<u32x2>(src);
+                            x[0] = __uint_as_float(w[0] << 16); x[1] = __uint_as_float(w[0] & 0xffff0000u);
+                            x[2] = __uint_as_float(w[1] << 16); x[3] = __uint_as_float(w[1] & 0xffff0000u);
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                if (col + e < t.col_end) x[e] = bf16_to_f32(gload<uint16_t>(src + e));
+                        }
+                    } else {
+                        const float* src = Cf + crow + col;
+                        if (vec_c && col + 3 < t.col_end) {
+                            x = gload<f32x4>(src);
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                if (col + e < t.col_end) x[e] = gload<float>(src + e);
+                        }
+                    }
+                    in[cc][g] = x;
+                }
+        }
+#pragma unroll
+        for (int cc = 0; cc < RB; ++cc)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int col = wcol0 + 32 * cc + 8 * g + 4 * lh;
+                if (col >= t.col_end) continue;
+                f32x4 o;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float v = acc[r][cc][4 * g + e];
+                    if (EPI == EPI_AXPBY) {
+                        v = read_c ? fmaf(alpha, v, beta * in[cc][g][e]) : alpha * v;
+                    } else if (EPI == EPI_SIGMOID) {
+                        v = 1.f / (1.f + __expf(-v));
+                    } else if (EPI == EPI_DSIGMOID) {
+                        const float a = in[cc][g][e];
+                        v = v * a * (1.f - a);
+                    }
+                    o[e] = v;
+                }
+                if (OUT_BF16) {
+                    uint16_t* dst = Cb + crow + col;
+                    if (vec_c && col + 3 < t.col_end) {
+                        u32x2 w;
+                        w[0] = (uint32_t)f32_to_bf16_rne(o[0]) | ((uint32_t)f32_to_bf16_rne(o[1]) << 16);
+                        w[1] = (uint32_t)f32_to_bf16_rne(o[2]) | ((uint32_t)f32_to_bf16_rne(o[3]) << 16);
+                        gstore<u32x2>(dst, w);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (col + e < t.col_end) gstore<uint16_t>(dst + e, f32_to_bf16_rne(o[e]));
+                    }
+                } else {
+                    float* dst = Cf + crow + col;
+                    if (vec_c && col + 3 < t.col_end) {
+                        gstore<f32x4>(dst, o);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (col + e < t.col_end) gstore<float>(dst + e, o[e]);
+                    }
+                }
+            }
+    }
+}
+
+// Fills the task grid, macro-tile and chunk counts of `p` for BM x BN macro tiles and chunks of
+// CHUNK_K; returns the grid size (0 if it does not fit a launch).
+inline int64_t fill_grid(GemmParams& p, const GemmDesc& d, int BM, int BN, int CHUNK_K)
+{
+    const int64_t T = d.T;
+    p.n_i = (int)((d.M + T - 1) / T);
+    p.n_j = (int)((d.N + T - 1) / T);
+    const int64_t n_k = (d.K + T - 1) / T;
+    const int64_t last_m = d.M - (int64_t)(p.n_i - 1) * T;
+    const int64_t last_n = d.N - (int64_t)(p.n_j - 1) * T;
+    const int64_t full_m = p.n_i > 1 ? T : last_m, full_n = p.n_j > 1 ? T : last_n;
+    p.tpm = (int)((full_m + BM - 1) / BM);
+    p.tpn = (int)((full_n + BN - 1) / BN);
+    p.tpm_last = (int)((last_m + BM - 1) / BM);
+    p.tpn_last = (int)((last_n + BN - 1) / BN);
+    p.macro_cols = (p.n_j - 1) * p.tpn + p.tpn_last;
+    const int64_t macro_rows = (int64_t)(p.n_i - 1) * p.tpm + p.tpm_last;
+    const int64_t grid = macro_rows * p.macro_cols;
+    if (grid <= 0 || grid > 0x7fffffff) return 0;
+    const int64_t full_k = n_k > 1 ? T : d.K;
+    p.chunks_per_step = (int)((full_k + CHUNK_K - 1) / CHUNK_K);
+    const int64_t last_k = d.K - (n_k - 1) * T;
+    p.n_chunks = (int)((n_k - 1) * p.chunks_per_step + (last_k + CHUNK_K - 1) / CHUNK_K);
+    return grid;
+}
+
+// The direct-to-LDS kernel (gemm_bf16_dl.hip): 256 x 256 macro tiles.  It needs 16-byte aligned
+// operand rows and whole 32-k chunks; the launcher returns hipErrorNotSupported (and launches
+// nothing) when bf16_dl_applicable(d) is false.  d.T must already be clamped to the problem.
+bool bf16_dl_applicable(const GemmDesc& d);
+hipError_t launch_tile_gemm_bf16_dl(GemmParams p, const GemmDesc& d, hipStream_t stream);
+
+}  // namespace bf
+}  // namespace tg

@@ -49,7 +49,8 @@ struct GemmParams {
     int chunks_per_step;        // BK-chunks in a full k-step
     int n_chunks;               // BK-chunks over all k-steps
     float alpha, beta;
-    bool vec_a, vec_b, vec_c;   // 16-byte vector access is legal for this operand
+    bool vec_a, vec_b, vec_c;   // vector access is legal for this operand
+    bool vec_aux;               // bf16 kernels: 8-byte access to aux is legal
     bool fast_a, fast_b;        // interior tiles may use the unpredicated, 32-bit-offset load path
     bool fast_k;                // every k chunk is full (no ragged k-step tails)
     const void* const* b_tiles; // see GemmDesc

@@ -21,7 +21,7 @@ def _bf16(t):
 
 @pytest.fixture(scope="module")
 def ctxs():
-    made = {cfg: tg.tgemm_create(0, kernel_config=cfg) for cfg in (0, 2, 3)}
+    made = {cfg: tg.tgemm_create(0, kernel_config=cfg) for cfg in (0, 2, 3, 4)}
     yield made
     for c in made.values():
         tg.tgemm_destroy(c)
@@ -29,10 +29,14 @@ def ctxs():
 
 CASES = [(1, 1, 1, 1), (3, 5, 7, 2), (37, 53, 29, 16), (64, 64, 16, 1024), (257, 131, 77, 64),
          (300, 300, 300, 100), (513, 259, 1025, 256), (1000, 1000, 1000, 256), (130, 1030, 40, 512),
-         (700, 36, 2050, 1024), (256, 256, 64, 256), (384, 512, 200, 128)]
+         (700, 36, 2050, 1024), (256, 256, 64, 256), (384, 512, 200, 128),
+         # shapes the direct-to-LDS kernel takes under config 3 (whole 32-k chunks, N a multiple of 8):
+         # ragged edge tiles in M and N, one chunk, fewer chunks than stages, T above and below K
+         (1304, 1096, 1312, 256), (520, 264, 64, 256), (1000, 1000, 992, 1000), (264, 520, 96, 2048),
+         (40, 8, 32, 64), (2048, 1536, 1024, 512), (77, 640, 160, 32)]
 
 
-@pytest.mark.parametrize("cfg", [0, 2, 3])
+@pytest.mark.parametrize("cfg", [0, 2, 3, 4])
 @pytest.mark.parametrize("M,N,K,T", CASES)
 def test_integer_inputs_bit_exact(ctxs, oracle, M, N, K, T, cfg):
     announce("bf16 int", M, N, K, T, "cfg", cfg)
@@ -48,12 +52,13 @@ def test_integer_inputs_bit_exact(ctxs, oracle, M, N, K, T, cfg):
 
 
 def test_uniform_parity_and_unaligned(ctxs, oracle):
-    for (M, N, K, T) in [(1000, 1000, 1000, 256), (203, 157, 301, 64), (520, 264, 776, 128)]:
+    for (M, N, K, T) in [(1000, 1000, 1000, 256), (203, 157, 301, 64), (520, 264, 776, 128),
+                         (520, 264, 768, 128), (1304, 1096, 1312, 256)]:   # the last two: direct-to-LDS when aligned
         A = _bf16(inputs.uniform_matrix(1, M, K))
         B = _bf16(inputs.uniform_matrix(2, K, N))
         C0 = inputs.uniform_matrix(3, M, N)
         ref = oracle.gemm(inputs.bf16_bits(A), inputs.bf16_bits(B), c_in=C0.numpy())
-        for cfg in (0, 2, 3):
+        for cfg in (0, 2, 3, 4):
             announce("bf16 uniform", M, N, K, T, "cfg", cfg)
             # a 2-byte offset from an aligned base exercises the scalar load paths
             bufA = torch.empty(M * K + 1, dtype=torch.bfloat16, device="cuda")

@@ -83,11 +83,12 @@ def _check_passes(oracle, mlp, dims, batch, X, Ws, y, Wd, Xd, yd, dtype, tol, lr
 
 
 @pytest.mark.parametrize("dims,batch,T", [([64, 96, 80, 50], 33, 32), ([512, 1024, 768, 2000], 384, 256),
-                                          ([40, 30], 17, 16)])
-def test_bf16_in_core(oracle, dims, batch, T):
-    announce("mlp bf16 in-core", dims, batch, T)
+                                          ([40, 30], 17, 16), ([256, 512, 264, 1000], 200, 128)])
+@pytest.mark.parametrize("cfg", [0, 3, 4])      # automatic; large tiles (direct-to-LDS kernel where it applies); large, register-staged
+def test_bf16_in_core(oracle, dims, batch, T, cfg):
+    announce("mlp bf16 in-core", dims, batch, T, "cfg", cfg)
     X, Ws, y = _net(dims, batch, torch.bfloat16)
-    ctx = tg.tgemm_create(0)
+    ctx = tg.tgemm_create(0, kernel_config=cfg)
     try:
         Wd = [w.cuda() for w in Ws]
         Xd, yd = X.cuda(), y.cuda()
@@ -104,8 +105,9 @@ def test_bf16_in_core(oracle, dims, batch, T):
 @pytest.mark.parametrize("dims,batch,T,frac", [([512, 1024, 768, 2000], 384, 256, 0.4),
                                                ([300, 520, 1000], 100, 128, 0.6),
                                                ([512, 2048, 2048, 16384], 512, 256, 0.35)])
-def test_out_of_core(oracle, dims, batch, T, frac, dtype, tdt, tol, lr):
-    announce("mlp ooc", dims, batch, T, frac, "bf16" if dtype else "f32")
+@pytest.mark.parametrize("cfg", [0, 3])
+def test_out_of_core(oracle, dims, batch, T, frac, dtype, tdt, tol, lr, cfg):
+    announce("mlp ooc", dims, batch, T, frac, "bf16" if dtype else "f32", "cfg", cfg)
     X, Ws, y = _net(dims, batch, tdt)
     es = 2 if dtype == tg.TGEMM_BF16 else 4
     n_tiles = sum((-(-dims[l] // T)) * (-(-dims[l + 1] // T)) for l in range(len(Ws)))
@@ -113,7 +115,7 @@ def test_out_of_core(oracle, dims, batch, T, frac, dtype, tdt, tol, lr):
     n_slots = max(int(frac * n_tiles), 2 * max_tiles + 2)
     assert n_slots < n_tiles                                         # genuinely out-of-core
     budget = _workspace_bytes(dims, batch, es, T, True) + n_slots * T * T * es
-    ctx = tg.tgemm_create(0)
+    ctx = tg.tgemm_create(0, kernel_config=cfg)
     try:
         Wp = [w.clone().pin_memory() for w in Ws]
         Xd, yd = X.cuda(), y.cuda()
