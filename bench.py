@@ -142,13 +142,17 @@ def run_mlp(args, tg, inputs, torch, dims, batch, T, bf16, budget):
             w = inputs.normal_matrix(10 + l, dims[l], dims[l + 1], std=0.01, device="cuda").to(dt)
         W.append(w)
     torch.cuda.synchronize()
-    ctx = tg.tgemm_create(0, kernel_config=args.kernel_config)
+    # out-of-core: the write-back of a step's updated tiles may overlap the next step's forward pass;
+    # tgemm_sync inside the timed region waits for the last of them
+    ctx = tg.tgemm_create(0, kernel_config=args.kernel_config, deferred_writeback=0 if args.sync_writeback else 1)
     mlp = tg.mlp_create(ctx, dims, W, tg.TGEMM_BF16 if bf16 else tg.TGEMM_F32, T, hbm_budget=budget)
     for _ in range(args.warmup):
         tg.mlp_step(mlp, X, y, batch, 0.01)
+    tg.tgemm_sync(ctx)
     t0 = time.perf_counter()
     for _ in range(args.steps):
         loss = tg.mlp_step(mlp, X, y, batch, 0.01)
+    tg.tgemm_sync(ctx)
     wall = time.perf_counter() - t0
     st = tg.tgemm_last_stats(ctx)
     tg.mlp_destroy(mlp)
@@ -185,6 +189,8 @@ def main():
     ap.add_argument("--order", type=int, default=2, choices=[0, 1, 2],
                     help="out-of-core task order: 0 serpentine, 1 row-major, 2 strips (default)")
     ap.add_argument("--strip", type=int, default=0, help="strip width for --order 2; 0 = from the slot count")
+    ap.add_argument("--sync-writeback", action="store_true",
+                    help="out-of-core MLP: every step waits for its weight write-back (default: deferred)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run 5 plain device copies of 256 MiB (a known-size reference for HBM counters)")

@@ -71,7 +71,11 @@ typedef struct tgemm_opts {
     int32_t kernel_config; /* 0: automatic; 1..3 force a macro-tile shape (small, medium, large);
                               4: large, bf16 register-staged kernel even where the direct-to-LDS one applies */
     int32_t strip_width;   /* TGEMM_ORDER_STRIPS: tile columns per strip; 0 = from the slot count */
-    int32_t reserved[2];
+    int32_t deferred_writeback; /* 1: an out-of-core mlp_step returns once its kernels are done and lets
+                              the write-back of updated weight tiles run on into the next call; the
+                              host weights are complete after tgemm_sync, mlp_forward, mlp_backward
+                              or mlp_destroy */
+    int32_t reserved[1];
 } tgemm_opts;
 
 /* One output tile C_ij = one task (section 3.1; Algorithm 1, "decode").
@@ -172,7 +176,9 @@ int tgemm_queue_selftest(int64_t n, int32_t producers, int32_t consumers, int32_
  *            Pinned host pointers: out-of-core.  T x T weight tiles are staged through an HBM tile
  *            cache (LRU, section 3.4); the forward pass fetches each tile once, the backward pass
  *            uses a tile for D W^T, updates it and writes it back.  On return of every call the
- *            host weights are complete and no modified tile remains only on the device.
+ *            host weights are complete and no modified tile remains only on the device (with
+ *            opts.deferred_writeback an mlp_step leaves its last write-backs in flight; they are
+ *            ordered before any later use of the tile and complete by tgemm_sync).
  *   dtype    TGEMM_F32, or TGEMM_BF16: weights, X, activations and errors are bf16, logits,
  *            probabilities, dW outputs and all accumulation float; the updated weights are
  *            bf16_round_to_nearest_even(float(W) - lr * dW).

@@ -24,7 +24,8 @@ EXPORTS = [
 class tgemm_opts(ctypes.Structure):
     _fields_ = [("trace", ctypes.c_int32), ("order", ctypes.c_int32), ("affinity_core", ctypes.c_int32),
                 ("async_incore", ctypes.c_int32), ("kernel_config", ctypes.c_int32),
-                ("strip_width", ctypes.c_int32), ("reserved", ctypes.c_int32 * 2)]
+                ("strip_width", ctypes.c_int32), ("deferred_writeback", ctypes.c_int32),
+                ("reserved", ctypes.c_int32 * 1)]
 
 
 class tgemm_task(ctypes.Structure):
@@ -114,10 +115,11 @@ def tgemm_last_error():
 
 
 def tgemm_create(device=0, streams=None, trace=0, order=TGEMM_ORDER_STRIPS, affinity_core=-1,
-                 async_incore=0, kernel_config=0, strip_width=0):
+                 async_incore=0, kernel_config=0, strip_width=0, deferred_writeback=0):
     lib = load()
     o = tgemm_opts(trace=trace, order=order, affinity_core=affinity_core, async_incore=async_incore,
-                   kernel_config=kernel_config, strip_width=strip_width)
+                   kernel_config=kernel_config, strip_width=strip_width,
+                   deferred_writeback=deferred_writeback)
     arr = None
     if streams is not None:
         if len(streams) != 4:

@@ -21,6 +21,7 @@
 
 #include <algorithm>
 #include <chrono>
+#include <deque>
 #include <unordered_map>
 #include <vector>
 
@@ -33,60 +34,145 @@ namespace {
 // ---- weight tile cache (out-of-core mode) -------------------------------------------------------
 struct WSlot {
     int64_t key = -1;
-    hipEvent_t ready = nullptr;      // fetch finished (stream 0)
-    hipEvent_t read = nullptr;       // last product using the tile finished (stream 1)
-    hipEvent_t flushed = nullptr;    // write-back finished (stream 3)
+    hipEvent_t ready = nullptr;      // fetch finished (stream 0); owned by the slot
+    // Events of whole launches / whole write-back groups (not owned, recycled by their owners): a
+    // recycled event stands for newer work, so waiting on it waits at least long enough.
+    hipEvent_t read = nullptr;       // the last product using the tile finished (stream 1)
+    hipEvent_t flushed = nullptr;    // its write-back finished (stream 3)
     bool read_pending = false, flush_pending = false;
-    int prev = -1, next = -1;
+    int64_t pos_f = -1, pos_b = -1;  // the tile's place in the forward / backward sweep of a training step
+    int64_t last_launch = -1;        // launch group that used the slot last
+    int64_t fetch_seq = 0, read_seq = 0, flush_seq = 0;   // sequence numbers of its fetch / pending read / write-back
 };
 
+// Replacement: a training step sweeps every weight tile twice in a fixed order (forward: layer by
+// layer, tile column by tile column; backward: layers in reverse, tile row by tile row), so the
+// next use of every cached tile is known.  The victim is the tile whose next use lies farthest
+// ahead (for a cyclic sweep over more tiles than slots, LRU evicts exactly the tiles needed next
+// and misses about twice as often).  Tiles of the launch being assembled are never evicted, and
+// tiles that a launch still reads or whose write-back is still in flight are passed over while
+// any settled slot is left, so that fetches keep running ahead of the products instead of
+// queueing behind the write-back stream.
 struct WeightCache {
     char* pool = nullptr;
     size_t slot_bytes = 0;
     int n_slots = 0, n_used = 0;
     std::vector<WSlot> slots;
     std::unordered_map<int64_t, int> dir;
-    int lru_head = -1, lru_tail = -1;
+    int64_t period = 0;                      // accesses per training step (two per tile)
+    int64_t launch_id = 0;                   // current launch group (one tile column / tile row)
+    std::vector<int64_t> base_f, base_b;     // first sweep position of layer l, forward / backward
+    // Reads finish in launch order and write-backs in issue order (one stream each), so "has this
+    // slot's last read / write-back finished" is a comparison with the newest finished sequence
+    // number; the queues hold (sequence number, event) of what is still in flight.
+    struct InFlight { int64_t seq; hipEvent_t ev; };
+    std::deque<InFlight> reads, flushes;
+    int64_t read_issue = 0, read_done = 0, flush_issue = 0, flush_done = 0;
+    int64_t fetch_issue = 0, fetch_waited = 0;   // fetches issued; newest one the compute stream waits for
+    std::vector<hipEvent_t> flush_pool;      // one event per write-back group, reused round robin
+    size_t flush_next = 0;
 
     ~WeightCache() { release(); }
     void release()
     {
-        for (auto& s : slots) {
+        for (auto& s : slots)
             if (s.ready) (void)hipEventDestroy(s.ready);
-            if (s.read) (void)hipEventDestroy(s.read);
-            if (s.flushed) (void)hipEventDestroy(s.flushed);
-        }
         slots.clear();
+        for (auto& e : flush_pool)
+            if (e) (void)hipEventDestroy(e);
+        flush_pool.clear();
+        flush_next = 0;
+        fetch_issue = fetch_waited = 0;
         if (pool) (void)hipFree(pool);
         pool = nullptr;
         dir.clear();
         n_slots = n_used = 0;
-        lru_head = lru_tail = -1;
+        launch_id = 0;
+        reads.clear(); flushes.clear();
+        read_issue = read_done = flush_issue = flush_done = 0;
     }
     char* ptr(int slot) const { return pool + (size_t)slot * slot_bytes; }
-    void unlink(int i)
+    void all_reads_done() { reads.clear(); read_done = read_issue; }
+    void reads_done_upto(int64_t seq)
     {
-        WSlot& s = slots[i];
-        if (s.prev >= 0) slots[s.prev].next = s.next; else lru_head = s.next;
-        if (s.next >= 0) slots[s.next].prev = s.prev; else lru_tail = s.prev;
-        s.prev = s.next = -1;
+        while (!reads.empty() && reads.front().seq <= seq) reads.pop_front();
+        read_done = std::max(read_done, seq);
     }
-    void push_mru(int i)
+    // An event for the next write-back group: the pool's next one, once it is out of the queue.
+    int next_flush_event(hipEvent_t* out)
     {
-        WSlot& s = slots[i];
-        s.prev = lru_tail;
-        s.next = -1;
-        if (lru_tail >= 0) slots[lru_tail].next = i; else lru_head = i;
-        lru_tail = i;
+        hipEvent_t e = flush_pool[flush_next];
+        flush_next = (flush_next + 1) % flush_pool.size();
+        while (!flushes.empty() && flushes.size() >= flush_pool.size()) {
+            TG_HIP(hipEventSynchronize(flushes.front().ev));
+            flush_done = flushes.front().seq;
+            flushes.pop_front();
+        }
+        *out = e;
+        return TGEMM_OK;
+    }
+    void all_flushes_done() { flushes.clear(); flush_done = flush_issue; }
+    static void advance(std::deque<InFlight>& q, int64_t& done)
+    {
+        while (!q.empty() && hipEventQuery(q.front().ev) == hipSuccess) {
+            done = q.front().seq;
+            q.pop_front();
+        }
+        (void)hipGetLastError();    // hipErrorNotReady from the query is not an error
+    }
+    bool settled(WSlot& s)
+    {
+        if (s.read_pending && s.read_seq <= read_done) s.read_pending = false;
+        if (s.flush_pending && s.flush_seq <= flush_done) s.flush_pending = false;
+        return !s.read_pending && !s.flush_pending;
+    }
+    // accesses from sweep position `cur` until the slot's tile is wanted again
+    int64_t next_use(const WSlot& s, int64_t cur) const
+    {
+        const int64_t df = ((s.pos_f - cur - 1) % period + period) % period;
+        const int64_t db = ((s.pos_b - cur - 1) % period + period) % period;
+        return std::min(df, db);
+    }
+    // Victim for a fetch at sweep position `cur`; -1 if every slot belongs to the current launch.
+    // Candidates are the slots whose next use is at least half as far away as the farthest one.
+    // Among them a settled slot (no read or write-back in flight) with the farthest next use wins.
+    // If none is settled -- the host queues launches well ahead of the GPU, so every cached tile may
+    // still have work queued -- the one whose pending work finishes first: a slot that only waits
+    // for reads (the one used longest ago) before any slot with a write-back queued (write-backs
+    // trail the products by a long queue, and a fetch waiting for one holds up every later fetch).
+    int pick_victim(int64_t cur)
+    {
+        advance(reads, read_done);
+        advance(flushes, flush_done);
+        int64_t dmax = -1;
+        for (int i = 0; i < n_slots; ++i)
+            if (slots[i].last_launch != launch_id) dmax = std::max(dmax, next_use(slots[i], cur));
+        if (dmax < 0) return -1;
+        int best_settled = -1, oldest = -1;
+        int64_t bsd = -1;
+        for (int i = 0; i < n_slots; ++i) {
+            WSlot& s = slots[i];
+            if (s.last_launch == launch_id) continue;
+            const int64_t d = next_use(s, cur);
+            if (2 * d < dmax) continue;
+            const bool is_settled = settled(s);     // also refreshes the pending flags
+            if (d > bsd && is_settled) { bsd = d; best_settled = i; }
+            if (oldest < 0) { oldest = i; continue; }
+            const WSlot& o = slots[oldest];
+            if (s.flush_pending != o.flush_pending) { if (!s.flush_pending) oldest = i; }
+            else if (s.flush_pending ? s.flush_seq < o.flush_seq : s.last_launch < o.last_launch) oldest = i;
+        }
+        return best_settled >= 0 ? best_settled : oldest;
     }
 };
 
 struct TableRing {
-    static constexpr int N = 32;
+    static constexpr int N = 96;
     void** dev[N] = {};
     void** host[N] = {};
     hipEvent_t done[N] = {};
     bool used[N] = {};
+    int64_t seq[N] = {};     // read sequence number of the launch that used the entry last
     int next = 0;
     int cap = 0;   // pointers per entry
 };
@@ -250,15 +336,20 @@ int ensure_workspaces(tgemm_mlp* m, int64_t batch)
     if (ok && m->ooc) {
         WeightCache& c = m->cache;
         c.slot_bytes = slot_bytes;
+        c.base_f.assign((size_t)L + 2, 0);
+        c.base_b.assign((size_t)L + 2, 0);
+        const int64_t all = total_tiles(m);
+        c.period = 2 * all;
+        int64_t at = 0;
+        for (int l = 1; l <= L; ++l) { c.base_f[(size_t)l] = at; at += cdiv(m->dims[l - 1], m->T) * cdiv(m->dims[l], m->T); }
+        for (int l = L; l >= 1; --l) { c.base_b[(size_t)l] = at; at += cdiv(m->dims[l - 1], m->T) * cdiv(m->dims[l], m->T); }
         ok = alloc((void**)&c.pool, (size_t)n_slots * slot_bytes);
         if (ok) {
             c.n_slots = (int)n_slots;
             c.slots.resize((size_t)n_slots);
-            for (auto& s : c.slots) {
-                ok = ok && hipEventCreateWithFlags(&s.ready, hipEventDisableTiming) == hipSuccess &&
-                     hipEventCreateWithFlags(&s.read, hipEventDisableTiming) == hipSuccess &&
-                     hipEventCreateWithFlags(&s.flushed, hipEventDisableTiming) == hipSuccess;
-            }
+            for (auto& s : c.slots) ok = ok && hipEventCreateWithFlags(&s.ready, hipEventDisableTiming) == hipSuccess;
+            c.flush_pool.assign(256, nullptr);
+            for (auto& e : c.flush_pool) ok = ok && hipEventCreateWithFlags(&e, hipEventDisableTiming) == hipSuccess;
         }
         TableRing& r = m->ring;
         r.cap = (int)max_tiles;
@@ -280,16 +371,19 @@ int ensure_workspaces(tgemm_mlp* m, int64_t batch)
 // ---- out-of-core helpers ------------------------------------------------------------------------
 
 // Tile (r, c) of W_l into the cache (section 3.4: hit -> use it, miss -> fetch from host memory).
-int acquire_tile(tgemm_mlp* m, int l, int64_t r, int64_t c, int* slot_out)
+// bwd: the access belongs to the backward sweep.
+int acquire_tile(tgemm_mlp* m, int l, int64_t r, int64_t c, bool bwd, int* slot_out)
 {
     WeightCache& wc = m->cache;
     tgemm_ctx* ctx = m->ctx;
     hipStream_t fetch = ctx->streams[0];
     const int64_t key = wkey(l, r, c);
+    const int64_t T = m->T, nc = m->dims[l];
+    const int64_t n_r = cdiv(m->dims[l - 1], T), n_c = cdiv(nc, T);
+    const int64_t pos_f = wc.base_f[(size_t)l] + c * n_r + r, pos_b = wc.base_b[(size_t)l] + r * n_c + c;
     auto it = wc.dir.find(key);
     if (it != wc.dir.end()) {
-        wc.unlink(it->second);
-        wc.push_mru(it->second);
+        wc.slots[it->second].last_launch = wc.launch_id;
         ctx->stats.hits++;
         *slot_out = it->second;
         return TGEMM_OK;
@@ -299,26 +393,29 @@ int acquire_tile(tgemm_mlp* m, int l, int64_t r, int64_t c, int* slot_out)
     if (wc.n_used < wc.n_slots) {
         slot = wc.n_used++;
     } else {
-        slot = wc.lru_head;
-        wc.unlink(slot);
-        wc.dir.erase(wc.slots[slot].key);
-        ctx->stats.evictions++;
+        slot = wc.pick_victim(bwd ? pos_b : pos_f);
+        if (slot < 0) return fail(TGEMM_EBUDGET, "mlp: the weight-tile cache cannot hold the tiles of one launch");
         WSlot& s = wc.slots[slot];
+        wc.dir.erase(s.key);
+        ctx->stats.evictions++;
+        (void)wc.settled(s);      // the flags are fresh: a pending one's event has not been recycled
         if (s.read_pending) TG_HIP(hipStreamWaitEvent(fetch, s.read, 0));
         if (s.flush_pending) TG_HIP(hipStreamWaitEvent(fetch, s.flushed, 0));
         s.read_pending = s.flush_pending = false;
     }
     WSlot& s = wc.slots[slot];
     s.key = key;
+    s.pos_f = pos_f;
+    s.pos_b = pos_b;
+    s.last_launch = wc.launch_id;
     wc.dir[key] = slot;
-    wc.push_mru(slot);
-    const int64_t T = m->T, nc = m->dims[l];
     const int64_t rows = std::min(T, m->dims[l - 1] - r * T), cols = std::min(T, nc - c * T);
     const char* src = m->W[l - 1] + ((size_t)(r * T) * nc + (size_t)c * T) * m->es;
     TG_HIP(hipMemcpy2DAsync(wc.ptr(slot), (size_t)T * m->es, src, (size_t)nc * m->es, (size_t)cols * m->es, (size_t)rows,
                             hipMemcpyHostToDevice, fetch));
     ctx->stats.h2d_bytes += rows * cols * (int64_t)m->es;
     TG_HIP(hipEventRecord(s.ready, fetch));
+    s.fetch_seq = ++wc.fetch_issue;
     *slot_out = slot;
     return TGEMM_OK;
 }
@@ -330,7 +427,10 @@ int ring_claim(tgemm_mlp* m, int* entry)
     TableRing& r = m->ring;
     const int e = r.next;
     r.next = (r.next + 1) % TableRing::N;
-    if (r.used[e]) TG_HIP(hipEventSynchronize(r.done[e]));
+    if (r.used[e]) {
+        TG_HIP(hipEventSynchronize(r.done[e]));
+        m->cache.reads_done_upto(r.seq[e]);      // launches finish in order
+    }
     r.used[e] = false;
     *entry = e;
     return TGEMM_OK;
@@ -341,10 +441,18 @@ int ring_claim(tgemm_mlp* m, int* entry)
 int ring_publish(tgemm_mlp* m, int entry, const int* tile_slots, int n)
 {
     TableRing& r = m->ring;
+    WeightCache& wc = m->cache;
     hipStream_t comp = m->ctx->streams[1];
+    // fetches complete in issue order: waiting for the newest of the launch's tiles covers all
+    int newest = -1;
     for (int i = 0; i < n; ++i) {
-        r.host[entry][i] = m->cache.ptr(tile_slots[i]);
-        TG_HIP(hipStreamWaitEvent(comp, m->cache.slots[tile_slots[i]].ready, 0));
+        r.host[entry][i] = wc.ptr(tile_slots[i]);
+        const WSlot& s = wc.slots[tile_slots[i]];
+        if (s.fetch_seq > wc.fetch_waited && (newest < 0 || s.fetch_seq > wc.slots[newest].fetch_seq)) newest = tile_slots[i];
+    }
+    if (newest >= 0) {
+        TG_HIP(hipStreamWaitEvent(comp, wc.slots[newest].ready, 0));
+        wc.fetch_waited = wc.slots[newest].fetch_seq;
     }
     TG_HIP(hipMemcpyAsync(r.dev[entry], r.host[entry], (size_t)n * sizeof(void*), hipMemcpyHostToDevice, comp));
     return TGEMM_OK;
@@ -356,11 +464,16 @@ int ring_finish(tgemm_mlp* m, int entry, const int* tile_slots, int n)
     hipStream_t comp = m->ctx->streams[1];
     TG_HIP(hipEventRecord(r.done[entry], comp));
     r.used[entry] = true;
+    WeightCache& wc = m->cache;
+    const int64_t seq = ++wc.read_issue;
+    r.seq[entry] = seq;
     for (int i = 0; i < n; ++i) {
-        WSlot& s = m->cache.slots[tile_slots[i]];
-        TG_HIP(hipEventRecord(s.read, comp));
+        WSlot& s = wc.slots[tile_slots[i]];
+        s.read = r.done[entry];
         s.read_pending = true;
+        s.read_seq = seq;
     }
+    wc.reads.push_back({seq, r.done[entry]});
     return TGEMM_OK;
 }
 
@@ -405,7 +518,7 @@ int forward_layer(tgemm_mlp* m, int l, const char* in, int64_t batch)
         int entry, rc;
         if ((rc = ring_claim(m, &entry)) != TGEMM_OK) return rc;
         for (int64_t k = 0; k < n_k; ++k)
-            if ((rc = acquire_tile(m, l, k, j, &tiles[(size_t)k])) != TGEMM_OK) return rc;
+            if ((rc = acquire_tile(m, l, k, j, false, &tiles[(size_t)k])) != TGEMM_OK) return rc;
         if ((rc = ring_publish(m, entry, tiles.data(), (int)n_k)) != TGEMM_OK) return rc;
         d.b_tiles = (const void* const*)m->ring.dev[entry];
         d.B = m->cache.ptr(tiles[0]); d.ldb = T;
@@ -413,6 +526,7 @@ int forward_layer(tgemm_mlp* m, int l, const char* in, int64_t batch)
         d.N = std::min(T, m->dims[l] - j * T);
         if ((rc = launch(m, d, compute_stream(m))) != TGEMM_OK) return rc;
         if ((rc = ring_finish(m, entry, tiles.data(), (int)n_k)) != TGEMM_OK) return rc;
+        ++m->cache.launch_id;
     }
     return TGEMM_OK;
 }
@@ -451,6 +565,23 @@ int sync_all(tgemm_mlp* m)
 {
     for (int s = 0; s < 4; ++s) TG_HIP(hipStreamSynchronize(m->ctx->streams[s]));
     for (auto& s : m->cache.slots) s.read_pending = s.flush_pending = false;
+    m->cache.all_reads_done();
+    m->cache.all_flushes_done();
+    m->cache.fetch_waited = m->cache.fetch_issue;
+    for (auto& u : m->ring.used) u = false;
+    return TGEMM_OK;
+}
+
+// End of a step with deferred write-back: fetches and kernels are complete, the write-backs queued on
+// the flush stream are not.  A slot keeps flush_pending; whoever overwrites it next (an eviction's
+// fetch, the next update) waits for its `flushed` event first.
+int sync_compute(tgemm_mlp* m)
+{
+    for (int s = 0; s < 3; ++s) TG_HIP(hipStreamSynchronize(m->ctx->streams[s]));
+    for (auto& s : m->cache.slots) s.read_pending = false;
+    m->cache.all_reads_done();
+    m->cache.fetch_waited = m->cache.fetch_issue;
+    WeightCache::advance(m->cache.flushes, m->cache.flush_done);     // keeps the queue to what is in flight
     for (auto& u : m->ring.used) u = false;
     return TGEMM_OK;
 }
@@ -521,7 +652,7 @@ int backward_layer(tgemm_mlp* m, int l, float* dW_out, bool update, float lr)
         const bool need_tiles = (l > 1) || update;
         if (need_tiles)
             for (int64_t c = 0; c < n_c; ++c)
-                if ((rc = acquire_tile(m, l, r, c, &tiles[(size_t)c])) != TGEMM_OK) return rc;
+                if ((rc = acquire_tile(m, l, r, c, true, &tiles[(size_t)c])) != TGEMM_OK) return rc;
         if (l > 1) {
             if ((rc = ring_claim(m, &entry)) != TGEMM_OK) return rc;
             if ((rc = ring_publish(m, entry, tiles.data(), (int)n_c)) != TGEMM_OK) return rc;
@@ -536,6 +667,17 @@ int backward_layer(tgemm_mlp* m, int l, float* dW_out, bool update, float lr)
         dw.A = a_prev + (size_t)(r * T) * m->es;
         dw.M = rows;
         if (update) {
+            // a write-back of the previous step may still be reading these tiles
+            WeightCache::advance(m->cache.flushes, m->cache.flush_done);
+            hipEvent_t waited = nullptr;
+            for (int64_t c = 0; c < n_c; ++c) {
+                WSlot& s = m->cache.slots[tiles[(size_t)c]];
+                (void)m->cache.settled(s);
+                if (s.flush_pending && s.flushed != waited) {
+                    TG_HIP(hipStreamWaitEvent(comp, s.flushed, 0));
+                    waited = s.flushed;
+                }
+            }
             if ((rc = ring_claim(m, &entry)) != TGEMM_OK) return rc;
             if ((rc = ring_publish(m, entry, tiles.data(), (int)n_c)) != TGEMM_OK) return rc;
             dw.c_tiles = (void* const*)m->ring.dev[entry];
@@ -545,6 +687,9 @@ int backward_layer(tgemm_mlp* m, int l, float* dW_out, bool update, float lr)
             if ((rc = ring_finish(m, entry, tiles.data(), (int)n_c)) != TGEMM_OK) return rc;
             // write the updated row of tiles back (stream 3) once the launch has finished
             TG_HIP(hipStreamWaitEvent(flush, m->ring.done[entry], 0));
+            hipEvent_t group;
+            if ((rc = m->cache.next_flush_event(&group)) != TGEMM_OK) return rc;
+            const int64_t flush_seq = ++m->cache.flush_issue;
             for (int64_t c = 0; c < n_c; ++c) {
                 const int64_t cols = std::min(T, m->dims[l] - c * T);
                 char* dst = m->W[l - 1] + ((size_t)(r * T) * m->dims[l] + (size_t)c * T) * m->es;
@@ -552,15 +697,19 @@ int backward_layer(tgemm_mlp* m, int l, float* dW_out, bool update, float lr)
                                         (size_t)cols * m->es, (size_t)rows, hipMemcpyDeviceToHost, flush));
                 m->ctx->stats.d2h_bytes += rows * cols * (int64_t)m->es;
                 WSlot& s = m->cache.slots[tiles[(size_t)c]];
-                TG_HIP(hipEventRecord(s.flushed, flush));
+                s.flushed = group;
                 s.flush_pending = true;
+                s.flush_seq = flush_seq;
             }
+            TG_HIP(hipEventRecord(group, flush));
+            m->cache.flushes.push_back({flush_seq, group});
         } else if (dW_out) {
             dw.c_tiles = nullptr;
             dw.C = dW_out + (size_t)(r * T) * m->dims[l]; dw.ldc = m->dims[l];
             dw.alpha = 1.f; dw.beta = 0.f; dw.out_bf16 = 0;
             if ((rc = launch(m, dw, comp)) != TGEMM_OK) return rc;
         }
+        ++m->cache.launch_id;
     }
     return TGEMM_OK;
 }
@@ -688,7 +837,7 @@ int mlp_step(tgemm_mlp* m, const void* X, const int32_t* labels, int64_t batch, 
     if ((rc = softmax(m, labels, nullptr, true)) != TGEMM_OK) return rc;
     if ((rc = backward(m, nullptr, true, lr)) != TGEMM_OK) return rc;
     if ((rc = read_loss(m, loss)) != TGEMM_OK) return rc;
-    if ((rc = sync_all(m)) != TGEMM_OK) return rc;
+    if ((rc = (m->ooc && m->ctx->opts.deferred_writeback) ? sync_compute(m) : sync_all(m)) != TGEMM_OK) return rc;
     m->have_delta = true;
     m->ctx->stats.wall_ms = now_ms() - t0;
     return TGEMM_OK;

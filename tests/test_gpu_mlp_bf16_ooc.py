@@ -38,13 +38,22 @@ def _read(mlp, what, layer, rows, cols, dtype):
     return _f64(out)
 
 
+def _step_sweep(dims, T):
+    """Weight tiles in the order one training step touches them."""
+    cd = lambda a: -(-a // T)
+    L = len(dims) - 1
+    seq = [(l, k, j) for l in range(1, L + 1) for j in range(cd(dims[l])) for k in range(cd(dims[l - 1]))]
+    seq += [(l, r, c) for l in range(L, 0, -1) for r in range(cd(dims[l - 1])) for c in range(cd(dims[l]))]
+    return seq
+
+
 def _workspace_bytes(dims, batch, es, T, ooc):
     L = len(dims) - 1
     total = batch * 4 + batch * dims[L] * 4
     for l in range(1, L + 1):
         total += batch * dims[l] * es * (2 if l < L else 1)
     if ooc:
-        total += 32 * max(-(-d // T) for d in dims) * 8
+        total += 96 * max(-(-d // T) for d in dims) * 8
     return total
 
 
@@ -145,7 +154,51 @@ def test_out_of_core(oracle, dims, batch, T, frac, dtype, tdt, tol, lr, cfg):
         assert l_ooc == l_ic
         for l in range(len(Ws)):
             assert torch.equal(Wd[l].cpu(), Wp[l]), ("second step", l)
+        # steady state: the cache evicts by next use in the step's fixed sweep (forward: tile columns
+        # layer by layer; backward: tile rows, layers reversed) and must not miss more often than
+        # strict LRU would on the same sweep, nor less often than the tiles that cannot fit
+        tg.mlp_step(mlp, Xd, yd, batch, lr)
+        st = tg.tgemm_last_stats(ctx)
+        sweep = _step_sweep(dims, T)
+        _, lru = oracle.lru_simulate(sweep * 4, n_slots)
+        _, lru3 = oracle.lru_simulate(sweep * 3, n_slots)
+        lru_per_step = lru["misses"] - lru3["misses"]
+        print("misses per step", st["misses"], "strict LRU", lru_per_step, "tiles", n_tiles, "slots", n_slots)
+        assert st["hits"] + st["misses"] == 2 * n_tiles
+        assert n_tiles - n_slots <= st["misses"] <= lru_per_step
         tg.mlp_destroy(ref)
         tg.mlp_destroy(mlp)
     finally:
         tg.tgemm_destroy(ctx)
+
+
+@pytest.mark.parametrize("dtype,tdt", [(tg.TGEMM_F32, torch.float32), (tg.TGEMM_BF16, torch.bfloat16)])
+def test_deferred_writeback_gives_the_same_weights(dtype, tdt):
+    """With deferred write-back a step returns while its updated tiles still travel to the host; they
+    must be ordered before the next step's update of the same slot and before any re-fetch, so after
+    tgemm_sync the host weights and the losses equal those of the synchronous mode bit for bit."""
+    dims, batch, T = [512, 1024, 768, 2000], 384, 256
+    announce("mlp ooc deferred write-back", dims, batch, T, "bf16" if dtype else "f32")
+    X, Ws, y = _net(dims, batch, tdt)
+    es = 2 if dtype == tg.TGEMM_BF16 else 4
+    n_tiles = sum((-(-dims[l] // T)) * (-(-dims[l + 1] // T)) for l in range(len(Ws)))
+    n_slots = max(int(0.4 * n_tiles), 2 * max(-(-d // T) for d in dims) + 2)
+    budget = _workspace_bytes(dims, batch, es, T, True) + n_slots * T * T * es
+    Xd, yd = X.cuda(), y.cuda()
+    torch.cuda.synchronize()
+    results = []
+    for deferred in (0, 1):
+        ctx = tg.tgemm_create(0, deferred_writeback=deferred)
+        try:
+            Wp = [w.clone().pin_memory() for w in Ws]
+            mlp = tg.mlp_create(ctx, dims, Wp, dtype, T, hbm_budget=budget)
+            losses = [tg.mlp_step(mlp, Xd, yd, batch, 0.5) for _ in range(4)]
+            tg.tgemm_sync(ctx)
+            results.append((losses, [w.clone() for w in Wp]))
+            tg.mlp_destroy(mlp)
+        finally:
+            tg.tgemm_destroy(ctx)
+    assert results[0][0] == results[1][0]
+    for l in range(len(Ws)):
+        assert torch.equal(results[0][1][l], results[1][1][l]), ("weights", l)
+        assert not torch.equal(results[0][1][l], Ws[l])              # the steps did change them
