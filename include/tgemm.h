@@ -194,6 +194,17 @@ int mlp_create(tgemm_ctx* ctx, tgemm_mlp** out, int32_t n_layers, const int64_t*
                void* const* W, int32_t dtype, int32_t T, size_t hbm_budget);
 int mlp_destroy(tgemm_mlp* mlp);
 
+/* Hidden-layer activation (section 2 leaves the function open: the passes stay matrix products
+ * whatever it is).  A_l = act(Z_l) in the forward product's epilogue; the backward pass multiplies
+ * by the slope written in terms of the stored activation a = act(z):
+ *   TGEMM_ACT_SIGMOID  1 / (1 + exp(-z)),  slope a (1 - a)     (default)
+ *   TGEMM_ACT_TANH     tanh(z),            slope 1 - a^2
+ *   TGEMM_ACT_RELU     max(0, z),          slope 1 where a > 0, else 0
+ * Takes effect from the next mlp_forward / mlp_step; a pending forward pass is discarded
+ * (mlp_backward then reports TGEMM_ESTATE).  TGEMM_EARG for an unknown code. */
+enum { TGEMM_ACT_SIGMOID = 0, TGEMM_ACT_TANH = 1, TGEMM_ACT_RELU = 2 };
+int mlp_set_activation(tgemm_mlp* mlp, int32_t act);
+
 /* Equation 1 for every layer: Z_l = A_{l-1} W_l, A_l = sigmoid(Z_l); last layer: logits.
  *   X      device pointer, batch x dims[0], dtype elements.
  *   probs  NULL, or device pointer to batch x dims[n_layers] floats receiving softmax(logits). */

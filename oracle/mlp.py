@@ -9,11 +9,12 @@ The equations themselves are not printed, so the textbook forms are taken:
 
     A_0 = X                               [batch x n_0]
     Z_l = A_{l-1} W_l                     l = 1..L      (no bias)
-    A_l = sigmoid(Z_l)                    l < L
+    A_l = act(Z_l)                        l < L      (act: sigmoid by default; tanh, relu)
     P   = softmax over each row of Z_L;   loss = -mean_b log P[b, y_b]
     D_L = (P - onehot(y)) / batch
     dW_l     = A_{l-1}^T D_l
-    dA_{l-1} = D_l W_l^T ;   D_{l-1} = dA_{l-1} * A_{l-1} * (1 - A_{l-1})
+    dA_{l-1} = D_l W_l^T ;   D_{l-1} = dA_{l-1} * act'(Z_{l-1})
+             act' = A (1 - A) for the sigmoid, 1 - A^2 for tanh, [Z > 0] for relu
     W_l <- W_l - lr * dW_l               (every dW from the pre-update weights)
 
 numpy's fp64 matmul is the library primitive used for the products.
@@ -30,37 +31,63 @@ def _f64(a):
     return a.astype(np.float64)
 
 
-def mlp_forward(X, Ws):
-    """Returns (acts, logits, probs): acts[l] is the input of layer l+1 (acts[0] = X)."""
+def _act(z, act):
+    if act == "sigmoid":
+        return 1.0 / (1.0 + np.exp(-z))
+    if act == "tanh":
+        return np.tanh(z)
+    if act == "relu":
+        return np.where(z > 0.0, z, 0.0)
+    raise ValueError(act)
+
+
+def _act_slope(z, a, act):
+    """d act / d z at pre-activation z (a = act(z))."""
+    if act == "sigmoid":
+        return a * (1.0 - a)
+    if act == "tanh":
+        return 1.0 - a * a
+    if act == "relu":
+        return (z > 0.0).astype(np.float64)
+    raise ValueError(act)
+
+
+def mlp_forward(X, Ws, act="sigmoid", return_pre=False):
+    """Returns (acts, logits, probs): acts[l] is the input of layer l+1 (acts[0] = X).
+    With return_pre also the hidden pre-activations Z_l as a fourth value."""
     a = _f64(X)
     acts = [a]
+    pre = [None]
     L = len(Ws)
     z = None
     for l, W in enumerate(Ws):
         z = a @ _f64(W)
         if l < L - 1:
-            a = 1.0 / (1.0 + np.exp(-z))
+            a = _act(z, act)
             acts.append(a)
+            pre.append(z)
     zmax = z.max(axis=1, keepdims=True)
     e = np.exp(z - zmax)
     probs = e / e.sum(axis=1, keepdims=True)
+    if return_pre:
+        return acts, z, probs, pre
     return acts, z, probs
 
 
-def mlp_loss(X, Ws, y):
-    _, z, _ = mlp_forward(X, Ws)
+def mlp_loss(X, Ws, y, act="sigmoid"):
+    _, z, _ = mlp_forward(X, Ws, act)
     y = np.asarray(y, dtype=np.int64)
     zmax = z.max(axis=1)
     lse = zmax + np.log(np.exp(z - zmax[:, None]).sum(axis=1))
     return float(np.mean(lse - z[np.arange(z.shape[0]), y]))
 
 
-def mlp_backward(X, Ws, y):
+def mlp_backward(X, Ws, y, act="sigmoid"):
     """Returns (loss, dWs, deltas): deltas[l] is the error at the output of layer l+1."""
-    acts, z, probs = mlp_forward(X, Ws)
+    acts, z, probs, pre = mlp_forward(X, Ws, act, return_pre=True)
     y = np.asarray(y, dtype=np.int64)
     B = z.shape[0]
-    loss = mlp_loss(X, Ws, y)
+    loss = mlp_loss(X, Ws, y, act)
     d = probs.copy()
     d[np.arange(B), y] -= 1.0
     d /= B
@@ -72,12 +99,12 @@ def mlp_backward(X, Ws, y):
         dWs[l] = acts[l].T @ d
         if l > 0:
             dA = d @ _f64(Ws[l]).T
-            d = dA * acts[l] * (1.0 - acts[l])
+            d = dA * _act_slope(pre[l], acts[l], act)
     return loss, dWs, deltas
 
 
-def mlp_step(X, Ws, y, lr):
+def mlp_step(X, Ws, y, lr, act="sigmoid"):
     """One SGD step.  Returns (loss before the update, new weights in fp64, dWs)."""
-    loss, dWs, _ = mlp_backward(X, Ws, y)
+    loss, dWs, _ = mlp_backward(X, Ws, y, act)
     new = [_f64(W) - lr * g for W, g in zip(Ws, dWs)]
     return loss, new, dWs

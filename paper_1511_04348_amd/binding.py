@@ -13,11 +13,12 @@ LIB_PATH = os.path.join(_HERE, "libtgemm.so")
 TGEMM_F32, TGEMM_BF16 = 0, 1
 TGEMM_OK, TGEMM_EARG, TGEMM_ENOMEM, TGEMM_EUNPINNED, TGEMM_EBUDGET, TGEMM_EHIP, TGEMM_ESTATE = 0, -1, -2, -3, -4, -5, -6
 TGEMM_ORDER_SERPENTINE, TGEMM_ORDER_ROW_MAJOR, TGEMM_ORDER_STRIPS = 0, 1, 2
+TGEMM_ACT_SIGMOID, TGEMM_ACT_TANH, TGEMM_ACT_RELU = 0, 1, 2
 
 EXPORTS = [
     "tgemm_strerror", "tgemm_last_error", "tgemm_create", "tgemm_destroy", "tgemm_run", "tgemm_sync",
     "tgemm_plan", "tgemm_task_order", "tgemm_last_stats", "tgemm_trace", "tgemm_queue_selftest",
-    "mlp_create", "mlp_destroy", "mlp_forward", "mlp_backward", "mlp_step", "mlp_read",
+    "mlp_create", "mlp_destroy", "mlp_set_activation", "mlp_forward", "mlp_backward", "mlp_step", "mlp_read",
 ]
 
 
@@ -80,6 +81,7 @@ def load():
     lib.tgemm_queue_selftest.argtypes = [i64, i32, i32, P(i32)]
     lib.mlp_create.argtypes = [vp, P(vp), i32, P(i64), P(vp), i32, i32, sz]
     lib.mlp_destroy.argtypes = [vp]
+    lib.mlp_set_activation.argtypes = [vp, i32]
     lib.mlp_forward.argtypes = [vp, vp, i64, vp]
     lib.mlp_backward.argtypes = [vp, vp, P(vp), P(ctypes.c_float)]
     lib.mlp_step.argtypes = [vp, vp, vp, i64, ctypes.c_float, P(ctypes.c_float)]
@@ -191,6 +193,10 @@ def mlp_create(ctx, dims, weights, dtype=TGEMM_F32, T=1024, hbm_budget=0):
 
 def mlp_destroy(mlp):
     _check(load().mlp_destroy(mlp))
+
+
+def mlp_set_activation(mlp, act):
+    _check(load().mlp_set_activation(mlp, act))
 
 
 def mlp_forward(mlp, X, batch, probs=None):

@@ -417,8 +417,8 @@ static hipError_t launch_cfg(GemmParams& p, const GemmDesc& d, hipStream_t strea
 #define TGB_EPI(AK, BKC)                                                            \
     if (d.epilogue == EPI_AXPBY && !d.out_bf16) { TGB_LAUNCH(AK, BKC, EPI_AXPBY, false); }    \
     if (d.epilogue == EPI_AXPBY && d.out_bf16) { TGB_LAUNCH(AK, BKC, EPI_AXPBY, true); }      \
-    if (d.epilogue == EPI_SIGMOID && d.out_bf16) { TGB_LAUNCH(AK, BKC, EPI_SIGMOID, true); }  \
-    if (d.epilogue == EPI_DSIGMOID && d.out_bf16) { TGB_LAUNCH(AK, BKC, EPI_DSIGMOID, true); } \
+    if (d.epilogue == EPI_ACT && d.out_bf16) { TGB_LAUNCH(AK, BKC, EPI_ACT, true); }  \
+    if (d.epilogue == EPI_DACT && d.out_bf16) { TGB_LAUNCH(AK, BKC, EPI_DACT, true); } \
     return hipErrorInvalidValue;
     if (d.a_kcontig && !d.b_kcontig) { TGB_EPI(true, false) }
     if (!d.a_kcontig && !d.b_kcontig) { TGB_EPI(false, false) }
@@ -442,7 +442,7 @@ hipError_t launch_tile_gemm_bf16(const GemmDesc& d, hipStream_t stream)
     const int64_t big = (d.M > d.N ? d.M : d.N) > d.K ? (d.M > d.N ? d.M : d.N) : d.K;
     if (T > big) T = big > 0 ? big : 1;
     p.T = (int)T;
-    p.alpha = d.alpha; p.beta = d.beta;
+    p.alpha = d.alpha; p.beta = d.beta; p.act = d.act;
     p.b_tiles = d.b_tiles; p.c_tiles = d.c_tiles;
     // k-contiguous operands use 16-byte loads (8 elements), m/n-contiguous ones 8-byte loads (4)
     auto ok = [&](const void* q, int64_t ld, bool kc) {

@@ -85,14 +85,14 @@ __device__ inline void epilogue(const GemmParams& p, const TileCoord& t, const f
         if (row >= t.row_end) continue;
         const int64_t crow = (int64_t)row * p.ldc;
         f32x4 in[RB][4];     // C (AXPBY) or the activation (DSIGMOID) at this lane's 4 x RB quads
-        if (read_c || EPI == EPI_DSIGMOID) {
+        if (read_c || EPI == EPI_DACT) {
 #pragma unroll
             for (int cc = 0; cc < RB; ++cc)
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     const int col = wcol0 + 32 * cc + 8 * g + 4 * lh;
                     f32x4 x = {0.f, 0.f, 0.f, 0.f};
-                    if (EPI == EPI_DSIGMOID) {
+                    if (EPI == EPI_DACT) {
                         const uint16_t* src = aux + (int64_t)row * p.ldaux + col;
                         if (vec_aux && col + 3 < t.col_end) {
                             const u32x2 w = gload<u32x2>(src);
@@ -139,11 +139,10 @@ __device__ inline void epilogue(const GemmParams& p, const TileCoord& t, const f
                     float v = acc[r][cc][4 * g + e];
                     if (EPI == EPI_AXPBY) {
                         v = read_c ? fmaf(alpha, v, beta * in[cc][g][e]) : alpha * v;
-                    } else if (EPI == EPI_SIGMOID) {
-                        v = 1.f / (1.f + __expf(-v));
-                    } else if (EPI == EPI_DSIGMOID) {
-                        const float a = in[cc][g][e];
-                        v = v * a * (1.f - a);
+                    } else if (EPI == EPI_ACT) {
+                        v = act_apply(p.act, v);
+                    } else if (EPI == EPI_DACT) {
+                        v = v * act_slope(p.act, in[cc][g][e]);
                     }
                     o[e] = v;
                 }

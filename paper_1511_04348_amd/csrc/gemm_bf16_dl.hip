@@ -311,8 +311,8 @@ hipError_t launch_tile_gemm_bf16_dl(GemmParams p, const GemmDesc& d, hipStream_t
 #define TGD_EPI(AK, BKC)                                                            \
     if (d.epilogue == EPI_AXPBY && !d.out_bf16) { TGD_LAUNCH(AK, BKC, EPI_AXPBY, false); }    \
     if (d.epilogue == EPI_AXPBY && d.out_bf16) { TGD_LAUNCH(AK, BKC, EPI_AXPBY, true); }      \
-    if (d.epilogue == EPI_SIGMOID && d.out_bf16) { TGD_LAUNCH(AK, BKC, EPI_SIGMOID, true); }  \
-    if (d.epilogue == EPI_DSIGMOID && d.out_bf16) { TGD_LAUNCH(AK, BKC, EPI_DSIGMOID, true); } \
+    if (d.epilogue == EPI_ACT && d.out_bf16) { TGD_LAUNCH(AK, BKC, EPI_ACT, true); }  \
+    if (d.epilogue == EPI_DACT && d.out_bf16) { TGD_LAUNCH(AK, BKC, EPI_DACT, true); } \
     return hipErrorNotSupported;
     if (d.a_kcontig && !d.b_kcontig) { TGD_EPI(true, false) }
     if (!d.a_kcontig && !d.b_kcontig) { TGD_EPI(false, false) }

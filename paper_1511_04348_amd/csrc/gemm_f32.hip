@@ -345,16 +345,15 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
 #pragma unroll
                     for (int cc = 0; cc < RB; ++cc) o[cc] = alpha * o[cc];
                 }
-            } else if (EPI == EPI_SIGMOID) {
+            } else if (EPI == EPI_ACT) {
 #pragma unroll
-                for (int cc = 0; cc < RB; ++cc) o[cc] = 1.f / (1.f + __expf(-o[cc]));
-            } else if (EPI == EPI_DSIGMOID) {
+                for (int cc = 0; cc < RB; ++cc) o[cc] = act_apply(p.act, o[cc]);
+            } else if (EPI == EPI_DACT) {
                 const float* ax = aux + (int64_t)row * p.ldaux + colb;
 #pragma unroll
                 for (int cc = 0; cc < RB; ++cc)
                     if (colb + cc < col_end) {
-                        const float a = gload<float>(ax + cc);
-                        o[cc] = o[cc] * a * (1.f - a);
+                        o[cc] = o[cc] * act_slope(p.act, gload<float>(ax + cc));
                     }
             }
             if (cvec) {
@@ -422,8 +421,8 @@ static hipError_t launch_cfg(GemmParams& p, const GemmDesc& d, hipStream_t strea
 #define TG_EPI(AK, BKC)                                            \
     switch (d.epilogue) {                                          \
         case EPI_AXPBY: TG_LAUNCH(AK, BKC, EPI_AXPBY);             \
-        case EPI_SIGMOID: TG_LAUNCH(AK, BKC, EPI_SIGMOID);         \
-        case EPI_DSIGMOID: TG_LAUNCH(AK, BKC, EPI_DSIGMOID);       \
+        case EPI_ACT: TG_LAUNCH(AK, BKC, EPI_ACT);         \
+        case EPI_DACT: TG_LAUNCH(AK, BKC, EPI_DACT);       \
         default: return hipErrorInvalidValue;                      \
     }
     if (d.a_kcontig && !d.b_kcontig) { TG_EPI(true, false) }
@@ -473,7 +472,7 @@ hipError_t launch_tile_gemm_f32(const GemmDesc& d, hipStream_t stream)
     const int64_t big = (d.M > d.N ? d.M : d.N) > d.K ? (d.M > d.N ? d.M : d.N) : d.K;
     if (T > big) T = big > 0 ? big : 1;
     p.T = (int)T;
-    p.alpha = d.alpha; p.beta = d.beta;
+    p.alpha = d.alpha; p.beta = d.beta; p.act = d.act;
     p.b_tiles = d.b_tiles; p.c_tiles = d.c_tiles;
     const bool t4 = (T % 4 == 0);
     auto al16 = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15) == 0; };

@@ -5,12 +5,14 @@
 
 namespace tg {
 
-enum { EPI_AXPBY = 0, EPI_SIGMOID = 1, EPI_DSIGMOID = 2 };
+enum { EPI_AXPBY = 0, EPI_ACT = 1, EPI_DACT = 2 };
+enum { ACT_SIGMOID = 0, ACT_TANH = 1, ACT_RELU = 2 };   // same values as TGEMM_ACT_* of the C ABI
 
 // What a caller asks for: out = epilogue(op(A) op(B)), tiled by T (section 3.1 of the paper).
 //   EPI_AXPBY    C = alpha * (A B) + beta * C       (beta == 0: C is not read)
-//   EPI_SIGMOID  C = sigmoid(A B)
-//   EPI_DSIGMOID C = (A B) * aux * (1 - aux)         (aux: M x N, leading dimension ldaux)
+//   EPI_ACT      C = act(A B)                        act: sigmoid, tanh or max(0, .)
+//   EPI_DACT     C = (A B) * act'(z) with act' written in terms of the stored activation aux = act(z)
+//                (aux: M x N, leading dimension ldaux): aux (1 - aux), 1 - aux^2, or [aux > 0]
 // a_kcontig: A stored M x K row-major (k contiguous); otherwise stored K x M (m contiguous).
 // b_kcontig: B stored N x K row-major (k contiguous); otherwise stored K x N (n contiguous).
 struct GemmDesc {
@@ -26,6 +28,7 @@ struct GemmDesc {
     float alpha, beta;
     int32_t config;   // 0 = automatic, 1..3 = small / medium / large macro tile
     int32_t out_bf16; // bf16 kernel only: C (and aux) hold bf16 bit patterns instead of float
+    int32_t act;      // ACT_* for EPI_ACT / EPI_DACT
     // Optional tile tables (device arrays of device pointers) for operands that live as separate
     // T x T tiles in cache slots instead of one dense matrix.  Entry [step * n_j + tj] of b_tiles
     // is the B tile of k-step `step` and task column tj; entry [ti * n_j + tj] of c_tiles is the C
@@ -49,6 +52,7 @@ struct GemmParams {
     int chunks_per_step;        // BK-chunks in a full k-step
     int n_chunks;               // BK-chunks over all k-steps
     float alpha, beta;
+    int act;                    // ACT_* for the activation epilogues
     bool vec_a, vec_b, vec_c;   // vector access is legal for this operand
     bool vec_aux;               // bf16 kernels: 8-byte access to aux is legal
     bool fast_a, fast_b;        // interior tiles may use the unpredicated, 32-bit-offset load path
@@ -68,6 +72,23 @@ inline hipError_t launch_tile_gemm(const GemmDesc& d, int dtype_bf16, hipStream_
 }
 
 #ifdef __HIPCC__
+// Activation and its slope in terms of the activation's own value (what the backward pass has stored).
+__device__ inline float act_apply(int act, float z)
+{
+    if (act == ACT_RELU) return fmaxf(z, 0.f);
+    if (act == ACT_TANH) {
+        const float t = __expf(-2.f * fabsf(z));
+        return copysignf((1.f - t) / (1.f + t), z);
+    }
+    return 1.f / (1.f + __expf(-z));
+}
+__device__ inline float act_slope(int act, float a)
+{
+    if (act == ACT_RELU) return a > 0.f ? 1.f : 0.f;
+    if (act == ACT_TANH) return 1.f - a * a;
+    return a * (1.f - a);
+}
+
 // Loads / stores through explicitly global (address space 1) pointers.  Operand pointers that come
 // out of a tile table are "generic" to the compiler, which would otherwise emit flat memory
 // instructions; those count against the LDS wait counter and stall the LDS reads behind every

@@ -188,6 +188,7 @@ struct tgemm_mlp {
     std::vector<int64_t> dims;
     std::vector<char*> W;         // caller-owned weights (device or pinned host)
     int32_t dtype = TGEMM_F32;
+    int32_t act_kind = TGEMM_ACT_SIGMOID;   // hidden-layer activation
     size_t es = 4;                // bytes per weight / activation / error element
     int32_t T = 0;
     size_t budget = 0;
@@ -500,7 +501,8 @@ int forward_layer(tgemm_mlp* m, int l, const char* in, int64_t batch)
     d.A = in; d.lda = m->dims[l - 1]; d.a_kcontig = 1;                  // A_{l-1}: batch x n_{l-1}
     d.b_kcontig = 0;                                                     // W_l: n_{l-1} x n_l
     d.M = batch; d.K = m->dims[l - 1];
-    d.epilogue = (l < L) ? EPI_SIGMOID : EPI_AXPBY;
+    d.epilogue = (l < L) ? EPI_ACT : EPI_AXPBY;
+    d.act = m->act_kind;
     d.alpha = 1.f; d.beta = 0.f;
     d.out_bf16 = (bf && l < L) ? 1 : 0;                                  // logits stay float
     char* out = (l < L) ? m->act[l] : (char*)m->logits;
@@ -613,7 +615,8 @@ int backward_layer(tgemm_mlp* m, int l, float* dW_out, bool update, float lr)
     da.b_kcontig = 1;                                                      // W_l stored n_{l-1} x n_l = N x K
     da.M = batch; da.K = m->dims[l];
     da.ldc = m->dims[l - 1]; da.ldaux = m->dims[l - 1];
-    da.epilogue = EPI_DSIGMOID; da.alpha = 1.f; da.beta = 0.f;
+    da.epilogue = EPI_DACT; da.alpha = 1.f; da.beta = 0.f;
+    da.act = m->act_kind;
     da.out_bf16 = bf ? 1 : 0;
 
     GemmDesc dw;   // dW_l = A_{l-1}^T D_l
@@ -779,6 +782,19 @@ int mlp_create(tgemm_ctx* ctx, tgemm_mlp** out, int32_t n_layers, const int64_t*
     m->act.assign(n_layers + 1, nullptr);
     m->delta.assign(n_layers + 1, nullptr);
     *out = m;
+    return TGEMM_OK;
+}
+
+int mlp_set_activation(tgemm_mlp* m, int32_t act)
+{
+    if (!m) return fail(TGEMM_EARG, "mlp_set_activation: object is NULL");
+    if (act != TGEMM_ACT_SIGMOID && act != TGEMM_ACT_TANH && act != TGEMM_ACT_RELU)
+        return fail(TGEMM_EARG, "mlp_set_activation: unknown activation %d", act);
+    static_assert(TGEMM_ACT_SIGMOID == ACT_SIGMOID && TGEMM_ACT_TANH == ACT_TANH && TGEMM_ACT_RELU == ACT_RELU,
+                  "activation codes of the ABI and of the kernels");
+    m->act_kind = act;
+    m->batch = 0;          // activations of an earlier forward pass belong to the old function
+    m->have_delta = false;
     return TGEMM_OK;
 }
 

@@ -57,11 +57,11 @@ def _workspace_bytes(dims, batch, es, T, ooc):
     return total
 
 
-def _check_passes(oracle, mlp, dims, batch, X, Ws, y, Wd, Xd, yd, dtype, tol, lr):
+def _check_passes(oracle, mlp, dims, batch, X, Ws, y, Wd, Xd, yd, dtype, tol, lr, act="sigmoid"):
     L = len(Ws)
     tdt = X.dtype
-    acts, z, P = oracle.mlp_forward(_np(X), [_np(w) for w in Ws])
-    loss_ref, dW_ref, delta_ref = oracle.mlp_backward(_np(X), [_np(w) for w in Ws], y.numpy())
+    acts, z, P = oracle.mlp_forward(_np(X), [_np(w) for w in Ws], act)
+    loss_ref, dW_ref, delta_ref = oracle.mlp_backward(_np(X), [_np(w) for w in Ws], y.numpy(), act=act)
     probs = torch.empty(batch, dims[-1], device="cuda")
     torch.cuda.synchronize()
     tg.mlp_forward(mlp, Xd, batch, probs)
@@ -202,3 +202,59 @@ def test_deferred_writeback_gives_the_same_weights(dtype, tdt):
     for l in range(len(Ws)):
         assert torch.equal(results[0][1][l], results[1][1][l]), ("weights", l)
         assert not torch.equal(results[0][1][l], Ws[l])              # the steps did change them
+
+
+ACT_CODE = {"sigmoid": tg.TGEMM_ACT_SIGMOID, "tanh": tg.TGEMM_ACT_TANH, "relu": tg.TGEMM_ACT_RELU}
+
+
+def _dyadic_net(dims, batch, dtype):
+    """Small integers for X and small integers / 32 for the weights: every hidden pre-activation is a
+    dyadic rational that fp32 and fp64 both hold exactly, so the GPU and the oracle take the same
+    relu on/off decisions (a decision taken in different precisions could flip at a pre-activation
+    within rounding of zero, and one flipped unit is far above the fp32 tolerance)."""
+    X = inputs.int_matrix(1, batch, dims[0]).to(dtype)
+    Ws = [(inputs.int_matrix(10 + l, dims[l], dims[l + 1]) / 32.0).to(dtype) for l in range(len(dims) - 1)]
+    return X, Ws, inputs.labels(5, batch, dims[-1])
+
+
+@pytest.mark.parametrize("ooc", [False, True])
+@pytest.mark.parametrize("dtype,tdt,tol,lr", [(tg.TGEMM_F32, torch.float32, 1e-5, 0.01),
+                                              (tg.TGEMM_BF16, torch.bfloat16, 1e-2, 20.0)])
+@pytest.mark.parametrize("act", ["tanh", "relu"])
+def test_other_activations(oracle, act, dtype, tdt, tol, lr, ooc):
+    """Forward, backward and step with tanh / relu hidden layers against the oracle, in-core and with
+    the weights out-of-core (section 2 fixes only that the passes are matrix products)."""
+    dims, batch, T = [512, 1024, 768, 2000], 384, 256
+    announce("mlp activation", act, "bf16" if dtype else "f32", "ooc" if ooc else "in-core")
+    if act == "relu":
+        X, Ws, y = _dyadic_net(dims, batch, tdt)
+    else:
+        X, Ws, y = _net(dims, batch, tdt)
+    es = 2 if dtype == tg.TGEMM_BF16 else 4
+    ctx = tg.tgemm_create(0, kernel_config=3 if dtype == tg.TGEMM_BF16 else 0)
+    try:
+        Xd, yd = X.cuda(), y.cuda()
+        if ooc:
+            n_tiles = sum((-(-dims[l] // T)) * (-(-dims[l + 1] // T)) for l in range(len(Ws)))
+            n_slots = max(int(0.4 * n_tiles), 2 * max(-(-d // T) for d in dims) + 2)
+            Wx = [w.clone().pin_memory() for w in Ws]
+            budget = _workspace_bytes(dims, batch, es, T, True) + n_slots * T * T * es
+        else:
+            Wx = [w.cuda() for w in Ws]
+            budget = 0
+        torch.cuda.synchronize()
+        mlp = tg.mlp_create(ctx, dims, Wx, dtype, T, hbm_budget=budget)
+        tg.mlp_set_activation(mlp, ACT_CODE[act])
+        _check_passes(oracle, mlp, dims, batch, X, Ws, y, Wx, Xd, yd, dtype, tol, lr, act=act)
+        # changing the function discards the pending forward pass
+        tg.mlp_forward(mlp, Xd, batch)
+        tg.mlp_set_activation(mlp, tg.TGEMM_ACT_SIGMOID)
+        with pytest.raises(tg.TgemmError) as e:
+            tg.mlp_backward(mlp, yd, None)
+        assert e.value.code == tg.TGEMM_ESTATE
+        with pytest.raises(tg.TgemmError) as e:
+            tg.mlp_set_activation(mlp, 7)
+        assert e.value.code == tg.TGEMM_EARG
+        tg.mlp_destroy(mlp)
+    finally:
+        tg.tgemm_destroy(ctx)

@@ -102,3 +102,84 @@ def test_bf16_inputs_widen_exactly(oracle):
     l1 = oracle.mlp_backward(Xb, Wb, y)
     l2 = oracle.mlp_backward(Xf, Wf, y)
     assert l1[0] == l2[0] and all(np.array_equal(a, b) for a, b in zip(l1[1], l2[1]))
+
+
+# ---- other hidden activations (tanh, relu) ---------------------------------------------------------
+
+def _fd_check(oracle, act, seed):
+    X, Ws, y = _net(seed, [5, 7, 6, 4], 3)
+    loss, dWs, _ = oracle.mlp_backward(X, Ws, y, act=act)
+    h = 1e-6
+    W64 = [w.astype(np.float64) for w in Ws]
+    for l, W in enumerate(W64):
+        num = np.zeros_like(W)
+        for idx in np.ndindex(*W.shape):
+            old = W[idx]
+            W[idx] = old + h
+            lp = oracle.mlp_loss(X, W64, y, act=act)
+            W[idx] = old - h
+            lm = oracle.mlp_loss(X, W64, y, act=act)
+            W[idx] = old
+            num[idx] = (lp - lm) / (2 * h)
+        err = np.linalg.norm(num - dWs[l]) / np.linalg.norm(dWs[l])
+        assert err < 1e-6, (act, l, err)
+
+
+def test_finite_differences_tanh_and_relu(oracle):
+    _fd_check(oracle, "tanh", 3)
+    # relu has a kink at 0; with these seeded weights no pre-activation lies within 1e-3 of it
+    X, Ws, y = _net(4, [5, 7, 6, 4], 3)
+    _, _, _, pre = oracle.mlp_forward(X, Ws, "relu", return_pre=True)
+    assert min(np.abs(z).min() for z in pre[1:]) > 1e-3
+    _fd_check(oracle, "relu", 4)
+
+
+def test_activation_values_written_out(oracle):
+    """One input row through an identity first layer: the hidden activations are the function's
+    values at 1, -2 and 0.5 (tanh(1) = 0.76159415595576, tanh(2) = 0.96402758007582,
+    tanh(0.5) = 0.46211715726001; logistic function at 1, -2, 0.5: 0.73105857863000,
+    0.11920292202212, 0.62245933120185 -- standard table values)."""
+    X = np.array([[1.0, -2.0, 0.5]], dtype=np.float32)
+    Ws = [np.eye(3, dtype=np.float32), np.ones((3, 2), dtype=np.float32)]
+    acts, z, P = oracle.mlp_forward(X, Ws, "tanh")
+    assert np.allclose(acts[1], [[0.76159415595576, -0.96402758007582, 0.46211715726001]], rtol=0, atol=1e-13)
+    acts, z, P = oracle.mlp_forward(X, Ws, "relu")
+    assert np.array_equal(acts[1], [[1.0, 0.0, 0.5]]) and np.array_equal(z, [[1.5, 1.5]])
+    acts, z, P = oracle.mlp_forward(X, Ws, "sigmoid")
+    assert np.allclose(acts[1], [[0.73105857863000, 0.11920292202212, 0.62245933120185]], rtol=0, atol=1e-13)
+
+
+def test_activation_symmetries(oracle):
+    """tanh is odd: without biases the logits change sign with the input.  relu is positively
+    homogeneous: the logits scale with the input.  Zero weights: tanh and relu hidden layers are 0."""
+    X, Ws, y = _net(5, [6, 9, 7, 5], 4)
+    X = X.astype(np.float64)          # so that -X and 3 X are exact
+    _, z, _ = oracle.mlp_forward(X, Ws, "tanh")
+    _, zn, _ = oracle.mlp_forward(-X, Ws, "tanh")
+    assert np.allclose(zn, -z, rtol=0, atol=1e-14) and np.abs(z).max() > 0.1
+    _, z, _ = oracle.mlp_forward(X, Ws, "relu")
+    _, z3, _ = oracle.mlp_forward(3.0 * X, Ws, "relu")
+    assert np.allclose(z3, 3.0 * z, rtol=1e-13, atol=1e-13) and np.abs(z).max() > 0.1
+    _, zneg, _ = oracle.mlp_forward(-X, Ws, "relu")
+    assert not np.allclose(zneg, z) and not np.allclose(zneg, -z)        # neither even nor odd
+    Z0 = [np.zeros_like(w) for w in Ws]
+    for act in ("tanh", "relu"):
+        acts, _, P = oracle.mlp_forward(X, Z0, act)
+        assert all(np.array_equal(a, np.zeros_like(a)) for a in acts[1:])
+        assert np.allclose(P, 0.2, rtol=0, atol=1e-16)
+    # the relu slope is 0 or 1: the error reaching layer 1 vanishes exactly where the unit is off
+    acts, _, _, pre = oracle.mlp_forward(X, Ws, "relu", return_pre=True)
+    _, _, deltas = oracle.mlp_backward(X, Ws, y, act="relu")
+    assert np.array_equal(deltas[0] == 0.0, pre[1] <= 0.0)
+
+
+def test_step_descends_for_every_activation(oracle):
+    for act in ("tanh", "relu"):
+        X, Ws, y = _net(6, [8, 10, 6], 5)
+        loss, dWs, _ = oracle.mlp_backward(X, Ws, y, act=act)
+        lr = 1e-4
+        l0, new, _ = oracle.mlp_step(X, Ws, y, lr, act=act)
+        assert l0 == loss
+        l1 = oracle.mlp_loss(X, new, y, act=act)
+        g2 = sum((g ** 2).sum() for g in dWs)
+        assert abs((l1 - l0) + lr * g2) < 5e-2 * lr * g2

@@ -54,21 +54,33 @@ def _killed_by(ns, pins):
 
 MLP_PINS = [(pins_mlp.test_finite_differences_every_weight, ()), (pins_mlp.test_zero_weights_closed_form, ()),
             (pins_mlp.test_single_layer_is_softmax_regression, ()), (pins_mlp.test_invariants_and_orientation, ()),
-            (pins_mlp.test_step_descends_first_order, ()), (pins_mlp.test_bf16_inputs_widen_exactly, ())]
+            (pins_mlp.test_step_descends_first_order, ()), (pins_mlp.test_bf16_inputs_widen_exactly, ()),
+            (pins_mlp.test_finite_differences_tanh_and_relu, ()), (pins_mlp.test_activation_values_written_out, ()),
+            (pins_mlp.test_activation_symmetries, ()), (pins_mlp.test_step_descends_for_every_activation, ())]
 
 MLP_MUTANTS = [
-    ("sigmoid sign", "a = 1.0 / (1.0 + np.exp(-z))", "a = 1.0 / (1.0 + np.exp(z))"),
+    ("sigmoid sign", "        return 1.0 / (1.0 + np.exp(-z))", "        return 1.0 / (1.0 + np.exp(z))"),
+    ("tanh of 2z", "        return np.tanh(z)", "        return np.tanh(2.0 * z)"),
+    ("tanh replaced by the sigmoid", "        return np.tanh(z)", "        return 1.0 / (1.0 + np.exp(-z))"),
+    ("relu replaced by abs", "        return np.where(z > 0.0, z, 0.0)", "        return np.abs(z)"),
+    ("relu passes negatives scaled", "        return np.where(z > 0.0, z, 0.0)", "        return np.where(z > 0.0, z, 0.1 * z)"),
     ("softmax axis", "probs = e / e.sum(axis=1, keepdims=True)", "probs = e / e.sum(axis=0, keepdims=True)"),
     ("loss sum instead of mean", "return float(np.mean(lse - z[np.arange(z.shape[0]), y]))",
      "return float(np.sum(lse - z[np.arange(z.shape[0]), y]))"),
     ("one-hot sign", "d[np.arange(B), y] -= 1.0", "d[np.arange(B), y] += 1.0"),
     ("dropped 1/batch", "    d /= B\n", "    d = d\n"),
-    ("dropped (1 - a) factor", "d = dA * acts[l] * (1.0 - acts[l])", "d = dA * acts[l]"),
-    ("dropped a factor", "d = dA * acts[l] * (1.0 - acts[l])", "d = dA * (1.0 - acts[l])"),
+    ("sigmoid slope: dropped (1 - a) factor", "        return a * (1.0 - a)", "        return a"),
+    ("sigmoid slope: dropped a factor", "        return a * (1.0 - a)", "        return 1.0 - a"),
+    ("tanh slope: a instead of a squared", "        return 1.0 - a * a", "        return 1.0 - a"),
+    ("relu slope: always on", "        return (z > 0.0).astype(np.float64)", "        return np.ones_like(z)"),
+    ("relu slope: sign flipped", "        return (z > 0.0).astype(np.float64)", "        return (z < 0.0).astype(np.float64)"),
+    ("slope dropped from the error", "d = dA * _act_slope(pre[l], acts[l], act)", "d = dA"),
+    ("slope of the wrong layer", "d = dA * _act_slope(pre[l], acts[l], act)", "d = dA * _act_slope(pre[l], acts[l], 'sigmoid')"),
     ("dW from the wrong activation", "dWs[l] = acts[l].T @ d", "dWs[l] = acts[max(l - 1, 0)].T @ d"),
     ("delta not propagated", "dA = d @ _f64(Ws[l]).T", "dA = d @ np.abs(_f64(Ws[l])).T"),
     ("update sign", "new = [_f64(W) - lr * g for W, g in zip(Ws, dWs)]", "new = [_f64(W) + lr * g for W, g in zip(Ws, dWs)]"),
     ("update without lr", "new = [_f64(W) - lr * g for W, g in zip(Ws, dWs)]", "new = [_f64(W) - g for W, g in zip(Ws, dWs)]"),
+    ("loss ignores the activation", "    _, z, _ = mlp_forward(X, Ws, act)", "    _, z, _ = mlp_forward(X, Ws)"),
 ]
 
 
