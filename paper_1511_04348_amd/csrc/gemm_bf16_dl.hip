@@ -220,9 +220,11 @@ __global__ __launch_bounds__(DL_NW * 64) void tile_gemm_bf16_dl(const GemmParams
     // Phase boundary.  In the steady state a wave has its shares of three chunks outstanding; the
     // oldest must have landed before anyone reads it.  Near the end fewer are outstanding than the
     // constant assumes, so the last boundaries wait for everything.
+    // The LDS reads of the phase must have completed as well (lgkmcnt): the stage they came from is
+    // overwritten by other waves' direct loads after a later barrier.
     auto boundary = [&](bool drain) {
-        if (drain) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(%0)" :: "n"(2 * PER) : "memory");
+        if (drain) asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" :: "n"(2 * PER) : "memory");
         __syncthreads();
     };
 
