@@ -60,6 +60,19 @@ __device__ inline void dma16(uint32_t lds_addr, uint32_t voff, const void* sbase
                  :: "s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
 }
 
+// Entry `idx` (the same in every lane) of a table of device pointers, through the scalar unit: the
+// compiler would use a vector load here (the direct loads above are opaque memory operations to it)
+// and wait for it with vmcnt(0), which also drains every direct load in flight.
+__device__ inline const void* table_entry(const void* const* table, int64_t idx)
+{
+    const uint64_t a = reinterpret_cast<uint64_t>(table + idx);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)a), hi = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32));
+    const uint64_t addr = ((uint64_t)hi << 32) | lo;
+    uint64_t v;
+    asm volatile("s_load_dwordx2 %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(addr) : "memory");
+    return reinterpret_cast<const void*>(v);
+}
+
 // ---- k-contiguous operand: BMN rows of 64 bytes per stage -----------------------------------------
 // A 1 KB block is 16 rows x 4 pieces; wave w moves blocks w, w + NW, ...
 template <int BMN>
@@ -175,7 +188,16 @@ __global__ __launch_bounds__(DL_NW * 64) void tile_gemm_bf16_dl(const GemmParams
     const int wm = wave / WN, wn = wave % WN;
     const int li = lane & 31, lh = lane >> 5;
 
-    const TileCoord tc = decode_tile<BM, BN>(p);
+    // the tile coordinates are the same in every lane; kept in scalar registers they make the tile
+    // table lookups scalar loads (a vector load there would have to be waited for with vmcnt(0),
+    // draining the direct loads in flight)
+    TileCoord tc = decode_tile<BM, BN>(p);
+    tc.ti = __builtin_amdgcn_readfirstlane(tc.ti);
+    tc.tj = __builtin_amdgcn_readfirstlane(tc.tj);
+    tc.row0 = __builtin_amdgcn_readfirstlane(tc.row0);
+    tc.col0 = __builtin_amdgcn_readfirstlane(tc.col0);
+    tc.row_end = __builtin_amdgcn_readfirstlane(tc.row_end);
+    tc.col_end = __builtin_amdgcn_readfirstlane(tc.col_end);
     const int tj = tc.tj, row0 = tc.row0, col0 = tc.col0;
     const uint16_t* __restrict__ A = reinterpret_cast<const uint16_t*>(p.A);
     const uint16_t* __restrict__ B = reinterpret_cast<const uint16_t*>(p.B);
@@ -205,7 +227,7 @@ __global__ __launch_bounds__(DL_NW * 64) void tile_gemm_bf16_dl(const GemmParams
     const int64_t b_adv = B_KC ? (int64_t)DL_BK : (int64_t)DL_BK * p.ldb;
     auto issue = [&]() {
         if (p.b_tiles && ld_within == 0) {
-            const uint16_t* t = reinterpret_cast<const uint16_t*>(p.b_tiles[(int64_t)ld_step * p.n_j + tj]);
+            const uint16_t* t = reinterpret_cast<const uint16_t*>(table_entry(p.b_tiles, (int64_t)ld_step * p.n_j + tj));
             b_org = LB::chunk_origin(t, p.ldb, bcol, 0);
         }
         const uint32_t st = lds0 + (uint32_t)(ld_chunk & (DL_STAGES - 1)) * STAGE;
