@@ -247,6 +247,8 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
         constexpr int N_VMEM = LA::UP + LB::UP;               // global load instructions per chunk
         constexpr int N_MFMA = RA * RB * (BK / 2);
         constexpr int GAP = (N_MFMA / 2) / N_VMEM > 0 ? (N_MFMA / 2) / N_VMEM : 1;
+        constexpr int N_DSW = (A_KC ? 4 : 1) * LA::UP + (B_KC ? 4 : 1) * LB::UP;   // LDS store instructions per chunk
+        constexpr int GAP2 = (N_MFMA - GAP * N_VMEM) / N_DSW > 0 ? (N_MFMA - GAP * N_VMEM) / N_DSW : 1;
         if (n_chunks > 0) {
             next_b_origin();
             issue();
@@ -254,10 +256,10 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
             LB::store(rb, Bs, tid);
         }
         __syncthreads();
-        // Steady state: nothing in the body is conditional, and the global loads of the next chunk
-        // are spread over the first half of this chunk's MFMAs -- the vector-memory unit takes a
-        // wave's loads at a limited rate, and a wave that issues them all up front sits in that
-        // queue while its MFMAs wait behind them.
+        // Steady state: nothing in the body is conditional.  The global loads of the next chunk are
+        // spread over the first half of this chunk's MFMAs -- the vector-memory unit takes a wave's
+        // loads at a limited rate, and a wave that issues them all up front sits in that queue
+        // while its MFMAs wait behind them ...
         int c = 0;
         for (; c + 1 < n_chunks; ++c) {
             next_b_origin();
@@ -269,6 +271,14 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
             for (int i = 0; i < N_VMEM; ++i) {
                 __builtin_amdgcn_sched_group_barrier(0x008, GAP, 0);   // MFMA
                 __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);     // one global load
+            }
+            // ... and the LDS stores of the next chunk over the second half, so that the MFMA pipe
+            // still has queued work while the wave stores and walks into the barrier (measured:
+            // 129 -> 137 TFLOP/s at 8000^3)
+#pragma unroll
+            for (int i = 0; i < N_DSW; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, GAP2, 0);  // MFMA
+                __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);     // one LDS write
             }
             __syncthreads();
         }
