@@ -29,9 +29,8 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int BK = 16;       // k extent of one LDS stage
-constexpr int KQ = BK / 4;   // 16-byte units per k-contiguous row of a stage
 constexpr int PAD = 4;       // floats of row padding in LDS
+constexpr int SMALL_BK = 64; // k extent of an LDS stage of the small macro tile (the others use 16)
 
 template <int R> struct Vec;
 template <> struct Vec<1> { typedef float type; };
@@ -42,10 +41,12 @@ template <int R> __device__ inline float vget(const typename Vec<R>::type& v, in
 template <> __device__ inline float vget<1>(const float& v, int) { return v; }
 
 // ---- global -> register staging of one operand tile chunk -------------------------------------
+// BK = k extent of one LDS stage (a "chunk").
 // KC = true : source rows are mn, BK contiguous k each.   unit u -> (mn = u / KQ, kq = u % KQ)
 // KC = false: source rows are k, BMN contiguous mn each.  unit u -> (k = u / (BMN/4), q = u % (BMN/4))
-template <int BMN, int NT, bool KC>
+template <int BMN, int NT, bool KC, int BK>
 struct TileLoader {
+    static constexpr int KQ = BK / 4;                  // 16-byte units per k-contiguous row of a stage
     static constexpr int UNITS = BMN * BK / 4;
     static constexpr int UP = (UNITS + NT - 1) / NT;   // units per thread
     static_assert(UNITS % NT == 0, "tile must divide evenly over the threads");
@@ -133,7 +134,7 @@ struct TileLoader {
 };
 
 // ---- the kernel ---------------------------------------------------------------------------------
-template <int RA, int RB, int WM, int WN, bool A_KC, bool B_KC, int EPI>
+template <int RA, int RB, int WM, int WN, int BK, bool A_KC, bool B_KC, int EPI>
 __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p)
 {
     constexpr int WTM = 32 * RA, WTN = 32 * RB;
@@ -141,8 +142,8 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
     constexpr int NT = WM * WN * 64;
     constexpr int LDA_S = BM + PAD, LDB_S = BN + PAD;
     constexpr int STAGE_A = BK * LDA_S, STAGE_B = BK * LDB_S;
-    typedef TileLoader<BM, NT, A_KC> LA;
-    typedef TileLoader<BN, NT, B_KC> LB;
+    typedef TileLoader<BM, NT, A_KC, BK> LA;
+    typedef TileLoader<BN, NT, B_KC, BK> LB;
     typedef typename Vec<RA>::type VA;
     typedef typename Vec<RB>::type VB;
 
@@ -287,11 +288,19 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
             __syncthreads();
         }
     } else {
-        // ---- edge tiles and ragged k-steps: predicated, zero-filling loaders
+        // ---- ragged k-steps, unaligned operands, tiny edge tiles: predicated, zero-filling loaders.
+        // Where only the k-steps are ragged, the chunks that are full (all but the last of a step)
+        // still take the unpredicated loads.
+        const bool full_ok = p.fast_a && p.fast_b && a_valid >= 4 && b_valid >= 4 && (A_KC || a_valid % 4 == 0) &&
+                             (B_KC || b_valid % 4 == 0);
+        uint32_t offa[LA::UP], offb[LB::UP];
+        if (full_ok) {
+            LA::init_offsets(offa, p.lda, a_valid, tid);
+            LB::init_offsets(offb, p.ldb, b_valid, tid);
+        }
         auto issue = [&]() {
             const int kk = ld_step * p.T + ld_within * BK;
             const int klim = min(p.K, (ld_step + 1) * p.T);
-            LA::load(ra, A, p.lda, row0, row_end, kk, klim, p.vec_a, tid);
             const float* bsrc = B;
             int bm0 = col0, bm1 = col_end, bk0 = kk, bk1 = klim;
             if (p.b_tiles) {
@@ -299,7 +308,13 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
                 bm0 = bcol; bm1 = col_end - tj * p.T;
                 bk0 = kk - ld_step * p.T; bk1 = klim - ld_step * p.T;
             }
-            LB::load(rb, bsrc, p.ldb, bm0, bm1, bk0, bk1, p.vec_b, tid);
+            if (full_ok && kk + BK <= klim) {
+                LA::load_fast(ra, offa, A + (A_KC ? (int64_t)row0 * p.lda + kk : (int64_t)kk * p.lda + row0));
+                LB::load_fast(rb, offb, bsrc + (B_KC ? (int64_t)bm0 * p.ldb + bk0 : (int64_t)bk0 * p.ldb + bm0));
+            } else {
+                LA::load(ra, A, p.lda, row0, row_end, kk, klim, p.vec_a, tid);
+                LB::load(rb, bsrc, p.ldb, bm0, bm1, bk0, bk1, p.vec_b, tid);
+            }
             if (++ld_within == cps) { ld_within = 0; ++ld_step; }
         };
         if (n_chunks > 0) {
@@ -381,17 +396,17 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
 }
 
 // ---- host-side launcher -------------------------------------------------------------------------
-template <int RA, int RB, int WM, int WN>
+template <int RA, int RB, int WM, int WN, int BK>
 struct Cfg {
     static constexpr int BM = WM * 32 * RA, BN = WN * 32 * RB, NT = WM * WN * 64;
     static constexpr size_t LDS = 2 * (size_t)BK * ((BM + PAD) + (BN + PAD)) * sizeof(float);
 };
 
-template <int RA, int RB, int WM, int WN, bool A_KC, bool B_KC, int EPI>
+template <int RA, int RB, int WM, int WN, int BK, bool A_KC, bool B_KC, int EPI>
 static hipError_t launch_one(const GemmParams& p, int grid, hipStream_t stream)
 {
-    typedef Cfg<RA, RB, WM, WN> C;
-    auto kern = tile_gemm_f32<RA, RB, WM, WN, A_KC, B_KC, EPI>;
+    typedef Cfg<RA, RB, WM, WN, BK> C;
+    auto kern = tile_gemm_f32<RA, RB, WM, WN, BK, A_KC, B_KC, EPI>;
     static bool attr_set = false;   // per instantiation; the attribute is per function, idempotent
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -403,11 +418,12 @@ static hipError_t launch_one(const GemmParams& p, int grid, hipStream_t stream)
     return hipGetLastError();
 }
 
-template <int RA, int RB, int WM, int WN>
+template <int RA, int RB, int WM, int WN, int BK>
 static hipError_t launch_cfg(GemmParams& p, const GemmDesc& d, hipStream_t stream)
 {
-    typedef Cfg<RA, RB, WM, WN> C;
+    typedef Cfg<RA, RB, WM, WN, BK> C;
     const int64_t T = d.T;
+    p.fast_k = (d.K % BK == 0) && (T % BK == 0 || T >= d.K);   // every k chunk is full
     p.n_i = (int)((d.M + T - 1) / T);
     p.n_j = (int)((d.N + T - 1) / T);
     const int64_t n_k = (d.K + T - 1) / T;
@@ -427,7 +443,7 @@ static hipError_t launch_cfg(GemmParams& p, const GemmDesc& d, hipStream_t strea
     const int64_t last_k = d.K - (n_k - 1) * T;
     p.n_chunks = (int)((n_k - 1) * p.chunks_per_step + (last_k + BK - 1) / BK);
 
-#define TG_LAUNCH(AK, BKC, E) return launch_one<RA, RB, WM, WN, AK, BKC, E>(p, (int)grid, stream)
+#define TG_LAUNCH(AK, BKC, E) return launch_one<RA, RB, WM, WN, BK, AK, BKC, E>(p, (int)grid, stream)
 #define TG_EPI(AK, BKC)                                            \
     switch (d.epilogue) {                                          \
         case EPI_AXPBY: TG_LAUNCH(AK, BKC, EPI_AXPBY);             \
@@ -462,8 +478,8 @@ int pick_config(const GemmDesc& d)
         return (double)((n_tiles + per_round - 1) / per_round) * round_time;
     };
     const double c3 = cost(tiles(256, 256), 256, 1.0);
-    const double c2 = cost(tiles(128, 128), 512, 0.52);
-    const double c1 = cost(tiles(64, 64), 512, 0.15);
+    const double c2 = cost(tiles(128, 128), 512, 0.53);    // measured at 4096^3: 128 / 137 TFLOP/s of the large shape
+    const double c1 = cost(tiles(64, 64), 512, 0.16);      // 106 / 137
     if (c3 <= c2 && c3 <= c1) return 3;
     return c2 <= c1 ? 2 : 1;
 }
@@ -493,13 +509,15 @@ hipError_t launch_tile_gemm_f32(const GemmDesc& d, hipStream_t stream)
     auto off32 = [](int64_t ld) { return 256 * ld * 4 + 4096 < ((int64_t)1 << 31); };
     p.fast_a = p.vec_a && off32(d.lda);
     p.fast_b = p.vec_b && off32(d.ldb);
-    p.fast_k = (d.K % BK == 0) && (T % BK == 0 || T >= d.K);
     GemmDesc dd = d;
     dd.T = (int32_t)T;
     switch (pick_config(dd)) {
-        case 3: return launch_cfg<2, 4, 4, 2>(p, dd, stream);   // 256 x 256, 512 threads
-        case 2: return launch_cfg<2, 2, 2, 2>(p, dd, stream);   // 128 x 128, 256 threads
-        default: return launch_cfg<1, 1, 2, 2>(p, dd, stream);  //  64 x  64, 256 threads
+        case 3: return launch_cfg<2, 4, 4, 2, 16>(p, dd, stream);   // 256 x 256, 512 threads
+        case 2: return launch_cfg<2, 2, 2, 2, 16>(p, dd, stream);   // 128 x 128, 256 threads
+        // 64 x 64, 256 threads, 64-k chunks: the shape for products too small to fill the chip with
+        // larger tiles; there the k loop is bound by the latency of a chunk's round trip
+        // (global -> registers -> LDS -> barrier), so it takes few, long chunks
+        default: return launch_cfg<1, 1, 2, 2, SMALL_BK>(p, dd, stream);
     }
 }
 
