@@ -121,3 +121,32 @@ def test_supplementary_8192_sampled(ctxs, oracle):
     ref = oracle.gemm_samples(inputs.bf16_bits(A), inputs.bf16_bits(B), rows, cols)
     err = rel_fro(C.cpu().numpy()[rows, cols], ref)
     assert err <= BAR and err <= SANITY, err
+
+
+def test_direct_to_lds_kernel_equals_register_staged_kernel_bitwise(ctxs, oracle):
+    """Seeded random shapes that the direct-to-LDS kernel accepts (whole 32-k chunks, N a multiple
+    of 8, aligned pointers): ragged edge tiles in M and N, tile sizes below, at and above the
+    dimensions, 1 to 60 chunks.  Both 256 x 256 kernels run the same sequence of 16-k MFMAs per
+    output element, so their results must agree bit for bit; every fourth shape is also compared with
+    the oracle."""
+    rnd = np.random.default_rng(20240607)
+    for case in range(32):
+        M = int(rnd.integers(1, 1400))
+        N = 8 * int(rnd.integers(1, 170))
+        K = 32 * int(rnd.integers(1, 60))
+        T = int(rnd.choice([32, 64, 96, 128, 256, 512, 2048]))
+        announce("bf16 dl vs staged", case, M, N, K, T)
+        A = _bf16(inputs.uniform_matrix(100 + case, M, K)).cuda()
+        B = _bf16(inputs.uniform_matrix(200 + case, K, N)).cuda()
+        C0 = inputs.uniform_matrix(300 + case, M, N)
+        outs = []
+        for cfg in (3, 4):
+            C = C0.cuda()
+            torch.cuda.synchronize()
+            tg.tgemm_run(ctxs[cfg], A, B, C, M, N, K, T, tg.TGEMM_BF16, 0)
+            outs.append(C.cpu())
+        assert torch.equal(outs[0], outs[1]), (M, N, K, T)
+        if case % 4 == 0:
+            ref = oracle.gemm(inputs.bf16_bits(A.cpu()), inputs.bf16_bits(B.cpu()), c_in=C0.numpy())
+            err = rel_fro(outs[0].numpy(), ref)
+            assert err <= BAR and err <= SANITY, (M, N, K, T, err)
