@@ -146,6 +146,8 @@ def run_mlp(args, tg, inputs, torch, dims, batch, T, bf16, budget):
     # tgemm_sync inside the timed region waits for the last of them
     ctx = tg.tgemm_create(0, kernel_config=args.kernel_config, deferred_writeback=0 if args.sync_writeback else 1)
     mlp = tg.mlp_create(ctx, dims, W, tg.TGEMM_BF16 if bf16 else tg.TGEMM_F32, T, hbm_budget=budget)
+    if bf16 and args.stochastic_rounding:
+        tg.mlp_set_rounding(mlp, tg.TGEMM_ROUND_STOCHASTIC, 1)
     for _ in range(args.warmup):
         tg.mlp_step(mlp, X, y, batch, 0.01)
     tg.tgemm_sync(ctx)
@@ -165,7 +167,7 @@ def run_mlp(args, tg, inputs, torch, dims, batch, T, bf16, budget):
                     "MLP train step %s, layers %s, batch %d, sigmoid hidden, softmax + cross-entropy, SGD lr 0.01, T=%d%s"
                     % ("bf16 storage / fp32 accumulate" if bf16 else "fp32", "->".join(str(d) for d in dims), batch, T,
                        ", weights in pinned host memory, HBM budget %d bytes" % budget if budget else ", in-core"),
-                    {"tile": T, "loss": loss})
+                    {"tile": T, "loss": loss, "rounding": "stochastic" if bf16 and args.stochastic_rounding else "nearest"})
     out["roofline"] = {"bound": "mfma", "achieved": tfl, "peak": peak, "unit": "TFLOP/s", "frac": tfl / peak,
                        "traffic": None, "kernel": "tile_gemm_%s (whole step)" % ("bf16" if bf16 else "f32"),
                        "flops_per_step": flops}
@@ -191,6 +193,8 @@ def main():
     ap.add_argument("--strip", type=int, default=0, help="strip width for --order 2; 0 = from the slot count")
     ap.add_argument("--sync-writeback", action="store_true",
                     help="out-of-core MLP: every step waits for its weight write-back (default: deferred)")
+    ap.add_argument("--stochastic-rounding", action="store_true",
+                    help="c5: round the updated bf16 weights stochastically (mlp_set_rounding) instead of to nearest")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run 5 plain device copies of 256 MiB (a known-size reference for HBM counters)")

@@ -205,6 +205,25 @@ int mlp_destroy(tgemm_mlp* mlp);
 enum { TGEMM_ACT_SIGMOID = 0, TGEMM_ACT_TANH = 1, TGEMM_ACT_RELU = 2 };
 int mlp_set_activation(tgemm_mlp* mlp, int32_t act);
 
+/* Rounding of the updated weights in mlp_step for bf16 networks (section 2's update, W_l - lr dW_l,
+ * is formed in fp32 in the product's epilogue and then stored as bf16).
+ *   TGEMM_ROUND_NEAREST     round to nearest even (default).  An update below half an ulp of the
+ *                           weight (2^-9 relative) is lost entirely.
+ *   TGEMM_ROUND_STOCHASTIC  add 16 uniform random bits below the bf16 cut and truncate: the stored
+ *                           value is one of the two bf16 neighbours of the fp32 result, the upper one
+ *                           (in magnitude) with probability equal to the dropped fraction, so its
+ *                           expectation is the fp32 result; exactly representable results never move.
+ * The random bits are a pure function of (seed, layer l = 1..n_layers, step, row, col) with
+ * mix32 = the 32-bit finalizer of MurmurHash3 (x ^= x >> 16; x *= 0x85ebca6b; x ^= x >> 13;
+ * x *= 0xc2b2ae35; x ^= x >> 16) and arithmetic modulo 2^32:
+ *   key  = mix32(mix32(mix32(mix32(seed mod 2^32) ^ (seed >> 32)) ^ l) ^ step)
+ *   bits = mix32(mix32(row + key) + (col / 2) * 0x9E3779B9);  even col takes bits mod 2^16, odd col bits >> 16
+ * (row, col index W_l; step counts the mlp_step calls since this function was last called), so a
+ * run is reproducible whatever the tile size, kernel or residency mode.
+ * TGEMM_EARG for an unknown mode, or for the stochastic mode on an fp32 network. */
+enum { TGEMM_ROUND_NEAREST = 0, TGEMM_ROUND_STOCHASTIC = 1 };
+int mlp_set_rounding(tgemm_mlp* mlp, int32_t mode, uint64_t seed);
+
 /* Equation 1 for every layer: Z_l = A_{l-1} W_l, A_l = sigmoid(Z_l); last layer: logits.
  *   X      device pointer, batch x dims[0], dtype elements.
  *   probs  NULL, or device pointer to batch x dims[n_layers] floats receiving softmax(logits). */

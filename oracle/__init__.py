@@ -4,11 +4,14 @@ Plain, slow, obviously-correct definitions of everything the GPU library
 computes: the GEMM (section 3.1 of the paper: tile products accumulated over
 k), the tile plan (section 3.1, Algorithm 1 "decode"), the L1 tile cache
 behaviour under LRU (section 3.4, Algorithm 1 lookups) and the MLP passes
-(section 2, equations 1, 3, 4).
+(section 2, equations 1, 3, 4), with the optional stochastic rounding of
+updated bf16 weights.
 
 Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
 ``bench.py`` may import this package.  It never imports the GPU package and
-shares no code, table or constant with it.
+shares no code or table with it (the random bits of the stochastic rounding
+are an interface written out in the library's header, which each side
+implements on its own).
 
 Parity pins: every function here is pinned by ``tests/test_oracle_*.py``
 against closed forms, brute force, numpy's fp64 matmul, finite differences
@@ -18,4 +21,5 @@ from .build import build_oracle, lib_path  # noqa: F401
 from .gemm import gemm, gemm_tiled, gemm_samples, num_threads, bf16_to_f64  # noqa: F401
 from .plan import plan_tiles, tile_counts, decode_task, kstep_ranges  # noqa: F401
 from .lru import lru_simulate, tgemm_access_sequence, task_order, auto_strip  # noqa: F401
-from .mlp import mlp_forward, mlp_backward, mlp_step, mlp_loss  # noqa: F401
+from .mlp import mlp_forward, mlp_backward, mlp_step, mlp_step_stochastic, mlp_loss  # noqa: F401
+from .rounding import mix32, step_key, rounding_bits, stochastic_round_bf16, stochastic_round_matrix  # noqa: F401

@@ -22,6 +22,7 @@ numpy's fp64 matmul is the library primitive used for the products.
 import numpy as np
 
 from .gemm import bf16_to_f64
+from .rounding import stochastic_round_matrix
 
 
 def _f64(a):
@@ -108,3 +109,14 @@ def mlp_step(X, Ws, y, lr, act="sigmoid"):
     loss, dWs, _ = mlp_backward(X, Ws, y, act)
     new = [_f64(W) - lr * g for W, g in zip(Ws, dWs)]
     return loss, new, dWs
+
+
+def mlp_step_stochastic(X, Ws, y, lr, seed, step, act="sigmoid"):
+    """One SGD step of a bf16 network whose updated weights are rounded stochastically.
+
+    The exact update is formed in fp64, brought to fp32 (the precision in which the rounding
+    decision is taken) and rounded with the bits of (seed, layer, step).  Returns (loss, new
+    weights as bf16 bit patterns, new weights in fp64 before any rounding)."""
+    loss, exact, _ = mlp_step(X, Ws, y, lr, act)
+    bits = [stochastic_round_matrix(w.astype(np.float32), seed, l + 1, step) for l, w in enumerate(exact)]
+    return loss, bits, exact

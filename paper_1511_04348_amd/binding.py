@@ -14,11 +14,12 @@ TGEMM_F32, TGEMM_BF16 = 0, 1
 TGEMM_OK, TGEMM_EARG, TGEMM_ENOMEM, TGEMM_EUNPINNED, TGEMM_EBUDGET, TGEMM_EHIP, TGEMM_ESTATE = 0, -1, -2, -3, -4, -5, -6
 TGEMM_ORDER_SERPENTINE, TGEMM_ORDER_ROW_MAJOR, TGEMM_ORDER_STRIPS = 0, 1, 2
 TGEMM_ACT_SIGMOID, TGEMM_ACT_TANH, TGEMM_ACT_RELU = 0, 1, 2
+TGEMM_ROUND_NEAREST, TGEMM_ROUND_STOCHASTIC = 0, 1
 
 EXPORTS = [
     "tgemm_strerror", "tgemm_last_error", "tgemm_create", "tgemm_destroy", "tgemm_run", "tgemm_sync",
     "tgemm_plan", "tgemm_task_order", "tgemm_last_stats", "tgemm_trace", "tgemm_queue_selftest",
-    "mlp_create", "mlp_destroy", "mlp_set_activation", "mlp_forward", "mlp_backward", "mlp_step", "mlp_read",
+    "mlp_create", "mlp_destroy", "mlp_set_activation", "mlp_set_rounding", "mlp_forward", "mlp_backward", "mlp_step", "mlp_read",
 ]
 
 
@@ -82,6 +83,7 @@ def load():
     lib.mlp_create.argtypes = [vp, P(vp), i32, P(i64), P(vp), i32, i32, sz]
     lib.mlp_destroy.argtypes = [vp]
     lib.mlp_set_activation.argtypes = [vp, i32]
+    lib.mlp_set_rounding.argtypes = [vp, i32, ctypes.c_uint64]
     lib.mlp_forward.argtypes = [vp, vp, i64, vp]
     lib.mlp_backward.argtypes = [vp, vp, P(vp), P(ctypes.c_float)]
     lib.mlp_step.argtypes = [vp, vp, vp, i64, ctypes.c_float, P(ctypes.c_float)]
@@ -197,6 +199,10 @@ def mlp_destroy(mlp):
 
 def mlp_set_activation(mlp, act):
     _check(load().mlp_set_activation(mlp, act))
+
+
+def mlp_set_rounding(mlp, mode, seed=0):
+    _check(load().mlp_set_rounding(mlp, mode, seed))
 
 
 def mlp_forward(mlp, X, batch, probs=None):

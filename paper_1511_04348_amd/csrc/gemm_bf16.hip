@@ -443,6 +443,8 @@ hipError_t launch_tile_gemm_bf16(const GemmDesc& d, hipStream_t stream)
     if (T > big) T = big > 0 ? big : 1;
     p.T = (int)T;
     p.alpha = d.alpha; p.beta = d.beta; p.act = d.act;
+    p.sr = (d.sr && d.out_bf16 && d.epilogue == EPI_AXPBY) ? 1 : 0;
+    p.sr_key = d.sr_key; p.sr_row0 = (uint32_t)d.sr_row0;
     p.b_tiles = d.b_tiles; p.c_tiles = d.c_tiles;
     // k-contiguous operands use 16-byte loads (8 elements), m/n-contiguous ones 8-byte loads (4)
     auto ok = [&](const void* q, int64_t ld, bool kc) {

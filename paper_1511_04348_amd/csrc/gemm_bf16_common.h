@@ -23,6 +23,18 @@ __device__ inline uint16_t f32_to_bf16_rne(float f)
     return (uint16_t)(u >> 16);
 }
 
+// Stochastic rounding: the 16 bits below the bf16 cut plus 16 uniform random bits carry into the kept
+// half with probability (dropped fraction), so the expected result is the unrounded value; a value
+// that bf16 holds exactly never moves.  Infinities and NaNs go the nearest-even way.
+__device__ inline uint16_t f32_to_bf16_sr(float f, uint32_t r16)
+{
+    const uint32_t u = __float_as_uint(f);
+    if ((u & 0x7f800000u) == 0x7f800000u) return f32_to_bf16_rne(f);
+    return (uint16_t)((u + r16) >> 16);
+}
+// 32 random bits shared by columns 2 (col / 2) and 2 (col / 2) + 1 of a row (hrow: the row's hash)
+__device__ inline uint32_t pair_bits(uint32_t hrow, int col) { return mix32(hrow + (uint32_t)(col >> 1) * 0x9E3779B9u); }
+
 // Which macro tile a workgroup owns.  Workgroups are numbered XCD by XCD (consecutive logical ids
 // stay on one XCD and share its L2) and task by task (the T x T task grid is the L2 blocking).
 struct TileCoord {
@@ -147,16 +159,32 @@ __device__ inline void epilogue(const GemmParams& p, const TileCoord& t, const f
                     o[e] = v;
                 }
                 if (OUT_BF16) {
+                    uint16_t b[4];
+                    if (EPI == EPI_AXPBY && p.sr) {
+                        // col is even when T is (pairs col / 2 and col / 2 + 1); odd tile sizes go column by column
+                        const uint32_t hrow = mix32(p.sr_row0 + (uint32_t)row + p.sr_key);
+                        const bool even = (col & 1) == 0;
+                        const uint32_t b0 = pair_bits(hrow, col), b1 = pair_bits(hrow, col + 2);
+                        const uint32_t bm = even ? b0 : pair_bits(hrow, col + 1);
+                        const uint32_t be = even ? b1 : pair_bits(hrow, col + 3);
+                        b[0] = f32_to_bf16_sr(o[0], even ? b0 & 0xffffu : b0 >> 16);
+                        b[1] = f32_to_bf16_sr(o[1], even ? b0 >> 16 : bm & 0xffffu);
+                        b[2] = f32_to_bf16_sr(o[2], even ? b1 & 0xffffu : bm >> 16);
+                        b[3] = f32_to_bf16_sr(o[3], even ? b1 >> 16 : be & 0xffffu);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) b[e] = f32_to_bf16_rne(o[e]);
+                    }
                     uint16_t* dst = Cb + crow + col;
                     if (vec_c && col + 3 < t.col_end) {
                         u32x2 w;
-                        w[0] = (uint32_t)f32_to_bf16_rne(o[0]) | ((uint32_t)f32_to_bf16_rne(o[1]) << 16);
-                        w[1] = (uint32_t)f32_to_bf16_rne(o[2]) | ((uint32_t)f32_to_bf16_rne(o[3]) << 16);
+                        w[0] = (uint32_t)b[0] | ((uint32_t)b[1] << 16);
+                        w[1] = (uint32_t)b[2] | ((uint32_t)b[3] << 16);
                         gstore<u32x2>(dst, w);
                     } else {
 #pragma unroll
                         for (int e = 0; e < 4; ++e)
-                            if (col + e < t.col_end) gstore<uint16_t>(dst + e, f32_to_bf16_rne(o[e]));
+                            if (col + e < t.col_end) gstore<uint16_t>(dst + e, b[e]);
                     }
                 } else {
                     float* dst = Cf + crow + col;

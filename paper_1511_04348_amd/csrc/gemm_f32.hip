@@ -499,6 +499,7 @@ hipError_t launch_tile_gemm_f32(const GemmDesc& d, hipStream_t stream)
     if (T > big) T = big > 0 ? big : 1;
     p.T = (int)T;
     p.alpha = d.alpha; p.beta = d.beta; p.act = d.act;
+    p.sr = 0; p.sr_key = 0; p.sr_row0 = 0;
     p.b_tiles = d.b_tiles; p.c_tiles = d.c_tiles;
     const bool t4 = (T % 4 == 0);
     auto al16 = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15) == 0; };

@@ -29,6 +29,12 @@ struct GemmDesc {
     int32_t config;   // 0 = automatic, 1..3 = small / medium / large macro tile
     int32_t out_bf16; // bf16 kernel only: C (and aux) hold bf16 bit patterns instead of float
     int32_t act;      // ACT_* for EPI_ACT / EPI_DACT
+    // bf16 kernel, EPI_AXPBY with out_bf16: round the result stochastically instead of to nearest.
+    // Entry (row, col) of this launch draws its 16 random bits from rounding_bits(sr_key,
+    // sr_row0 + row, col); sr_row0 places a launch that covers a band of rows inside the whole matrix.
+    int32_t sr;
+    uint32_t sr_key;
+    int64_t sr_row0;
     // Optional tile tables (device arrays of device pointers) for operands that live as separate
     // T x T tiles in cache slots instead of one dense matrix.  Entry [step * n_j + tj] of b_tiles
     // is the B tile of k-step `step` and task column tj; entry [ti * n_j + tj] of c_tiles is the C
@@ -53,6 +59,9 @@ struct GemmParams {
     int n_chunks;               // BK-chunks over all k-steps
     float alpha, beta;
     int act;                    // ACT_* for the activation epilogues
+    int sr;                     // stochastic rounding of a bf16 result (see GemmDesc)
+    uint32_t sr_key;
+    uint32_t sr_row0;
     bool vec_a, vec_b, vec_c;   // vector access is legal for this operand
     bool vec_aux;               // bf16 kernels: 8-byte access to aux is legal
     bool fast_a, fast_b;        // interior tiles may use the unpredicated, 32-bit-offset load path
@@ -69,6 +78,23 @@ hipError_t launch_tile_gemm_bf16(const GemmDesc& d, hipStream_t stream);
 inline hipError_t launch_tile_gemm(const GemmDesc& d, int dtype_bf16, hipStream_t stream)
 {
     return dtype_bf16 ? launch_tile_gemm_bf16(d, stream) : launch_tile_gemm_f32(d, stream);
+}
+
+// Counter-based random bits for stochastic rounding.  mix32 is the 32-bit finalizer of MurmurHash3
+// (a bijection of the 32-bit integers with good avalanche); all arithmetic is modulo 2^32.
+//   step_key(seed, layer, step) = mix32(mix32(mix32(mix32(seed_lo) ^ seed_hi) ^ layer) ^ step)
+//   pair_bits(key, row, col)    = mix32(mix32(row + key) + (col / 2) * 0x9E3779B9)
+//   rounding_bits(key, row, col) = 16 bits of pair_bits: the low half for even col, the high half for odd col
+__host__ __device__ inline uint32_t mix32(uint32_t x)
+{
+    x ^= x >> 16; x *= 0x85ebca6bu;
+    x ^= x >> 13; x *= 0xc2b2ae35u;
+    x ^= x >> 16;
+    return x;
+}
+inline uint32_t sr_step_key(uint64_t seed, uint32_t layer, uint32_t step)
+{
+    return mix32(mix32(mix32(mix32((uint32_t)seed) ^ (uint32_t)(seed >> 32)) ^ layer) ^ step);
 }
 
 #ifdef __HIPCC__

@@ -189,6 +189,9 @@ struct tgemm_mlp {
     std::vector<char*> W;         // caller-owned weights (device or pinned host)
     int32_t dtype = TGEMM_F32;
     int32_t act_kind = TGEMM_ACT_SIGMOID;   // hidden-layer activation
+    int32_t round_mode = TGEMM_ROUND_NEAREST;   // how mlp_step rounds updated bf16 weights
+    uint64_t sr_seed = 0;
+    uint32_t sr_step = 0;         // mlp_step calls since mlp_set_rounding
     size_t es = 4;                // bytes per weight / activation / error element
     int32_t T = 0;
     size_t budget = 0;
@@ -635,7 +638,11 @@ int backward_layer(tgemm_mlp* m, int l, float* dW_out, bool update, float lr)
         }
         if (update || dW_out) {
             dw.A = a_prev; dw.M = m->dims[l - 1]; dw.ldc = m->dims[l];
-            if (update) { dw.C = (float*)m->W[l - 1]; dw.alpha = -lr; dw.beta = 1.f; dw.out_bf16 = bf ? 1 : 0; }
+            if (update) {
+                dw.C = (float*)m->W[l - 1]; dw.alpha = -lr; dw.beta = 1.f; dw.out_bf16 = bf ? 1 : 0;
+                dw.sr = (bf && m->round_mode == TGEMM_ROUND_STOCHASTIC) ? 1 : 0;
+                dw.sr_key = sr_step_key(m->sr_seed, (uint32_t)l, m->sr_step); dw.sr_row0 = 0;
+            }
             else { dw.C = dW_out; dw.alpha = 1.f; dw.beta = 0.f; dw.out_bf16 = 0; }
             const int rc = launch(m, dw, comp);
             if (rc != TGEMM_OK) return rc;
@@ -686,6 +693,8 @@ int backward_layer(tgemm_mlp* m, int l, float* dW_out, bool update, float lr)
             dw.c_tiles = (void* const*)m->ring.dev[entry];
             dw.C = (float*)m->cache.ptr(tiles[0]); dw.ldc = T;
             dw.alpha = -lr; dw.beta = 1.f; dw.out_bf16 = bf ? 1 : 0;
+            dw.sr = (bf && m->round_mode == TGEMM_ROUND_STOCHASTIC) ? 1 : 0;
+            dw.sr_key = sr_step_key(m->sr_seed, (uint32_t)l, m->sr_step); dw.sr_row0 = r * T;
             if ((rc = launch(m, dw, comp)) != TGEMM_OK) return rc;
             if ((rc = ring_finish(m, entry, tiles.data(), (int)n_c)) != TGEMM_OK) return rc;
             // write the updated row of tiles back (stream 3) once the launch has finished
@@ -798,6 +807,19 @@ int mlp_set_activation(tgemm_mlp* m, int32_t act)
     return TGEMM_OK;
 }
 
+int mlp_set_rounding(tgemm_mlp* m, int32_t mode, uint64_t seed)
+{
+    if (!m) return fail(TGEMM_EARG, "mlp_set_rounding: object is NULL");
+    if (mode != TGEMM_ROUND_NEAREST && mode != TGEMM_ROUND_STOCHASTIC)
+        return fail(TGEMM_EARG, "mlp_set_rounding: unknown mode %d", mode);
+    if (mode == TGEMM_ROUND_STOCHASTIC && m->dtype != TGEMM_BF16)
+        return fail(TGEMM_EARG, "mlp_set_rounding: stochastic rounding applies to bf16 weights only");
+    m->round_mode = mode;
+    m->sr_seed = seed;
+    m->sr_step = 0;
+    return TGEMM_OK;
+}
+
 int mlp_destroy(tgemm_mlp* m)
 {
     if (!m) return TGEMM_OK;
@@ -855,6 +877,7 @@ int mlp_step(tgemm_mlp* m, const void* X, const int32_t* labels, int64_t batch, 
     if ((rc = read_loss(m, loss)) != TGEMM_OK) return rc;
     if ((rc = (m->ooc && m->ctx->opts.deferred_writeback) ? sync_compute(m) : sync_all(m)) != TGEMM_OK) return rc;
     m->have_delta = true;
+    ++m->sr_step;
     m->ctx->stats.wall_ms = now_ms() - t0;
     return TGEMM_OK;
 }

@@ -14,6 +14,7 @@ import pytest
 import test_oracle_gemm as pins_gemm
 import test_oracle_mlp as pins_mlp
 import test_oracle_plan_lru as pins_plan
+import test_oracle_rounding as pins_round
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -168,6 +169,48 @@ GEMM_C_MUTANTS = [
 ]
 
 
+ROUNDING_PINS = [(pins_round.test_mix32_known_answers, ()), (pins_round.test_mix32_is_inverted_by_the_closed_form_inverse, ()),
+                 (pins_round.test_step_key_depends_on_every_argument, ()),
+                 (pins_round.test_rounding_over_all_random_values_is_exactly_unbiased, ()),
+                 (pins_round.test_rounding_special_values, ()), (pins_round.test_rounding_bits_layout_and_statistics, ()),
+                 (pins_round.test_rounding_a_matrix_is_unbiased_where_nearest_loses_the_update, ()),
+                 (pins_round.test_mlp_step_stochastic_brackets_the_exact_update, ())]
+
+ROUNDING_MUTANTS = [
+    ("finalizer: wrong middle shift", "    x = x ^ (x >> np.uint64(13))", "    x = x ^ (x >> np.uint64(15))"),
+    ("finalizer: last xor-shift dropped", "    x = (x * np.uint64(0xC2B2AE35)) & _M32\n    x = x ^ (x >> np.uint64(16))",
+     "    x = (x * np.uint64(0xC2B2AE35)) & _M32"),
+    ("finalizer: multipliers swapped", "    x = (x * np.uint64(0x85EBCA6B)) & _M32", "    x = (x * np.uint64(0xC2B2AE35)) & _M32 if False else (x * np.uint64(0xC2B2AE37)) & _M32"),
+    ("key ignores the step", "    k = mix32(k ^ np.uint64(int(step) & 0xFFFFFFFF))", "    k = mix32(k)"),
+    ("key ignores the layer", "    k = mix32(k ^ np.uint64(int(layer) & 0xFFFFFFFF))", "    k = mix32(k)"),
+    ("key ignores the high half of the seed", "    k = mix32(k ^ np.uint64((seed >> 32) & 0xFFFFFFFF))", "    k = mix32(k)"),
+    ("bits ignore the row", "    hrow = mix32((rows + np.uint64(key)) & _M32)", "    hrow = mix32((rows * np.uint64(0) + np.uint64(key)) & _M32)"),
+    ("bits: one word per column instead of per pair", "(((cols >> np.uint64(1)) * np.uint64(0x9E3779B9)) & _M32)",
+     "((cols * np.uint64(0x9E3779B9)) & _M32)"),
+    ("bits: halves swapped", "np.where(odd, bits >> np.uint64(16), bits & np.uint64(0xFFFF))",
+     "np.where(odd, bits & np.uint64(0xFFFF), bits >> np.uint64(16))"),
+    ("bits: only 15 random bits", "np.where(odd, bits >> np.uint64(16), bits & np.uint64(0xFFFF))",
+     "np.where(odd, bits >> np.uint64(17), bits & np.uint64(0x7FFF))"),
+    ("rounding: random bits not added (truncation)", "    out = ((u + r) >> np.uint64(16)) & np.uint64(0xFFFF)",
+     "    out = (u >> np.uint64(16)) & np.uint64(0xFFFF)"),
+    ("rounding: nearest instead of stochastic", "    out = ((u + r) >> np.uint64(16)) & np.uint64(0xFFFF)",
+     "    out = ((u + np.uint64(0x8000)) >> np.uint64(16)) & np.uint64(0xFFFF)"),
+    ("rounding: one added to the random bits (rounds exact values up)", "    out = ((u + r) >> np.uint64(16)) & np.uint64(0xFFFF)",
+     "    out = ((u + r + np.uint64(1)) >> np.uint64(16)) & np.uint64(0xFFFF)"),
+    ("rounding: NaN not kept quiet", "np.where(is_nan, np.uint64(0x40), np.uint64(0))", "np.where(is_nan, np.uint64(0), np.uint64(0))"),
+    ("matrix: rows and columns swapped", "np.arange(n_r, dtype=np.uint64)[:, None], np.arange(n_c, dtype=np.uint64)[None, :]",
+     "np.arange(n_c, dtype=np.uint64)[None, :], np.arange(n_r, dtype=np.uint64)[:, None]"),
+]
+
+
+@pytest.mark.parametrize("name,old,new", ROUNDING_MUTANTS, ids=[m[0] for m in ROUNDING_MUTANTS])
+def test_rounding_mutant_is_caught(oracle, name, old, new):
+    mod = _mutated_module(oracle, "rounding.py", old, new)
+    killers = _killed_by(_stand_in(oracle, mod), ROUNDING_PINS)
+    print(name, "->", killers)
+    assert killers, "no pin notices: " + name
+
+
 @pytest.fixture(scope="module")
 def mutant_dir(tmp_path_factory):
     return tmp_path_factory.mktemp("oracle_mutants")
@@ -197,5 +240,7 @@ def test_the_untouched_oracle_passes_every_pin(oracle):
     assert _killed_by(_stand_in(oracle, ident), PLAN_LRU_PINS) == []
     ident = _mutated_module(oracle, "plan.py", "def _ceil_div(a, b):", "def _ceil_div(a, b):")
     assert _killed_by(_stand_in(oracle, ident), PLAN_LRU_PINS) == []
+    ident = _mutated_module(oracle, "rounding.py", "import numpy as np\n", "import numpy as np\n")
+    assert _killed_by(_stand_in(oracle, ident), ROUNDING_PINS) == []
     ident = _mutated_module(oracle, "gemm.py", "from .build import build_oracle\n", "from .build import build_oracle\n")
     assert _killed_by(_stand_in(oracle, ident), GEMM_PINS) == []
