@@ -205,6 +205,22 @@ int mlp_destroy(tgemm_mlp* mlp);
 enum { TGEMM_ACT_SIGMOID = 0, TGEMM_ACT_TANH = 1, TGEMM_ACT_RELU = 2 };
 int mlp_set_activation(tgemm_mlp* mlp, int32_t act);
 
+/* Bias terms (section 2 writes each layer as a matrix product; a bias row is the usual extension,
+ * equivalent to a constant-one input column): Z_l = A_{l-1} W_l + 1 b_l^T, added in the forward
+ * product's epilogue before the activation / before the logits are stored.  The backward pass gets
+ * db_l = 1^T D_l (column sums of the error matrix over the batch, summed in a fixed order: bands of
+ * 512 rows, then the bands in ascending order); mlp_step applies b_l <- b_l - lr db_l.
+ *   b   array of n_layers device pointers, b[l-1] -> dims[l] floats (fp32 also for bf16 networks),
+ *       caller-owned like the weights and updated in place by mlp_step; always device memory, also
+ *       when the weights are out-of-core.  NULL removes the bias terms (the default).
+ *   db  NULL, or array of n_layers device pointers (entries may be NULL): mlp_backward and mlp_step
+ *       store db_l there.
+ * Waits for outstanding work, discards a pending forward pass and, when bias terms come or go,
+ * releases the workspaces (the next pass sizes them again; the column-sum scratch of
+ * ceil(batch / 512) x max_l dims[l] floats counts against hbm_budget).
+ * TGEMM_EARG for a NULL entry of b, a pointer that is not device memory, or db without b. */
+int mlp_set_bias(tgemm_mlp* mlp, void* const* b, void* const* db);
+
 /* Rounding of the updated weights in mlp_step for bf16 networks (section 2's update, W_l - lr dW_l,
  * is formed in fp32 in the product's epilogue and then stored as bf16).
  *   TGEMM_ROUND_NEAREST     round to nearest even (default).  An update below half an ulp of the

@@ -8,14 +8,14 @@ the parameters (equation 3) and with respect to the layer outputs (equation
 The equations themselves are not printed, so the textbook forms are taken:
 
     A_0 = X                               [batch x n_0]
-    Z_l = A_{l-1} W_l                     l = 1..L      (no bias)
+    Z_l = A_{l-1} W_l  (+ 1 b_l^T)        l = 1..L      (bias rows b_l optional: bs=None means none)
     A_l = act(Z_l)                        l < L      (act: sigmoid by default; tanh, relu)
     P   = softmax over each row of Z_L;   loss = -mean_b log P[b, y_b]
     D_L = (P - onehot(y)) / batch
-    dW_l     = A_{l-1}^T D_l
+    dW_l     = A_{l-1}^T D_l ;   db_l = 1^T D_l  (column sums over the batch)
     dA_{l-1} = D_l W_l^T ;   D_{l-1} = dA_{l-1} * act'(Z_{l-1})
              act' = A (1 - A) for the sigmoid, 1 - A^2 for tanh, [Z > 0] for relu
-    W_l <- W_l - lr * dW_l               (every dW from the pre-update weights)
+    W_l <- W_l - lr * dW_l ;  b_l <- b_l - lr * db_l     (every gradient from the pre-update values)
 
 numpy's fp64 matmul is the library primitive used for the products.
 """
@@ -53,7 +53,7 @@ def _act_slope(z, a, act):
     raise ValueError(act)
 
 
-def mlp_forward(X, Ws, act="sigmoid", return_pre=False):
+def mlp_forward(X, Ws, act="sigmoid", return_pre=False, bs=None):
     """Returns (acts, logits, probs): acts[l] is the input of layer l+1 (acts[0] = X).
     With return_pre also the hidden pre-activations Z_l as a fourth value."""
     a = _f64(X)
@@ -63,6 +63,8 @@ def mlp_forward(X, Ws, act="sigmoid", return_pre=False):
     z = None
     for l, W in enumerate(Ws):
         z = a @ _f64(W)
+        if bs is not None:
+            z = z + np.asarray(bs[l], dtype=np.float64)[None, :]
         if l < L - 1:
             a = _act(z, act)
             acts.append(a)
@@ -75,20 +77,21 @@ def mlp_forward(X, Ws, act="sigmoid", return_pre=False):
     return acts, z, probs
 
 
-def mlp_loss(X, Ws, y, act="sigmoid"):
-    _, z, _ = mlp_forward(X, Ws, act)
+def mlp_loss(X, Ws, y, act="sigmoid", bs=None):
+    _, z, _ = mlp_forward(X, Ws, act, bs=bs)
     y = np.asarray(y, dtype=np.int64)
     zmax = z.max(axis=1)
     lse = zmax + np.log(np.exp(z - zmax[:, None]).sum(axis=1))
     return float(np.mean(lse - z[np.arange(z.shape[0]), y]))
 
 
-def mlp_backward(X, Ws, y, act="sigmoid"):
-    """Returns (loss, dWs, deltas): deltas[l] is the error at the output of layer l+1."""
-    acts, z, probs, pre = mlp_forward(X, Ws, act, return_pre=True)
+def mlp_backward(X, Ws, y, act="sigmoid", bs=None):
+    """Returns (loss, dWs, deltas): deltas[l] is the error at the output of layer l+1.
+    With bias rows (bs) a fourth value: the bias gradients dbs."""
+    acts, z, probs, pre = mlp_forward(X, Ws, act, return_pre=True, bs=bs)
     y = np.asarray(y, dtype=np.int64)
     B = z.shape[0]
-    loss = mlp_loss(X, Ws, y, act)
+    loss = mlp_loss(X, Ws, y, act, bs=bs)
     d = probs.copy()
     d[np.arange(B), y] -= 1.0
     d /= B
@@ -101,14 +104,23 @@ def mlp_backward(X, Ws, y, act="sigmoid"):
         if l > 0:
             dA = d @ _f64(Ws[l]).T
             d = dA * _act_slope(pre[l], acts[l], act)
+    if bs is not None:
+        return loss, dWs, deltas, [dl.sum(axis=0) for dl in deltas]
     return loss, dWs, deltas
 
 
-def mlp_step(X, Ws, y, lr, act="sigmoid"):
-    """One SGD step.  Returns (loss before the update, new weights in fp64, dWs)."""
-    loss, dWs, _ = mlp_backward(X, Ws, y, act)
+def mlp_step(X, Ws, y, lr, act="sigmoid", bs=None):
+    """One SGD step.  Returns (loss before the update, new weights in fp64, dWs); with bias rows
+    (bs) also the new bias rows and their gradients."""
+    if bs is None:
+        loss, dWs, _ = mlp_backward(X, Ws, y, act)
+    else:
+        loss, dWs, _, dbs = mlp_backward(X, Ws, y, act, bs=bs)
     new = [_f64(W) - lr * g for W, g in zip(Ws, dWs)]
-    return loss, new, dWs
+    if bs is None:
+        return loss, new, dWs
+    new_bs = [np.asarray(b, dtype=np.float64) - lr * g for b, g in zip(bs, dbs)]
+    return loss, new, dWs, new_bs, dbs
 
 
 def mlp_step_stochastic(X, Ws, y, lr, seed, step, act="sigmoid"):

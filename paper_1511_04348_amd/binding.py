@@ -19,7 +19,7 @@ TGEMM_ROUND_NEAREST, TGEMM_ROUND_STOCHASTIC = 0, 1
 EXPORTS = [
     "tgemm_strerror", "tgemm_last_error", "tgemm_create", "tgemm_destroy", "tgemm_run", "tgemm_sync",
     "tgemm_plan", "tgemm_task_order", "tgemm_last_stats", "tgemm_trace", "tgemm_queue_selftest",
-    "mlp_create", "mlp_destroy", "mlp_set_activation", "mlp_set_rounding", "mlp_forward", "mlp_backward", "mlp_step", "mlp_read",
+    "mlp_create", "mlp_destroy", "mlp_set_activation", "mlp_set_rounding", "mlp_set_bias", "mlp_forward", "mlp_backward", "mlp_step", "mlp_read",
 ]
 
 
@@ -84,6 +84,7 @@ def load():
     lib.mlp_destroy.argtypes = [vp]
     lib.mlp_set_activation.argtypes = [vp, i32]
     lib.mlp_set_rounding.argtypes = [vp, i32, ctypes.c_uint64]
+    lib.mlp_set_bias.argtypes = [vp, P(vp), P(vp)]
     lib.mlp_forward.argtypes = [vp, vp, i64, vp]
     lib.mlp_backward.argtypes = [vp, vp, P(vp), P(ctypes.c_float)]
     lib.mlp_step.argtypes = [vp, vp, vp, i64, ctypes.c_float, P(ctypes.c_float)]
@@ -203,6 +204,13 @@ def mlp_set_activation(mlp, act):
 
 def mlp_set_rounding(mlp, mode, seed=0):
     _check(load().mlp_set_rounding(mlp, mode, seed))
+
+
+def mlp_set_bias(mlp, b, db=None):
+    """b: list of float device tensors (one row per layer) or None; db: optional list (entries may be None)."""
+    arr_b = (ctypes.c_void_p * len(b))(*[_p(x) for x in b]) if b is not None else None
+    arr_db = (ctypes.c_void_p * len(db))(*[_p(x) for x in db]) if db is not None else None
+    _check(load().mlp_set_bias(mlp, arr_b, arr_db))
 
 
 def mlp_forward(mlp, X, batch, probs=None):

@@ -434,6 +434,8 @@ hipError_t launch_tile_gemm_bf16(const GemmDesc& d, hipStream_t stream)
 {
     if (d.M <= 0 || d.N <= 0 || d.K < 0 || d.T <= 0) return hipErrorInvalidValue;
     if (d.M > 0x3fffffff || d.N > 0x3fffffff || d.K > 0x3fffffff) return hipErrorInvalidValue;
+    // a bias row goes with the forward products only: activation, or plain fp32 result
+    if (d.bias && !(d.epilogue == EPI_ACT || (d.epilogue == EPI_AXPBY && !d.out_bf16))) return hipErrorInvalidValue;
     GemmParams p;
     p.A = d.A; p.B = d.B; p.C = d.C; p.aux = d.aux;
     p.lda = d.lda; p.ldb = d.ldb; p.ldc = d.ldc; p.ldaux = d.ldaux;
@@ -445,6 +447,8 @@ hipError_t launch_tile_gemm_bf16(const GemmDesc& d, hipStream_t stream)
     p.alpha = d.alpha; p.beta = d.beta; p.act = d.act;
     p.sr = (d.sr && d.out_bf16 && d.epilogue == EPI_AXPBY) ? 1 : 0;
     p.sr_key = d.sr_key; p.sr_row0 = (uint32_t)d.sr_row0;
+    p.bias = d.bias;
+    p.vec_bias = d.bias && ((reinterpret_cast<uintptr_t>(d.bias) & 15) == 0) && (T % 4 == 0);
     p.b_tiles = d.b_tiles; p.c_tiles = d.c_tiles;
     // k-contiguous operands use 16-byte loads (8 elements), m/n-contiguous ones 8-byte loads (4)
     auto ok = [&](const void* q, int64_t ld, bool kc) {

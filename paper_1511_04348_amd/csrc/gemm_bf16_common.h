@@ -145,10 +145,20 @@ __device__ inline void epilogue(const GemmParams& p, const TileCoord& t, const f
             for (int g = 0; g < 4; ++g) {
                 const int col = wcol0 + 32 * cc + 8 * g + 4 * lh;
                 if (col >= t.col_end) continue;
+                f32x4 bv = {0.f, 0.f, 0.f, 0.f};   // this quad's columns of the bias row
+                if ((EPI == EPI_ACT || (EPI == EPI_AXPBY && !OUT_BF16)) && p.bias) {   // the forward products
+                    if (col + 3 < t.col_end && p.vec_bias) {
+                        bv = gload<f32x4>(p.bias + col);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (col + e < t.col_end) bv[e] = gload<float>(p.bias + col + e);
+                    }
+                }
                 f32x4 o;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    float v = acc[r][cc][4 * g + e];
+                    float v = acc[r][cc][4 * g + e] + bv[e];
                     if (EPI == EPI_AXPBY) {
                         v = read_c ? fmaf(alpha, v, beta * in[cc][g][e]) : alpha * v;
                     } else if (EPI == EPI_ACT) {

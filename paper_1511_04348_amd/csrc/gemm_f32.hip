@@ -345,6 +345,9 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
     const float alpha = p.alpha, beta = p.beta;
     const int colb = col0 + wn * WTN + RB * li;
     const bool cvec = p.vec_c && (RB == 4) && (colb + 3 < col_end);
+    float bv[RB];   // this lane's columns of the bias row
+#pragma unroll
+    for (int cc = 0; cc < RB; ++cc) bv[cc] = (p.bias && colb + cc < col_end) ? gload<float>(p.bias + colb + cc) : 0.f;
 #pragma unroll
     for (int r = 0; r < RA; ++r) {
 #pragma unroll
@@ -353,7 +356,7 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
             if (row >= row_end) continue;
             float o[RB];
 #pragma unroll
-            for (int cc = 0; cc < RB; ++cc) o[cc] = acc[r][cc][v];
+            for (int cc = 0; cc < RB; ++cc) o[cc] = acc[r][cc][v] + bv[cc];
             float* dst = C + (int64_t)row * p.ldc + colb;
             if (EPI == EPI_AXPBY) {
                 if (beta != 0.f) {
@@ -499,7 +502,7 @@ hipError_t launch_tile_gemm_f32(const GemmDesc& d, hipStream_t stream)
     if (T > big) T = big > 0 ? big : 1;
     p.T = (int)T;
     p.alpha = d.alpha; p.beta = d.beta; p.act = d.act;
-    p.sr = 0; p.sr_key = 0; p.sr_row0 = 0;
+    p.sr = 0; p.sr_key = 0; p.sr_row0 = 0; p.bias = d.bias; p.vec_bias = false;
     p.b_tiles = d.b_tiles; p.c_tiles = d.c_tiles;
     const bool t4 = (T % 4 == 0);
     auto al16 = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15) == 0; };

@@ -29,6 +29,10 @@ struct GemmDesc {
     int32_t config;   // 0 = automatic, 1..3 = small / medium / large macro tile
     int32_t out_bf16; // bf16 kernel only: C (and aux) hold bf16 bit patterns instead of float
     int32_t act;      // ACT_* for EPI_ACT / EPI_DACT
+    // Optional row vector (N floats, device) added to every row of A B before the epilogue function:
+    // EPI_ACT gives act(A B + 1 bias^T), EPI_AXPBY alpha (A B + 1 bias^T) + beta C.  NULL = none.
+    // The bf16 kernels take it with EPI_ACT and with EPI_AXPBY into a float C only.
+    const float* bias;
     // bf16 kernel, EPI_AXPBY with out_bf16: round the result stochastically instead of to nearest.
     // Entry (row, col) of this launch draws its 16 random bits from rounding_bits(sr_key,
     // sr_row0 + row, col); sr_row0 places a launch that covers a band of rows inside the whole matrix.
@@ -59,11 +63,13 @@ struct GemmParams {
     int n_chunks;               // BK-chunks over all k-steps
     float alpha, beta;
     int act;                    // ACT_* for the activation epilogues
+    const float* bias;          // see GemmDesc
     int sr;                     // stochastic rounding of a bf16 result (see GemmDesc)
     uint32_t sr_key;
     uint32_t sr_row0;
     bool vec_a, vec_b, vec_c;   // vector access is legal for this operand
     bool vec_aux;               // bf16 kernels: 8-byte access to aux is legal
+    bool vec_bias;              // bf16 kernels: 16-byte access to bias is legal
     bool fast_a, fast_b;        // interior tiles may use the unpredicated, 32-bit-offset load path
     bool fast_k;                // every k chunk is full (no ragged k-step tails)
     const void* const* b_tiles; // see GemmDesc

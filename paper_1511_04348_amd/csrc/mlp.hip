@@ -187,6 +187,9 @@ struct tgemm_mlp {
     int n_layers = 0;
     std::vector<int64_t> dims;
     std::vector<char*> W;         // caller-owned weights (device or pinned host)
+    std::vector<float*> bias;     // caller-owned bias rows b_l (device, float), empty: no bias terms
+    std::vector<float*> dbias;    // caller-owned destinations of mlp_backward's bias gradients, may hold NULLs
+    float* colsum_part = nullptr; // partial column sums of an error matrix: COLSUM_CHUNKS x max n_l floats
     int32_t dtype = TGEMM_F32;
     int32_t act_kind = TGEMM_ACT_SIGMOID;   // hidden-layer activation
     int32_t round_mode = TGEMM_ROUND_NEAREST;   // how mlp_step rounds updated bf16 weights
@@ -270,6 +273,60 @@ __global__ __launch_bounds__(256) void softmax_xent_rows(const float* __restrict
     if (tid == 0 && labels) row_loss[row] = (y >= 0 && y < n) ? (logf(s) + m - z[y]) : NAN;
 }
 
+// Bias gradient db = 1^T D (column sums of the batch x n error matrix), in two deterministic passes:
+// partial sums over bands of COLSUM_ROWS rows, then the bands in ascending order.  The second pass
+// stores the sum (db != NULL) and / or applies b <- b - lr * sum (b != NULL).
+constexpr int COLSUM_ROWS = 512;
+// VEC = 4: a thread owns four adjacent columns (one 8- or 16-byte load per row; needs n % 4 == 0 and a
+// 16-byte aligned matrix); VEC = 1: one column per thread.  Rows are added in ascending order either way.
+template <bool BF16, int VEC>
+__global__ __launch_bounds__(256) void colsum_partial(const void* __restrict__ D, int64_t ld, int64_t rows, int n,
+                                                      float* __restrict__ part)
+{
+    const int col = (blockIdx.x * 256 + threadIdx.x) * VEC;
+    if (col >= n) return;
+    const int64_t r0 = (int64_t)blockIdx.y * COLSUM_ROWS, r1 = min(rows, r0 + COLSUM_ROWS);
+    float s[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) s[e] = 0.f;
+    if (BF16) {
+        const uint16_t* d = reinterpret_cast<const uint16_t*>(D) + col;
+#pragma unroll 4
+        for (int64_t r = r0; r < r1; ++r) {
+            if (VEC == 4) {
+                const uint2 w = *reinterpret_cast<const uint2*>(d + r * ld);
+                s[0] += __uint_as_float(w.x << 16); s[1 % VEC] += __uint_as_float(w.x & 0xffff0000u);
+                s[2 % VEC] += __uint_as_float(w.y << 16); s[3 % VEC] += __uint_as_float(w.y & 0xffff0000u);
+            } else {
+                s[0] += __uint_as_float((uint32_t)d[r * ld] << 16);
+            }
+        }
+    } else {
+        const float* d = reinterpret_cast<const float*>(D) + col;
+#pragma unroll 4
+        for (int64_t r = r0; r < r1; ++r) {
+            if (VEC == 4) {
+                const float4 w = *reinterpret_cast<const float4*>(d + r * ld);
+                s[0] += w.x; s[1 % VEC] += w.y; s[2 % VEC] += w.z; s[3 % VEC] += w.w;
+            } else {
+                s[0] += d[r * ld];
+            }
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) part[(int64_t)blockIdx.y * n + col + e] = s[e];
+}
+__global__ __launch_bounds__(256) void colsum_finish(const float* __restrict__ part, int bands, int n, float lr,
+                                                     float* __restrict__ b, float* __restrict__ db)
+{
+    const int col = blockIdx.x * 256 + threadIdx.x;
+    if (col >= n) return;
+    float s = 0.f;
+    for (int k = 0; k < bands; ++k) s += part[(int64_t)k * n + col];
+    if (db) db[col] = s;
+    if (b) b[col] -= lr * s;
+}
+
 double now_ms()
 {
     return std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now().time_since_epoch()).count();
@@ -283,7 +340,8 @@ void free_workspaces(tgemm_mlp* m)
     for (auto& p : m->delta) { if (p) (void)hipFree(p); p = nullptr; }
     if (m->logits) (void)hipFree(m->logits);
     if (m->row_loss) (void)hipFree(m->row_loss);
-    m->logits = nullptr; m->row_loss = nullptr;
+    if (m->colsum_part) (void)hipFree(m->colsum_part);
+    m->logits = nullptr; m->row_loss = nullptr; m->colsum_part = nullptr;
     m->cap_batch = 0; m->batch = 0; m->have_delta = false;
     m->cache.release();
     TableRing& r = m->ring;
@@ -310,6 +368,13 @@ int ensure_workspaces(tgemm_mlp* m, int64_t batch)
     const int L = m->n_layers;
     size_t total = (size_t)batch * 4 + (size_t)batch * m->dims[L] * 4;
     for (int l = 1; l <= L; ++l) total += (size_t)batch * m->dims[l] * m->es * (l < L ? 2 : 1);
+    size_t colsum_bytes = 0;
+    if (!m->bias.empty()) {
+        int64_t widest = 0;
+        for (int l = 1; l <= L; ++l) widest = std::max(widest, m->dims[l]);
+        colsum_bytes = (size_t)cdiv(batch, COLSUM_ROWS) * widest * 4;
+        total += colsum_bytes;
+    }
     // out-of-core: the rest of the budget is the weight tile cache
     int64_t max_tiles = 0, n_slots = 0;
     const size_t slot_bytes = (size_t)m->T * m->T * m->es;
@@ -333,6 +398,7 @@ int ensure_workspaces(tgemm_mlp* m, int64_t batch)
         return true;
     };
     bool ok = alloc((void**)&m->row_loss, (size_t)batch * 4) && alloc((void**)&m->logits, (size_t)batch * m->dims[L] * 4);
+    if (colsum_bytes) ok = ok && alloc((void**)&m->colsum_part, colsum_bytes);
     for (int l = 1; l <= L && ok; ++l) {
         if (l < L) ok = ok && alloc((void**)&m->act[l], (size_t)batch * m->dims[l] * m->es);
         ok = ok && alloc((void**)&m->delta[l], (size_t)batch * m->dims[l] * m->es);
@@ -511,9 +577,11 @@ int forward_layer(tgemm_mlp* m, int l, const char* in, int64_t batch)
     char* out = (l < L) ? m->act[l] : (char*)m->logits;
     const size_t out_es = (l < L) ? m->es : 4;
     d.ldc = m->dims[l];
+    const float* b = m->bias.empty() ? nullptr : m->bias[(size_t)l - 1];
     if (!m->ooc) {
         d.B = m->W[l - 1]; d.ldb = m->dims[l];
         d.C = (float*)out; d.N = m->dims[l];
+        d.bias = b;
         return launch(m, d, compute_stream(m));
     }
     // out-of-core: one launch per tile column j of W_l, over the whole batch and all k-steps
@@ -529,6 +597,7 @@ int forward_layer(tgemm_mlp* m, int l, const char* in, int64_t batch)
         d.B = m->cache.ptr(tiles[0]); d.ldb = T;
         d.C = (float*)(out + (size_t)(j * T) * out_es);
         d.N = std::min(T, m->dims[l] - j * T);
+        d.bias = b ? b + j * T : nullptr;
         if ((rc = launch(m, d, compute_stream(m))) != TGEMM_OK) return rc;
         if ((rc = ring_finish(m, entry, tiles.data(), (int)n_k)) != TGEMM_OK) return rc;
         ++m->cache.launch_id;
@@ -611,6 +680,24 @@ int backward_layer(tgemm_mlp* m, int l, float* dW_out, bool update, float lr)
     const int64_t batch = m->batch, T = m->T;
     const char* a_prev = (l == 1) ? m->X : m->act[l - 1];
     hipStream_t comp = compute_stream(m);
+
+    if (!m->bias.empty()) {   // db_l = 1^T D_l; D_l is complete on the compute stream at this point
+        float* db = m->dbias.empty() ? nullptr : m->dbias[(size_t)l - 1];
+        float* b = update ? m->bias[(size_t)l - 1] : nullptr;
+        if (db || b) {
+            const int n = (int)m->dims[l], bands = (int)cdiv(batch, COLSUM_ROWS);
+            const bool vec = (n % 4 == 0) && ((reinterpret_cast<uintptr_t>(m->delta[l]) & 15) == 0);
+            const dim3 grid((unsigned)cdiv(n, vec ? 1024 : 256), (unsigned)bands);
+            const void* D = m->delta[l];
+            if (bf && vec) hipLaunchKernelGGL((colsum_partial<true, 4>), grid, dim3(256), 0, comp, D, (int64_t)n, batch, n, m->colsum_part);
+            else if (bf) hipLaunchKernelGGL((colsum_partial<true, 1>), grid, dim3(256), 0, comp, D, (int64_t)n, batch, n, m->colsum_part);
+            else if (vec) hipLaunchKernelGGL((colsum_partial<false, 4>), grid, dim3(256), 0, comp, D, (int64_t)n, batch, n, m->colsum_part);
+            else hipLaunchKernelGGL((colsum_partial<false, 1>), grid, dim3(256), 0, comp, D, (int64_t)n, batch, n, m->colsum_part);
+            hipLaunchKernelGGL(colsum_finish, dim3((unsigned)cdiv(n, 256)), dim3(256), 0, comp,
+                               (const float*)m->colsum_part, bands, n, lr, b, db);
+            TG_HIP(hipGetLastError());
+        }
+    }
 
     GemmDesc da;   // D_{l-1} = (D_l W_l^T) * A_{l-1} * (1 - A_{l-1})
     memset(&da, 0, sizeof da);
@@ -803,6 +890,41 @@ int mlp_set_activation(tgemm_mlp* m, int32_t act)
                   "activation codes of the ABI and of the kernels");
     m->act_kind = act;
     m->batch = 0;          // activations of an earlier forward pass belong to the old function
+    m->have_delta = false;
+    return TGEMM_OK;
+}
+
+int mlp_set_bias(tgemm_mlp* m, void* const* b, void* const* db)
+{
+    if (!m) return fail(TGEMM_EARG, "mlp_set_bias: object is NULL");
+    TG_HIP(hipSetDevice(m->ctx->device));
+    if (!b) {
+        if (db) return fail(TGEMM_EARG, "mlp_set_bias: gradient destinations without bias rows");
+    } else {
+        for (int l = 0; l < m->n_layers; ++l) {
+            if (!b[l]) return fail(TGEMM_EARG, "mlp_set_bias: b[%d] is NULL", l);
+            hipPointerAttribute_t at;
+            if (hipPointerGetAttributes(&at, b[l]) != hipSuccess || at.type != hipMemoryTypeDevice) {
+                (void)hipGetLastError();
+                return fail(TGEMM_EARG, "mlp_set_bias: b[%d] is not device memory", l);
+            }
+            if (db && db[l] && (hipPointerGetAttributes(&at, db[l]) != hipSuccess || at.type != hipMemoryTypeDevice)) {
+                (void)hipGetLastError();
+                return fail(TGEMM_EARG, "mlp_set_bias: db[%d] is not device memory", l);
+            }
+        }
+    }
+    int rc = sync_all(m);
+    if (rc != TGEMM_OK) return rc;
+    const bool had = !m->bias.empty();
+    m->bias.clear();
+    m->dbias.clear();
+    if (b) {
+        for (int l = 0; l < m->n_layers; ++l) m->bias.push_back((float*)b[l]);
+        if (db) for (int l = 0; l < m->n_layers; ++l) m->dbias.push_back((float*)db[l]);
+    }
+    if (had != !m->bias.empty()) free_workspaces(m);   // the column-sum scratch comes or goes with the bias terms
+    m->batch = 0;            // a pending forward pass belongs to the old function
     m->have_delta = false;
     return TGEMM_OK;
 }

@@ -183,3 +183,106 @@ def test_step_descends_for_every_activation(oracle):
         l1 = oracle.mlp_loss(X, new, y, act=act)
         g2 = sum((g ** 2).sum() for g in dWs)
         assert abs((l1 - l0) + lr * g2) < 5e-2 * lr * g2
+
+
+# ---- bias rows -----------------------------------------------------------------------------------
+
+def _biases(seed, dims):
+    r = np.random.default_rng(seed)
+    return [r.normal(0, 0.5, n).astype(np.float32) for n in dims[1:]]
+
+
+def test_bias_finite_differences(oracle):
+    for act in ("sigmoid", "tanh"):
+        dims = [5, 6, 6, 4]          # two layers of one width: a bias row taken from the wrong layer still fits
+        X, Ws, y = _net(20, dims, 3)
+        bs = [b.astype(np.float64) for b in _biases(21, dims)]
+        loss, dWs, _, dbs = oracle.mlp_backward(X, Ws, y, act, bs=bs)
+        assert abs(loss - oracle.mlp_loss(X, Ws, y, act, bs=bs)) < 1e-15
+        h = 1e-5
+        for l, b in enumerate(bs):
+            num = np.zeros_like(b)
+            for i in range(b.size):
+                old = b[i]
+                b[i] = old + h
+                lp = oracle.mlp_loss(X, Ws, y, act, bs=bs)
+                b[i] = old - h
+                lm = oracle.mlp_loss(X, Ws, y, act, bs=bs)
+                b[i] = old
+                num[i] = (lp - lm) / (2 * h)
+            assert np.linalg.norm(num - dbs[l]) / np.linalg.norm(dbs[l]) < 1e-6, (act, l)
+        # the weight gradients with bias rows present, one layer by finite differences
+        W64 = [w.astype(np.float64) for w in Ws]
+        num = np.zeros_like(W64[1])
+        for idx in np.ndindex(*W64[1].shape):
+            old = W64[1][idx]
+            W64[1][idx] = old + h
+            lp = oracle.mlp_loss(X, W64, y, act, bs=bs)
+            W64[1][idx] = old - h
+            lm = oracle.mlp_loss(X, W64, y, act, bs=bs)
+            W64[1][idx] = old
+            num[idx] = (lp - lm) / (2 * h)
+        assert np.linalg.norm(num - dWs[1]) / np.linalg.norm(dWs[1]) < 1e-6
+
+
+def test_bias_is_a_constant_one_input_column(oracle):
+    """A bias row equals one more weight row fed by an input that is always 1 (layer by layer: the
+    augmented activation is [A_l, 1])."""
+    X, Ws, y = _net(22, [6, 5], 8)
+    b = _biases(23, [6, 5])
+    X1 = np.concatenate([X, np.ones((8, 1), dtype=np.float32)], axis=1)
+    W1 = [np.concatenate([Ws[0], b[0][None, :]], axis=0)]
+    loss_b, dW_b, _, db = oracle.mlp_backward(X, Ws, y, bs=b)
+    loss_1, dW_1, _ = oracle.mlp_backward(X1, W1, y)
+    assert abs(loss_b - loss_1) < 1e-15
+    assert np.allclose(dW_1[0][:-1], dW_b[0], atol=1e-16) and np.allclose(dW_1[0][-1], db[0], atol=1e-16)
+    # two layers, by hand: hidden activations of the biased net feed an augmented second layer
+    X, Ws, y = _net(24, [4, 6, 3], 5)
+    b = _biases(25, [4, 6, 3])
+    acts, z, P = oracle.mlp_forward(X, Ws, bs=b)
+    h = 1.0 / (1.0 + np.exp(-(X.astype(np.float64) @ Ws[0] + b[0])))
+    assert np.allclose(acts[1], h, atol=1e-15)
+    assert np.allclose(z, np.concatenate([h, np.ones((5, 1))], 1) @ np.concatenate([Ws[1], b[1][None, :]], 0), atol=1e-14)
+
+
+def test_bias_closed_forms(oracle):
+    # zero weights: the logits are the last bias row whatever the input; P = softmax(b_L)
+    dims = [6, 8, 5]
+    X, Ws, y = _net(26, dims, 4)
+    Ws = [np.zeros_like(w) for w in Ws]
+    b = _biases(27, dims)
+    acts, z, P = oracle.mlp_forward(X, Ws, bs=b)
+    sm = np.exp(b[1].astype(np.float64))
+    sm /= sm.sum()
+    assert np.allclose(z, np.tile(b[1].astype(np.float64), (4, 1)), atol=0) and np.allclose(P, np.tile(sm, (4, 1)), atol=1e-16)
+    assert np.allclose(acts[1], np.tile(1 / (1 + np.exp(-b[0].astype(np.float64))), (4, 1)), atol=1e-16)
+    loss, dWs, deltas, dbs = oracle.mlp_backward(X, Ws, y, bs=b)
+    # db_L = softmax(b_L) - class frequencies
+    freq = np.bincount(y, minlength=5) / 4.0
+    assert np.allclose(dbs[1], sm - freq, atol=1e-15)
+    assert abs(dbs[1].sum()) < 1e-15                       # rows of D_L sum to zero
+    assert np.array_equal(dbs[0], np.zeros(8))             # nothing flows back through zero weights
+    # zero bias rows change nothing
+    X, Ws, y = _net(28, [5, 7, 4], 6)
+    zb = [np.zeros(7), np.zeros(4)]
+    l0, g0, d0 = oracle.mlp_backward(X, Ws, y)
+    l1, g1, d1, db1 = oracle.mlp_backward(X, Ws, y, bs=zb)
+    assert l0 == l1 and all(np.array_equal(a, c) for a, c in zip(g0, g1))
+    assert all(np.array_equal(d.sum(axis=0), g) for d, g in zip(d1, db1)) and db1[0].shape == (7,) and db1[1].shape == (4,)
+
+
+def test_bias_step(oracle):
+    dims = [6, 9, 5]
+    X, Ws, y = _net(29, dims, 16)
+    b = _biases(30, dims)
+    loss, new, dWs, new_b, dbs = oracle.mlp_step(X, Ws, y, 0.05, bs=b)
+    _, g, _, gb = oracle.mlp_backward(X, Ws, y, bs=b)
+    for l in range(2):
+        assert np.array_equal(new[l], Ws[l].astype(np.float64) - 0.05 * g[l])
+        assert np.array_equal(new_b[l], b[l].astype(np.float64) - 0.05 * gb[l]) and np.array_equal(dbs[l], gb[l])
+    # first-order descent including the bias part of the gradient
+    after = oracle.mlp_loss(X, new, y, bs=new_b)
+    pred = loss - 0.05 * (sum((x ** 2).sum() for x in g) + sum((x ** 2).sum() for x in gb))
+    assert after < loss and abs(after - pred) < 0.05 * (loss - pred) + 1e-6
+    # moving only the bias rows along -db lowers the loss too
+    assert oracle.mlp_loss(X, Ws, y, bs=new_b) < loss

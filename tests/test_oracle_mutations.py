@@ -57,7 +57,9 @@ MLP_PINS = [(pins_mlp.test_finite_differences_every_weight, ()), (pins_mlp.test_
             (pins_mlp.test_single_layer_is_softmax_regression, ()), (pins_mlp.test_invariants_and_orientation, ()),
             (pins_mlp.test_step_descends_first_order, ()), (pins_mlp.test_bf16_inputs_widen_exactly, ()),
             (pins_mlp.test_finite_differences_tanh_and_relu, ()), (pins_mlp.test_activation_values_written_out, ()),
-            (pins_mlp.test_activation_symmetries, ()), (pins_mlp.test_step_descends_for_every_activation, ())]
+            (pins_mlp.test_activation_symmetries, ()), (pins_mlp.test_step_descends_for_every_activation, ()),
+            (pins_mlp.test_bias_finite_differences, ()), (pins_mlp.test_bias_is_a_constant_one_input_column, ()),
+            (pins_mlp.test_bias_closed_forms, ()), (pins_mlp.test_bias_step, ())]
 
 MLP_MUTANTS = [
     ("sigmoid sign", "        return 1.0 / (1.0 + np.exp(-z))", "        return 1.0 / (1.0 + np.exp(z))"),
@@ -81,7 +83,22 @@ MLP_MUTANTS = [
     ("delta not propagated", "dA = d @ _f64(Ws[l]).T", "dA = d @ np.abs(_f64(Ws[l])).T"),
     ("update sign", "new = [_f64(W) - lr * g for W, g in zip(Ws, dWs)]", "new = [_f64(W) + lr * g for W, g in zip(Ws, dWs)]"),
     ("update without lr", "new = [_f64(W) - lr * g for W, g in zip(Ws, dWs)]", "new = [_f64(W) - g for W, g in zip(Ws, dWs)]"),
-    ("loss ignores the activation", "    _, z, _ = mlp_forward(X, Ws, act)", "    _, z, _ = mlp_forward(X, Ws)"),
+    ("loss ignores the activation", "    _, z, _ = mlp_forward(X, Ws, act, bs=bs)", "    _, z, _ = mlp_forward(X, Ws, bs=bs)"),
+    ("loss ignores the bias rows", "    _, z, _ = mlp_forward(X, Ws, act, bs=bs)", "    _, z, _ = mlp_forward(X, Ws, act)"),
+    ("bias added along the batch", "            z = z + np.asarray(bs[l], dtype=np.float64)[None, :]",
+     "            z = z + np.asarray(bs[l], dtype=np.float64)[None, :].mean()"),
+    ("bias subtracted", "            z = z + np.asarray(bs[l], dtype=np.float64)[None, :]",
+     "            z = z - np.asarray(bs[l], dtype=np.float64)[None, :]"),
+    ("bias of the wrong layer", "            z = z + np.asarray(bs[l], dtype=np.float64)[None, :]",
+     "            z = z + np.asarray(bs[l if l == 0 or bs[l - 1].shape != bs[l].shape else l - 1], dtype=np.float64)[None, :]"),
+    ("backward pass forgets the bias in its forward", "    acts, z, probs, pre = mlp_forward(X, Ws, act, return_pre=True, bs=bs)",
+     "    acts, z, probs, pre = mlp_forward(X, Ws, act, return_pre=True)"),
+    ("db summed over the wrong axis", "[dl.sum(axis=0) for dl in deltas]", "[dl.sum(axis=1) for dl in deltas]"),
+    ("db averaged instead of summed", "[dl.sum(axis=0) for dl in deltas]", "[dl.mean(axis=0) for dl in deltas]"),
+    ("bias update sign", "new_bs = [np.asarray(b, dtype=np.float64) - lr * g for b, g in zip(bs, dbs)]",
+     "new_bs = [np.asarray(b, dtype=np.float64) + lr * g for b, g in zip(bs, dbs)]"),
+    ("bias update without lr", "new_bs = [np.asarray(b, dtype=np.float64) - lr * g for b, g in zip(bs, dbs)]",
+     "new_bs = [np.asarray(b, dtype=np.float64) - g for b, g in zip(bs, dbs)]"),
 ]
 
 
