@@ -214,16 +214,6 @@ struct tgemm_mlp {
 namespace tg {
 namespace {
 
-__device__ inline float wave_max(float v)
-{
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-    return v;
-}
-__device__ inline float wave_sum(float v)
-{
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-    return v;
-}
 __device__ inline uint16_t to_bf16_rne(float f)
 {
     uint32_t u = __float_as_uint(f);
@@ -235,38 +225,76 @@ __device__ inline uint16_t to_bf16_rne(float f)
 // One workgroup per row of the logits.  P = softmax(z) with the row maximum subtracted;
 // row_loss = -log P[label]; delta = (P - onehot(label)) * inv_batch (float, or bf16 rounded to
 // nearest even).  probs / delta / labels may be NULL (no labels: no loss, no delta).
-template <bool DELTA_BF16>
+// The row is read twice: once for the maximum and the sum together (each thread keeps a running
+// maximum m and the sum of exp(z - m), rescaled whenever m grows; threads, then waves, are merged the
+// same way), once to write the results.  VEC: four adjacent columns per access (n % 4 == 0, aligned).
+__device__ inline void softmax_merge(float& m, float& s, float m2, float s2)
+{
+    const float mn = fmaxf(m, m2);
+    if (mn == -INFINITY) return;                         // nothing but -inf so far on both sides
+    s = s * expf(m - mn) + s2 * expf(m2 - mn);
+    m = mn;
+}
+template <bool DELTA_BF16, bool VEC>
 __global__ __launch_bounds__(256) void softmax_xent_rows(const float* __restrict__ logits, int64_t ld, int n,
                                                          const int32_t* __restrict__ labels, float inv_batch,
                                                          void* __restrict__ delta, float* __restrict__ probs,
                                                          float* __restrict__ row_loss)
 {
-    __shared__ float red[4];
+    __shared__ float red_m[4], red_s[4];
     const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float* z = logits + (int64_t)row * ld;
-    float m = -INFINITY;
-    for (int c = tid; c < n; c += 256) m = fmaxf(m, z[c]);
-    m = wave_max(m);
-    if (lane == 0) red[wave] = m;
+    float m = -INFINITY, s = 0.f;
+    if (VEC) {
+        for (int c = 4 * tid; c < n; c += 1024) {
+            const float4 x = *reinterpret_cast<const float4*>(z + c);
+            const float mn = fmaxf(m, fmaxf(fmaxf(x.x, x.y), fmaxf(x.z, x.w)));
+            if (mn > -INFINITY) {
+                s = s * expf(m - mn) + ((expf(x.x - mn) + expf(x.y - mn)) + (expf(x.z - mn) + expf(x.w - mn)));
+                m = mn;
+            }
+        }
+    } else {
+        for (int c = tid; c < n; c += 256) softmax_merge(m, s, z[c], 1.f);
+    }
+    for (int o = 32; o > 0; o >>= 1) softmax_merge(m, s, __shfl_xor(m, o, 64), __shfl_xor(s, o, 64));
+    if (lane == 0) { red_m[wave] = m; red_s[wave] = s; }
     __syncthreads();
-    m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
-    __syncthreads();
-    float s = 0.f;
-    for (int c = tid; c < n; c += 256) s += expf(z[c] - m);
-    s = wave_sum(s);
-    if (lane == 0) red[wave] = s;
-    __syncthreads();
-    s = (red[0] + red[1]) + (red[2] + red[3]);
+    m = red_m[0]; s = red_s[0];
+    for (int w = 1; w < 4; ++w) softmax_merge(m, s, red_m[w], red_s[w]);
     const int y = labels ? labels[row] : -1;
     const float inv = 1.f / s;
     if (probs || delta) {
-        for (int c = tid; c < n; c += 256) {
-            const float p = expf(z[c] - m) * inv;
-            if (probs) probs[(int64_t)row * ld + c] = p;
-            if (delta) {
-                const float d = (p - (c == y ? 1.f : 0.f)) * inv_batch;
-                if (DELTA_BF16) reinterpret_cast<uint16_t*>(delta)[(int64_t)row * ld + c] = to_bf16_rne(d);
-                else reinterpret_cast<float*>(delta)[(int64_t)row * ld + c] = d;
+        if (VEC) {
+            for (int c = 4 * tid; c < n; c += 1024) {
+                const float4 x = *reinterpret_cast<const float4*>(z + c);
+                float4 p;
+                p.x = expf(x.x - m) * inv; p.y = expf(x.y - m) * inv;
+                p.z = expf(x.z - m) * inv; p.w = expf(x.w - m) * inv;
+                if (probs) *reinterpret_cast<float4*>(probs + (int64_t)row * ld + c) = p;
+                if (delta) {
+                    float4 d;
+                    d.x = (p.x - (c == y ? 1.f : 0.f)) * inv_batch; d.y = (p.y - (c + 1 == y ? 1.f : 0.f)) * inv_batch;
+                    d.z = (p.z - (c + 2 == y ? 1.f : 0.f)) * inv_batch; d.w = (p.w - (c + 3 == y ? 1.f : 0.f)) * inv_batch;
+                    if (DELTA_BF16) {
+                        uint2 w;
+                        w.x = (uint32_t)to_bf16_rne(d.x) | ((uint32_t)to_bf16_rne(d.y) << 16);
+                        w.y = (uint32_t)to_bf16_rne(d.z) | ((uint32_t)to_bf16_rne(d.w) << 16);
+                        *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(delta) + (int64_t)row * ld + c) = w;
+                    } else {
+                        *reinterpret_cast<float4*>(reinterpret_cast<float*>(delta) + (int64_t)row * ld + c) = d;
+                    }
+                }
+            }
+        } else {
+            for (int c = tid; c < n; c += 256) {
+                const float p = expf(z[c] - m) * inv;
+                if (probs) probs[(int64_t)row * ld + c] = p;
+                if (delta) {
+                    const float d = (p - (c == y ? 1.f : 0.f)) * inv_batch;
+                    if (DELTA_BF16) reinterpret_cast<uint16_t*>(delta)[(int64_t)row * ld + c] = to_bf16_rne(d);
+                    else reinterpret_cast<float*>(delta)[(int64_t)row * ld + c] = d;
+                }
             }
         }
     }
@@ -624,12 +652,15 @@ int softmax(tgemm_mlp* m, const int32_t* labels, float* probs, bool want_delta)
     const int L = m->n_layers;
     const int64_t n = m->dims[L];
     void* delta = want_delta ? (void*)m->delta[L] : nullptr;
-    if (m->dtype == TGEMM_BF16)
-        hipLaunchKernelGGL(softmax_xent_rows<true>, dim3((unsigned)m->batch), dim3(256), 0, compute_stream(m),
-                           m->logits, n, (int)n, labels, 1.f / (float)m->batch, delta, probs, m->row_loss);
-    else
-        hipLaunchKernelGGL(softmax_xent_rows<false>, dim3((unsigned)m->batch), dim3(256), 0, compute_stream(m),
-                           m->logits, n, (int)n, labels, 1.f / (float)m->batch, delta, probs, m->row_loss);
+    const bool vec = (n % 4 == 0) && ((reinterpret_cast<uintptr_t>(probs) & 15) == 0);   // the workspaces are aligned
+    const dim3 grid((unsigned)m->batch), block(256);
+    const float inv_batch = 1.f / (float)m->batch;
+    hipStream_t st = compute_stream(m);
+#define TG_SOFTMAX(BF, V) \
+    hipLaunchKernelGGL((softmax_xent_rows<BF, V>), grid, block, 0, st, m->logits, n, (int)n, labels, inv_batch, delta, probs, m->row_loss)
+    if (m->dtype == TGEMM_BF16) { if (vec) TG_SOFTMAX(true, true); else TG_SOFTMAX(true, false); }
+    else { if (vec) TG_SOFTMAX(false, true); else TG_SOFTMAX(false, false); }
+#undef TG_SOFTMAX
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(TGEMM_EHIP, "mlp: softmax launch failed: %s", hipGetErrorString(e));
     return TGEMM_OK;
