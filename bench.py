@@ -151,6 +151,9 @@ def run_mlp(args, tg, inputs, torch, dims, batch, T, bf16, budget):
     if args.bias:
         bias = [torch.zeros(dims[l + 1], device="cuda") for l in range(len(dims) - 1)]
         tg.mlp_set_bias(mlp, bias)
+    if args.momentum is not None and not budget:
+        vel = [torch.zeros(dims[l], dims[l + 1], device="cuda") for l in range(len(dims) - 1)]
+        tg.mlp_set_momentum(mlp, args.momentum, vel)
     for _ in range(args.warmup):
         tg.mlp_step(mlp, X, y, batch, 0.01)
     tg.tgemm_sync(ctx)
@@ -170,7 +173,7 @@ def run_mlp(args, tg, inputs, torch, dims, batch, T, bf16, budget):
                     "MLP train step %s, layers %s, batch %d, sigmoid hidden, softmax + cross-entropy, SGD lr 0.01, T=%d%s"
                     % ("bf16 storage / fp32 accumulate" if bf16 else "fp32", "->".join(str(d) for d in dims), batch, T,
                        ", weights in pinned host memory, HBM budget %d bytes" % budget if budget else ", in-core"),
-                    {"tile": T, "loss": loss, "rounding": "stochastic" if bf16 and args.stochastic_rounding else "nearest", "bias": bool(args.bias)})
+                    {"tile": T, "loss": loss, "rounding": "stochastic" if bf16 and args.stochastic_rounding else "nearest", "bias": bool(args.bias), "momentum": args.momentum if not budget else None})
     out["roofline"] = {"bound": "mfma", "achieved": tfl, "peak": peak, "unit": "TFLOP/s", "frac": tfl / peak,
                        "traffic": None, "kernel": "tile_gemm_%s (whole step)" % ("bf16" if bf16 else "f32"),
                        "flops_per_step": flops}
@@ -199,6 +202,7 @@ def main():
     ap.add_argument("--stochastic-rounding", action="store_true",
                     help="c5: round the updated bf16 weights stochastically (mlp_set_rounding) instead of to nearest")
     ap.add_argument("--bias", action="store_true", help="c4 / c5: train bias rows too (mlp_set_bias)")
+    ap.add_argument("--momentum", type=float, default=None, help="c4: SGD with this momentum coefficient (mlp_set_momentum)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run 5 plain device copies of 256 MiB (a known-size reference for HBM counters)")

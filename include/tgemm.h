@@ -221,6 +221,20 @@ int mlp_set_activation(tgemm_mlp* mlp, int32_t act);
  * TGEMM_EARG for a NULL entry of b, a pointer that is not device memory, or db without b. */
 int mlp_set_bias(tgemm_mlp* mlp, void* const* b, void* const* db);
 
+/* Momentum for mlp_step (section 2 only says that the parameters are updated after the two passes;
+ * this is the classical heavy-ball rule):  V_l <- mu V_l + dW_l;  W_l <- W_l - lr V_l, both inside
+ * the dW product's epilogue (the gradient is never stored).  With mu = 0 the weights move exactly as
+ * without momentum (and V_l receives dW_l).
+ *   mu  in [0, 1).
+ *   V   array of n_layers device pointers, V[l-1] -> dims[l-1] x dims[l] floats, row-major (fp32 also
+ *       for bf16 networks), caller-owned and caller-initialised (zeros for a fresh run); NULL
+ *       switches momentum off (the default).
+ *   Vb  NULL, or array of n_layers device pointers to dims[l] floats: velocities of the bias rows
+ *       (used when bias rows are set; without Vb the bias rows take plain SGD steps).
+ * Device-resident weights only: TGEMM_EARG for an out-of-core network, for mu outside [0, 1), for a
+ * pointer that is not device memory, or for Vb without V.  Waits for outstanding work. */
+int mlp_set_momentum(tgemm_mlp* mlp, float mu, void* const* V, void* const* Vb);
+
 /* Rounding of the updated weights in mlp_step for bf16 networks (section 2's update, W_l - lr dW_l,
  * is formed in fp32 in the product's epilogue and then stored as bf16).
  *   TGEMM_ROUND_NEAREST     round to nearest even (default).  An update below half an ulp of the

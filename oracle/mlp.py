@@ -16,6 +16,7 @@ The equations themselves are not printed, so the textbook forms are taken:
     dA_{l-1} = D_l W_l^T ;   D_{l-1} = dA_{l-1} * act'(Z_{l-1})
              act' = A (1 - A) for the sigmoid, 1 - A^2 for tanh, [Z > 0] for relu
     W_l <- W_l - lr * dW_l ;  b_l <- b_l - lr * db_l     (every gradient from the pre-update values)
+    with momentum:  V_l <- mu V_l + dW_l ;  W_l <- W_l - lr V_l
 
 numpy's fp64 matmul is the library primitive used for the products.
 """
@@ -121,6 +122,26 @@ def mlp_step(X, Ws, y, lr, act="sigmoid", bs=None):
         return loss, new, dWs
     new_bs = [np.asarray(b, dtype=np.float64) - lr * g for b, g in zip(bs, dbs)]
     return loss, new, dWs, new_bs, dbs
+
+
+def mlp_step_momentum(X, Ws, y, lr, mu, Vs, act="sigmoid", bs=None, Vbs=None):
+    """One step of SGD with (heavy-ball) momentum:  V <- mu V + dW;  W <- W - lr V, the same for the
+    bias rows when they and their velocities Vbs are given (bias rows without velocities take the
+    plain step).  Returns (loss, new weights, new velocities) and, with bias rows, also
+    (new bias rows, new bias velocities or None)."""
+    if bs is None:
+        loss, dWs, _ = mlp_backward(X, Ws, y, act)
+    else:
+        loss, dWs, _, dbs = mlp_backward(X, Ws, y, act, bs=bs)
+    new_V = [mu * np.asarray(V, dtype=np.float64) + g for V, g in zip(Vs, dWs)]
+    new_W = [_f64(W) - lr * V for W, V in zip(Ws, new_V)]
+    if bs is None:
+        return loss, new_W, new_V
+    if Vbs is None:
+        return loss, new_W, new_V, [np.asarray(b, dtype=np.float64) - lr * g for b, g in zip(bs, dbs)], None
+    new_Vb = [mu * np.asarray(v, dtype=np.float64) + g for v, g in zip(Vbs, dbs)]
+    new_b = [np.asarray(b, dtype=np.float64) - lr * v for b, v in zip(bs, new_Vb)]
+    return loss, new_W, new_V, new_b, new_Vb
 
 
 def mlp_step_stochastic(X, Ws, y, lr, seed, step, act="sigmoid"):

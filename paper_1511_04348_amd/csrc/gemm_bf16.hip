@@ -421,7 +421,10 @@ static hipError_t launch_cfg(GemmParams& p, const GemmDesc& d, hipStream_t strea
     if (d.epilogue == EPI_DACT && d.out_bf16) { TGB_LAUNCH(AK, BKC, EPI_DACT, true); } \
     return hipErrorInvalidValue;
     if (d.a_kcontig && !d.b_kcontig) { TGB_EPI(true, false) }
-    if (!d.a_kcontig && !d.b_kcontig) { TGB_EPI(false, false) }
+    if (!d.a_kcontig && !d.b_kcontig) {
+        if (d.epilogue == EPI_MOMENTUM && d.out_bf16) { TGB_LAUNCH(false, false, EPI_MOMENTUM, true); }
+        TGB_EPI(false, false)
+    }
     if (d.a_kcontig && d.b_kcontig) { TGB_EPI(true, true) }
     return hipErrorInvalidValue;
 #undef TGB_EPI
@@ -445,7 +448,9 @@ hipError_t launch_tile_gemm_bf16(const GemmDesc& d, hipStream_t stream)
     if (T > big) T = big > 0 ? big : 1;
     p.T = (int)T;
     p.alpha = d.alpha; p.beta = d.beta; p.act = d.act;
-    p.sr = (d.sr && d.out_bf16 && d.epilogue == EPI_AXPBY) ? 1 : 0;
+    p.sr = (d.sr && d.out_bf16 && (d.epilogue == EPI_AXPBY || d.epilogue == EPI_MOMENTUM)) ? 1 : 0;
+    p.state = d.state; p.ldstate = d.ldstate; p.mu = d.mu;
+    if (d.epilogue == EPI_MOMENTUM && (!d.state || d.c_tiles || d.a_kcontig || d.b_kcontig)) return hipErrorInvalidValue;
     p.sr_key = d.sr_key; p.sr_row0 = (uint32_t)d.sr_row0;
     p.bias = d.bias;
     p.vec_bias = d.bias && ((reinterpret_cast<uintptr_t>(d.bias) & 15) == 0) && (T % 4 == 0);

@@ -161,6 +161,15 @@ __device__ inline void epilogue(const GemmParams& p, const TileCoord& t, const f
                     float v = acc[r][cc][4 * g + e] + bv[e];
                     if (EPI == EPI_AXPBY) {
                         v = read_c ? fmaf(alpha, v, beta * in[cc][g][e]) : alpha * v;
+                    } else if (EPI == EPI_MOMENTUM) {
+                        if (col + e < t.col_end) {   // S = mu S + acc; C = C + alpha S (C read here, entry by entry)
+                            float* st = p.state + (int64_t)row * p.ldstate + col + e;
+                            const float vel = fmaf(p.mu, gload<float>(st), v);
+                            gstore<float>(st, vel);
+                            const float c_old = OUT_BF16 ? bf16_to_f32(gload<uint16_t>(Cb + crow + col + e))
+                                                         : gload<float>(Cf + crow + col + e);
+                            v = fmaf(alpha, vel, c_old);
+                        }
                     } else if (EPI == EPI_ACT) {
                         v = act_apply(p.act, v);
                     } else if (EPI == EPI_DACT) {
@@ -170,7 +179,7 @@ __device__ inline void epilogue(const GemmParams& p, const TileCoord& t, const f
                 }
                 if (OUT_BF16) {
                     uint16_t b[4];
-                    if (EPI == EPI_AXPBY && p.sr) {
+                    if ((EPI == EPI_AXPBY || EPI == EPI_MOMENTUM) && p.sr) {
                         // col is even when T is (pairs col / 2 and col / 2 + 1); odd tile sizes go column by column
                         const uint32_t hrow = mix32(p.sr_row0 + (uint32_t)row + p.sr_key);
                         const bool even = (col & 1) == 0;

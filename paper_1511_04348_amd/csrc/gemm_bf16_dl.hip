@@ -339,7 +339,10 @@ hipError_t launch_tile_gemm_bf16_dl(GemmParams p, const GemmDesc& d, hipStream_t
     if (d.epilogue == EPI_DACT && d.out_bf16) { TGD_LAUNCH(AK, BKC, EPI_DACT, true); } \
     return hipErrorNotSupported;
     if (d.a_kcontig && !d.b_kcontig) { TGD_EPI(true, false) }
-    if (!d.a_kcontig && !d.b_kcontig) { TGD_EPI(false, false) }
+    if (!d.a_kcontig && !d.b_kcontig) {
+        if (d.epilogue == EPI_MOMENTUM && d.out_bf16) { TGD_LAUNCH(false, false, EPI_MOMENTUM, true); }
+        TGD_EPI(false, false)
+    }
     if (d.a_kcontig && d.b_kcontig) { TGD_EPI(true, true) }
     return hipErrorNotSupported;
 #undef TGD_EPI

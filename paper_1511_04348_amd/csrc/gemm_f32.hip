@@ -373,6 +373,15 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
 #pragma unroll
                     for (int cc = 0; cc < RB; ++cc) o[cc] = alpha * o[cc];
                 }
+            } else if (EPI == EPI_MOMENTUM) {
+                float* st = p.state + (int64_t)row * p.ldstate + colb;
+#pragma unroll
+                for (int cc = 0; cc < RB; ++cc)
+                    if (colb + cc < col_end) {
+                        const float v = fmaf(p.mu, gload<float>(st + cc), o[cc]);
+                        gstore<float>(st + cc, v);
+                        o[cc] = fmaf(alpha, v, gload<float>(dst + cc));
+                    }
             } else if (EPI == EPI_ACT) {
 #pragma unroll
                 for (int cc = 0; cc < RB; ++cc) o[cc] = act_apply(p.act, o[cc]);
@@ -455,7 +464,10 @@ static hipError_t launch_cfg(GemmParams& p, const GemmDesc& d, hipStream_t strea
         default: return hipErrorInvalidValue;                      \
     }
     if (d.a_kcontig && !d.b_kcontig) { TG_EPI(true, false) }
-    if (!d.a_kcontig && !d.b_kcontig) { TG_EPI(false, false) }
+    if (!d.a_kcontig && !d.b_kcontig) {
+        if (d.epilogue == EPI_MOMENTUM) TG_LAUNCH(false, false, EPI_MOMENTUM);
+        TG_EPI(false, false)
+    }
     if (d.a_kcontig && d.b_kcontig) { TG_EPI(true, true) }
     return hipErrorInvalidValue;   // (m-contiguous A) x (k-contiguous B) is not used by any pass
 #undef TG_EPI
@@ -503,6 +515,8 @@ hipError_t launch_tile_gemm_f32(const GemmDesc& d, hipStream_t stream)
     p.T = (int)T;
     p.alpha = d.alpha; p.beta = d.beta; p.act = d.act;
     p.sr = 0; p.sr_key = 0; p.sr_row0 = 0; p.bias = d.bias; p.vec_bias = false;
+    p.state = d.state; p.ldstate = d.ldstate; p.mu = d.mu;
+    if (d.epilogue == EPI_MOMENTUM && (!d.state || d.c_tiles)) return hipErrorInvalidValue;
     p.b_tiles = d.b_tiles; p.c_tiles = d.c_tiles;
     const bool t4 = (T % 4 == 0);
     auto al16 = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15) == 0; };

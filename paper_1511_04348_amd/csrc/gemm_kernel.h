@@ -5,7 +5,7 @@
 
 namespace tg {
 
-enum { EPI_AXPBY = 0, EPI_ACT = 1, EPI_DACT = 2 };
+enum { EPI_AXPBY = 0, EPI_ACT = 1, EPI_DACT = 2, EPI_MOMENTUM = 3 };
 enum { ACT_SIGMOID = 0, ACT_TANH = 1, ACT_RELU = 2 };   // same values as TGEMM_ACT_* of the C ABI
 
 // What a caller asks for: out = epilogue(op(A) op(B)), tiled by T (section 3.1 of the paper).
@@ -13,6 +13,9 @@ enum { ACT_SIGMOID = 0, ACT_TANH = 1, ACT_RELU = 2 };   // same values as TGEMM_
 //   EPI_ACT      C = act(A B)                        act: sigmoid, tanh or max(0, .)
 //   EPI_DACT     C = (A B) * act'(z) with act' written in terms of the stored activation aux = act(z)
 //                (aux: M x N, leading dimension ldaux): aux (1 - aux), 1 - aux^2, or [aux > 0]
+//   EPI_MOMENTUM S = mu * S + (A B);  C = C + alpha * S   (S: M x N floats, leading dimension ldstate;
+//                the update with a velocity matrix).  Dense C only; offered for the layout of the
+//                dW product (both operands m/n-contiguous).
 // a_kcontig: A stored M x K row-major (k contiguous); otherwise stored K x M (m contiguous).
 // b_kcontig: B stored N x K row-major (k contiguous); otherwise stored K x N (n contiguous).
 struct GemmDesc {
@@ -39,6 +42,9 @@ struct GemmDesc {
     int32_t sr;
     uint32_t sr_key;
     int64_t sr_row0;
+    float* state;     // EPI_MOMENTUM: S
+    int64_t ldstate;
+    float mu;
     // Optional tile tables (device arrays of device pointers) for operands that live as separate
     // T x T tiles in cache slots instead of one dense matrix.  Entry [step * n_j + tj] of b_tiles
     // is the B tile of k-step `step` and task column tj; entry [ti * n_j + tj] of c_tiles is the C
@@ -64,6 +70,9 @@ struct GemmParams {
     float alpha, beta;
     int act;                    // ACT_* for the activation epilogues
     const float* bias;          // see GemmDesc
+    float* state;               // EPI_MOMENTUM
+    int64_t ldstate;
+    float mu;
     int sr;                     // stochastic rounding of a bf16 result (see GemmDesc)
     uint32_t sr_key;
     uint32_t sr_row0;

@@ -189,6 +189,9 @@ struct tgemm_mlp {
     std::vector<char*> W;         // caller-owned weights (device or pinned host)
     std::vector<float*> bias;     // caller-owned bias rows b_l (device, float), empty: no bias terms
     std::vector<float*> dbias;    // caller-owned destinations of mlp_backward's bias gradients, may hold NULLs
+    std::vector<float*> vel;      // caller-owned velocity matrices V_l (device, float), empty: plain SGD
+    std::vector<float*> vel_bias; // velocity rows of the bias terms (may be empty)
+    float mu = 0.f;               // momentum coefficient
     float* colsum_part = nullptr; // partial column sums of an error matrix: COLSUM_CHUNKS x max n_l floats
     int32_t dtype = TGEMM_F32;
     int32_t act_kind = TGEMM_ACT_SIGMOID;   // hidden-layer activation
@@ -344,15 +347,23 @@ __global__ __launch_bounds__(256) void colsum_partial(const void* __restrict__ D
 #pragma unroll
     for (int e = 0; e < VEC; ++e) part[(int64_t)blockIdx.y * n + col + e] = s[e];
 }
+// With a velocity row vb (momentum): vb <- mu vb + sum; b <- b - lr vb.
 __global__ __launch_bounds__(256) void colsum_finish(const float* __restrict__ part, int bands, int n, float lr,
-                                                     float* __restrict__ b, float* __restrict__ db)
+                                                     float* __restrict__ b, float* __restrict__ db, float mu,
+                                                     float* __restrict__ vb)
 {
     const int col = blockIdx.x * 256 + threadIdx.x;
     if (col >= n) return;
     float s = 0.f;
     for (int k = 0; k < bands; ++k) s += part[(int64_t)k * n + col];
     if (db) db[col] = s;
-    if (b) b[col] -= lr * s;
+    if (b) {
+        if (vb) {
+            s = fmaf(mu, vb[col], s);
+            vb[col] = s;
+        }
+        b[col] = fmaf(-lr, s, b[col]);
+    }
 }
 
 double now_ms()
@@ -725,7 +736,8 @@ int backward_layer(tgemm_mlp* m, int l, float* dW_out, bool update, float lr)
             else if (vec) hipLaunchKernelGGL((colsum_partial<false, 4>), grid, dim3(256), 0, comp, D, (int64_t)n, batch, n, m->colsum_part);
             else hipLaunchKernelGGL((colsum_partial<false, 1>), grid, dim3(256), 0, comp, D, (int64_t)n, batch, n, m->colsum_part);
             hipLaunchKernelGGL(colsum_finish, dim3((unsigned)cdiv(n, 256)), dim3(256), 0, comp,
-                               (const float*)m->colsum_part, bands, n, lr, b, db);
+                               (const float*)m->colsum_part, bands, n, lr, b, db, m->mu,
+                               (b && !m->vel_bias.empty()) ? m->vel_bias[(size_t)l - 1] : (float*)nullptr);
             TG_HIP(hipGetLastError());
         }
     }
@@ -758,6 +770,10 @@ int backward_layer(tgemm_mlp* m, int l, float* dW_out, bool update, float lr)
             dw.A = a_prev; dw.M = m->dims[l - 1]; dw.ldc = m->dims[l];
             if (update) {
                 dw.C = (float*)m->W[l - 1]; dw.alpha = -lr; dw.beta = 1.f; dw.out_bf16 = bf ? 1 : 0;
+                if (!m->vel.empty()) {   // V <- mu V + dW; W <- W - lr V
+                    dw.epilogue = EPI_MOMENTUM;
+                    dw.state = m->vel[(size_t)l - 1]; dw.ldstate = m->dims[l]; dw.mu = m->mu;
+                }
                 dw.sr = (bf && m->round_mode == TGEMM_ROUND_STOCHASTIC) ? 1 : 0;
                 dw.sr_key = sr_step_key(m->sr_seed, (uint32_t)l, m->sr_step); dw.sr_row0 = 0;
             }
@@ -957,6 +973,40 @@ int mlp_set_bias(tgemm_mlp* m, void* const* b, void* const* db)
     if (had != !m->bias.empty()) free_workspaces(m);   // the column-sum scratch comes or goes with the bias terms
     m->batch = 0;            // a pending forward pass belongs to the old function
     m->have_delta = false;
+    return TGEMM_OK;
+}
+
+int mlp_set_momentum(tgemm_mlp* m, float mu, void* const* V, void* const* Vb)
+{
+    if (!m) return fail(TGEMM_EARG, "mlp_set_momentum: object is NULL");
+    TG_HIP(hipSetDevice(m->ctx->device));
+    if (!V) {
+        if (Vb) return fail(TGEMM_EARG, "mlp_set_momentum: bias velocities without weight velocities");
+    } else {
+        if (m->ooc) return fail(TGEMM_EARG, "mlp_set_momentum: needs device-resident weights (this network is out-of-core)");
+        if (!(mu >= 0.f && mu < 1.f)) return fail(TGEMM_EARG, "mlp_set_momentum: mu = %g is outside [0, 1)", (double)mu);
+        for (int l = 0; l < m->n_layers; ++l) {
+            hipPointerAttribute_t at;
+            if (!V[l] || hipPointerGetAttributes(&at, V[l]) != hipSuccess || at.type != hipMemoryTypeDevice) {
+                (void)hipGetLastError();
+                return fail(TGEMM_EARG, "mlp_set_momentum: V[%d] is not device memory", l);
+            }
+            if (Vb && (!Vb[l] || hipPointerGetAttributes(&at, Vb[l]) != hipSuccess || at.type != hipMemoryTypeDevice)) {
+                (void)hipGetLastError();
+                return fail(TGEMM_EARG, "mlp_set_momentum: Vb[%d] is not device memory", l);
+            }
+        }
+    }
+    int rc = sync_all(m);
+    if (rc != TGEMM_OK) return rc;
+    m->vel.clear();
+    m->vel_bias.clear();
+    m->mu = 0.f;
+    if (V) {
+        for (int l = 0; l < m->n_layers; ++l) m->vel.push_back((float*)V[l]);
+        if (Vb) for (int l = 0; l < m->n_layers; ++l) m->vel_bias.push_back((float*)Vb[l]);
+        m->mu = mu;
+    }
     return TGEMM_OK;
 }
 

@@ -1,0 +1,137 @@
+"""GPU parity of mlp_step with momentum (mlp_set_momentum) against the fp64 oracle: velocities and
+weights after each of three steps, fp32 (1e-5) and bf16 weights (1e-2), every kernel configuration,
+with and without bias rows; mu = 0 equals the plain step bit for bit; error paths."""
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import announce, rel_fro
+from paper_1511_04348_amd import binding as tg
+from paper_1511_04348_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+
+def _np(t):
+    return inputs.bf16_bits(t).copy() if t.dtype == torch.bfloat16 else t.cpu().numpy().copy()
+
+
+def _f64(t):
+    return t.cpu().to(torch.float64).numpy()
+
+
+def _net(dims, batch, tdt):
+    L = len(dims) - 1
+    X = inputs.normal_matrix(1, batch, dims[0]).to(tdt)
+    Ws = [inputs.normal_matrix(10 + l, dims[l], dims[l + 1], std=0.05).to(tdt) for l in range(L)]
+    bs = [inputs.normal_matrix(20 + l, 1, dims[l + 1], std=0.5).reshape(-1).contiguous() for l in range(L)]
+    return X, Ws, bs, inputs.labels(5, batch, dims[-1])
+
+
+@pytest.mark.parametrize("bias", [False, True])
+@pytest.mark.parametrize("dtype,tdt,tol,lr,cfgs", [(tg.TGEMM_F32, torch.float32, 1e-5, 0.05, (0, 1, 2, 3)),
+                                                   (tg.TGEMM_BF16, torch.bfloat16, 1e-2, 10.0, (2, 3, 4))])
+@pytest.mark.parametrize("dims,batch,T", [([256, 384, 320, 200], 192, 128), ([70, 90, 33], 50, 32)])
+def test_three_steps_with_momentum(oracle, dims, batch, T, dtype, tdt, tol, lr, cfgs, bias):
+    L, mu = len(dims) - 1, 0.9
+    X, Ws, bs, y = _net(dims, batch, tdt)
+    for cfg in cfgs:
+        announce("mlp momentum", dims, batch, T, "bf16" if dtype else "f32", "cfg", cfg, "bias" if bias else "")
+        ctx = tg.tgemm_create(0, kernel_config=cfg)
+        try:
+            Wd = [w.cuda() for w in Ws]
+            Vd = [inputs.normal_matrix(30 + l, dims[l], dims[l + 1], std=0.01).cuda() for l in range(L)]
+            bd = [b.cuda() for b in bs]
+            Vbd = [inputs.normal_matrix(40 + l, 1, dims[l + 1], std=0.01).reshape(-1).contiguous().cuda() for l in range(L)]
+            Xd, yd = X.cuda(), y.cuda()
+            torch.cuda.synchronize()
+            mlp = tg.mlp_create(ctx, dims, Wd, dtype, T)
+            if bias:
+                tg.mlp_set_bias(mlp, bd)
+            tg.mlp_set_momentum(mlp, mu, Vd, Vbd if bias else None)
+            for step in range(3):
+                # the oracle takes every step from the state the GPU holds
+                W0, V0 = [_np(w) for w in Wd], [_np(v) for v in Vd]
+                b0, Vb0 = [_np(b) for b in bd], [_np(v) for v in Vbd]
+                loss = tg.mlp_step(mlp, Xd, yd, batch, lr)
+                tg.tgemm_sync(ctx)
+                if bias:
+                    ref_loss, W1, V1, b1, Vb1 = oracle.mlp_step_momentum(_np(X), W0, y.numpy(), lr, mu, V0, bs=b0, Vbs=Vb0)
+                else:
+                    ref_loss, W1, V1 = oracle.mlp_step_momentum(_np(X), W0, y.numpy(), lr, mu, V0)
+                assert abs(loss - ref_loss) <= tol * abs(ref_loss)
+                for l in range(L):
+                    # velocities: V_new - mu V_old is the gradient
+                    v_old = V0[l].astype(np.float64)
+                    assert rel_fro(_f64(Vd[l]) - mu * v_old, V1[l] - mu * v_old) <= tol, ("velocity", step, l)
+                    w_old = oracle.bf16_to_f64(W0[l]).reshape(W0[l].shape) if dtype == tg.TGEMM_BF16 else W0[l].astype(np.float64)
+                    half_ulp = 2.0 ** -9 if dtype == tg.TGEMM_BF16 else 2.0 ** -24
+                    slack = np.linalg.norm(W1[l]) * half_ulp / np.linalg.norm(W1[l] - w_old)
+                    assert slack < 0.05, slack
+                    assert rel_fro(_f64(Wd[l]) - w_old, W1[l] - w_old) <= tol + slack, ("weights", step, l)
+                    if bias:
+                        vb_old = Vb0[l].astype(np.float64)
+                        assert rel_fro(_f64(Vbd[l]) - mu * vb_old, Vb1[l] - mu * vb_old) <= tol, ("bias velocity", step, l)
+                        slack_b = np.linalg.norm(b1[l]) * 2.0 ** -24 / np.linalg.norm(b1[l] - b0[l])
+                        assert rel_fro(_f64(bd[l]) - b0[l], b1[l] - b0[l].astype(np.float64)) <= tol + slack_b, ("bias", step, l)
+            tg.mlp_destroy(mlp)
+        finally:
+            tg.tgemm_destroy(ctx)
+
+
+@pytest.mark.parametrize("dtype,tdt", [(tg.TGEMM_F32, torch.float32), (tg.TGEMM_BF16, torch.bfloat16)])
+def test_mu_zero_is_the_plain_step_bit_for_bit(dtype, tdt):
+    dims, batch, T = [256, 384, 200], 192, 128
+    X, Ws, _, y = _net(dims, batch, tdt)
+    Xd, yd = X.cuda(), y.cuda()
+    out = []
+    for momentum in (False, True):
+        ctx = tg.tgemm_create(0)
+        try:
+            Wd = [w.cuda() for w in Ws]
+            Vd = [torch.full(w.shape, 3.0, device="cuda") for w in Ws]      # stale velocities must not matter
+            torch.cuda.synchronize()
+            mlp = tg.mlp_create(ctx, dims, Wd, dtype, T)
+            if momentum:
+                tg.mlp_set_momentum(mlp, 0.0, Vd)
+            losses = [tg.mlp_step(mlp, Xd, yd, batch, 0.5) for _ in range(2)]
+            tg.tgemm_sync(ctx)
+            out.append((losses, [w.cpu() for w in Wd]))
+            tg.mlp_destroy(mlp)
+        finally:
+            tg.tgemm_destroy(ctx)
+    assert out[0][0] == out[1][0]
+    for a, b in zip(out[0][1], out[1][1]):
+        assert torch.equal(a, b)
+
+
+def test_momentum_errors():
+    dims, T = [64, 48, 32], 32
+    Ws = [inputs.normal_matrix(10 + l, dims[l], dims[l + 1], std=0.1) for l in range(2)]
+    ctx = tg.tgemm_create(0)
+    try:
+        Wd = [w.cuda() for w in Ws]
+        Vd = [torch.zeros_like(w) for w in Wd]
+        mlp = tg.mlp_create(ctx, dims, Wd, tg.TGEMM_F32, T)
+        for bad_mu in (1.0, -0.1, float("nan")):
+            with pytest.raises(tg.TgemmError) as e:
+                tg.mlp_set_momentum(mlp, bad_mu, Vd)
+            assert e.value.code == tg.TGEMM_EARG
+        with pytest.raises(tg.TgemmError) as e:
+            tg.mlp_set_momentum(mlp, 0.5, [Vd[0], torch.zeros(48, 32)])      # host memory
+        assert e.value.code == tg.TGEMM_EARG
+        with pytest.raises(tg.TgemmError) as e:
+            tg.mlp_set_momentum(mlp, 0.5, None, [torch.zeros(48, device="cuda"), torch.zeros(32, device="cuda")])
+        assert e.value.code == tg.TGEMM_EARG
+        tg.mlp_set_momentum(mlp, 0.5, Vd)
+        tg.mlp_set_momentum(mlp, 0.0, None)
+        tg.mlp_destroy(mlp)
+        # out-of-core networks do not take momentum
+        Wp = [w.clone().pin_memory() for w in Ws]
+        mlp = tg.mlp_create(ctx, dims, Wp, tg.TGEMM_F32, T, hbm_budget=1 << 24)
+        with pytest.raises(tg.TgemmError) as e:
+            tg.mlp_set_momentum(mlp, 0.5, Vd)
+        assert e.value.code == tg.TGEMM_EARG
+        tg.mlp_destroy(mlp)
+    finally:
+        tg.tgemm_destroy(ctx)

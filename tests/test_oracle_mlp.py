@@ -286,3 +286,51 @@ def test_bias_step(oracle):
     assert after < loss and abs(after - pred) < 0.05 * (loss - pred) + 1e-6
     # moving only the bias rows along -db lowers the loss too
     assert oracle.mlp_loss(X, Ws, y, bs=new_b) < loss
+
+
+# ---- momentum --------------------------------------------------------------------------------------
+
+def test_momentum_reduces_to_sgd_and_heavy_ball_identity(oracle):
+    dims = [6, 9, 5]
+    X, Ws, y = _net(40, dims, 12)
+    r = np.random.default_rng(41)
+    V0 = [r.normal(0, 0.1, w.shape) for w in Ws]
+    lr, mu = 0.05, 0.8
+    # mu = 0: the plain step whatever the old velocity, and the velocity becomes the gradient
+    loss, W1, V1 = oracle.mlp_step_momentum(X, Ws, y, lr, 0.0, V0)
+    loss_s, W_s, g = oracle.mlp_step(X, Ws, y, lr)
+    assert loss == loss_s
+    assert all(np.array_equal(a, b) for a, b in zip(W1, W_s)) and all(np.array_equal(a, b) for a, b in zip(V1, g))
+    # one step written out
+    _, W1, V1 = oracle.mlp_step_momentum(X, Ws, y, lr, mu, V0)
+    for l in range(2):
+        assert np.allclose(V1[l], mu * V0[l] + g[l], rtol=0, atol=1e-16)
+        assert np.allclose(W1[l], Ws[l].astype(np.float64) - lr * mu * V0[l] - lr * g[l], rtol=0, atol=1e-15)
+    # two steps from rest: the heavy-ball form  W2 - W1 = mu (W1 - W0) - lr grad(W1)
+    zero = [np.zeros(w.shape) for w in Ws]
+    _, Wa, Va = oracle.mlp_step_momentum(X, Ws, y, lr, mu, zero)
+    _, Wb, Vb = oracle.mlp_step_momentum(X, Wa, y, lr, mu, Va)
+    _, g1, _ = oracle.mlp_backward(X, Wa, y)
+    for l in range(2):
+        assert np.allclose(Wb[l] - Wa[l], mu * (Wa[l] - Ws[l].astype(np.float64)) - lr * g1[l], rtol=0, atol=1e-15)
+    # a constant gradient direction accumulates: from rest, step 2 moves further than step 1 along -g
+    assert sum(((Wb[l] - Wa[l]) * g[l]).sum() for l in range(2)) < sum(((Wa[l] - Ws[l]) * g[l]).sum() for l in range(2)) < 0
+
+
+def test_momentum_with_bias_rows(oracle):
+    dims = [5, 7, 4]
+    X, Ws, y = _net(42, dims, 9)
+    b = _biases(43, dims)
+    r = np.random.default_rng(44)
+    V0 = [r.normal(0, 0.1, w.shape) for w in Ws]
+    Vb0 = [r.normal(0, 0.1, x.shape) for x in b]
+    lr, mu = 0.1, 0.5
+    _, g, _, gb = oracle.mlp_backward(X, Ws, y, bs=b)
+    loss, W1, V1, b1, Vb1 = oracle.mlp_step_momentum(X, Ws, y, lr, mu, V0, bs=b, Vbs=Vb0)
+    for l in range(2):
+        assert np.allclose(V1[l], mu * V0[l] + g[l], atol=1e-16) and np.allclose(Vb1[l], mu * Vb0[l] + gb[l], atol=1e-16)
+        assert np.allclose(W1[l], Ws[l] - lr * V1[l], atol=1e-16) and np.allclose(b1[l], b[l] - lr * Vb1[l], atol=1e-16)
+    # bias rows without velocities take the plain step
+    _, W2, V2, b2, none = oracle.mlp_step_momentum(X, Ws, y, lr, mu, V0, bs=b)
+    assert none is None and all(np.array_equal(a, c) for a, c in zip(W2, W1))
+    assert all(np.allclose(b2[l], b[l] - lr * gb[l], atol=1e-16) for l in range(2))

@@ -59,7 +59,8 @@ MLP_PINS = [(pins_mlp.test_finite_differences_every_weight, ()), (pins_mlp.test_
             (pins_mlp.test_finite_differences_tanh_and_relu, ()), (pins_mlp.test_activation_values_written_out, ()),
             (pins_mlp.test_activation_symmetries, ()), (pins_mlp.test_step_descends_for_every_activation, ()),
             (pins_mlp.test_bias_finite_differences, ()), (pins_mlp.test_bias_is_a_constant_one_input_column, ()),
-            (pins_mlp.test_bias_closed_forms, ()), (pins_mlp.test_bias_step, ())]
+            (pins_mlp.test_bias_closed_forms, ()), (pins_mlp.test_bias_step, ()),
+            (pins_mlp.test_momentum_reduces_to_sgd_and_heavy_ball_identity, ()), (pins_mlp.test_momentum_with_bias_rows, ())]
 
 MLP_MUTANTS = [
     ("sigmoid sign", "        return 1.0 / (1.0 + np.exp(-z))", "        return 1.0 / (1.0 + np.exp(z))"),
@@ -97,6 +98,20 @@ MLP_MUTANTS = [
     ("db averaged instead of summed", "[dl.sum(axis=0) for dl in deltas]", "[dl.mean(axis=0) for dl in deltas]"),
     ("bias update sign", "new_bs = [np.asarray(b, dtype=np.float64) - lr * g for b, g in zip(bs, dbs)]",
      "new_bs = [np.asarray(b, dtype=np.float64) + lr * g for b, g in zip(bs, dbs)]"),
+    ("momentum: mu on the gradient instead of the velocity", "new_V = [mu * np.asarray(V, dtype=np.float64) + g for V, g in zip(Vs, dWs)]",
+     "new_V = [np.asarray(V, dtype=np.float64) + mu * g for V, g in zip(Vs, dWs)]"),
+    ("momentum: gradient subtracted", "new_V = [mu * np.asarray(V, dtype=np.float64) + g for V, g in zip(Vs, dWs)]",
+     "new_V = [mu * np.asarray(V, dtype=np.float64) - g for V, g in zip(Vs, dWs)]"),
+    ("momentum: weights move by the gradient, not the velocity", "new_W = [_f64(W) - lr * V for W, V in zip(Ws, new_V)]",
+     "new_W = [_f64(W) - lr * V for W, V in zip(Ws, dWs)]"),
+    ("momentum: weights move by the old velocity", "new_W = [_f64(W) - lr * V for W, V in zip(Ws, new_V)]",
+     "new_W = [_f64(W) - lr * np.asarray(V) for W, V in zip(Ws, Vs)]"),
+    ("momentum: lr applied twice over", "new_W = [_f64(W) - lr * V for W, V in zip(Ws, new_V)]",
+     "new_W = [_f64(W) - lr * lr * V for W, V in zip(Ws, new_V)]"),
+    ("momentum: bias velocity ignores mu", "new_Vb = [mu * np.asarray(v, dtype=np.float64) + g for v, g in zip(Vbs, dbs)]",
+     "new_Vb = [np.asarray(v, dtype=np.float64) + g for v, g in zip(Vbs, dbs)]"),
+    ("momentum: bias rows move by the gradient", "new_b = [np.asarray(b, dtype=np.float64) - lr * v for b, v in zip(bs, new_Vb)]",
+     "new_b = [np.asarray(b, dtype=np.float64) - lr * v for b, v in zip(bs, dbs)]"),
     ("bias update without lr", "new_bs = [np.asarray(b, dtype=np.float64) - lr * g for b, g in zip(bs, dbs)]",
      "new_bs = [np.asarray(b, dtype=np.float64) - g for b, g in zip(bs, dbs)]"),
 ]
