@@ -134,7 +134,10 @@ struct TileLoader {
 };
 
 // ---- the kernel ---------------------------------------------------------------------------------
-template <int RA, int RB, int WM, int WN, int BK, bool A_KC, bool B_KC, int EPI>
+// TAIL: the instance for products whose last k chunk is ragged (K % BK != 0); its loop over full chunks
+// ends with one predicated, zero-filling chunk.  A separate kernel so that the plain instance's loop
+// is compiled exactly as if the tail did not exist.
+template <int RA, int RB, int WM, int WN, int BK, bool A_KC, bool B_KC, int EPI, bool TAIL>
 __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p)
 {
     constexpr int WTM = 32 * RA, WTN = 32 * RB;
@@ -250,9 +253,28 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
         constexpr int GAP = (N_MFMA / 2) / N_VMEM > 0 ? (N_MFMA / 2) / N_VMEM : 1;
         constexpr int N_DSW = (A_KC ? 4 : 1) * LA::UP + (B_KC ? 4 : 1) * LB::UP;   // LDS store instructions per chunk
         constexpr int GAP2 = (N_MFMA - GAP * N_VMEM) / N_DSW > 0 ? (N_MFMA - GAP * N_VMEM) / N_DSW : 1;
+        // Only the last chunk of the whole product can be ragged here (K % BK != 0): it takes the
+        // predicated, zero-filling loads, in an iteration of its own after the steady loop.
+        const int n_fast = TAIL ? n_chunks - 1 : n_chunks;
+        auto issue_tail = [&]() {
+            const int kk = (p.K / BK) * BK, step = (n_chunks - 1) / cps;
+            const float* bsrc = B;
+            int bm0 = col0, bm1 = col_end, bk0 = kk, bk1 = p.K;
+            if (p.b_tiles) {
+                bsrc = reinterpret_cast<const float*>(p.b_tiles[(int64_t)step * p.n_j + tj]);
+                bm0 = bcol; bm1 = col_end - tj * p.T;
+                bk0 = kk - step * p.T; bk1 = p.K - step * p.T;
+            }
+            LA::load(ra, A, p.lda, row0, row_end, kk, p.K, p.vec_a, tid);
+            LB::load(rb, bsrc, p.ldb, bm0, bm1, bk0, bk1, p.vec_b, tid);
+        };
         if (n_chunks > 0) {
-            next_b_origin();
-            issue();
+            if (!TAIL || n_fast > 0) {
+                next_b_origin();
+                issue();
+            } else {
+                issue_tail();
+            }
             LA::store(ra, As, tid);
             LB::store(rb, Bs, tid);
         }
@@ -262,7 +284,7 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
         // loads at a limited rate, and a wave that issues them all up front sits in that queue
         // while its MFMAs wait behind them ...
         int c = 0;
-        for (; c + 1 < n_chunks; ++c) {
+        for (; c + 1 < n_fast; ++c) {
             next_b_origin();
             issue();
             compute(c & 1);
@@ -282,6 +304,14 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
                 __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);     // one LDS write
             }
             __syncthreads();
+        }
+        if (TAIL && c + 1 < n_chunks) {
+            issue_tail();
+            compute(c & 1);
+            LA::store(ra, As + ((c + 1) & 1) * STAGE_A, tid);
+            LB::store(rb, Bs + ((c + 1) & 1) * STAGE_B, tid);
+            __syncthreads();
+            ++c;
         }
         if (c < n_chunks) {
             compute(c & 1);
@@ -414,11 +444,11 @@ struct Cfg {
     static constexpr size_t LDS = 2 * (size_t)BK * ((BM + PAD) + (BN + PAD)) * sizeof(float);
 };
 
-template <int RA, int RB, int WM, int WN, int BK, bool A_KC, bool B_KC, int EPI>
+template <int RA, int RB, int WM, int WN, int BK, bool A_KC, bool B_KC, int EPI, bool TAIL>
 static hipError_t launch_one(const GemmParams& p, int grid, hipStream_t stream)
 {
     typedef Cfg<RA, RB, WM, WN, BK> C;
-    auto kern = tile_gemm_f32<RA, RB, WM, WN, BK, A_KC, B_KC, EPI>;
+    auto kern = tile_gemm_f32<RA, RB, WM, WN, BK, A_KC, B_KC, EPI, TAIL>;
     static bool attr_set = false;   // per instantiation; the attribute is per function, idempotent
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -435,7 +465,7 @@ static hipError_t launch_cfg(GemmParams& p, const GemmDesc& d, hipStream_t strea
 {
     typedef Cfg<RA, RB, WM, WN, BK> C;
     const int64_t T = d.T;
-    p.fast_k = (d.K % BK == 0) && (T % BK == 0 || T >= d.K);   // every k chunk is full
+    p.fast_k = (T % BK == 0 || T >= d.K);   // every k chunk is full, except a ragged last one when K % BK != 0
     p.n_i = (int)((d.M + T - 1) / T);
     p.n_j = (int)((d.N + T - 1) / T);
     const int64_t n_k = (d.K + T - 1) / T;
@@ -455,7 +485,10 @@ static hipError_t launch_cfg(GemmParams& p, const GemmDesc& d, hipStream_t strea
     const int64_t last_k = d.K - (n_k - 1) * T;
     p.n_chunks = (int)((n_k - 1) * p.chunks_per_step + (last_k + BK - 1) / BK);
 
-#define TG_LAUNCH(AK, BKC, E) return launch_one<RA, RB, WM, WN, BK, AK, BKC, E>(p, (int)grid, stream)
+    const bool tail = p.fast_k && (d.K % BK != 0);   // ragged last chunk inside the unpredicated loop
+#define TG_LAUNCH(AK, BKC, E)                                                                        \
+    return tail ? launch_one<RA, RB, WM, WN, BK, AK, BKC, E, true>(p, (int)grid, stream)              \
+                : launch_one<RA, RB, WM, WN, BK, AK, BKC, E, false>(p, (int)grid, stream)
 #define TG_EPI(AK, BKC)                                            \
     switch (d.epilogue) {                                          \
         case EPI_AXPBY: TG_LAUNCH(AK, BKC, EPI_AXPBY);             \

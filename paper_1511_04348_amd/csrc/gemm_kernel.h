@@ -80,7 +80,7 @@ struct GemmParams {
     bool vec_aux;               // bf16 kernels: 8-byte access to aux is legal
     bool vec_bias;              // bf16 kernels: 16-byte access to bias is legal
     bool fast_a, fast_b;        // interior tiles may use the unpredicated, 32-bit-offset load path
-    bool fast_k;                // every k chunk is full (no ragged k-step tails)
+    bool fast_k;                // every k chunk is full (fp32 kernel: except a ragged last chunk of the product)
     const void* const* b_tiles; // see GemmDesc
     void* const* c_tiles;
 };
