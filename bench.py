@@ -209,7 +209,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
-    defaults = {"c1": (200, 20), "c2": (50, 5), "c3": (3, 1), "c4": (10, 3), "c5": (3, 2), "bf16": (50, 5)}
+    defaults = {"c1": (200, 20), "c2": (50, 5), "c3": (3, 1), "c4": (10, 3), "c5": (10, 2), "bf16": (50, 5)}
     if args.steps is None:
         args.steps = defaults[args.workload][0]
     if args.warmup is None:
