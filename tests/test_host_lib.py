@@ -80,3 +80,31 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(tg, "LIB_PATH", str(tmp_path / "nope.so"))
     with pytest.raises(RuntimeError, match="no CPU fallback"):
         tg.load()
+
+
+def test_header_is_plain_c_and_links_from_c(lib, tmp_path):
+    """include/tgemm.h compiles as C99 and as C++11 with -pedantic, and a plain C program linked
+    against the library sees the struct sizes the binding mirrors and can call host-only entry points."""
+    import shutil
+    import subprocess
+    gcc, gxx = shutil.which("gcc"), shutil.which("g++")
+    if gcc is None or gxx is None:
+        pytest.skip("no gcc / g++")
+    inc = os.path.join(ROOT, "include")
+    src = os.path.join(ROOT, "tests", "native", "abi_from_c.c")
+    for cmd in ([gcc, "-std=c99", "-x", "c"], [gxx, "-std=c++11", "-x", "c++"]):
+        r = subprocess.run(cmd + ["-Wall", "-Wextra", "-pedantic", "-Werror", "-I", inc, "-fsyntax-only", src],
+                           stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        assert r.returncode == 0, r.stdout
+    exe = str(tmp_path / "abi_from_c")
+    libdir = os.path.dirname(tg.LIB_PATH)
+    r = subprocess.run([gcc, "-std=c99", "-I", inc, src, "-o", exe, "-L", libdir, "-ltgemm", "-Wl,-rpath," + libdir],
+                       stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    assert r.returncode == 0, r.stdout
+    r = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=120)
+    assert r.returncode == 0, r.stdout
+    out = r.stdout.splitlines()
+    sizes = [ctypes.sizeof(t) for t in (tg.tgemm_opts, tg.tgemm_task, tg.tgemm_stats, tg.tgemm_trace_rec)]
+    assert out[0] == "sizes " + " ".join(str(s) for s in sizes)
+    assert out[1] == "order 0 1 2 3 7 6 5 4 8 9 10 11"
+    assert out[2].startswith("bad order -> %d" % tg.TGEMM_EARG)
