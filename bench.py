@@ -203,6 +203,7 @@ def main():
                     help="c5: round the updated bf16 weights stochastically (mlp_set_rounding) instead of to nearest")
     ap.add_argument("--bias", action="store_true", help="c4 / c5: train bias rows too (mlp_set_bias)")
     ap.add_argument("--momentum", type=float, default=None, help="c4: SGD with this momentum coefficient (mlp_set_momentum)")
+    ap.add_argument("--bf16", action="store_true", help="c4: bf16 storage with fp32 accumulation instead of fp32 (extra data point)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run 5 plain device copies of 256 MiB (a known-size reference for HBM counters)")
@@ -230,7 +231,7 @@ def main():
     elif w == "c3":
         out = run_gemm_ooc(args, tg, inputs, torch, args.size or 65536, args.tile or 4096, 8 * 10 ** 9)
     elif w == "c4":
-        out = run_mlp(args, tg, inputs, torch, [4096, 16384, 16384, 16384, 10000], 4096, args.tile or 1024, False, 0)
+        out = run_mlp(args, tg, inputs, torch, [4096, 16384, 16384, 16384, 10000], 4096, args.tile or 1024, args.bf16, 0)
     else:
         out = run_mlp(args, tg, inputs, torch, [8192, 32768, 32768, 262144], 8192, args.tile or 2048, True, 32 * 10 ** 9)
     print(json.dumps(out))
