@@ -20,6 +20,7 @@
 #include <stdint.h>
 
 #include <type_traits>
+#include <utility>
 
 #include "gemm_kernel.h"
 
@@ -111,6 +112,24 @@ struct TileLoader {
         for (int p = 0; p < UP; ++p) reg[p] = gload<f32x4>(base + off[p]);
     }
 
+    static constexpr int STORE_INSTS = KC ? 4 : 1;     // LDS store instructions per register of a thread
+    // one of the thread's registers -> LDS stage
+    __device__ static inline void store_one(const f32x4& r, float* __restrict__ S, int tid, int p)
+    {
+        constexpr int LD = BMN + PAD;
+        const int u = tid + p * NT;
+        if (KC) {
+            const int mn = u / KQ;
+            const int k = (u % KQ) << 2;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) S[(k + e) * LD + mn] = r[e];
+        } else {
+            constexpr int Q = BMN / 4;
+            const int k = u / Q;
+            const int mn = (u % Q) << 2;
+            *reinterpret_cast<f32x4*>(&S[k * LD + mn]) = r;
+        }
+    }
     // registers -> LDS stage (layout [BK][BMN + PAD])
     __device__ static inline void store(const f32x4 (&reg)[UP], float* __restrict__ S, int tid)
     {
@@ -132,6 +151,63 @@ struct TileLoader {
         }
     }
 };
+
+// ---- instruction order of the steady k loop ------------------------------------------------------
+// A chunk's LDS reads and the LDS stores of the next chunk may alias as far as the compiler can tell,
+// so it keeps them in source order; the loop body is therefore written in the order it should run:
+// for every k pair but the last, the fragment reads of the following pair, the pair's MFMAs, and --
+// in the first half of the pairs -- a share of the next chunk's global loads, in the second half the
+// stores of a share of the staged registers ("pieces": one f32x4 register of the thread each).
+// __builtin_amdgcn_sched_group_barrier(mask, n, 0) then asks the scheduler for n instructions of a
+// class next (0x008 MFMA, 0x020 global load, 0x100 LDS read, 0x200 LDS write), which spreads a pair's
+// loads or stores between its MFMAs.
+struct ChunkPlan {
+    // pairs 0 .. NKP-1 run before the barrier; H = first pair that takes stores
+    template <int NKP> static constexpr int first_store_pair() { return (NKP + 1) / 2; }
+    // the pair that stores piece q of NS
+    template <int NKP, int NS> static constexpr int pair_of_piece(int q)
+    {
+        constexpr int H = first_store_pair<NKP>();
+        return H + (q * (NKP - H)) / NS;
+    }
+    // LDS store instructions of pair kp: pieces 0 .. UPA-1 are A registers (IA instructions each),
+    // the others B registers (IB each)
+    template <int NKP, int UPA, int UPB, int IA, int IB> static constexpr int stores_of_pair(int kp)
+    {
+        int n = 0;
+        for (int q = 0; q < UPA + UPB; ++q)
+            if (pair_of_piece<NKP, UPA + UPB>(q) == kp) n += (q < UPA) ? IA : IB;
+        return n;
+    }
+    // global loads of pair kp (NV over the first H pairs)
+    template <int NKP, int NV> static constexpr int loads_of_pair(int kp)
+    {
+        constexpr int H = first_store_pair<NKP>();
+        return kp < H ? NV * (kp + 1) / H - NV * kp / H : 0;
+    }
+};
+template <class F, int... I>
+__device__ __attribute__((always_inline)) inline void for_each_index(std::integer_sequence<int, I...>, F&& f)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int MASK, int N>
+__device__ __attribute__((always_inline)) inline void sched_group()
+{
+    if constexpr (N > 0) __builtin_amdgcn_sched_group_barrier(MASK, N, 0);
+}
+// MF MFMAs with X instructions of class MASK spread between them
+template <int MF, int X, int MASK, int J = 0>
+__device__ __attribute__((always_inline)) inline void sched_mix()
+{
+    if constexpr (X == 0) {
+        sched_group<0x008, MF>();
+    } else if constexpr (J < X) {
+        sched_group<0x008, MF * (J + 1) / X - MF * J / X>();
+        sched_group<MASK, 1>();
+        sched_mix<MF, X, MASK, J + 1>();
+    }
+}
 
 // ---- the kernel ---------------------------------------------------------------------------------
 // TAIL: the instance for products whose last k chunk is ragged (K % BK != 0); its loop over full chunks
@@ -216,6 +292,32 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
         }
     };
 
+    // The same chunk in pieces, for the loop that carries the first k pair's fragments across the barrier.
+    auto read_frag = [&](int st, int kp, VA& a, VB& b) {
+        a = *reinterpret_cast<const VA*>(As + st * STAGE_A + (lh + 2 * kp) * LDA_S + a_off);
+        b = *reinterpret_cast<const VB*>(Bs + st * STAGE_B + (lh + 2 * kp) * LDB_S + b_off);
+    };
+    auto mfma_step = [&](const VA& a, const VB& b) {
+#pragma unroll
+        for (int r = 0; r < RA; ++r)
+#pragma unroll
+            for (int cc = 0; cc < RB; ++cc)
+                acc[r][cc] = __builtin_amdgcn_mfma_f32_32x32x2f32(vget<RA>(a, r), vget<RB>(b, cc), acc[r][cc], 0, 0, 0);
+    };
+    // k pairs 0 .. BK/2 - 2 of stage st, starting from the fragments of pair 0 in (a, b); on return
+    // (a, b) hold the fragments of the last pair, not yet multiplied
+    auto compute_head = [&](int st, VA& a, VB& b) {
+#pragma unroll
+        for (int kp = 0; kp + 1 < BK / 2; ++kp) {
+            VA an;
+            VB bn;
+            read_frag(st, kp + 1, an, bn);
+            mfma_step(a, b);
+            a = an;
+            b = bn;
+        }
+    };
+
     int ld_step = 0, ld_within = 0;      // chunk the next issue fetches
     const int bcol = col0 - tj * p.T;    // column inside the task's tile column (tile tables)
 
@@ -249,10 +351,8 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
             ld_step += (ld_within == 0);
         };
         constexpr int N_VMEM = LA::UP + LB::UP;               // global load instructions per chunk
-        constexpr int N_MFMA = RA * RB * (BK / 2);
-        constexpr int GAP = (N_MFMA / 2) / N_VMEM > 0 ? (N_MFMA / 2) / N_VMEM : 1;
-        constexpr int N_DSW = (A_KC ? 4 : 1) * LA::UP + (B_KC ? 4 : 1) * LB::UP;   // LDS store instructions per chunk
-        constexpr int GAP2 = (N_MFMA - GAP * N_VMEM) / N_DSW > 0 ? (N_MFMA - GAP * N_VMEM) / N_DSW : 1;
+        constexpr int NKP = BK / 2 - 1;                         // k pairs multiplied before the barrier
+        constexpr int N_LATE = RA * RB;                         // the last k pair, multiplied after the barrier
         // Only the last chunk of the whole product can be ragged here (K % BK != 0): it takes the
         // predicated, zero-filling loads, in an iteration of its own after the steady loop.
         const int n_fast = TAIL ? n_chunks - 1 : n_chunks;
@@ -279,42 +379,76 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
             LB::store(rb, Bs, tid);
         }
         __syncthreads();
+        VA fa;      // fragments of the first k pair of the chunk about to be multiplied
+        VB fb;
+        if (n_chunks > 0) read_frag(0, 0, fa, fb);
         // Steady state: nothing in the body is conditional.  The global loads of the next chunk are
         // spread over the first half of this chunk's MFMAs -- the vector-memory unit takes a wave's
         // loads at a limited rate, and a wave that issues them all up front sits in that queue
         // while its MFMAs wait behind them ...
+        // The barrier sits before the chunk's last k pair: by then every LDS read of the chunk has been
+        // issued, so the stage may be overwritten, and the first fragments of the next chunk are
+        // requested right behind the barrier, their latency covered by the last pair's MFMAs (otherwise
+        // both waves of a SIMD wait for those fragments together and the MFMA pipe idles).
         int c = 0;
         for (; c + 1 < n_fast; ++c) {
             next_b_origin();
             issue();
-            compute(c & 1);
-            LA::store(ra, As + ((c + 1) & 1) * STAGE_A, tid);
-            LB::store(rb, Bs + ((c + 1) & 1) * STAGE_B, tid);
+            {
+                const int st = c & 1;
+                float* a_next = As + ((c + 1) & 1) * STAGE_A;
+                float* b_next = Bs + ((c + 1) & 1) * STAGE_B;
+                for_each_index(std::make_integer_sequence<int, NKP>{}, [&](auto kp_tag) {
+                    constexpr int KP = decltype(kp_tag)::value;
+                    VA an;
+                    VB bn;
+                    read_frag(st, KP + 1, an, bn);
+                    mfma_step(fa, fb);
 #pragma unroll
-            for (int i = 0; i < N_VMEM; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x008, GAP, 0);   // MFMA
-                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);     // one global load
+                    for (int q = 0; q < LA::UP + LB::UP; ++q)
+                        if (ChunkPlan::pair_of_piece<NKP, LA::UP + LB::UP>(q) == KP) {
+                            if (q < LA::UP) LA::store_one(ra[q], a_next, tid, q);
+                            else LB::store_one(rb[q - LA::UP], b_next, tid, q - LA::UP);
+                        }
+                    sched_group<0x100, 2>();
+                    constexpr int NLD = ChunkPlan::loads_of_pair<NKP, N_VMEM>(KP);
+                    constexpr int NST = ChunkPlan::stores_of_pair<NKP, LA::UP, LB::UP, LA::STORE_INSTS, LB::STORE_INSTS>(KP);
+                    if constexpr (NLD > 0) sched_mix<RA * RB, NLD, 0x020>();
+                    else sched_mix<RA * RB, NST, 0x200>();
+                    fa = an;
+                    fb = bn;
+                });
             }
-            // ... and the LDS stores of the next chunk over the second half, so that the MFMA pipe
-            // still has queued work while the wave stores and walks into the barrier (measured:
-            // 129 -> 137 TFLOP/s at 8000^3)
-#pragma unroll
-            for (int i = 0; i < N_DSW; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x008, GAP2, 0);  // MFMA
-                __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);     // one LDS write
-            }
+            __builtin_amdgcn_sched_barrier(0);
             __syncthreads();
+            __builtin_amdgcn_sched_barrier(0);
+            VA na;
+            VB nb;
+            read_frag((c + 1) & 1, 0, na, nb);
+            mfma_step(fa, fb);
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);         // the two fragment reads first
+            __builtin_amdgcn_sched_group_barrier(0x008, N_LATE, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            fa = na;
+            fb = nb;
         }
         if (TAIL && c + 1 < n_chunks) {
             issue_tail();
-            compute(c & 1);
+            compute_head(c & 1, fa, fb);
             LA::store(ra, As + ((c + 1) & 1) * STAGE_A, tid);
             LB::store(rb, Bs + ((c + 1) & 1) * STAGE_B, tid);
             __syncthreads();
+            VA na;
+            VB nb;
+            read_frag((c + 1) & 1, 0, na, nb);
+            mfma_step(fa, fb);
+            fa = na;
+            fb = nb;
             ++c;
         }
         if (c < n_chunks) {
-            compute(c & 1);
+            compute_head(c & 1, fa, fb);
+            mfma_step(fa, fb);
             __syncthreads();
         }
     } else {
@@ -563,8 +697,8 @@ hipError_t launch_tile_gemm_f32(const GemmDesc& d, hipStream_t stream)
     GemmDesc dd = d;
     dd.T = (int32_t)T;
     switch (pick_config(dd)) {
-        case 3: return launch_cfg<2, 4, 4, 2, 16>(p, dd, stream);   // 256 x 256, 512 threads
-        case 2: return launch_cfg<2, 2, 2, 2, 16>(p, dd, stream);   // 128 x 128, 256 threads
+        case 3: return launch_cfg<2, 4, 4, 2, 32>(p, dd, stream);   // 256 x 256, 512 threads
+        case 2: return launch_cfg<2, 2, 2, 2, 32>(p, dd, stream);   // 128 x 128, 256 threads
         // 64 x 64, 256 threads, 64-k chunks: the shape for products too small to fill the chip with
         // larger tiles; there the k loop is bound by the latency of a chunk's round trip
         // (global -> registers -> LDS -> barrier), so it takes few, long chunks
