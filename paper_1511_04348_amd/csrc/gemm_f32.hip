@@ -152,6 +152,20 @@ struct TileLoader {
     }
 };
 
+// One direct global -> LDS load (gfx950 global_load_lds_dwordx4): lane l moves 16 bytes from
+// sbase + voff(l) to LDS byte address lds_addr + 16 l, without passing through registers.  The
+// compiler does not see the LDS write, so it inserts no waits for it: the consumer waits with an
+// explicit vmcnt(0) before the barrier that publishes the stage.
+__device__ inline void dma16(uint32_t lds_addr, uint32_t voff, const void* sbase)
+{
+    const uint64_t b = reinterpret_cast<uint64_t>(sbase);
+    const uint32_t blo = __builtin_amdgcn_readfirstlane((uint32_t)b), bhi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
+    sbase = reinterpret_cast<const void*>(((uint64_t)bhi << 32) | blo);
+    lds_addr = __builtin_amdgcn_readfirstlane(lds_addr);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
+}
+
 // ---- instruction order of the steady k loop ------------------------------------------------------
 // A chunk's LDS reads and the LDS stores of the next chunk may alias as far as the compiler can tell,
 // so it keeps them in source order; the loop body is therefore written in the order it should run:
@@ -342,15 +356,44 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
                 b_org = t + (B_KC ? (int64_t)bcol * p.ldb : (int64_t)bcol);
             }
         };
-        auto issue = [&]() {
-            LA::load_fast(ra, offa, a_org);
+        // An m/n-contiguous operand of the 256-wide shape goes straight into LDS: a k row of the stage
+        // is 256 floats = the 64 x 16 bytes of one direct load, thread tid's unit p of the register
+        // path is exactly lane tid % 64 of the load for row tid / 64 + 8 p, so the same offsets serve.
+        // A k-contiguous operand has to be transposed on the way and keeps the register path.
+        constexpr bool A_DMA = !A_KC && BM == 256 && NT == 512;
+        constexpr bool B_DMA = !B_KC && BN == 256 && NT == 512;
+        typedef __attribute__((address_space(3))) float lds_float;
+        const uint32_t lds_a = (uint32_t)(uintptr_t)((lds_float*)As), lds_b = (uint32_t)(uintptr_t)((lds_float*)Bs);
+        const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+        // one direct load (unit p) of the chunk that goes to stage st
+        auto dma_a = [&](int st, int pp) {
+            dma16(lds_a + (uint32_t)((st * STAGE_A + (wave_u + (NT / 64) * pp) * LDA_S) * 4), offa[pp], a_org);
+        };
+        auto dma_b = [&](int st, int pp) {
+            dma16(lds_b + (uint32_t)((st * STAGE_B + (wave_u + (NT / 64) * pp) * LDB_S) * 4), offb[pp], b_org);
+        };
+        // st: the stage the chunk is headed for (direct loads need it at issue time)
+        auto issue = [&](int st) {
+            if constexpr (A_DMA) {
+#pragma unroll
+                for (int pp = 0; pp < LA::UP; ++pp) dma_a(st, pp);
+            }
+            if constexpr (B_DMA) {
+#pragma unroll
+                for (int pp = 0; pp < LB::UP; ++pp) dma_b(st, pp);
+            }
+            if constexpr (!A_DMA) LA::load_fast(ra, offa, a_org);
             a_org += a_adv;
-            LB::load_fast(rb, offb, b_org);
+            if constexpr (!B_DMA) LB::load_fast(rb, offb, b_org);
             b_org += b_adv;
             ld_within = (ld_within + 1 == cps) ? 0 : ld_within + 1;
             ld_step += (ld_within == 0);
         };
-        constexpr int N_VMEM = LA::UP + LB::UP;               // global load instructions per chunk
+        auto dma_wait = [&]() {
+            if constexpr (A_DMA || B_DMA) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        };
+        constexpr int UPA = A_DMA ? 0 : LA::UP, UPB = B_DMA ? 0 : LB::UP;   // registers staged per chunk
+        constexpr int N_VMEM = UPA + UPB;                     // global load instructions per chunk (to registers)
         constexpr int NKP = BK / 2 - 1;                         // k pairs multiplied before the barrier
         constexpr int N_LATE = RA * RB;                         // the last k pair, multiplied after the barrier
         // Only the last chunk of the whole product can be ragged here (K % BK != 0): it takes the
@@ -371,12 +414,15 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
         if (n_chunks > 0) {
             if (!TAIL || n_fast > 0) {
                 next_b_origin();
-                issue();
+                issue(0);
+                if constexpr (!A_DMA) LA::store(ra, As, tid);
+                if constexpr (!B_DMA) LB::store(rb, Bs, tid);
+                dma_wait();
             } else {
                 issue_tail();
+                LA::store(ra, As, tid);
+                LB::store(rb, Bs, tid);
             }
-            LA::store(ra, As, tid);
-            LB::store(rb, Bs, tid);
         }
         __syncthreads();
         VA fa;      // fragments of the first k pair of the chunk about to be multiplied
@@ -393,7 +439,7 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
         int c = 0;
         for (; c + 1 < n_fast; ++c) {
             next_b_origin();
-            issue();
+            issue((c + 1) & 1);
             {
                 const int st = c & 1;
                 float* a_next = As + ((c + 1) & 1) * STAGE_A;
@@ -404,15 +450,18 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
                     VB bn;
                     read_frag(st, KP + 1, an, bn);
                     mfma_step(fa, fb);
+                    if constexpr (UPA + UPB > 0) {
 #pragma unroll
-                    for (int q = 0; q < LA::UP + LB::UP; ++q)
-                        if (ChunkPlan::pair_of_piece<NKP, LA::UP + LB::UP>(q) == KP) {
-                            if (q < LA::UP) LA::store_one(ra[q], a_next, tid, q);
-                            else LB::store_one(rb[q - LA::UP], b_next, tid, q - LA::UP);
-                        }
+                        for (int q = 0; q < UPA + UPB; ++q)
+                            if (ChunkPlan::pair_of_piece<NKP, (UPA + UPB > 0 ? UPA + UPB : 1)>(q) == KP) {
+                                if (q < UPA) LA::store_one(ra[q], a_next, tid, q);
+                                else LB::store_one(rb[q - UPA], b_next, tid, q - UPA);
+                            }
+                    }
                     sched_group<0x100, 2>();
                     constexpr int NLD = ChunkPlan::loads_of_pair<NKP, N_VMEM>(KP);
-                    constexpr int NST = ChunkPlan::stores_of_pair<NKP, LA::UP, LB::UP, LA::STORE_INSTS, LB::STORE_INSTS>(KP);
+                    constexpr int NST = (UPA + UPB > 0)
+                        ? ChunkPlan::stores_of_pair<NKP, UPA, (UPA + UPB > 0 ? UPB : 1), LA::STORE_INSTS, LB::STORE_INSTS>(KP) : 0;
                     if constexpr (NLD > 0) sched_mix<RA * RB, NLD, 0x020>();
                     else sched_mix<RA * RB, NST, 0x200>();
                     fa = an;
@@ -420,6 +469,7 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
                 });
             }
             __builtin_amdgcn_sched_barrier(0);
+            dma_wait();
             __syncthreads();
             __builtin_amdgcn_sched_barrier(0);
             VA na;
