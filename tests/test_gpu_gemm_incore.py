@@ -160,3 +160,38 @@ def test_config2_sampled_parity_full_size(ctxs, oracle):
     refi = oracle.gemm_samples(Ain, Bin, rows, cols)
     assert np.array_equal(Ci.cpu().numpy()[rows, cols].astype(np.float64), refi)
     assert np.array_equal(Ci.double().sum(1).cpu().numpy(), Ain.astype(np.float64) @ (Bin.astype(np.float64) @ ones))
+
+
+def test_seeded_random_shapes_integer_exact(ctxs, oracle):
+    """Seeded random shapes and tile sizes, every kernel shape: small-integer operands make every
+    partial sum exact in fp32, so the result must equal the oracle's bit for bit whatever path a
+    workgroup takes (full chunks with or without a ragged last one, ragged k-steps, clamped edge
+    tiles, direct-to-LDS or register staging, vector or scalar accesses)."""
+    rnd = np.random.default_rng(20240611)
+    for case in range(40):
+        kind = case % 4
+        if kind == 0:      # everything aligned: the unpredicated paths
+            M, N, K = (4 * int(rnd.integers(1, 200)) for _ in range(3))
+            T = int(rnd.choice([32, 64, 128, 256, 512, 1024]))
+        elif kind == 1:    # K not a multiple of the chunk depth, T a multiple: ragged last chunk only
+            M, N = (4 * int(rnd.integers(8, 160)) for _ in range(2))
+            K = 4 * int(rnd.integers(1, 300)) + 4
+            T = int(rnd.choice([64, 128, 256]))
+        elif kind == 2:    # odd everything
+            M, N, K = (int(rnd.integers(1, 500)) for _ in range(3))
+            T = int(rnd.integers(1, 300))
+        else:              # wide / tall / deep
+            dims = [4 * int(rnd.integers(1, 40)), 4 * int(rnd.integers(100, 400)), 4 * int(rnd.integers(1, 40))]
+            rnd.shuffle(dims)
+            M, N, K = (int(d) for d in dims)
+            T = int(rnd.choice([100, 128, 256, 2048]))
+        A = inputs.int_matrix(100 + case, M, K)
+        B = inputs.int_matrix(200 + case, K, N)
+        C0 = inputs.int_matrix(300 + case, M, N, lo=-7, hi=7)
+        ref = oracle.gemm(A.numpy(), B.numpy(), c_in=C0.numpy())
+        Ad, Bd = A.cuda(), B.cuda()
+        for cfg in (1, 2, 3):
+            announce("random int", case, M, N, K, T, "cfg", cfg)
+            C = C0.cuda()
+            run_incore(ctxs[cfg], Ad, Bd, C, T)
+            assert np.array_equal(C.cpu().numpy().astype(np.float64), ref), (M, N, K, T, cfg)
