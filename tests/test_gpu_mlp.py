@@ -133,3 +133,39 @@ def test_error_paths():
         tg.mlp_destroy(mlp)
     finally:
         tg.tgemm_destroy(ctx)
+
+
+def test_seeded_random_networks(oracle):
+    """Random depths, widths (aligned and odd), batches and tile sizes, every kernel shape: dW of every
+    layer and the probabilities against the oracle at the fp32 bar.  The three layouts of the passes
+    (forward NN, error NT, gradient TN) thereby meet ragged edges and ragged k-steps in all paths."""
+    rnd = np.random.default_rng(20240612)
+    for case in range(10):
+        L = int(rnd.integers(1, 5))
+        aligned = case % 2 == 0
+        pick = (lambda lo, hi: 4 * int(rnd.integers(lo // 4 + 1, hi // 4))) if aligned else (lambda lo, hi: int(rnd.integers(lo, hi)))
+        dims = [pick(8, 700) for _ in range(L + 1)]
+        batch = pick(4, 600)
+        T = int(rnd.choice([32, 64, 100, 128, 256, 1024]))
+        cfg = int(rnd.integers(0, 4))
+        announce("random mlp", case, dims, batch, T, "cfg", cfg)
+        X, Ws, y = _net(dims, batch, seed=case)
+        _, _, P = oracle.mlp_forward(X.numpy(), [w.numpy() for w in Ws])
+        loss_ref, dW_ref, _ = oracle.mlp_backward(X.numpy(), [w.numpy() for w in Ws], y.numpy())
+        ctx = tg.tgemm_create(0, kernel_config=cfg)
+        try:
+            Xd, yd = X.cuda(), y.cuda()
+            Wd = [w.cuda() for w in Ws]
+            dWd = [torch.zeros(w.shape, device="cuda") for w in Ws]
+            probs = torch.empty(batch, dims[-1], device="cuda")
+            torch.cuda.synchronize()
+            mlp = tg.mlp_create(ctx, dims, Wd, tg.TGEMM_F32, T)
+            tg.mlp_forward(mlp, Xd, batch, probs)
+            loss = tg.mlp_backward(mlp, yd, dWd)
+            assert rel_fro(probs.cpu().numpy(), P) <= TOL, (case, "probs")
+            assert abs(loss - loss_ref) <= TOL * abs(loss_ref), (case, "loss")
+            for l in range(L):
+                assert rel_fro(dWd[l].cpu().numpy(), dW_ref[l]) <= TOL, (case, "dW", l)
+            tg.mlp_destroy(mlp)
+        finally:
+            tg.tgemm_destroy(ctx)
