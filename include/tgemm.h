@@ -139,6 +139,9 @@ int tgemm_destroy(tgemm_ctx* ctx);
  *      harvest overlap on the 4 streams with 4 tasks in flight.  Every
  *      device byte allocated for the call (A/B slots + 4 C slots) stays within hbm_budget bytes;
  *      the minimum is 4 C slots + 8 A/B slots (TGEMM_EBUDGET otherwise, before any work).
+ *      The cache directory starts empty at every call (the pool of slots is kept): no tile survives
+ *      from one call to the next, so the caller may change A and B between calls and no call to
+ *      invalidate cached tiles is needed; on return no tile of C remains on the device only.
  *   M, N or K == 0 is legal (C unchanged).
  * Errors: TGEMM_EARG, TGEMM_EUNPINNED, TGEMM_EBUDGET, TGEMM_ENOMEM, TGEMM_EHIP. */
 int tgemm_run(tgemm_ctx* ctx, const void* A, const void* B, void* C,
@@ -174,8 +177,11 @@ int tgemm_queue_selftest(int64_t n, int32_t producers, int32_t consumers, int32_
  *   W        n_layers caller-owned matrices (dtype elements), all of one kind.
  *            Device pointers: in-core, every product is one launch.
  *            Pinned host pointers: out-of-core.  T x T weight tiles are staged through an HBM tile
- *            cache (LRU, section 3.4); the forward pass fetches each tile once, the backward pass
- *            uses a tile for D W^T, updates it and writes it back.  On return of every call the
+ *            cache (section 3.4; the tile evicted is the one whose next use in the fixed sweep of a
+ *            training step lies furthest ahead); the forward pass fetches each tile once, the
+ *            backward pass uses a tile for D W^T, updates it and writes it back.  Tiles stay cached
+ *            from one call to the next: while the object exists only the library may write to
+ *            out-of-core weights.  On return of every call the
  *            host weights are complete and no modified tile remains only on the device (with
  *            opts.deferred_writeback an mlp_step leaves its last write-backs in flight; they are
  *            ordered before any later use of the tile and complete by tgemm_sync).
