@@ -246,3 +246,25 @@ def test_config3_full_size(oracle):
     err = rel_fro(lhs, rhs)
     print("config3 Freivalds rel err", err, flush=True)
     assert err <= TOL_F32
+    # The same product with small-integer operands: every partial sum is an integer below 2^24, so
+    # the result is exact in any order and must equal the fp64 definition bit for bit -- on the
+    # sampled entries (tile corners included) and, through Freivalds' check, on every tile.
+    announce("config3 integer operands: fill")
+    inputs.fill(A, 11, "int", gen_device="cuda")
+    inputs.fill(B, 12, "int", gen_device="cuda")
+    C.zero_()
+    torch.cuda.synchronize()
+    ctx = tg.tgemm_create(0)
+    try:
+        announce("config3 integer operands: run")
+        tg.tgemm_run(ctx, A, B, C, n, n, n, T, tg.TGEMM_F32, budget)
+    finally:
+        tg.tgemm_destroy(ctx)
+    announce("config3 integer operands: sampled entries")
+    ref = oracle.gemm_samples(An, Bn, rows, cols)
+    assert np.array_equal(Cn[rows, cols].astype(np.float64), ref)
+    assert np.abs(ref).max() > 100                                  # not a trivially small result
+    announce("config3 integer operands: Freivalds")
+    lhs = _matvec64(Cn, x)
+    rhs = _matvec64(An, _matvec64(Bn, x))
+    assert np.array_equal(lhs, rhs)                                  # integers in fp64: exact on both sides
