@@ -147,6 +147,14 @@ int tgemm_destroy(tgemm_ctx* ctx);
 int tgemm_run(tgemm_ctx* ctx, const void* A, const void* B, void* C,
               int64_t M, int64_t N, int64_t K, int32_t T, int32_t dtype, size_t hbm_budget);
 
+/* Section 3.4 keeps tiles in the cache for later reuse; a caller who changes a host matrix would have
+ * to have its cached tiles dropped.  In this library tgemm_run starts every call with an empty cache
+ * directory, so no copy outlives a call and this function has nothing to drop: it checks its
+ * arguments and returns TGEMM_OK.  It exists so that callers written for a cache that survives
+ * calls need no change.  (Out-of-core MLP weights are different: see mlp_create.)
+ * TGEMM_EARG if ctx or host_base is NULL. */
+int tgemm_invalidate(tgemm_ctx* ctx, const void* host_base);
+
 /* Waits for everything enqueued on the context's streams (only needed with opts.async_incore). */
 int tgemm_sync(tgemm_ctx* ctx);
 

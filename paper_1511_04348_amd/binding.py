@@ -17,7 +17,7 @@ TGEMM_ACT_SIGMOID, TGEMM_ACT_TANH, TGEMM_ACT_RELU = 0, 1, 2
 TGEMM_ROUND_NEAREST, TGEMM_ROUND_STOCHASTIC = 0, 1
 
 EXPORTS = [
-    "tgemm_strerror", "tgemm_last_error", "tgemm_create", "tgemm_destroy", "tgemm_run", "tgemm_sync",
+    "tgemm_strerror", "tgemm_last_error", "tgemm_create", "tgemm_destroy", "tgemm_run", "tgemm_sync", "tgemm_invalidate",
     "tgemm_plan", "tgemm_task_order", "tgemm_last_stats", "tgemm_trace", "tgemm_queue_selftest",
     "mlp_create", "mlp_destroy", "mlp_set_activation", "mlp_set_rounding", "mlp_set_bias", "mlp_set_momentum", "mlp_forward", "mlp_backward", "mlp_step", "mlp_read",
 ]
@@ -75,6 +75,7 @@ def load():
     lib.tgemm_destroy.argtypes = [vp]
     lib.tgemm_run.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, i32, sz]
     lib.tgemm_sync.argtypes = [vp]
+    lib.tgemm_invalidate.argtypes = [vp, vp]
     lib.tgemm_plan.argtypes = [i64, i64, i64, i32, P(tgemm_task), i64, P(i64)]
     lib.tgemm_task_order.argtypes = [i64, i64, i32, i64, P(i64)]
     lib.tgemm_last_stats.argtypes = [vp, P(tgemm_stats)]
@@ -146,6 +147,10 @@ def tgemm_run(ctx, A, B, C, M, N, K, T, dtype=TGEMM_F32, hbm_budget=0):
 
 def tgemm_sync(ctx):
     _check(load().tgemm_sync(ctx))
+
+
+def tgemm_invalidate(ctx, host_matrix):
+    _check(load().tgemm_invalidate(ctx, _p(host_matrix)))
 
 
 def tgemm_plan(M, N, K, T):

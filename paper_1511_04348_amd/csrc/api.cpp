@@ -133,6 +133,15 @@ int tgemm_destroy(tgemm_ctx* ctx)
     return TGEMM_OK;
 }
 
+int tgemm_invalidate(tgemm_ctx* ctx, const void* host_base)
+{
+    if (!ctx) return fail(TGEMM_EARG, "tgemm_invalidate: ctx is NULL");
+    if (!host_base) return fail(TGEMM_EARG, "tgemm_invalidate: host_base is NULL");
+    // tgemm_run empties the tile cache directory at every call, so no copy of the caller's matrix
+    // outlives a call: there is never anything to drop
+    return TGEMM_OK;
+}
+
 int tgemm_sync(tgemm_ctx* ctx)
 {
     if (!ctx) return fail(TGEMM_EARG, "tgemm_sync: ctx is NULL");

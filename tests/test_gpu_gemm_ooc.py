@@ -168,6 +168,26 @@ def test_copy_kernel_transfers_match_dma(oracle, monkeypatch, dtype, M, N, K, T)
     assert torch.equal(Ap, A) and torch.equal(Bp, B)
 
 
+def test_changed_host_matrix_is_seen_by_the_next_call(oracle):
+    """No tile outlives a call: after the caller changes A in place the next product uses the new
+    values, with or without tgemm_invalidate (which has nothing to drop and says so by succeeding)."""
+    M = N = K = 192
+    T = 64
+    A = inputs.int_matrix(1, M, K).pin_memory()
+    B = inputs.int_matrix(2, K, N).pin_memory()
+    ctx = tg.tgemm_create(0)
+    try:
+        for k in range(3):
+            C = torch.zeros(M, N).pin_memory()
+            tg.tgemm_run(ctx, A, B, C, M, N, K, T, tg.TGEMM_F32, 40 * T * T * 4)
+            assert np.array_equal(C.numpy().astype(np.float64), oracle.gemm(A.numpy(), B.numpy()))
+            A.mul_(-2.0)                       # the caller rewrites its matrix between calls
+            if k == 1:
+                tg.tgemm_invalidate(ctx, A)
+    finally:
+        tg.tgemm_destroy(ctx)
+
+
 def test_error_paths():
     ctx = tg.tgemm_create(0)
     try:

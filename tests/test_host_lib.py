@@ -75,6 +75,10 @@ def test_argument_errors_without_gpu(lib):
     assert tg.tgemm_strerror(tg.TGEMM_EBUDGET).startswith("hbm_budget")
 
 
+def test_invalidate_rejects_null_arguments(lib):
+    assert lib.tgemm_invalidate(None, None) == tg.TGEMM_EARG
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(tg, "_lib", None)
     monkeypatch.setattr(tg, "LIB_PATH", str(tmp_path / "nope.so"))
