@@ -219,6 +219,184 @@ __device__ inline void epilogue(const GemmParams& p, const TileCoord& t, const f
     }
 }
 
+// ---- the same epilogue through a transposition in LDS ---------------------------------------------
+// In the accumulator layout a wave's global access covers 32 rows with 32 bytes each; every 128-byte
+// line of C is touched by four instructions, and a round of workgroups asks for all of C in that
+// shape at the same moment.  Here a wave first writes a 32-row block of its accumulators into a
+// private LDS area (row pitch 32 RB + 4 floats: conflict free for the 16-byte writes) and reads it back
+// row by row: lane l then holds columns 4 (l % LPR) .. + 3 of row l / LPR, so that one instruction
+// covers whole rows of the block (256 contiguous bytes each at RB = 2) for C, for the stored
+// activations and for the result.  Arithmetic, rounding and random bits per element are those of
+// `epilogue` above (tested bit for bit against it).
+// One quad = 4 consecutive columns col .. col + 3 of one row; x = the accumulator values.
+template <int EPI, bool OUT_BF16>
+__device__ inline f32x4 quad_input(const GemmParams& p, const TileCoord& t, const float* Cf, const uint16_t* Cb,
+                                   const uint16_t* aux, bool read_c, int row, int col)
+{
+    f32x4 x = {0.f, 0.f, 0.f, 0.f};
+    if (EPI == EPI_DACT) {
+        const uint16_t* src = aux + (int64_t)row * p.ldaux + col;
+        if (p.vec_aux && col + 3 < t.col_end) {
+            const u32x2 w = gload<u32x2>(src);
+            x[0] = __uint_as_float(w[0] << 16); x[1] = __uint_as_float(w[0] & 0xffff0000u);
+            x[2] = __uint_as_float(w[1] << 16); x[3] = __uint_as_float(w[1] & 0xffff0000u);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (col + e < t.col_end) x[e] = bf16_to_f32(gload<uint16_t>(src + e));
+        }
+    } else if (read_c) {
+        const int64_t at = (int64_t)row * p.ldc + col;
+        if (OUT_BF16) {
+            if (p.vec_c && col + 3 < t.col_end) {
+                const u32x2 w = gload<u32x2>(Cb + at);
+                x[0] = __uint_as_float(w[0] << 16); x[1] = __uint_as_float(w[0] & 0xffff0000u);
+                x[2] = __uint_as_float(w[1] << 16); x[3] = __uint_as_float(w[1] & 0xffff0000u);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (col + e < t.col_end) x[e] = bf16_to_f32(gload<uint16_t>(Cb + at + e));
+            }
+        } else {
+            if (p.vec_c && col + 3 < t.col_end) {
+                x = gload<f32x4>(Cf + at);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (col + e < t.col_end) x[e] = gload<float>(Cf + at + e);
+            }
+        }
+    }
+    return x;
+}
+
+template <int EPI, bool OUT_BF16>
+__device__ inline void quad_finish(const GemmParams& p, const TileCoord& t, float* Cf, uint16_t* Cb, bool read_c,
+                                   int row, int col, const f32x4& a, const f32x4& in)
+{
+    const float alpha = p.alpha, beta = p.beta;
+    const int64_t crow = (int64_t)row * p.ldc;
+    f32x4 bv = {0.f, 0.f, 0.f, 0.f};
+    if ((EPI == EPI_ACT || (EPI == EPI_AXPBY && !OUT_BF16)) && p.bias) {
+        if (col + 3 < t.col_end && p.vec_bias) {
+            bv = gload<f32x4>(p.bias + col);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (col + e < t.col_end) bv[e] = gload<float>(p.bias + col + e);
+        }
+    }
+    f32x4 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        float v = a[e] + bv[e];
+        if (EPI == EPI_AXPBY) {
+            v = read_c ? fmaf(alpha, v, beta * in[e]) : alpha * v;
+        } else if (EPI == EPI_MOMENTUM) {
+            if (col + e < t.col_end) {
+                float* st = p.state + (int64_t)row * p.ldstate + col + e;
+                const float vel = fmaf(p.mu, gload<float>(st), v);
+                gstore<float>(st, vel);
+                const float c_old = OUT_BF16 ? bf16_to_f32(gload<uint16_t>(Cb + crow + col + e))
+                                             : gload<float>(Cf + crow + col + e);
+                v = fmaf(alpha, vel, c_old);
+            }
+        } else if (EPI == EPI_ACT) {
+            v = act_apply(p.act, v);
+        } else if (EPI == EPI_DACT) {
+            v = v * act_slope(p.act, in[e]);
+        }
+        o[e] = v;
+    }
+    if (OUT_BF16) {
+        uint16_t b[4];
+        if ((EPI == EPI_AXPBY || EPI == EPI_MOMENTUM) && p.sr) {
+            const uint32_t hrow = mix32(p.sr_row0 + (uint32_t)row + p.sr_key);
+            const bool even = (col & 1) == 0;
+            const uint32_t b0 = pair_bits(hrow, col), b1 = pair_bits(hrow, col + 2);
+            const uint32_t bm = even ? b0 : pair_bits(hrow, col + 1);
+            const uint32_t be = even ? b1 : pair_bits(hrow, col + 3);
+            b[0] = f32_to_bf16_sr(o[0], even ? b0 & 0xffffu : b0 >> 16);
+            b[1] = f32_to_bf16_sr(o[1], even ? b0 >> 16 : bm & 0xffffu);
+            b[2] = f32_to_bf16_sr(o[2], even ? b1 & 0xffffu : bm >> 16);
+            b[3] = f32_to_bf16_sr(o[3], even ? b1 >> 16 : be & 0xffffu);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) b[e] = f32_to_bf16_rne(o[e]);
+        }
+        uint16_t* dst = Cb + crow + col;
+        if (p.vec_c && col + 3 < t.col_end) {
+            u32x2 w;
+            w[0] = (uint32_t)b[0] | ((uint32_t)b[1] << 16);
+            w[1] = (uint32_t)b[2] | ((uint32_t)b[3] << 16);
+            gstore<u32x2>(dst, w);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (col + e < t.col_end) gstore<uint16_t>(dst + e, b[e]);
+        }
+    } else {
+        float* dst = Cf + crow + col;
+        if (p.vec_c && col + 3 < t.col_end) {
+            gstore<f32x4>(dst, o);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (col + e < t.col_end) gstore<float>(dst + e, o[e]);
+        }
+    }
+}
+
+// lds: this wave's private area of 32 x (32 RB + 4) floats; every wave of the workgroup must be done
+// with whatever the area held before.
+template <int RA, int RB, int EPI, bool OUT_BF16>
+__device__ inline void epilogue_rows(const GemmParams& p, const TileCoord& t, const f32x16 (&acc)[RA][RB], int wrow0,
+                                     int wcol0, int lane, float* lds)
+{
+    constexpr int PITCH = 32 * RB + 4;
+    constexpr int LPR = 8 * RB;            // lanes per row of the block
+    constexpr int RPI = 64 / LPR;          // rows per instruction
+    constexpr int NI = 32 / RPI;           // instructions per 32-row block
+    const int li = lane & 31, lh = lane >> 5;
+    const int rl = lane / LPR, cl = 4 * (lane % LPR);
+    const int64_t c_shift = p.c_tiles ? ((int64_t)(t.ti * p.T) * p.ldc + t.tj * p.T) : 0;
+    void* c_base = p.c_tiles ? p.c_tiles[(int64_t)t.ti * p.n_j + t.tj] : (void*)p.C;
+    float* __restrict__ Cf = reinterpret_cast<float*>(c_base) - c_shift;
+    uint16_t* __restrict__ Cb = reinterpret_cast<uint16_t*>(c_base) - c_shift;
+    const uint16_t* __restrict__ aux = reinterpret_cast<const uint16_t*>(p.aux);
+    const bool read_c = (EPI == EPI_AXPBY) && p.beta != 0.f;
+    const int col = wcol0 + cl;
+#pragma unroll
+    for (int r = 0; r < RA; ++r) {
+        // what the block needs from memory, requested first
+        f32x4 in[NI];
+#pragma unroll
+        for (int j = 0; j < NI; ++j) {
+            const int row = wrow0 + 32 * r + RPI * j + rl;
+            in[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (row < t.row_end && col < t.col_end) in[j] = quad_input<EPI, OUT_BF16>(p, t, Cf, Cb, aux, read_c, row, col);
+        }
+        // accumulator layout -> LDS: lane (li, lh) owns row li, columns 32 cc + 8 g + 4 lh .. + 3
+#pragma unroll
+        for (int cc = 0; cc < RB; ++cc)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                f32x4 v;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = acc[r][cc][4 * g + e];
+                *reinterpret_cast<f32x4*>(lds + li * PITCH + 32 * cc + 8 * g + 4 * lh) = v;
+            }
+        // LDS -> row layout, finish, store (the area belongs to this wave alone; its LDS accesses
+        // execute in order)
+#pragma unroll
+        for (int j = 0; j < NI; ++j) {
+            const int row = wrow0 + 32 * r + RPI * j + rl;
+            const f32x4 a = *reinterpret_cast<const f32x4*>(lds + (RPI * j + rl) * PITCH + cl);
+            if (row < t.row_end && col < t.col_end) quad_finish<EPI, OUT_BF16>(p, t, Cf, Cb, read_c, row, col, a, in[j]);
+        }
+    }
+}
+
 // Fills the task grid, macro-tile and chunk counts of `p` for BM x BN macro tiles and chunks of
 // CHUNK_K; returns the grid size (0 if it does not fit a launch).
 inline int64_t fill_grid(GemmParams& p, const GemmDesc& d, int BM, int BN, int CHUNK_K)

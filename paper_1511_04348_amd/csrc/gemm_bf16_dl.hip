@@ -186,7 +186,6 @@ __global__ __launch_bounds__(DL_NW * 64) void tile_gemm_bf16_dl(const GemmParams
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const bool late = wave >= DL_NW / 2;       // waves w and w + 4 share a SIMD
     const int wm = wave / WN, wn = wave % WN;
-    const int li = lane & 31, lh = lane >> 5;
 
     // the tile coordinates are the same in every lane; kept in scalar registers they make the tile
     // table lookups scalar loads (a vector load there would have to be waited for with vmcnt(0),
@@ -284,7 +283,10 @@ __global__ __launch_bounds__(DL_NW * 64) void tile_gemm_bf16_dl(const GemmParams
     }
     if (!late) boundary(true);      // every wave passes the same number of barriers
 
-    epilogue<RA, RB, EPI, OUT_BF16>(p, tc, acc, row0 + wm * WTM, col0 + wn * WTN, li, lh);
+    // every wave has passed its last LDS read and all direct loads have landed: the stages are free, and
+    // each wave takes 32 x 68 floats of them for the transposition of its accumulators
+    epilogue_rows<RA, RB, EPI, OUT_BF16>(p, tc, acc, row0 + wm * WTM, col0 + wn * WTN, lane,
+                                         reinterpret_cast<float*>(smem) + wave * (32 * (32 * RB + 4)));
 }
 
 template <bool A_KC, bool B_KC, int EPI, bool OB>
