@@ -5,7 +5,7 @@ computes: the GEMM (section 3.1 of the paper: tile products accumulated over
 k), the tile plan (section 3.1, Algorithm 1 "decode"), the L1 tile cache
 behaviour under LRU (section 3.4, Algorithm 1 lookups) and the MLP passes
 (section 2, equations 1, 3, 4), with the optional stochastic rounding of
-updated bf16 weights.
+updated bf16 weights and fp32 master copies.
 
 Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
 ``bench.py`` may import this package.  It never imports the GPU package and
@@ -21,5 +21,5 @@ from .build import build_oracle, lib_path  # noqa: F401
 from .gemm import gemm, gemm_tiled, gemm_samples, num_threads, bf16_to_f64  # noqa: F401
 from .plan import plan_tiles, tile_counts, decode_task, kstep_ranges  # noqa: F401
 from .lru import lru_simulate, tgemm_access_sequence, task_order, auto_strip  # noqa: F401
-from .mlp import mlp_forward, mlp_backward, mlp_step, mlp_step_stochastic, mlp_step_momentum, mlp_loss  # noqa: F401
-from .rounding import mix32, step_key, rounding_bits, stochastic_round_bf16, stochastic_round_matrix  # noqa: F401
+from .mlp import mlp_forward, mlp_backward, mlp_step, mlp_step_stochastic, mlp_step_momentum, mlp_step_master, mlp_loss  # noqa: F401
+from .rounding import mix32, step_key, rounding_bits, stochastic_round_bf16, stochastic_round_matrix, round_bf16_nearest  # noqa: F401

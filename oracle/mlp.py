@@ -17,13 +17,15 @@ The equations themselves are not printed, so the textbook forms are taken:
              act' = A (1 - A) for the sigmoid, 1 - A^2 for tanh, [Z > 0] for relu
     W_l <- W_l - lr * dW_l ;  b_l <- b_l - lr * db_l     (every gradient from the pre-update values)
     with momentum:  V_l <- mu V_l + dW_l ;  W_l <- W_l - lr V_l
+    with fp32 master copies M_l of bf16 weights:  M_l <- fp32(M_l - lr dW_l) ;  W_l <- bf16(M_l),
+                    every product of the two passes taken with the bf16 W_l
 
 numpy's fp64 matmul is the library primitive used for the products.
 """
 import numpy as np
 
 from .gemm import bf16_to_f64
-from .rounding import stochastic_round_matrix
+from .rounding import stochastic_round_matrix, round_bf16_nearest
 
 
 def _f64(a):
@@ -153,3 +155,23 @@ def mlp_step_stochastic(X, Ws, y, lr, seed, step, act="sigmoid"):
     loss, exact, _ = mlp_step(X, Ws, y, lr, act)
     bits = [stochastic_round_matrix(w.astype(np.float32), seed, l + 1, step) for l, w in enumerate(exact)]
     return loss, bits, exact
+
+
+def mlp_step_master(X, Ws, y, lr, masters, act="sigmoid", mu=None, Vs=None):
+    """One step of a bf16 network that keeps an fp32 master copy M_l of every weight matrix.
+
+    Both passes use the bf16 weights Ws (bit patterns); the step is applied to the master copy, in
+    fp64 here and then brought to fp32 (the precision the master copy is stored in), and the bf16
+    weights become the master copy rounded to nearest even -- so steps below half a bf16 ulp are kept
+    in M_l and add up instead of being lost.  With mu and Vs the step is the momentum one
+    (V <- mu V + dW; M <- M - lr V).  Returns (loss, new bf16 bit patterns, new masters as fp32,
+    the new masters in fp64 before the fp32 rounding[, new velocities])."""
+    loss, dWs, _ = mlp_backward(X, Ws, y, act)
+    vel = None if Vs is None else [g + mu * np.asarray(V, dtype=np.float64) for g, V in zip(dWs, Vs)]
+    moves = dWs if Vs is None else vel
+    exact = [np.asarray(M, dtype=np.float32).astype(np.float64) - lr * d for M, d in zip(masters, moves)]
+    new_M = [e.astype(np.float32) for e in exact]
+    bits = [round_bf16_nearest(m) for m in new_M]
+    if Vs is None:
+        return loss, bits, new_M, exact
+    return loss, bits, new_M, exact, vel

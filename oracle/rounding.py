@@ -70,6 +70,27 @@ def stochastic_round_bf16(x, r16):
     return np.where(special, keep, out).astype(np.uint16)
 
 
+def round_bf16_nearest(x):
+    """fp32 array -> bf16 bit patterns (uint16), round to nearest, ties to the even bf16 pattern.
+
+    Written from the definition on the two neighbours, not as an add-and-shift: the candidate below
+    (in magnitude) is the pattern with the low 16 bits cut, the one above is the next bf16 pattern;
+    the nearer wins, and at the midpoint the one whose last kept bit is 0.  Infinities are unchanged
+    and NaNs stay NaNs (quiet bit set)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    u = x.view(np.uint32).astype(np.uint64)
+    low = u & np.uint64(0xFFFF)
+    down = u >> np.uint64(16)
+    up = down + np.uint64(1)              # sign-magnitude: the next pattern is the next magnitude
+    half = np.uint64(0x8000)
+    take_up = (low > half) | ((low == half) & ((down & np.uint64(1)) == np.uint64(1)))
+    out = np.where(take_up, up, down) & np.uint64(0xFFFF)
+    special = (u & np.uint64(0x7F800000)) == np.uint64(0x7F800000)
+    is_nan = special & ((u & np.uint64(0x007FFFFF)) != 0)
+    keep = np.where(is_nan, down | np.uint64(0x40), down)
+    return np.where(special, keep, out).astype(np.uint16)
+
+
 def stochastic_round_matrix(W32, seed, layer, step):
     """Rounds a whole weight matrix (fp32, 2-D) for update `step` of `layer`."""
     W32 = np.ascontiguousarray(W32, dtype=np.float32)

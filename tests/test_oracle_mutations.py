@@ -60,7 +60,8 @@ MLP_PINS = [(pins_mlp.test_finite_differences_every_weight, ()), (pins_mlp.test_
             (pins_mlp.test_activation_symmetries, ()), (pins_mlp.test_step_descends_for_every_activation, ()),
             (pins_mlp.test_bias_finite_differences, ()), (pins_mlp.test_bias_is_a_constant_one_input_column, ()),
             (pins_mlp.test_bias_closed_forms, ()), (pins_mlp.test_bias_step, ()),
-            (pins_mlp.test_momentum_reduces_to_sgd_and_heavy_ball_identity, ()), (pins_mlp.test_momentum_with_bias_rows, ())]
+            (pins_mlp.test_momentum_reduces_to_sgd_and_heavy_ball_identity, ()), (pins_mlp.test_momentum_with_bias_rows, ()),
+            (pins_round.test_master_step_written_out, ()), (pins_round.test_master_copies_keep_the_steps_that_bf16_storage_loses, ())]
 
 MLP_MUTANTS = [
     ("sigmoid sign", "        return 1.0 / (1.0 + np.exp(-z))", "        return 1.0 / (1.0 + np.exp(z))"),
@@ -112,6 +113,19 @@ MLP_MUTANTS = [
      "new_Vb = [np.asarray(v, dtype=np.float64) + g for v, g in zip(Vbs, dbs)]"),
     ("momentum: bias rows move by the gradient", "new_b = [np.asarray(b, dtype=np.float64) - lr * v for b, v in zip(bs, new_Vb)]",
      "new_b = [np.asarray(b, dtype=np.float64) - lr * v for b, v in zip(bs, dbs)]"),
+    ("master copies: gradient taken at the master copies", "    loss, dWs, _ = mlp_backward(X, Ws, y, act)\n    vel = None",
+     "    loss, dWs, _ = mlp_backward(X, [np.asarray(M, dtype=np.float64) for M in masters], y, act)\n    vel = None"),
+    ("master copies: step applied to the bf16 weights", "exact = [np.asarray(M, dtype=np.float32).astype(np.float64) - lr * d for M, d in zip(masters, moves)]",
+     "exact = [_f64(M) - lr * d for M, d in zip(Ws, moves)]"),
+    ("master copies: step added", "exact = [np.asarray(M, dtype=np.float32).astype(np.float64) - lr * d for M, d in zip(masters, moves)]",
+     "exact = [np.asarray(M, dtype=np.float32).astype(np.float64) + lr * d for M, d in zip(masters, moves)]"),
+    ("master copies: kept in fp64", "    new_M = [e.astype(np.float32) for e in exact]", "    new_M = [e for e in exact]"),
+    ("master copies: bf16 weights not refreshed", "    bits = [round_bf16_nearest(m) for m in new_M]", "    bits = [np.asarray(w) for w in Ws]"),
+    ("master copies: bf16 weights truncated", "    bits = [round_bf16_nearest(m) for m in new_M]",
+     "    bits = [(m.view(np.uint32) >> 16).astype(np.uint16) for m in new_M]"),
+    ("master copies: momentum step moves by the gradient", "    moves = dWs if Vs is None else vel", "    moves = dWs"),
+    ("master copies: velocity ignores mu", "[g + mu * np.asarray(V, dtype=np.float64) for g, V in zip(dWs, Vs)]",
+     "[g + np.asarray(V, dtype=np.float64) for g, V in zip(dWs, Vs)]"),
     ("bias update without lr", "new_bs = [np.asarray(b, dtype=np.float64) - lr * g for b, g in zip(bs, dbs)]",
      "new_bs = [np.asarray(b, dtype=np.float64) - g for b, g in zip(bs, dbs)]"),
 ]
@@ -206,7 +220,8 @@ ROUNDING_PINS = [(pins_round.test_mix32_known_answers, ()), (pins_round.test_mix
                  (pins_round.test_rounding_over_all_random_values_is_exactly_unbiased, ()),
                  (pins_round.test_rounding_special_values, ()), (pins_round.test_rounding_bits_layout_and_statistics, ()),
                  (pins_round.test_rounding_a_matrix_is_unbiased_where_nearest_loses_the_update, ()),
-                 (pins_round.test_mlp_step_stochastic_brackets_the_exact_update, ())]
+                 (pins_round.test_mlp_step_stochastic_brackets_the_exact_update, ()),
+                 (pins_round.test_nearest_even_against_torch_and_by_brute_force, ())]
 
 ROUNDING_MUTANTS = [
     ("finalizer: wrong middle shift", "    x = x ^ (x >> np.uint64(13))", "    x = x ^ (x >> np.uint64(15))"),
@@ -230,6 +245,12 @@ ROUNDING_MUTANTS = [
     ("rounding: one added to the random bits (rounds exact values up)", "    out = ((u + r) >> np.uint64(16)) & np.uint64(0xFFFF)",
      "    out = ((u + r + np.uint64(1)) >> np.uint64(16)) & np.uint64(0xFFFF)"),
     ("rounding: NaN not kept quiet", "np.where(is_nan, np.uint64(0x40), np.uint64(0))", "np.where(is_nan, np.uint64(0), np.uint64(0))"),
+    ("nearest: ties go up", "    take_up = (low > half) | ((low == half) & ((down & np.uint64(1)) == np.uint64(1)))", "    take_up = low >= half"),
+    ("nearest: ties go to the odd pattern", "((low == half) & ((down & np.uint64(1)) == np.uint64(1)))", "((low == half) & ((down & np.uint64(1)) == np.uint64(0)))"),
+    ("nearest: ties go down", "    take_up = (low > half) | ((low == half) & ((down & np.uint64(1)) == np.uint64(1)))", "    take_up = low > half"),
+    ("nearest: NaN loses its payload", "    keep = np.where(is_nan, down | np.uint64(0x40), down)", "    keep = np.where(is_nan, down & np.uint64(0xFF80), down)"),
+    ("nearest: infinities rounded like numbers", "    return np.where(special, keep, out).astype(np.uint16)\n\n\ndef stochastic_round_matrix",
+     "    return np.where(is_nan, keep, np.where(special, up, out)).astype(np.uint16)\n\n\ndef stochastic_round_matrix"),
     ("matrix: rows and columns swapped", "np.arange(n_r, dtype=np.uint64)[:, None], np.arange(n_c, dtype=np.uint64)[None, :]",
      "np.arange(n_c, dtype=np.uint64)[None, :], np.arange(n_r, dtype=np.uint64)[:, None]"),
 ]

@@ -153,3 +153,106 @@ def test_mlp_step_stochastic_brackets_the_exact_update(oracle):
         assert np.all((v == lo) | (v == hi))
         assert np.array_equal(b, oracle.stochastic_round_matrix(e32, 4, l + 1, 3))
         assert not np.array_equal(b, oracle.stochastic_round_matrix(e32, 4, l + 1, 2))
+
+
+# ---- round to nearest even, and the step with fp32 master copies -----------------------------------
+
+def test_nearest_even_against_torch_and_by_brute_force(oracle):
+    import torch
+    r = np.random.default_rng(21)
+    # every exponent, random mantissas, plus the midpoints and their neighbours
+    u = r.integers(0, 2 ** 32, 200000, dtype=np.uint64).astype(np.uint32)
+    mid = (r.integers(0, 2 ** 16, 4096, dtype=np.uint64).astype(np.uint32) << 16) | np.uint32(0x8000)
+    u = np.concatenate([u, mid, mid - 1, mid + 1, np.array([0, 0x80000000, 0x7F7FFFFF, 0x00000001, 0x3F808000, 0x3F818000], dtype=np.uint32)])
+    x = u.view(np.float32)
+    finite = np.isfinite(x)
+    got = oracle.round_bf16_nearest(x)
+    # a library's conversion (independent of the oracle's arithmetic)
+    ref = torch.from_numpy(x.copy()).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(got[finite], ref[finite])
+    # brute force on the value line: the result is the nearer neighbour; at a tie the even pattern
+    sel = np.flatnonzero(finite)
+    sel = np.concatenate([sel[:20000], sel[-12000:]])            # random values, and the midpoints with their neighbours
+    xs, g = x[sel].astype(np.float64), got[sel]
+    lo_bits = (u[sel] >> 16).astype(np.uint16)
+    lo, hi = _bf16_val(lo_bits), _bf16_val(lo_bits + np.uint16(1))
+    hi_ok = np.isfinite(hi)
+    v = _bf16_val(g)
+    with np.errstate(invalid="ignore"):
+        d_lo, d_hi = np.abs(xs - lo), np.abs(hi - xs)
+    nearer_lo, nearer_hi = hi_ok & (d_lo < d_hi), hi_ok & (d_hi < d_lo)
+    assert np.array_equal(g[nearer_lo], lo_bits[nearer_lo]) and np.array_equal(v[nearer_hi], hi[nearer_hi])
+    tie = hi_ok & (d_lo == d_hi) & (d_lo > 0)
+    assert tie.sum() > 100 and np.all((g[tie] & 1) == 0)
+    # written-out cases: 1 + 2^-8 is a tie between 1 (even) and 1 + 2^-7 (odd); 1 + 3 * 2^-8 ties upwards
+    assert oracle.round_bf16_nearest(np.float32(1 + 2.0 ** -8)).item() == 0x3F80
+    assert oracle.round_bf16_nearest(np.float32(1 + 3 * 2.0 ** -8)).item() == 0x3F82
+    assert oracle.round_bf16_nearest(np.float32(-(1 + 2.0 ** -8 + 2.0 ** -20))).item() == 0xBF81
+    # infinities stay, NaNs stay NaNs, the largest finite fp32 overflows to infinity
+    sp = oracle.round_bf16_nearest(np.array([np.inf, -np.inf, np.nan], dtype=np.float32))
+    assert sp[0] == 0x7F80 and sp[1] == 0xFF80 and (sp[2] & 0x7F80) == 0x7F80 and (sp[2] & 0x7F) != 0
+    assert oracle.round_bf16_nearest(np.array([0x7F7FFFFF], dtype=np.uint32).view(np.float32))[0] == 0x7F80
+
+
+def _small_net(seed, dims, B):
+    r = np.random.default_rng(seed)
+    to_bits = lambda a: (a.astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)
+    X = to_bits(r.normal(0, 1, (B, dims[0])))
+    Ws = [to_bits(r.normal(0, 0.3, (a, b))) for a, b in zip(dims[:-1], dims[1:])]
+    return X, Ws, r.integers(0, dims[-1], B)
+
+
+def test_master_step_written_out(oracle):
+    dims, B, lr = [7, 11, 5], 13, 0.25
+    X, Ws, y = _small_net(31, dims, B)
+    r = np.random.default_rng(32)
+    # master copies that differ from the bf16 weights by less than half an ulp of them
+    M = [(_bf16_val(w) * (1 + r.uniform(-1, 1, w.shape) * 2.0 ** -10)).astype(np.float32) for w in Ws]
+    assert all(np.array_equal(oracle.round_bf16_nearest(m), w) for m, w in zip(M, Ws))
+    loss, bits, M1, exact = oracle.mlp_step_master(X, Ws, y, lr, M)
+    # the gradient is that of the bf16 weights, not of the master copies
+    loss_w, g, _ = oracle.mlp_backward(X, Ws, y)
+    _, g_m, _ = oracle.mlp_backward(X, [m.astype(np.float64) for m in M], y)
+    assert loss == loss_w
+    for l in range(2):
+        assert np.array_equal(exact[l], M[l].astype(np.float64) - lr * g[l])
+        assert not np.allclose(exact[l], M[l].astype(np.float64) - lr * g_m[l], rtol=0, atol=1e-9)
+        assert M1[l].dtype == np.float32 and np.all(np.abs(M1[l].astype(np.float64) - exact[l]) <= np.abs(exact[l]) * 2.0 ** -24)
+        v = _bf16_val(bits[l])
+        assert np.all(np.abs(v - M1[l]) <= np.abs(M1[l]) * 2.0 ** -8)           # within half a bf16 ulp (2^-8 relative at most)
+        assert np.array_equal(bits[l], oracle.round_bf16_nearest(M1[l]))
+    # with momentum the master copy moves by the velocity
+    V0 = [r.normal(0, 0.1, w.shape) for w in Ws]
+    _, bits_m, M1m, exact_m, V1 = oracle.mlp_step_master(X, Ws, y, lr, M, mu=0.5, Vs=V0)
+    for l in range(2):
+        assert np.allclose(V1[l], 0.5 * V0[l] + g[l], rtol=0, atol=1e-16)
+        assert np.allclose(exact_m[l], M[l].astype(np.float64) - lr * (0.5 * V0[l] + g[l]), rtol=0, atol=1e-15)
+        assert np.array_equal(bits_m[l], oracle.round_bf16_nearest(exact_m[l].astype(np.float32)))
+
+
+def test_master_copies_keep_the_steps_that_bf16_storage_loses(oracle):
+    # steps far below half a bf16 ulp of the weights: the plain bf16 step returns the old weights every
+    # time; with master copies the steps add up and the bf16 weights start to move
+    dims, B = [6, 8, 4], 10
+    X, Ws, y = _small_net(33, dims, B)
+    W0 = [_bf16_val(w) for w in Ws]
+    _, g0, _ = oracle.mlp_backward(X, Ws, y)
+    lr = min(float(np.min(np.abs(w[w != 0])) * 2.0 ** -10 / np.max(np.abs(g))) for w, g in zip(W0, g0))
+    _, plain, _ = oracle.mlp_step(X, Ws, y, lr)
+    assert all(np.array_equal(oracle.round_bf16_nearest(p.astype(np.float32)), w) for p, w in zip(plain, Ws))
+    M = [w.astype(np.float32) for w in W0]
+    W, total, n = list(Ws), [np.zeros(w.shape) for w in Ws], 0
+    while n < 2000 and all(np.array_equal(a, b) for a, b in zip(W, Ws)):
+        _, g, _ = oracle.mlp_backward(X, W, y)
+        _, W, M, _ = oracle.mlp_step_master(X, W, y, lr, M)
+        total = [t + x for t, x in zip(total, g)]
+        n += 1
+    assert 2 < n < 2000                                   # no single step could move a weight; their sum does
+    for l in range(2):
+        # the master copy holds the sum of all steps (fp32 rounding of n additions aside)
+        assert np.allclose(M[l].astype(np.float64), W0[l] - lr * total[l], rtol=n * 2.0 ** -24, atol=0)
+        # and the weights that moved went one bf16 neighbour in the direction of -gradient
+        moved = W[l] != Ws[l]
+        if moved.any():
+            step = _bf16_val(W[l])[moved] - W0[l][moved]
+            assert np.all(np.sign(step) == -np.sign(total[l][moved]))
