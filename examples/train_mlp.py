@@ -2,7 +2,7 @@
 binding): bias rows, momentum, tanh hidden layers, mini-batches.  Every product, activation, error and
 update runs in the library's HIP kernels; torch only allocates the device buffers and draws the data.
 
-    python examples/train_mlp.py [--bf16] [--epochs N]
+    python examples/train_mlp.py [--bf16 [--master-weights]] [--epochs N]
 
 Prints the mean loss per epoch and the accuracy on held-out points."""
 import argparse
@@ -22,7 +22,7 @@ def blobs(n, n_classes, dim, gen):
     return x, y.to(torch.int32)
 
 
-def run(bf16=False, epochs=6, batch=512, quiet=False):
+def run(bf16=False, epochs=6, batch=512, quiet=False, master_weights=False):
     gen = torch.Generator().manual_seed(0)
     dims = [64, 256, 128, 16]
     x, y = blobs(20 * batch, dims[-1], dims[0], gen)
@@ -40,7 +40,10 @@ def run(bf16=False, epochs=6, batch=512, quiet=False):
     tg.mlp_set_activation(mlp, tg.TGEMM_ACT_TANH)
     tg.mlp_set_bias(mlp, b)
     tg.mlp_set_momentum(mlp, 0.9, V, Vb)
-    if bf16:
+    if bf16 and master_weights:      # fp32 master copies keep the small steps; the bf16 weights are their image
+        M = [w.float() for w in W]
+        tg.mlp_set_master_weights(mlp, M)
+    elif bf16:                       # without them, stochastic rounding keeps the steps in expectation
         tg.mlp_set_rounding(mlp, tg.TGEMM_ROUND_STOCHASTIC, 1)
     losses = []
     n_batches = x.shape[0] // batch
@@ -67,6 +70,7 @@ def run(bf16=False, epochs=6, batch=512, quiet=False):
 if __name__ == "__main__":
     ap = argparse.ArgumentParser()
     ap.add_argument("--bf16", action="store_true")
+    ap.add_argument("--master-weights", action="store_true", help="with --bf16: fp32 master copies instead of stochastic rounding")
     ap.add_argument("--epochs", type=int, default=6)
     a = ap.parse_args()
-    run(bf16=a.bf16, epochs=a.epochs)
+    run(bf16=a.bf16, epochs=a.epochs, master_weights=a.master_weights)

@@ -268,6 +268,20 @@ int mlp_set_momentum(tgemm_mlp* mlp, float mu, void* const* V, void* const* Vb);
 enum { TGEMM_ROUND_NEAREST = 0, TGEMM_ROUND_STOCHASTIC = 1 };
 int mlp_set_rounding(tgemm_mlp* mlp, int32_t mode, uint64_t seed);
 
+/* fp32 master copies of bf16 weights for mlp_step (section 2's update leaves the storage precision
+ * open; bf16 storage alone loses every step below half an ulp of the weight, see mlp_set_rounding).
+ * With master copies the two passes still read the bf16 W_l, while the step is applied in fp32 to
+ * the copy inside the dW product's epilogue:
+ *   M_l <- M_l - lr dW_l   (with momentum: M_l <- M_l - lr V_l);   W_l <- bf16(M_l)
+ * where bf16() rounds as mlp_set_rounding says (to nearest even by default).
+ *   Wm  array of n_layers device pointers, Wm[l-1] -> dims[l-1] x dims[l] floats, row-major,
+ *       caller-owned and caller-initialised (normally float(W_l)); the library never reads W_l to
+ *       form the step, so a copy that disagrees with W_l wins at the first step.  NULL removes the
+ *       master copies (the default).
+ * bf16 networks with device-resident weights only: TGEMM_EARG for an fp32 or an out-of-core network
+ * or a pointer that is not device memory.  Waits for outstanding work. */
+int mlp_set_master_weights(tgemm_mlp* mlp, void* const* Wm);
+
 /* Equation 1 for every layer: Z_l = A_{l-1} W_l, A_l = sigmoid(Z_l); last layer: logits.
  *   X      device pointer, batch x dims[0], dtype elements.
  *   probs  NULL, or device pointer to batch x dims[n_layers] floats receiving softmax(logits). */

@@ -19,7 +19,7 @@ TGEMM_ROUND_NEAREST, TGEMM_ROUND_STOCHASTIC = 0, 1
 EXPORTS = [
     "tgemm_strerror", "tgemm_last_error", "tgemm_create", "tgemm_destroy", "tgemm_run", "tgemm_sync", "tgemm_invalidate",
     "tgemm_plan", "tgemm_task_order", "tgemm_last_stats", "tgemm_trace", "tgemm_queue_selftest",
-    "mlp_create", "mlp_destroy", "mlp_set_activation", "mlp_set_rounding", "mlp_set_bias", "mlp_set_momentum", "mlp_forward", "mlp_backward", "mlp_step", "mlp_read",
+    "mlp_create", "mlp_destroy", "mlp_set_activation", "mlp_set_rounding", "mlp_set_bias", "mlp_set_momentum", "mlp_set_master_weights", "mlp_forward", "mlp_backward", "mlp_step", "mlp_read",
 ]
 
 
@@ -87,6 +87,7 @@ def load():
     lib.mlp_set_rounding.argtypes = [vp, i32, ctypes.c_uint64]
     lib.mlp_set_bias.argtypes = [vp, P(vp), P(vp)]
     lib.mlp_set_momentum.argtypes = [vp, ctypes.c_float, P(vp), P(vp)]
+    lib.mlp_set_master_weights.argtypes = [vp, P(vp)]
     lib.mlp_forward.argtypes = [vp, vp, i64, vp]
     lib.mlp_backward.argtypes = [vp, vp, P(vp), P(ctypes.c_float)]
     lib.mlp_step.argtypes = [vp, vp, vp, i64, ctypes.c_float, P(ctypes.c_float)]
@@ -224,6 +225,12 @@ def mlp_set_momentum(mlp, mu, V, Vb=None):
     arr_v = (ctypes.c_void_p * len(V))(*[_p(x) for x in V]) if V is not None else None
     arr_vb = (ctypes.c_void_p * len(Vb))(*[_p(x) for x in Vb]) if Vb is not None else None
     _check(load().mlp_set_momentum(mlp, mu, arr_v, arr_vb))
+
+
+def mlp_set_master_weights(mlp, Wm):
+    """Wm: list of float device tensors shaped like the (bf16) weights, or None."""
+    arr = (ctypes.c_void_p * len(Wm))(*[_p(x) for x in Wm]) if Wm is not None else None
+    _check(load().mlp_set_master_weights(mlp, arr))
 
 
 def mlp_forward(mlp, X, batch, probs=None):

@@ -452,6 +452,10 @@ hipError_t launch_tile_gemm_bf16(const GemmDesc& d, hipStream_t stream)
     p.state = d.state; p.ldstate = d.ldstate; p.mu = d.mu;
     if (d.epilogue == EPI_MOMENTUM && (!d.state || d.c_tiles || d.a_kcontig || d.b_kcontig)) return hipErrorInvalidValue;
     p.sr_key = d.sr_key; p.sr_row0 = (uint32_t)d.sr_row0;
+    // an fp32 master copy goes with the updates of a dense bf16 C only
+    p.master = d.master; p.ldmaster = d.ldmaster;
+    if (d.master && (!d.out_bf16 || d.c_tiles || !(d.epilogue == EPI_MOMENTUM || (d.epilogue == EPI_AXPBY && d.beta != 0.f))))
+        return hipErrorInvalidValue;
     p.bias = d.bias;
     p.vec_bias = d.bias && ((reinterpret_cast<uintptr_t>(d.bias) & 15) == 0) && (T % 4 == 0);
     p.b_tiles = d.b_tiles; p.c_tiles = d.c_tiles;
@@ -467,6 +471,7 @@ hipError_t launch_tile_gemm_bf16(const GemmDesc& d, hipStream_t stream)
     {
         const uintptr_t need = d.out_bf16 ? 7 : 15;
         p.vec_c = (d.ldc % 4 == 0) && ((reinterpret_cast<uintptr_t>(d.C) & need) == 0) && (T % 4 == 0);
+        if (d.master) p.vec_c = p.vec_c && (d.ldmaster % 4 == 0) && ((reinterpret_cast<uintptr_t>(d.master) & 15) == 0);
         p.vec_aux = d.aux && (d.ldaux % 4 == 0) && ((reinterpret_cast<uintptr_t>(d.aux) & 7) == 0) && (T % 4 == 0);
     }
     // the unpredicated load path keeps per-thread byte offsets in 32 bits
@@ -498,6 +503,7 @@ hipError_t launch_tile_gemm_bf16(const GemmDesc& d, hipStream_t stream)
         cfg = c3 <= c2 ? 3 : 2;
     }
     if (cfg == 3 && dl_ok) return bf::launch_tile_gemm_bf16_dl(p, dd, stream);
+    if (d.master) cfg = 2;   // of the register-staged shapes only the smaller one carries a master copy
     if (cfg >= 3) return bf::launch_cfg<2, 4, 4, 2, 1>(p, dd, stream);   // 256 x 256, 8 waves of 64 x 128
     return bf::launch_cfg<2, 2, 2, 2, 1>(p, dd, stream);                  // 128 x 128, 4 waves of 64 x 64
 }

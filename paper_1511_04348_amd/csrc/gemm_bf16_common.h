@@ -69,6 +69,21 @@ __device__ inline TileCoord decode_tile(const GemmParams& p)
     return t;
 }
 
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// The fp32 result of an update goes back into the master copy of a bf16 C (quad: columns col .. col + 3).
+__device__ inline void store_master(const GemmParams& p, const TileCoord& t, int row, int col, const f32x4& o, bool vec)
+{
+    float* dst = p.master + (int64_t)row * p.ldmaster + col;
+    if (vec && col + 3 < t.col_end) {
+        gstore<f32x4>(dst, o);
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (col + e < t.col_end) gstore<float>(dst + e, o[e]);
+    }
+}
+
 // The kernels feed the MFMA with the B fragment as its first and the A fragment as its second
 // operand, i.e. they accumulate the transposed 32 x 32 block: a lane then owns one row of C and
 // four consecutive columns per register quad,
@@ -76,8 +91,6 @@ __device__ inline TileCoord decode_tile(const GemmParams& p)
 // which turns the epilogue's traffic into 16-byte (fp32) or 8-byte (bf16) accesses.  Everything the
 // epilogue reads for one r is requested before the first value is used.
 // wrow0 / wcol0: first row / column of the wave tile in the matrix.
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-
 template <int RA, int RB, int EPI, bool OUT_BF16>
 __device__ inline void epilogue(const GemmParams& p, const TileCoord& t, const f32x16 (&acc)[RA][RB], int wrow0,
                                 int wcol0, int li, int lh)
@@ -89,7 +102,12 @@ __device__ inline void epilogue(const GemmParams& p, const TileCoord& t, const f
     float* __restrict__ Cf = reinterpret_cast<float*>(c_base) - c_shift;
     uint16_t* __restrict__ Cb = reinterpret_cast<uint16_t*>(c_base) - c_shift;
     const uint16_t* __restrict__ aux = reinterpret_cast<const uint16_t*>(p.aux);
-    const bool read_c = (EPI == EPI_AXPBY) && beta != 0.f;
+    // with an fp32 master copy the old value is read from it quad by quad in the second loop
+    // (wave tiles of up to 64 x 64 only: the 64 x 128 wave tile has no registers to spare for it, and
+    // the launcher sends updates with a master copy to the smaller shape)
+    constexpr bool MASTER = OUT_BF16 && RA * RB <= 4 && (EPI == EPI_AXPBY || EPI == EPI_MOMENTUM);
+    const bool from_master = MASTER && (EPI == EPI_AXPBY) && p.master != nullptr;
+    const bool read_c = (EPI == EPI_AXPBY) && beta != 0.f && !from_master;
     const bool vec_c = p.vec_c, vec_aux = p.vec_aux;
 #pragma unroll
     for (int r = 0; r < RA; ++r) {
@@ -155,19 +173,31 @@ __device__ inline void epilogue(const GemmParams& p, const TileCoord& t, const f
                             if (col + e < t.col_end) bv[e] = gload<float>(p.bias + col + e);
                     }
                 }
+                f32x4 old = {0.f, 0.f, 0.f, 0.f};
+                if (MASTER && EPI == EPI_AXPBY && from_master) {
+                    const float* src = p.master + (int64_t)row * p.ldmaster + col;
+                    if (vec_c && col + 3 < t.col_end) {
+                        old = gload<f32x4>(src);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (col + e < t.col_end) old[e] = gload<float>(src + e);
+                    }
+                }
                 f32x4 o;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     float v = acc[r][cc][4 * g + e] + bv[e];
                     if (EPI == EPI_AXPBY) {
-                        v = read_c ? fmaf(alpha, v, beta * in[cc][g][e]) : alpha * v;
+                        v = from_master ? fmaf(alpha, v, beta * old[e]) : read_c ? fmaf(alpha, v, beta * in[cc][g][e]) : alpha * v;
                     } else if (EPI == EPI_MOMENTUM) {
                         if (col + e < t.col_end) {   // S = mu S + acc; C = C + alpha S (C read here, entry by entry)
                             float* st = p.state + (int64_t)row * p.ldstate + col + e;
                             const float vel = fmaf(p.mu, gload<float>(st), v);
                             gstore<float>(st, vel);
-                            const float c_old = OUT_BF16 ? bf16_to_f32(gload<uint16_t>(Cb + crow + col + e))
-                                                         : gload<float>(Cf + crow + col + e);
+                            const float c_old = !OUT_BF16 ? gload<float>(Cf + crow + col + e)
+                                                : (MASTER && p.master) ? gload<float>(p.master + (int64_t)row * p.ldmaster + col + e)
+                                                                       : bf16_to_f32(gload<uint16_t>(Cb + crow + col + e));
                             v = fmaf(alpha, vel, c_old);
                         }
                     } else if (EPI == EPI_ACT) {
@@ -178,6 +208,7 @@ __device__ inline void epilogue(const GemmParams& p, const TileCoord& t, const f
                     o[e] = v;
                 }
                 if (OUT_BF16) {
+                    if (MASTER && p.master) store_master(p, t, row, col, o, vec_c);
                     uint16_t b[4];
                     if ((EPI == EPI_AXPBY || EPI == EPI_MOMENTUM) && p.sr) {
                         // col is even when T is (pairs col / 2 and col / 2 + 1); odd tile sizes go column by column
@@ -247,7 +278,16 @@ __device__ inline f32x4 quad_input(const GemmParams& p, const TileCoord& t, cons
         }
     } else if (read_c) {
         const int64_t at = (int64_t)row * p.ldc + col;
-        if (OUT_BF16) {
+        if (OUT_BF16 && p.master) {
+            const float* src = p.master + (int64_t)row * p.ldmaster + col;
+            if (p.vec_c && col + 3 < t.col_end) {
+                x = gload<f32x4>(src);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (col + e < t.col_end) x[e] = gload<float>(src + e);
+            }
+        } else if (OUT_BF16) {
             if (p.vec_c && col + 3 < t.col_end) {
                 const u32x2 w = gload<u32x2>(Cb + at);
                 x[0] = __uint_as_float(w[0] << 16); x[1] = __uint_as_float(w[0] & 0xffff0000u);
@@ -297,8 +337,9 @@ __device__ inline void quad_finish(const GemmParams& p, const TileCoord& t, floa
                 float* st = p.state + (int64_t)row * p.ldstate + col + e;
                 const float vel = fmaf(p.mu, gload<float>(st), v);
                 gstore<float>(st, vel);
-                const float c_old = OUT_BF16 ? bf16_to_f32(gload<uint16_t>(Cb + crow + col + e))
-                                             : gload<float>(Cf + crow + col + e);
+                const float c_old = !OUT_BF16 ? gload<float>(Cf + crow + col + e)
+                                    : p.master ? gload<float>(p.master + (int64_t)row * p.ldmaster + col + e)
+                                               : bf16_to_f32(gload<uint16_t>(Cb + crow + col + e));
                 v = fmaf(alpha, vel, c_old);
             }
         } else if (EPI == EPI_ACT) {
@@ -309,6 +350,8 @@ __device__ inline void quad_finish(const GemmParams& p, const TileCoord& t, floa
         o[e] = v;
     }
     if (OUT_BF16) {
+        if ((EPI == EPI_AXPBY || EPI == EPI_MOMENTUM) && p.master)
+            store_master(p, t, row, col, o, p.vec_c);
         uint16_t b[4];
         if ((EPI == EPI_AXPBY || EPI == EPI_MOMENTUM) && p.sr) {
             const uint32_t hrow = mix32(p.sr_row0 + (uint32_t)row + p.sr_key);

@@ -733,6 +733,8 @@ hipError_t launch_tile_gemm_f32(const GemmDesc& d, hipStream_t stream)
     p.alpha = d.alpha; p.beta = d.beta; p.act = d.act;
     p.sr = 0; p.sr_key = 0; p.sr_row0 = 0; p.bias = d.bias; p.vec_bias = false;
     p.state = d.state; p.ldstate = d.ldstate; p.mu = d.mu;
+    p.master = nullptr; p.ldmaster = 0;
+    if (d.master) return hipErrorInvalidValue;   // fp32 C is its own master copy
     if (d.epilogue == EPI_MOMENTUM && (!d.state || d.c_tiles)) return hipErrorInvalidValue;
     p.b_tiles = d.b_tiles; p.c_tiles = d.c_tiles;
     const bool t4 = (T % 4 == 0);

@@ -45,6 +45,11 @@ struct GemmDesc {
     float* state;     // EPI_MOMENTUM: S
     int64_t ldstate;
     float mu;
+    // bf16 kernel, EPI_AXPBY (beta != 0) or EPI_MOMENTUM with out_bf16: an fp32 copy of C (M x N,
+    // leading dimension ldmaster).  The old value of C is taken from it instead of from the bf16 C,
+    // the fp32 result is stored back into it, and C receives that result rounded to bf16.  Dense C only.
+    float* master;
+    int64_t ldmaster;
     // Optional tile tables (device arrays of device pointers) for operands that live as separate
     // T x T tiles in cache slots instead of one dense matrix.  Entry [step * n_j + tj] of b_tiles
     // is the B tile of k-step `step` and task column tj; entry [ti * n_j + tj] of c_tiles is the C
@@ -73,6 +78,8 @@ struct GemmParams {
     float* state;               // EPI_MOMENTUM
     int64_t ldstate;
     float mu;
+    float* master;              // fp32 copy of a bf16 C (see GemmDesc); vec_c then also covers it
+    int64_t ldmaster;
     int sr;                     // stochastic rounding of a bf16 result (see GemmDesc)
     uint32_t sr_key;
     uint32_t sr_row0;

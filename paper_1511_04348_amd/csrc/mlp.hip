@@ -191,6 +191,7 @@ struct tgemm_mlp {
     std::vector<float*> dbias;    // caller-owned destinations of mlp_backward's bias gradients, may hold NULLs
     std::vector<float*> vel;      // caller-owned velocity matrices V_l (device, float), empty: plain SGD
     std::vector<float*> vel_bias; // velocity rows of the bias terms (may be empty)
+    std::vector<float*> master;   // caller-owned fp32 copies of bf16 weights (device), empty: none
     float mu = 0.f;               // momentum coefficient
     float* colsum_part = nullptr; // partial column sums of an error matrix: COLSUM_CHUNKS x max n_l floats
     int32_t dtype = TGEMM_F32;
@@ -774,6 +775,9 @@ int backward_layer(tgemm_mlp* m, int l, float* dW_out, bool update, float lr)
                     dw.epilogue = EPI_MOMENTUM;
                     dw.state = m->vel[(size_t)l - 1]; dw.ldstate = m->dims[l]; dw.mu = m->mu;
                 }
+                if (!m->master.empty()) {   // the step goes to the fp32 copy; W becomes its rounded image
+                    dw.master = m->master[(size_t)l - 1]; dw.ldmaster = m->dims[l];
+                }
                 dw.sr = (bf && m->round_mode == TGEMM_ROUND_STOCHASTIC) ? 1 : 0;
                 dw.sr_key = sr_step_key(m->sr_seed, (uint32_t)l, m->sr_step); dw.sr_row0 = 0;
             }
@@ -1007,6 +1011,29 @@ int mlp_set_momentum(tgemm_mlp* m, float mu, void* const* V, void* const* Vb)
         if (Vb) for (int l = 0; l < m->n_layers; ++l) m->vel_bias.push_back((float*)Vb[l]);
         m->mu = mu;
     }
+    return TGEMM_OK;
+}
+
+int mlp_set_master_weights(tgemm_mlp* m, void* const* Wm)
+{
+    if (!m) return fail(TGEMM_EARG, "mlp_set_master_weights: object is NULL");
+    TG_HIP(hipSetDevice(m->ctx->device));
+    if (Wm) {
+        if (m->dtype != TGEMM_BF16) return fail(TGEMM_EARG, "mlp_set_master_weights: fp32 weights need no master copy");
+        if (m->ooc)
+            return fail(TGEMM_EARG, "mlp_set_master_weights: needs device-resident weights (this network is out-of-core)");
+        for (int l = 0; l < m->n_layers; ++l) {
+            hipPointerAttribute_t at;
+            if (!Wm[l] || hipPointerGetAttributes(&at, Wm[l]) != hipSuccess || at.type != hipMemoryTypeDevice) {
+                (void)hipGetLastError();
+                return fail(TGEMM_EARG, "mlp_set_master_weights: Wm[%d] is not device memory", l);
+            }
+        }
+    }
+    int rc = sync_all(m);
+    if (rc != TGEMM_OK) return rc;
+    m->master.clear();
+    if (Wm) for (int l = 0; l < m->n_layers; ++l) m->master.push_back((float*)Wm[l]);
     return TGEMM_OK;
 }
 

@@ -1,6 +1,6 @@
 """End to end: the example trainer (bias rows, momentum, tanh, mini-batches through mlp_step) must
 actually learn -- the loss falls from about ln 16 to a small value and held-out accuracy is high -- in
-fp32 and with bf16 weights rounded stochastically."""
+fp32, with bf16 weights rounded stochastically, and with bf16 weights that follow fp32 master copies."""
 import math
 import os
 import sys
@@ -13,11 +13,11 @@ sys.path.insert(0, os.path.join(ROOT, "examples"))
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("bf16", [False, True])
-def test_example_trainer_learns(bf16):
+@pytest.mark.parametrize("bf16,master", [(False, False), (True, False), (True, True)])
+def test_example_trainer_learns(bf16, master):
     import train_mlp
-    print("[case] example trainer", "bf16" if bf16 else "f32", flush=True)
-    losses, acc = train_mlp.run(bf16=bf16, epochs=5, quiet=True)
+    print("[case] example trainer", "bf16" if bf16 else "f32", "master copies" if master else "", flush=True)
+    losses, acc = train_mlp.run(bf16=bf16, epochs=5, quiet=True, master_weights=master)
     assert losses[0] < math.log(16) + 0.5
     assert all(b <= a + 1e-3 for a, b in zip(losses, losses[1:])), losses
     assert losses[-1] < 0.1 * losses[0], losses

@@ -1,0 +1,176 @@
+"""GPU parity of mlp_step with fp32 master copies of bf16 weights (mlp_set_master_weights) against the
+oracle: master copies after each of three steps (1e-2 on the step, the bar of the bf16 passes), the
+bf16 weights bit for bit the rounded image of the master copies the GPU holds (nearest even, or the
+documented random bits), with and without momentum, every kernel configuration; steps below half a
+bf16 ulp add up in the master copies while the plain bf16 step loses them; error paths."""
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import announce, rel_fro
+from paper_1511_04348_amd import binding as tg
+from paper_1511_04348_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+
+def _bits(t):
+    return inputs.bf16_bits(t).copy()
+
+
+def _net(dims, batch):
+    L = len(dims) - 1
+    X = inputs.normal_matrix(1, batch, dims[0]).to(torch.bfloat16)
+    Ws = [inputs.normal_matrix(10 + l, dims[l], dims[l + 1], std=0.05).to(torch.bfloat16) for l in range(L)]
+    return X, Ws, inputs.labels(5, batch, dims[-1])
+
+
+@pytest.mark.parametrize("momentum", [False, True])
+@pytest.mark.parametrize("dims,batch,T", [([256, 384, 320, 200], 192, 128), ([70, 90, 33], 50, 32), ([512, 256, 512], 256, 256)])
+def test_three_steps_with_master_copies(oracle, dims, batch, T, momentum):
+    L, mu, lr, tol = len(dims) - 1, 0.9, 2.0, 1e-2
+    X, Ws, y = _net(dims, batch)
+    for cfg in (0, 2, 3, 4):
+        announce("mlp master copies", dims, batch, T, "cfg", cfg, "momentum" if momentum else "")
+        ctx = tg.tgemm_create(0, kernel_config=cfg)
+        try:
+            Wd = [w.cuda() for w in Ws]
+            # master copies within half an ulp of the bf16 weights, not equal to them
+            Md = [(w.float() * (1 + 2.0 ** -10 * inputs.normal_matrix(50 + l, *w.shape).clamp(-1, 1))).cuda() for l, w in enumerate(Ws)]
+            Vd = [inputs.normal_matrix(30 + l, dims[l], dims[l + 1], std=0.01).cuda() for l in range(L)]
+            Xd, yd = X.cuda(), y.cuda()
+            torch.cuda.synchronize()
+            mlp = tg.mlp_create(ctx, dims, Wd, tg.TGEMM_BF16, T)
+            tg.mlp_set_master_weights(mlp, Md)
+            if momentum:
+                tg.mlp_set_momentum(mlp, mu, Vd)
+            for step in range(3):
+                W0, M0, V0 = [_bits(w) for w in Wd], [m.cpu().numpy().copy() for m in Md], [v.cpu().numpy().copy() for v in Vd]
+                loss = tg.mlp_step(mlp, Xd, yd, batch, lr)
+                tg.tgemm_sync(ctx)
+                if momentum:
+                    ref_loss, _, M1, exact, V1 = oracle.mlp_step_master(_bits(X), W0, y.numpy(), lr, M0, mu=mu, Vs=V0)
+                else:
+                    ref_loss, _, M1, exact = oracle.mlp_step_master(_bits(X), W0, y.numpy(), lr, M0)
+                assert abs(loss - ref_loss) <= tol * abs(ref_loss)
+                for l in range(L):
+                    m_gpu = Md[l].cpu().numpy()
+                    m_old = M0[l].astype(np.float64)
+                    slack = np.linalg.norm(exact[l]) * 2.0 ** -24 / np.linalg.norm(exact[l] - m_old)
+                    assert slack < 0.01, slack
+                    assert rel_fro(m_gpu.astype(np.float64) - m_old, exact[l] - m_old) <= tol + slack, ("master", step, l)
+                    # the bf16 weights are the rounded image of the master copy the GPU holds, bit for bit
+                    assert np.array_equal(_bits(Wd[l]), oracle.round_bf16_nearest(m_gpu)), ("weights", step, l)
+                    if momentum:
+                        v_old = V0[l].astype(np.float64)
+                        assert rel_fro(Vd[l].cpu().numpy().astype(np.float64) - mu * v_old, V1[l] - mu * v_old) <= tol, ("velocity", step, l)
+            tg.mlp_destroy(mlp)
+        finally:
+            tg.tgemm_destroy(ctx)
+
+
+def test_master_copies_with_stochastic_rounding(oracle):
+    dims, batch, T, lr, seed = [256, 384, 200], 192, 128, 2.0, 0x1234567890ABCDEF
+    X, Ws, y = _net(dims, batch)
+    ctx = tg.tgemm_create(0)
+    try:
+        Wd = [w.cuda() for w in Ws]
+        Md = [w.float().cuda() for w in Ws]
+        Xd, yd = X.cuda(), y.cuda()
+        mlp = tg.mlp_create(ctx, dims, Wd, tg.TGEMM_BF16, T)
+        tg.mlp_set_master_weights(mlp, Md)
+        tg.mlp_set_rounding(mlp, tg.TGEMM_ROUND_STOCHASTIC, seed)
+        for step in range(2):
+            announce("mlp master copies + stochastic rounding, step", step)
+            tg.mlp_step(mlp, Xd, yd, batch, lr)
+            tg.tgemm_sync(ctx)
+            for l in range(2):
+                m_gpu = Md[l].cpu().numpy()
+                assert np.array_equal(_bits(Wd[l]), oracle.stochastic_round_matrix(m_gpu, seed, l + 1, step)), (step, l)
+                assert not np.array_equal(_bits(Wd[l]), oracle.round_bf16_nearest(m_gpu))
+        tg.mlp_destroy(mlp)
+    finally:
+        tg.tgemm_destroy(ctx)
+
+
+def test_small_steps_add_up_in_the_master_copies(oracle):
+    dims, batch, T, n = [128, 192, 64], 96, 64, 24
+    X, Ws, y = _net(dims, batch)
+    # weights of one order of magnitude (0.04 .. 0.06 in absolute value), so that a step that is below
+    # half an ulp everywhere is still far above the fp32 resolution of the master copies
+    Ws = [(torch.sign(w.float()) * (0.04 + 0.2 * w.float().abs().clamp(max=0.1))).to(torch.bfloat16) for w in Ws]
+    _, g0, _ = oracle.mlp_backward(_bits(X), [_bits(w) for w in Ws], y.numpy())
+    # every step moves every weight by at most 1 / 8 of half an ulp (half an ulp >= 2^-9 abs(w)); the
+    # weight that attains the bound has crossed to a neighbour after 24 steps
+    lr = np.inf
+    for w, g in zip(Ws, g0):
+        w = np.abs(w.float().numpy().astype(np.float64))
+        ok = (w != 0) & (g != 0)
+        lr = min(lr, float(np.min(w[ok] * 2.0 ** -12 / np.abs(g[ok]))))
+    Xd, yd = X.cuda(), y.cuda()
+    out = {}
+    for master in (False, True):
+        announce("mlp small steps, master copies", master)
+        ctx = tg.tgemm_create(0)
+        try:
+            Wd = [w.cuda() for w in Ws]
+            Md = [w.float().cuda() for w in Ws]
+            mlp = tg.mlp_create(ctx, dims, Wd, tg.TGEMM_BF16, T)
+            if master:
+                tg.mlp_set_master_weights(mlp, Md)
+            M_ref = [w.float().numpy() for w in Ws]
+            for step in range(n):
+                W0 = [_bits(w) for w in Wd]
+                tg.mlp_step(mlp, Xd, yd, batch, lr)
+                tg.tgemm_sync(ctx)
+                if master:      # the oracle follows with its own master copies, from the weights the GPU holds
+                    _, _, M_ref, _ = oracle.mlp_step_master(_bits(X), W0, y.numpy(), lr, M_ref)
+            out[master] = ([_bits(w) for w in Wd], [m.cpu().numpy() for m in Md], M_ref)
+            tg.mlp_destroy(mlp)
+        finally:
+            tg.tgemm_destroy(ctx)
+    start = [_bits(w) for w in Ws]
+    # plain bf16 storage: nothing ever moved
+    assert all(np.array_equal(a, b) for a, b in zip(out[False][0], start))
+    # master copies: the sum of the steps is there, and it has carried weights over to a neighbour
+    W1, M1, M_ref = out[True]
+    for l in range(2):
+        s = Ws[l].float().numpy().astype(np.float64)
+        moved = M_ref[l].astype(np.float64) - s
+        slack = np.linalg.norm(s) * 2.0 ** -24 * np.sqrt(n) / np.linalg.norm(moved)     # n fp32 roundings of the copy
+        assert slack < 5e-3, slack
+        assert rel_fro(M1[l].astype(np.float64) - s, moved) <= 1e-2 + slack, l
+        assert np.array_equal(W1[l], oracle.round_bf16_nearest(M1[l]))
+    assert sum(int((a != b).sum()) for a, b in zip(W1, start)) > 0
+
+
+def test_master_copy_errors():
+    dims, T = [64, 48, 32], 32
+    Ws = [inputs.normal_matrix(10 + l, dims[l], dims[l + 1], std=0.1) for l in range(2)]
+    ctx = tg.tgemm_create(0)
+    try:
+        Md = [w.cuda() for w in Ws]
+        # fp32 networks have no use for it
+        mlp = tg.mlp_create(ctx, dims, [w.cuda() for w in Ws], tg.TGEMM_F32, T)
+        with pytest.raises(tg.TgemmError) as e:
+            tg.mlp_set_master_weights(mlp, Md)
+        assert e.value.code == tg.TGEMM_EARG
+        tg.mlp_set_master_weights(mlp, None)
+        tg.mlp_destroy(mlp)
+        Wb = [w.to(torch.bfloat16).cuda() for w in Ws]
+        mlp = tg.mlp_create(ctx, dims, Wb, tg.TGEMM_BF16, T)
+        with pytest.raises(tg.TgemmError) as e:
+            tg.mlp_set_master_weights(mlp, [Md[0], Ws[1]])                  # host memory
+        assert e.value.code == tg.TGEMM_EARG
+        tg.mlp_set_master_weights(mlp, Md)
+        tg.mlp_set_master_weights(mlp, None)
+        tg.mlp_destroy(mlp)
+        # out-of-core networks do not take master copies
+        Wp = [w.to(torch.bfloat16).pin_memory() for w in Ws]
+        mlp = tg.mlp_create(ctx, dims, Wp, tg.TGEMM_BF16, T, hbm_budget=1 << 24)
+        with pytest.raises(tg.TgemmError) as e:
+            tg.mlp_set_master_weights(mlp, Md)
+        assert e.value.code == tg.TGEMM_EARG
+        tg.mlp_destroy(mlp)
+    finally:
+        tg.tgemm_destroy(ctx)
