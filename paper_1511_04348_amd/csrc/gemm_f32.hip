@@ -45,7 +45,7 @@ template <> __device__ inline float vget<1>(const float& v, int) { return v; }
 // BK = k extent of one LDS stage (a "chunk").
 // KC = true : source rows are mn, BK contiguous k each.   unit u -> (mn = u / KQ, kq = u % KQ)
 // KC = false: source rows are k, BMN contiguous mn each.  unit u -> (k = u / (BMN/4), q = u % (BMN/4))
-template <int BMN, int NT, bool KC, int BK>
+template <int BMN, int NT, bool KC, int BK, int PADX = PAD>
 struct TileLoader {
     static constexpr int KQ = BK / 4;                  // 16-byte units per k-contiguous row of a stage
     static constexpr int UNITS = BMN * BK / 4;
@@ -116,7 +116,7 @@ struct TileLoader {
     // one of the thread's registers -> LDS stage
     __device__ static inline void store_one(const f32x4& r, float* __restrict__ S, int tid, int p)
     {
-        constexpr int LD = BMN + PAD;
+        constexpr int LD = BMN + PADX;
         const int u = tid + p * NT;
         if (KC) {
             const int mn = u / KQ;
@@ -133,7 +133,7 @@ struct TileLoader {
     // registers -> LDS stage (layout [BK][BMN + PAD])
     __device__ static inline void store(const f32x4 (&reg)[UP], float* __restrict__ S, int tid)
     {
-        constexpr int LD = BMN + PAD;
+        constexpr int LD = BMN + PADX;
 #pragma unroll
         for (int p = 0; p < UP; ++p) {
             const int u = tid + p * NT;
@@ -233,10 +233,15 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
     constexpr int WTM = 32 * RA, WTN = 32 * RB;
     constexpr int BM = WM * WTM, BN = WN * WTN;
     constexpr int NT = WM * WN * 64;
-    constexpr int LDA_S = BM + PAD, LDB_S = BN + PAD;
+    // Row padding of a stage.  A k-contiguous operand is stored transposed, four k rows per register:
+    // with a row pitch = 4 mod 64 banks the 16 k quads of a wave's store fall on 4 bank groups (a
+    // 4-way conflict), with an odd pitch on 16.  Scalar fragments (one 32 x 32 block per wave) need no
+    // alignment, so that shape takes the odd pitch for such operands.
+    constexpr int PAD_A = (A_KC && RA == 1) ? 1 : PAD, PAD_B = (B_KC && RB == 1) ? 1 : PAD;
+    constexpr int LDA_S = BM + PAD_A, LDB_S = BN + PAD_B;
     constexpr int STAGE_A = BK * LDA_S, STAGE_B = BK * LDB_S;
-    typedef TileLoader<BM, NT, A_KC, BK> LA;
-    typedef TileLoader<BN, NT, B_KC, BK> LB;
+    typedef TileLoader<BM, NT, A_KC, BK, PAD_A> LA;
+    typedef TileLoader<BN, NT, B_KC, BK, PAD_B> LB;
     typedef typename Vec<RA>::type VA;
     typedef typename Vec<RB>::type VB;
 
@@ -399,7 +404,7 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
         // Only the last chunk of the whole product can be ragged here (K % BK != 0): it takes the
         // predicated, zero-filling loads, in an iteration of its own after the steady loop.
         const int n_fast = TAIL ? n_chunks - 1 : n_chunks;
-        auto issue_tail = [&]() {
+        auto issue_tail_to = [&](f32x4 (&xa)[LA::UP], f32x4 (&xb)[LB::UP]) {
             const int kk = (p.K / BK) * BK, step = (n_chunks - 1) / cps;
             const float* bsrc = B;
             int bm0 = col0, bm1 = col_end, bk0 = kk, bk1 = p.K;
@@ -408,9 +413,118 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
                 bm0 = bcol; bm1 = col_end - tj * p.T;
                 bk0 = kk - step * p.T; bk1 = p.K - step * p.T;
             }
-            LA::load(ra, A, p.lda, row0, row_end, kk, p.K, p.vec_a, tid);
-            LB::load(rb, bsrc, p.ldb, bm0, bm1, bk0, bk1, p.vec_b, tid);
+            LA::load(xa, A, p.lda, row0, row_end, kk, p.K, p.vec_a, tid);
+            LB::load(xb, bsrc, p.ldb, bm0, bm1, bk0, bk1, p.vec_b, tid);
         };
+        auto issue_tail = [&]() { issue_tail_to(ra, rb); };
+        // ---- small macro tile (one MFMA per k pair, one wave per SIMD): two chunks of loads in flight.
+        // A chunk's 32 MFMAs last 0.85 us; loads issued in one half of a chunk and stored in the other
+        // had a quarter of a microsecond to arrive, less than the memory latency, and with a single
+        // wave per SIMD nothing else fills the wait.  Here chunk c + 2 is requested at the top of the
+        // iteration that multiplies chunk c and goes into the second of two register sets; it is
+        // stored to LDS in the second half of iteration c + 1, one and a half chunk times later.
+        // Chunk i lives in register set i % 2 and in LDS stage i % 2.
+        constexpr bool DEEP = (RA * RB == 1);
+        if constexpr (DEEP) {
+            f32x4 ra2[LA::UP], rb2[LB::UP];
+            enum { FETCH_FAST = 0, FETCH_TAIL = 1, FETCH_NONE = 2 };
+            auto kind_of = [&](int i) { return i >= n_chunks ? FETCH_NONE : (i < n_fast ? FETCH_FAST : FETCH_TAIL); };
+            // (a request behind a branch makes the compiler's wait counts assume the path without it, and
+            // the stores of the older set then wait for the newer loads as well: the steady loop below
+            // requests unconditionally, only the first and last iterations pass `kind` at run time)
+            auto fetch = [&](auto set_tag, int kind) {
+                constexpr int S = decltype(set_tag)::value;
+                if (kind == FETCH_FAST) {
+                    next_b_origin();
+                    if constexpr (S == 0) { LA::load_fast(ra, offa, a_org); LB::load_fast(rb, offb, b_org); }
+                    else { LA::load_fast(ra2, offa, a_org); LB::load_fast(rb2, offb, b_org); }
+                    a_org += a_adv;
+                    b_org += b_adv;
+                    ld_within = (ld_within + 1 == cps) ? 0 : ld_within + 1;
+                    ld_step += (ld_within == 0);
+                } else if (TAIL && kind == FETCH_TAIL) {
+                    if constexpr (S == 0) issue_tail_to(ra, rb);
+                    else issue_tail_to(ra2, rb2);
+                }
+            };
+            // Fragments run FD k pairs ahead of the MFMAs: an LDS read takes longer than the one MFMA
+            // (64 cycles) that a distance of one pair would give it.  Slot j % FD holds pair j; the
+            // number of pairs of a chunk is a multiple of FD, so the slots carry over from chunk to chunk.
+            constexpr int FD = 4, NP = BK / 2;
+            static_assert(NP % FD == 0 && NP > FD, "fragment ring must divide the chunk");
+            float fra[FD], frb[FD];
+            auto ring_read = [&](int st, int pair, int slot) { read_frag(st, pair, fra[slot], frb[slot]); };
+            // multiplies chunk c (parity P), requests chunk c + 2, stores chunk c + 1
+            auto chunk = [&](auto par_tag, auto kind) {     // kind: an int, or an integral_constant
+                constexpr int P = decltype(par_tag)::value;
+                fetch(par_tag, kind);
+                sched_group<0x020, LA::UP + LB::UP>();      // the requests first, not wherever the scheduler has room
+                float* a_next = As + (1 - P) * STAGE_A;
+                float* b_next = Bs + (1 - P) * STAGE_B;
+                constexpr int UPT = LA::UP + LB::UP;
+                for_each_index(std::make_integer_sequence<int, NKP>{}, [&](auto kp_tag) {
+                    constexpr int KP = decltype(kp_tag)::value;
+                    mfma_step(fra[KP % FD], frb[KP % FD]);
+                    if constexpr (KP + FD < NP) ring_read(P, KP + FD, KP % FD);
+#pragma unroll
+                    for (int q = 0; q < UPT; ++q)
+                        if (ChunkPlan::pair_of_piece<NKP, UPT>(q) == KP) {
+                            if constexpr (P == 0) {
+                                if (q < LA::UP) LA::store_one(ra2[q], a_next, tid, q);
+                                else LB::store_one(rb2[q - LA::UP], b_next, tid, q - LA::UP);
+                            } else {
+                                if (q < LA::UP) LA::store_one(ra[q], a_next, tid, q);
+                                else LB::store_one(rb[q - LA::UP], b_next, tid, q - LA::UP);
+                            }
+                        }
+                    sched_group<0x008, 1>();
+                    sched_group<0x100, (KP + FD < NP ? 2 : 0)>();
+                    constexpr int NST = ChunkPlan::stores_of_pair<NKP, LA::UP, LB::UP, LA::STORE_INSTS, LB::STORE_INSTS>(KP);
+                    sched_group<0x200, NST>();
+                });
+                __builtin_amdgcn_sched_barrier(0);
+                __syncthreads();
+                __builtin_amdgcn_sched_barrier(0);
+                // the stage of chunk c + 1 is complete: its first pairs, around the last MFMA of chunk c
+#pragma unroll
+                for (int j = 0; j + 1 < FD; ++j) ring_read(1 - P, j, j);
+                mfma_step(fra[FD - 1], frb[FD - 1]);
+                ring_read(1 - P, FD - 1, FD - 1);
+                __builtin_amdgcn_sched_group_barrier(0x100, 2 * (FD - 1), 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            };
+            if (n_chunks > 0) {
+                fetch(std::integral_constant<int, 0>{}, kind_of(0));
+                LA::store(ra, As, tid);
+                LB::store(rb, Bs, tid);
+                fetch(std::integral_constant<int, 1>{}, kind_of(1));
+            }
+            __syncthreads();
+            if (n_chunks > 0) {
+#pragma unroll
+                for (int j = 0; j < FD; ++j) ring_read(0, j, j);
+            }
+            int c = 0;
+            for (; c + 3 < n_fast; c += 2) {
+                chunk(std::integral_constant<int, 0>{}, std::integral_constant<int, FETCH_FAST>{});
+                chunk(std::integral_constant<int, 1>{}, std::integral_constant<int, FETCH_FAST>{});
+            }
+            for (; c + 1 < n_chunks; ++c) {
+                if (c & 1) chunk(std::integral_constant<int, 1>{}, kind_of(c + 2));
+                else chunk(std::integral_constant<int, 0>{}, kind_of(c + 2));
+            }
+            if (c < n_chunks) {   // the last chunk: nothing left to request or store
+                const int st = c & 1;
+                for_each_index(std::make_integer_sequence<int, NP>{}, [&](auto kp_tag) {
+                    constexpr int KP = decltype(kp_tag)::value;
+                    mfma_step(fra[KP % FD], frb[KP % FD]);
+                    if constexpr (KP + FD < NP) ring_read(st, KP + FD, KP % FD);
+                });
+                __syncthreads();
+            }
+        } else {
         if (n_chunks > 0) {
             if (!TAIL || n_fast > 0) {
                 next_b_origin();
@@ -501,6 +615,7 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
             mfma_step(fa, fb);
             __syncthreads();
         }
+        }   // !DEEP
     } else {
         // ---- ragged k-steps, unaligned operands, tiny edge tiles: predicated, zero-filling loaders.
         // Where only the k-steps are ragged, the chunks that are full (all but the last of a step)
