@@ -151,11 +151,20 @@ def run_mlp(args, tg, inputs, torch, dims, batch, T, bf16, budget):
     if args.bias:
         bias = [torch.zeros(dims[l + 1], device="cuda") for l in range(len(dims) - 1)]
         tg.mlp_set_bias(mlp, bias)
-    if args.momentum is not None and not budget:
-        vel = [torch.zeros(dims[l], dims[l + 1], device="cuda") for l in range(len(dims) - 1)]
+    # velocities and master copies live where the weights live (out-of-core: pinned host memory)
+    if args.momentum is not None:
+        vel = [torch.zeros(dims[l], dims[l + 1], pin_memory=True) if budget else torch.zeros(dims[l], dims[l + 1], device="cuda")
+               for l in range(len(dims) - 1)]
         tg.mlp_set_momentum(mlp, args.momentum, vel)
-    if args.master_weights and bf16 and not budget:
-        master = [w.float() for w in W]
+    if args.master_weights and bf16:
+        master = []
+        for w in W:
+            if budget:
+                mw = torch.empty(w.shape, dtype=torch.float32, pin_memory=True)
+                mw.copy_(w)
+            else:
+                mw = w.float()
+            master.append(mw)
         tg.mlp_set_master_weights(mlp, master)
     for _ in range(args.warmup):
         tg.mlp_step(mlp, X, y, batch, 0.01)
@@ -176,8 +185,8 @@ def run_mlp(args, tg, inputs, torch, dims, batch, T, bf16, budget):
                     "MLP train step %s, layers %s, batch %d, sigmoid hidden, softmax + cross-entropy, SGD lr 0.01, T=%d%s"
                     % ("bf16 storage / fp32 accumulate" if bf16 else "fp32", "->".join(str(d) for d in dims), batch, T,
                        ", weights in pinned host memory, HBM budget %d bytes" % budget if budget else ", in-core"),
-                    {"tile": T, "loss": loss, "rounding": "stochastic" if bf16 and args.stochastic_rounding else "nearest", "bias": bool(args.bias), "momentum": args.momentum if not budget else None,
-                     "master_weights": bool(args.master_weights and bf16 and not budget)})
+                    {"tile": T, "loss": loss, "rounding": "stochastic" if bf16 and args.stochastic_rounding else "nearest", "bias": bool(args.bias), "momentum": args.momentum,
+                     "master_weights": bool(args.master_weights and bf16)})
     out["roofline"] = {"bound": "mfma", "achieved": tfl, "peak": peak, "unit": "TFLOP/s", "frac": tfl / peak,
                        "traffic": None, "kernel": "tile_gemm_%s (whole step)" % ("bf16" if bf16 else "f32"),
                        "flops_per_step": flops}
@@ -206,9 +215,9 @@ def main():
     ap.add_argument("--stochastic-rounding", action="store_true",
                     help="c5: round the updated bf16 weights stochastically (mlp_set_rounding) instead of to nearest")
     ap.add_argument("--bias", action="store_true", help="c4 / c5: train bias rows too (mlp_set_bias)")
-    ap.add_argument("--momentum", type=float, default=None, help="c4: SGD with this momentum coefficient (mlp_set_momentum)")
+    ap.add_argument("--momentum", type=float, default=None, help="c4 / c5: SGD with this momentum coefficient (mlp_set_momentum)")
     ap.add_argument("--master-weights", action="store_true",
-                    help="c4 --bf16: keep fp32 master copies of the bf16 weights (mlp_set_master_weights)")
+                    help="c4 --bf16 / c5: keep fp32 master copies of the bf16 weights (mlp_set_master_weights)")
     ap.add_argument("--bf16", action="store_true", help="c4: bf16 storage with fp32 accumulation instead of fp32 (extra data point)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",

@@ -240,13 +240,20 @@ int mlp_set_bias(tgemm_mlp* mlp, void* const* b, void* const* db);
  * the dW product's epilogue (the gradient is never stored).  With mu = 0 the weights move exactly as
  * without momentum (and V_l receives dW_l).
  *   mu  in [0, 1).
- *   V   array of n_layers device pointers, V[l-1] -> dims[l-1] x dims[l] floats, row-major (fp32 also
+ *   V   array of n_layers pointers, V[l-1] -> dims[l-1] x dims[l] floats, row-major (fp32 also
  *       for bf16 networks), caller-owned and caller-initialised (zeros for a fresh run); NULL
- *       switches momentum off (the default).
+ *       switches momentum off (the default).  The velocities live where the weights live: device
+ *       memory for device-resident weights, pinned host memory for out-of-core weights.  Out-of-core,
+ *       the T rows of V_l that one launch of the dW product updates are fetched into one of two
+ *       device buffers (T x max_l dims[l] floats each, counted against hbm_budget), updated there and
+ *       written back, 8 bytes per weight and step over the host link; like the weights they are
+ *       complete in host memory when the call returns (with opts.deferred_writeback: after
+ *       tgemm_sync), and while momentum is set only the library may write to them.
  *   Vb  NULL, or array of n_layers device pointers to dims[l] floats: velocities of the bias rows
  *       (used when bias rows are set; without Vb the bias rows take plain SGD steps).
- * Device-resident weights only: TGEMM_EARG for an out-of-core network, for mu outside [0, 1), for a
- * pointer that is not device memory, or for Vb without V.  Waits for outstanding work. */
+ * TGEMM_EARG for mu outside [0, 1), for a V[l] of the wrong kind of memory, for a Vb[l] that is not
+ * device memory, or for Vb without V.  Waits for outstanding work; on an out-of-core network a change
+ * between with and without momentum releases the workspaces (the next pass sizes them again). */
 int mlp_set_momentum(tgemm_mlp* mlp, float mu, void* const* V, void* const* Vb);
 
 /* Rounding of the updated weights in mlp_step for bf16 networks (section 2's update, W_l - lr dW_l,
@@ -274,12 +281,15 @@ int mlp_set_rounding(tgemm_mlp* mlp, int32_t mode, uint64_t seed);
  * the copy inside the dW product's epilogue:
  *   M_l <- M_l - lr dW_l   (with momentum: M_l <- M_l - lr V_l);   W_l <- bf16(M_l)
  * where bf16() rounds as mlp_set_rounding says (to nearest even by default).
- *   Wm  array of n_layers device pointers, Wm[l-1] -> dims[l-1] x dims[l] floats, row-major,
+ *   Wm  array of n_layers pointers, Wm[l-1] -> dims[l-1] x dims[l] floats, row-major,
  *       caller-owned and caller-initialised (normally float(W_l)); the library never reads W_l to
  *       form the step, so a copy that disagrees with W_l wins at the first step.  NULL removes the
- *       master copies (the default).
- * bf16 networks with device-resident weights only: TGEMM_EARG for an fp32 or an out-of-core network
- * or a pointer that is not device memory.  Waits for outstanding work. */
+ *       master copies (the default).  Device memory for device-resident weights, pinned host memory
+ *       for out-of-core weights (then streamed through two device row buffers like the velocities
+ *       of mlp_set_momentum, with the same cost and the same rules).
+ * bf16 networks only: TGEMM_EARG for an fp32 network or a pointer of the wrong kind of memory.
+ * Waits for outstanding work; on an out-of-core network a change between with and without master
+ * copies releases the workspaces. */
 int mlp_set_master_weights(tgemm_mlp* mlp, void* const* Wm);
 
 /* Equation 1 for every layer: Z_l = A_{l-1} W_l, A_l = sigmoid(Z_l); last layer: logits.

@@ -450,11 +450,11 @@ hipError_t launch_tile_gemm_bf16(const GemmDesc& d, hipStream_t stream)
     p.alpha = d.alpha; p.beta = d.beta; p.act = d.act;
     p.sr = (d.sr && d.out_bf16 && (d.epilogue == EPI_AXPBY || d.epilogue == EPI_MOMENTUM)) ? 1 : 0;
     p.state = d.state; p.ldstate = d.ldstate; p.mu = d.mu;
-    if (d.epilogue == EPI_MOMENTUM && (!d.state || d.c_tiles || d.a_kcontig || d.b_kcontig)) return hipErrorInvalidValue;
+    if (d.epilogue == EPI_MOMENTUM && (!d.state || d.a_kcontig || d.b_kcontig)) return hipErrorInvalidValue;
     p.sr_key = d.sr_key; p.sr_row0 = (uint32_t)d.sr_row0;
-    // an fp32 master copy goes with the updates of a dense bf16 C only
+    // an fp32 master copy goes with the updates of a bf16 C only (C dense or in tiles; the copy is dense)
     p.master = d.master; p.ldmaster = d.ldmaster;
-    if (d.master && (!d.out_bf16 || d.c_tiles || !(d.epilogue == EPI_MOMENTUM || (d.epilogue == EPI_AXPBY && d.beta != 0.f))))
+    if (d.master && (!d.out_bf16 || !(d.epilogue == EPI_MOMENTUM || (d.epilogue == EPI_AXPBY && d.beta != 0.f))))
         return hipErrorInvalidValue;
     p.bias = d.bias;
     p.vec_bias = d.bias && ((reinterpret_cast<uintptr_t>(d.bias) & 15) == 0) && (T % 4 == 0);

@@ -850,7 +850,7 @@ hipError_t launch_tile_gemm_f32(const GemmDesc& d, hipStream_t stream)
     p.state = d.state; p.ldstate = d.ldstate; p.mu = d.mu;
     p.master = nullptr; p.ldmaster = 0;
     if (d.master) return hipErrorInvalidValue;   // fp32 C is its own master copy
-    if (d.epilogue == EPI_MOMENTUM && (!d.state || d.c_tiles)) return hipErrorInvalidValue;
+    if (d.epilogue == EPI_MOMENTUM && !d.state) return hipErrorInvalidValue;
     p.b_tiles = d.b_tiles; p.c_tiles = d.c_tiles;
     const bool t4 = (T % 4 == 0);
     auto al16 = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15) == 0; };

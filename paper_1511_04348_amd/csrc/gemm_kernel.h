@@ -14,7 +14,7 @@ enum { ACT_SIGMOID = 0, ACT_TANH = 1, ACT_RELU = 2 };   // same values as TGEMM_
 //   EPI_DACT     C = (A B) * act'(z) with act' written in terms of the stored activation aux = act(z)
 //                (aux: M x N, leading dimension ldaux): aux (1 - aux), 1 - aux^2, or [aux > 0]
 //   EPI_MOMENTUM S = mu * S + (A B);  C = C + alpha * S   (S: M x N floats, leading dimension ldstate;
-//                the update with a velocity matrix).  Dense C only; offered for the layout of the
+//                the update with a velocity matrix; S is dense also when C is a tile table).  Offered for the layout of the
 //                dW product (both operands m/n-contiguous).
 // a_kcontig: A stored M x K row-major (k contiguous); otherwise stored K x M (m contiguous).
 // b_kcontig: B stored N x K row-major (k contiguous); otherwise stored K x N (n contiguous).
@@ -47,7 +47,7 @@ struct GemmDesc {
     float mu;
     // bf16 kernel, EPI_AXPBY (beta != 0) or EPI_MOMENTUM with out_bf16: an fp32 copy of C (M x N,
     // leading dimension ldmaster).  The old value of C is taken from it instead of from the bf16 C,
-    // the fp32 result is stored back into it, and C receives that result rounded to bf16.  Dense C only.
+    // the fp32 result is stored back into it, and C receives that result rounded to bf16.  The copy is dense also when C is a tile table.
     float* master;
     int64_t ldmaster;
     // Optional tile tables (device arrays of device pointers) for operands that live as separate

@@ -177,6 +177,28 @@ struct TableRing {
     int cap = 0;   // pointers per entry
 };
 
+// Out-of-core velocity / master-copy matrices (pinned host, fp32): the T rows that one launch of the
+// dW product updates pass through one of two device buffers -- fetched whole (the rows are contiguous
+// in the host matrix), updated in place by the epilogue, written back whole.
+struct RowStream {
+    float* buf[2] = {};
+    hipEvent_t ready[2] = {}, freed[2] = {};
+    bool in_use[2] = {};          // `freed` has been recorded for the buffer's last use
+    hipEvent_t last_freed = nullptr;   // the newest write-back (all earlier ones precede it on the flush stream)
+    size_t bytes = 0;             // capacity of one buffer
+    int next = 0;
+    void release()
+    {
+        for (int i = 0; i < 2; ++i) {
+            if (buf[i]) (void)hipFree(buf[i]);
+            if (ready[i]) (void)hipEventDestroy(ready[i]);
+            if (freed[i]) (void)hipEventDestroy(freed[i]);
+            buf[i] = nullptr; ready[i] = freed[i] = nullptr; in_use[i] = false;
+        }
+        last_freed = nullptr; bytes = 0; next = 0;
+    }
+};
+
 inline int64_t wkey(int layer, int64_t r, int64_t c) { return ((int64_t)layer << 56) | (r << 28) | c; }
 
 }  // namespace
@@ -189,9 +211,9 @@ struct tgemm_mlp {
     std::vector<char*> W;         // caller-owned weights (device or pinned host)
     std::vector<float*> bias;     // caller-owned bias rows b_l (device, float), empty: no bias terms
     std::vector<float*> dbias;    // caller-owned destinations of mlp_backward's bias gradients, may hold NULLs
-    std::vector<float*> vel;      // caller-owned velocity matrices V_l (device, float), empty: plain SGD
+    std::vector<float*> vel;      // caller-owned velocity matrices V_l (float; device, or pinned host for out-of-core weights), empty: plain SGD
     std::vector<float*> vel_bias; // velocity rows of the bias terms (may be empty)
-    std::vector<float*> master;   // caller-owned fp32 copies of bf16 weights (device), empty: none
+    std::vector<float*> master;   // caller-owned fp32 copies of bf16 weights (device, or pinned host for out-of-core weights), empty: none
     float mu = 0.f;               // momentum coefficient
     float* colsum_part = nullptr; // partial column sums of an error matrix: COLSUM_CHUNKS x max n_l floats
     int32_t dtype = TGEMM_F32;
@@ -213,6 +235,7 @@ struct tgemm_mlp {
     bool have_delta = false;
     tg::WeightCache cache;
     tg::TableRing ring;
+    tg::RowStream vel_rows, master_rows;   // out-of-core networks with velocities / master copies
 };
 
 namespace tg {
@@ -384,6 +407,8 @@ void free_workspaces(tgemm_mlp* m)
     m->logits = nullptr; m->row_loss = nullptr; m->colsum_part = nullptr;
     m->cap_batch = 0; m->batch = 0; m->have_delta = false;
     m->cache.release();
+    m->vel_rows.release();
+    m->master_rows.release();
     TableRing& r = m->ring;
     for (int i = 0; i < TableRing::N; ++i) {
         if (r.dev[i]) (void)hipFree(r.dev[i]);
@@ -415,6 +440,14 @@ int ensure_workspaces(tgemm_mlp* m, int64_t batch)
         colsum_bytes = (size_t)cdiv(batch, COLSUM_ROWS) * widest * 4;
         total += colsum_bytes;
     }
+    // out-of-core velocities / master copies: two buffers of T rows of the widest weight matrix each
+    size_t row_bytes = 0;
+    if (m->ooc && (!m->vel.empty() || !m->master.empty())) {
+        int64_t widest = 0;
+        for (int l = 1; l <= L; ++l) widest = std::max(widest, m->dims[l]);
+        row_bytes = (size_t)m->T * widest * 4;
+        total += 2 * row_bytes * ((m->vel.empty() ? 0 : 1) + (m->master.empty() ? 0 : 1));
+    }
     // out-of-core: the rest of the budget is the weight tile cache
     int64_t max_tiles = 0, n_slots = 0;
     const size_t slot_bytes = (size_t)m->T * m->T * m->es;
@@ -443,6 +476,15 @@ int ensure_workspaces(tgemm_mlp* m, int64_t batch)
         if (l < L) ok = ok && alloc((void**)&m->act[l], (size_t)batch * m->dims[l] * m->es);
         ok = ok && alloc((void**)&m->delta[l], (size_t)batch * m->dims[l] * m->es);
     }
+    auto alloc_rows = [&](RowStream& rs) {
+        rs.bytes = row_bytes;
+        for (int i = 0; i < 2 && ok; ++i)
+            ok = alloc((void**)&rs.buf[i], row_bytes) &&
+                 hipEventCreateWithFlags(&rs.ready[i], hipEventDisableTiming) == hipSuccess &&
+                 hipEventCreateWithFlags(&rs.freed[i], hipEventDisableTiming) == hipSuccess;
+    };
+    if (ok && row_bytes && !m->vel.empty()) alloc_rows(m->vel_rows);
+    if (ok && row_bytes && !m->master.empty()) alloc_rows(m->master_rows);
     if (ok && m->ooc) {
         WeightCache& c = m->cache;
         c.slot_bytes = slot_bytes;
@@ -715,6 +757,34 @@ int read_loss(tgemm_mlp* m, float* loss)
     return TGEMM_OK;
 }
 
+// T rows of an out-of-core fp32 matrix into the next device buffer (fetch stream); the compute stream
+// waits for them.  The buffer's previous contents have been written back.
+int rows_fetch(tgemm_mlp* m, RowStream& rs, const float* host_rows, size_t bytes, hipStream_t comp, int* which)
+{
+    hipStream_t fetch = m->ctx->streams[0];
+    const int b = rs.next;
+    rs.next ^= 1;
+    if (rs.in_use[b]) TG_HIP(hipStreamWaitEvent(fetch, rs.freed[b], 0));
+    TG_HIP(hipMemcpyAsync(rs.buf[b], host_rows, bytes, hipMemcpyHostToDevice, fetch));
+    TG_HIP(hipEventRecord(rs.ready[b], fetch));
+    TG_HIP(hipStreamWaitEvent(comp, rs.ready[b], 0));
+    m->ctx->stats.h2d_bytes += (int64_t)bytes;
+    *which = b;
+    return TGEMM_OK;
+}
+// ... and back to the host matrix (flush stream, which already waits for the launch that updated them)
+int rows_writeback(tgemm_mlp* m, RowStream& rs, int b, float* host_rows, size_t bytes)
+{
+    hipStream_t flush = m->ctx->streams[3];
+    TG_HIP(hipMemcpyAsync(host_rows, rs.buf[b], bytes, hipMemcpyDeviceToHost, flush));
+    TG_HIP(hipEventRecord(rs.freed[b], flush));
+    rs.in_use[b] = true;
+    rs.last_freed = rs.freed[b];
+    m->ctx->stats.d2h_bytes += (int64_t)bytes;
+    return TGEMM_OK;
+}
+
+
 // equations 4 and 3 for layer l.  update: W_l <- W_l - lr dW_l in place of storing dW_l; dW_out:
 // optional dense float destination for the plain gradient.
 int backward_layer(tgemm_mlp* m, int l, float* dW_out, bool update, float lr)
@@ -833,10 +903,24 @@ int backward_layer(tgemm_mlp* m, int l, float* dW_out, bool update, float lr)
             dw.alpha = -lr; dw.beta = 1.f; dw.out_bf16 = bf ? 1 : 0;
             dw.sr = (bf && m->round_mode == TGEMM_ROUND_STOCHASTIC) ? 1 : 0;
             dw.sr_key = sr_step_key(m->sr_seed, (uint32_t)l, m->sr_step); dw.sr_row0 = r * T;
+            // velocities / master copies of these rows: host -> device buffer -> epilogue -> host
+            const size_t band_bytes = (size_t)rows * m->dims[l] * 4, band_at = (size_t)(r * T) * m->dims[l];
+            int vb = -1, mb = -1;
+            if (!m->vel.empty()) {
+                if ((rc = rows_fetch(m, m->vel_rows, m->vel[(size_t)l - 1] + band_at, band_bytes, comp, &vb)) != TGEMM_OK) return rc;
+                dw.epilogue = EPI_MOMENTUM;
+                dw.state = m->vel_rows.buf[vb]; dw.ldstate = m->dims[l]; dw.mu = m->mu;
+            }
+            if (!m->master.empty()) {
+                if ((rc = rows_fetch(m, m->master_rows, m->master[(size_t)l - 1] + band_at, band_bytes, comp, &mb)) != TGEMM_OK) return rc;
+                dw.master = m->master_rows.buf[mb]; dw.ldmaster = m->dims[l];
+            }
             if ((rc = launch(m, dw, comp)) != TGEMM_OK) return rc;
             if ((rc = ring_finish(m, entry, tiles.data(), (int)n_c)) != TGEMM_OK) return rc;
             // write the updated row of tiles back (stream 3) once the launch has finished
             TG_HIP(hipStreamWaitEvent(flush, m->ring.done[entry], 0));
+            if (vb >= 0 && (rc = rows_writeback(m, m->vel_rows, vb, m->vel[(size_t)l - 1] + band_at, band_bytes)) != TGEMM_OK) return rc;
+            if (mb >= 0 && (rc = rows_writeback(m, m->master_rows, mb, m->master[(size_t)l - 1] + band_at, band_bytes)) != TGEMM_OK) return rc;
             hipEvent_t group;
             if ((rc = m->cache.next_flush_event(&group)) != TGEMM_OK) return rc;
             const int64_t flush_seq = ++m->cache.flush_issue;
@@ -866,6 +950,10 @@ int backward_layer(tgemm_mlp* m, int l, float* dW_out, bool update, float lr)
 
 int backward(tgemm_mlp* m, void* const* dW, bool update, float lr)
 {
+    // rows written back by an earlier step (deferred write-back) are on the host before this step
+    // fetches any of them again
+    for (RowStream* rs : {&m->vel_rows, &m->master_rows})
+        if (update && rs->last_freed) TG_HIP(hipStreamWaitEvent(m->ctx->streams[0], rs->last_freed, 0));
     for (int l = m->n_layers; l >= 1; --l) {
         const int rc = backward_layer(m, l, dW ? (float*)dW[l - 1] : nullptr, update, lr);
         if (rc != TGEMM_OK) return rc;
@@ -987,14 +1075,13 @@ int mlp_set_momentum(tgemm_mlp* m, float mu, void* const* V, void* const* Vb)
     if (!V) {
         if (Vb) return fail(TGEMM_EARG, "mlp_set_momentum: bias velocities without weight velocities");
     } else {
-        if (m->ooc) return fail(TGEMM_EARG, "mlp_set_momentum: needs device-resident weights (this network is out-of-core)");
         if (!(mu >= 0.f && mu < 1.f)) return fail(TGEMM_EARG, "mlp_set_momentum: mu = %g is outside [0, 1)", (double)mu);
         for (int l = 0; l < m->n_layers; ++l) {
             hipPointerAttribute_t at;
-            if (!V[l] || hipPointerGetAttributes(&at, V[l]) != hipSuccess || at.type != hipMemoryTypeDevice) {
-                (void)hipGetLastError();
-                return fail(TGEMM_EARG, "mlp_set_momentum: V[%d] is not device memory", l);
-            }
+            // the velocities live where the weights live
+            if (!V[l] || classify_pointer(V[l], m->ctx->device) != (m->ooc ? PTR_PINNED : PTR_DEVICE))
+                return fail(TGEMM_EARG, "mlp_set_momentum: V[%d] is not %s", l,
+                            m->ooc ? "page-locked host memory (the weights are out-of-core)" : "device memory");
             if (Vb && (!Vb[l] || hipPointerGetAttributes(&at, Vb[l]) != hipSuccess || at.type != hipMemoryTypeDevice)) {
                 (void)hipGetLastError();
                 return fail(TGEMM_EARG, "mlp_set_momentum: Vb[%d] is not device memory", l);
@@ -1003,6 +1090,7 @@ int mlp_set_momentum(tgemm_mlp* m, float mu, void* const* V, void* const* Vb)
     }
     int rc = sync_all(m);
     if (rc != TGEMM_OK) return rc;
+    if (m->ooc && (V != nullptr) != !m->vel.empty()) free_workspaces(m);   // the row buffers come or go
     m->vel.clear();
     m->vel_bias.clear();
     m->mu = 0.f;
@@ -1020,18 +1108,14 @@ int mlp_set_master_weights(tgemm_mlp* m, void* const* Wm)
     TG_HIP(hipSetDevice(m->ctx->device));
     if (Wm) {
         if (m->dtype != TGEMM_BF16) return fail(TGEMM_EARG, "mlp_set_master_weights: fp32 weights need no master copy");
-        if (m->ooc)
-            return fail(TGEMM_EARG, "mlp_set_master_weights: needs device-resident weights (this network is out-of-core)");
-        for (int l = 0; l < m->n_layers; ++l) {
-            hipPointerAttribute_t at;
-            if (!Wm[l] || hipPointerGetAttributes(&at, Wm[l]) != hipSuccess || at.type != hipMemoryTypeDevice) {
-                (void)hipGetLastError();
-                return fail(TGEMM_EARG, "mlp_set_master_weights: Wm[%d] is not device memory", l);
-            }
-        }
+        for (int l = 0; l < m->n_layers; ++l)
+            if (!Wm[l] || classify_pointer(Wm[l], m->ctx->device) != (m->ooc ? PTR_PINNED : PTR_DEVICE))
+                return fail(TGEMM_EARG, "mlp_set_master_weights: Wm[%d] is not %s", l,
+                            m->ooc ? "page-locked host memory (the weights are out-of-core)" : "device memory");
     }
     int rc = sync_all(m);
     if (rc != TGEMM_OK) return rc;
+    if (m->ooc && (Wm != nullptr) != !m->master.empty()) free_workspaces(m);   // the row buffers come or go
     m->master.clear();
     if (Wm) for (int l = 0; l < m->n_layers; ++l) m->master.push_back((float*)Wm[l]);
     return TGEMM_OK;

@@ -165,12 +165,50 @@ def test_master_copy_errors():
         tg.mlp_set_master_weights(mlp, Md)
         tg.mlp_set_master_weights(mlp, None)
         tg.mlp_destroy(mlp)
-        # out-of-core networks do not take master copies
+        # the master copies of an out-of-core network live in pinned host memory, not on the device
         Wp = [w.to(torch.bfloat16).pin_memory() for w in Ws]
         mlp = tg.mlp_create(ctx, dims, Wp, tg.TGEMM_BF16, T, hbm_budget=1 << 24)
         with pytest.raises(tg.TgemmError) as e:
             tg.mlp_set_master_weights(mlp, Md)
         assert e.value.code == tg.TGEMM_EARG
+        tg.mlp_set_master_weights(mlp, [w.clone().pin_memory() for w in Ws])
         tg.mlp_destroy(mlp)
     finally:
         tg.tgemm_destroy(ctx)
+
+
+@pytest.mark.parametrize("momentum,stochastic", [(False, False), (True, False), (True, True)])
+@pytest.mark.parametrize("dims,batch,T,budget", [([256, 384, 320, 200], 192, 128, 3 << 20), ([70, 90, 33], 50, 32, 1 << 18)])
+def test_out_of_core_master_copies_equal_in_core_bit_for_bit(dims, batch, T, budget, momentum, stochastic):
+    """bf16 weights, fp32 master copies (and velocities) in pinned host memory against the same four
+    steps on the device: weights, master copies, velocities and losses agree bit for bit."""
+    L = len(dims) - 1
+    X, Ws, y = _net(dims, batch)
+    out = []
+    for ooc in (False, True):
+        announce("mlp master copies", "out-of-core" if ooc else "in-core", dims, batch, T, "momentum" if momentum else "", "stochastic" if stochastic else "")
+        ctx = tg.tgemm_create(0, deferred_writeback=1)
+        try:
+            place = (lambda t: t.clone().pin_memory()) if ooc else (lambda t: t.cuda())
+            Wd = [place(w) for w in Ws]
+            Md = [place(w.float()) for w in Ws]
+            Vd = [place(inputs.normal_matrix(30 + l, dims[l], dims[l + 1], std=0.01)) for l in range(L)]
+            Xd, yd = X.cuda(), y.cuda()
+            torch.cuda.synchronize()
+            mlp = tg.mlp_create(ctx, dims, Wd, tg.TGEMM_BF16, T, hbm_budget=budget if ooc else 0)
+            tg.mlp_set_master_weights(mlp, Md)
+            if momentum:
+                tg.mlp_set_momentum(mlp, 0.9, Vd)
+            if stochastic:
+                tg.mlp_set_rounding(mlp, tg.TGEMM_ROUND_STOCHASTIC, 77)
+            losses = [tg.mlp_step(mlp, Xd, yd, batch, 2.0) for _ in range(4)]
+            tg.tgemm_sync(ctx)
+            out.append((losses, [w.cpu().clone() for w in Wd], [x.cpu().clone() for x in Md], [v.cpu().clone() for v in Vd]))
+            tg.mlp_destroy(mlp)
+        finally:
+            tg.tgemm_destroy(ctx)
+    assert out[0][0] == out[1][0]
+    for k in (1, 2, 3):
+        for a, b in zip(out[0][k], out[1][k]):
+            assert torch.equal(a, b), k
+    assert not torch.equal(out[1][2][0], Ws[0].float())

@@ -126,12 +126,59 @@ def test_momentum_errors():
         tg.mlp_set_momentum(mlp, 0.5, Vd)
         tg.mlp_set_momentum(mlp, 0.0, None)
         tg.mlp_destroy(mlp)
-        # out-of-core networks do not take momentum
+        # the velocities of an out-of-core network live in pinned host memory, not on the device
         Wp = [w.clone().pin_memory() for w in Ws]
         mlp = tg.mlp_create(ctx, dims, Wp, tg.TGEMM_F32, T, hbm_budget=1 << 24)
         with pytest.raises(tg.TgemmError) as e:
             tg.mlp_set_momentum(mlp, 0.5, Vd)
         assert e.value.code == tg.TGEMM_EARG
+        with pytest.raises(tg.TgemmError) as e:
+            tg.mlp_set_momentum(mlp, 0.5, [torch.zeros_like(w) for w in Ws])    # pageable
+        assert e.value.code == tg.TGEMM_EARG
+        tg.mlp_set_momentum(mlp, 0.5, [torch.zeros_like(w).pin_memory() for w in Ws])
         tg.mlp_destroy(mlp)
     finally:
         tg.tgemm_destroy(ctx)
+
+
+@pytest.mark.parametrize("bias", [False, True])
+@pytest.mark.parametrize("dtype,tdt,lr", [(tg.TGEMM_F32, torch.float32, 0.05), (tg.TGEMM_BF16, torch.bfloat16, 4.0)])
+@pytest.mark.parametrize("dims,batch,T,budget", [([256, 384, 320, 200], 192, 128, 3 << 20), ([70, 90, 33], 50, 32, 1 << 18)])
+def test_out_of_core_momentum_equals_in_core_bit_for_bit(dims, batch, T, budget, dtype, tdt, lr, bias):
+    """Weights and velocities in pinned host memory, streamed through the tile cache and the row
+    buffers, against the same four steps with everything on the device: the same kernels in the same
+    order, so weights, velocities, bias rows and losses must agree bit for bit (deferred write-back on,
+    so that a step's write-backs run into the next step)."""
+    L, mu = len(dims) - 1, 0.9
+    X, Ws, bs, y = _net(dims, batch, tdt)
+    out = []
+    for ooc in (False, True):
+        announce("mlp momentum", "out-of-core" if ooc else "in-core", dims, batch, T, "bf16" if dtype else "f32", "bias" if bias else "")
+        ctx = tg.tgemm_create(0, deferred_writeback=1)
+        try:
+            place = (lambda t: t.clone().pin_memory()) if ooc else (lambda t: t.cuda())
+            Wd = [place(w) for w in Ws]
+            Vd = [place(inputs.normal_matrix(30 + l, dims[l], dims[l + 1], std=0.01)) for l in range(L)]
+            bd = [b.cuda() for b in bs]
+            Vbd = [torch.zeros_like(b) for b in bd]
+            Xd, yd = X.cuda(), y.cuda()
+            torch.cuda.synchronize()
+            mlp = tg.mlp_create(ctx, dims, Wd, dtype, T, hbm_budget=budget if ooc else 0)
+            if bias:
+                tg.mlp_set_bias(mlp, bd)
+            tg.mlp_set_momentum(mlp, mu, Vd, Vbd if bias else None)
+            losses = [tg.mlp_step(mlp, Xd, yd, batch, lr) for _ in range(4)]
+            tg.tgemm_sync(ctx)
+            if ooc:
+                st = tg.tgemm_last_stats(ctx)
+                assert st["d2h_bytes"] > 0 and st["h2d_bytes"] > 0
+            out.append((losses, [w.cpu().clone() for w in Wd], [v.cpu().clone() for v in Vd], [b.cpu() for b in bd]))
+            tg.mlp_destroy(mlp)
+        finally:
+            tg.tgemm_destroy(ctx)
+    assert out[0][0] == out[1][0]
+    for k in (1, 2, 3):
+        for a, b in zip(out[0][k], out[1][k]):
+            assert torch.equal(a, b), k
+    # and the velocities did move
+    assert not torch.equal(out[1][2][0], inputs.normal_matrix(30, dims[0], dims[1], std=0.01))
