@@ -819,14 +819,18 @@ int pick_config(const GemmDesc& d)
         return ((n_i - 1) * ((fm + bm - 1) / bm) + (lm + bm - 1) / bm) *
                ((n_j - 1) * ((fn + bn - 1) / bn) + (ln + bn - 1) / bn);
     };
-    // cost model: rounds of 256 CUs (one large or two medium/small workgroups per CU) times the
-    // relative time of one round
-    auto cost = [&](int64_t n_tiles, int64_t per_round, double round_time) {
-        return (double)((n_tiles + per_round - 1) / per_round) * round_time;
-    };
-    const double c3 = cost(tiles(256, 256), 256, 1.0);
-    const double c2 = cost(tiles(128, 128), 512, 0.53);    // measured at 4096^3: 128 / 137 TFLOP/s of the large shape
-    const double c1 = cost(tiles(64, 64), 512, 0.16);      // 106 / 137
+    // Cost model, fitted to square NN products of 1536 .. 8192 with T = 512 (times in us per unit of K
+    // for the busiest CU; tiles per CU = ceil(tiles / 256)):
+    //   256 x 256: one workgroup per CU, 0.230 per tile;
+    //   128 x 128: two workgroups share a CU, 0.061 per tile (0.081 for a single tile, 0.067 each for two);
+    //   64 x 64:   two per CU, 0.0155 per tile plus 1.2 tiles' worth of ramp and tail.
+    // It reproduces the measured order at every size of that sweep (64 x 64 wins up to 3584 and at
+    // 4608 / 5120, 256 x 256 at 4096 and from 7168, 128 x 128 at 6144).
+    auto per_cu = [&](int64_t n_tiles) { return (double)((n_tiles + 255) / 256); };
+    const double t3 = per_cu(tiles(256, 256)), t2 = per_cu(tiles(128, 128)), t1 = per_cu(tiles(64, 64));
+    const double c3 = 0.230 * t3;
+    const double c2 = t2 <= 1.0 ? 0.081 : t2 <= 2.0 ? 0.134 : 0.061 * t2;
+    const double c1 = 0.0155 * (t1 + 1.2);
     if (c3 <= c2 && c3 <= c1) return 3;
     return c2 <= c1 ? 2 : 1;
 }
