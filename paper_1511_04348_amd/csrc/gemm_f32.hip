@@ -31,7 +31,8 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int PAD = 4;       // floats of row padding in LDS
-constexpr int SMALL_BK = 64; // k extent of an LDS stage of the small macro tile (the others use 16)
+constexpr int SMALL_BK = 32; // k extent of an LDS stage of the small macro tile (the same as the others: four
+                             // of its workgroups fit a CU; with 64-k stages, two, and it was slower up to 2048^3)
 
 template <int R> struct Vec;
 template <> struct Vec<1> { typedef float type; };
@@ -870,9 +871,9 @@ hipError_t launch_tile_gemm_f32(const GemmDesc& d, hipStream_t stream)
     switch (pick_config(dd)) {
         case 3: return launch_cfg<2, 4, 4, 2, 32>(p, dd, stream);   // 256 x 256, 512 threads
         case 2: return launch_cfg<2, 2, 2, 2, 32>(p, dd, stream);   // 128 x 128, 256 threads
-        // 64 x 64, 256 threads, 64-k chunks: the shape for products too small to fill the chip with
-        // larger tiles; there the k loop is bound by the latency of a chunk's round trip
-        // (global -> registers -> LDS -> barrier), so it takes few, long chunks
+        // 64 x 64, 256 threads: the shape for products too small to fill the chip with larger tiles, or
+        // whose large tiles would leave a last round mostly empty; its k loop keeps two chunks of loads
+        // in flight (see the kernel)
         default: return launch_cfg<1, 1, 2, 2, SMALL_BK>(p, dd, stream);
     }
 }
