@@ -182,3 +182,30 @@ def test_out_of_core_momentum_equals_in_core_bit_for_bit(dims, batch, T, budget,
             assert torch.equal(a, b), k
     # and the velocities did move
     assert not torch.equal(out[1][2][0], inputs.normal_matrix(30, dims[0], dims[1], std=0.01))
+
+
+def test_row_buffers_count_against_the_budget():
+    """The two device row buffers of out-of-core velocities are part of hbm_budget: a budget that holds
+    the plain step but not the buffers is refused (before any work) once momentum is set, and accepted
+    again once it is removed."""
+    dims, T, batch = [64, 48, 32], 32, 16
+    Ws = [inputs.normal_matrix(10 + l, dims[l], dims[l + 1], std=0.1).pin_memory() for l in range(2)]
+    V = [torch.zeros(dims[l], dims[l + 1]).pin_memory() for l in range(2)]
+    X = inputs.normal_matrix(1, batch, dims[0]).cuda()
+    y = inputs.labels(5, batch, dims[-1]).cuda()
+    ctx = tg.tgemm_create(0)
+    try:
+        announce("mlp momentum out-of-core, budget without room for the row buffers")
+        mlp = tg.mlp_create(ctx, dims, Ws, tg.TGEMM_F32, T, hbm_budget=40 * 1024)
+        tg.mlp_step(mlp, X, y, batch, 0.1)
+        tg.mlp_set_momentum(mlp, 0.5, V)
+        before = [w.clone() for w in Ws]
+        with pytest.raises(tg.TgemmError) as e:
+            tg.mlp_step(mlp, X, y, batch, 0.1)
+        assert e.value.code == tg.TGEMM_EBUDGET
+        assert all(torch.equal(a, b) for a, b in zip(before, Ws)) and all(float(v.abs().max()) == 0.0 for v in V)
+        tg.mlp_set_momentum(mlp, 0.0, None)
+        tg.mlp_step(mlp, X, y, batch, 0.1)
+        tg.mlp_destroy(mlp)
+    finally:
+        tg.tgemm_destroy(ctx)
