@@ -1,6 +1,7 @@
 """End to end: the example trainer (bias rows, momentum, tanh, mini-batches through mlp_step) must
 actually learn -- the loss falls from about ln 16 to a small value and held-out accuracy is high -- in
-fp32, with bf16 weights rounded stochastically, and with bf16 weights that follow fp32 master copies."""
+fp32, with bf16 weights rounded stochastically, and with bf16 weights that follow fp32 master copies;
+the out-of-core GEMM example must be right under every task order and show the cache's effect."""
 import math
 import os
 import sys
@@ -22,3 +23,16 @@ def test_example_trainer_learns(bf16, master):
     assert all(b <= a + 1e-3 for a, b in zip(losses, losses[1:])), losses
     assert losses[-1] < 0.1 * losses[0], losses
     assert acc > 0.97, acc
+
+
+def test_example_out_of_core_gemm():
+    import ooc_gemm
+    print("[case] example out-of-core GEMM", flush=True)
+    res = {name: (st, err) for name, st, err in ooc_gemm.run(n=4096, tile=512, budget_mb=48, quiet=True)}
+    for name, (st, err) in res.items():
+        assert err < 1e-5, (name, err)
+        assert st["in_core"] == 0 and st["n_tasks"] == 64 and st["n_tile_gemms"] == 512
+        assert st["d2h_bytes"] == 4096 * 4096 * 4                       # every C tile harvested once
+        assert st["hits"] + st["misses"] == 2 * 512                     # one A and one B lookup per tile product
+    # the strip order reuses what the cache holds; row-major order re-fetches B for every task row
+    assert res["strips"][0]["misses"] < res["serpentine"][0]["misses"] <= res["row-major"][0]["misses"]
