@@ -56,25 +56,77 @@ def tgemm_access_sequence(M, N, K, T, order="serpentine", strip=None):
     return seq
 
 
-def lru_simulate(keys, n_slots):
-    """Runs strict LRU over hashable keys.  Returns (events, stats); events[t] =
-    (hit, evicted_key_or_None)."""
-    if n_slots < 1:
-        raise ValueError("need at least one slot")
-    cache = OrderedDict()
-    events = []
-    hits = misses = evictions = 0
-    for key in keys:
+class _Lru:
+    """Strict LRU over hashable keys with `n_slots` entries; a lookup touches the key."""
+
+    def __init__(self, n_slots):
+        if n_slots < 1:
+            raise ValueError("need at least one slot")
+        self.n_slots = n_slots
+        self.cache = OrderedDict()
+        self.hits = self.misses = self.evictions = 0
+
+    def __contains__(self, key):
+        return key in self.cache
+
+    def lookup(self, key):
+        """Returns (hit, evicted_key_or_None)."""
+        cache, n_slots = self.cache, self.n_slots
         if key in cache:
             cache.move_to_end(key)
-            hits += 1
-            events.append((True, None))
-            continue
-        misses += 1
+            self.hits += 1
+            return (True, None)
+        self.misses += 1
         victim = None
         if len(cache) >= n_slots:
             victim, _ = cache.popitem(last=False)
-            evictions += 1
+            self.evictions += 1
         cache[key] = True
-        events.append((False, victim))
-    return events, dict(hits=hits, misses=misses, evictions=evictions)
+        return (False, victim)
+
+    def stats(self):
+        return dict(hits=self.hits, misses=self.misses, evictions=self.evictions)
+
+
+def lru_simulate(keys, n_slots):
+    """Runs strict LRU over hashable keys.  Returns (events, stats); events[t] =
+    (hit, evicted_key_or_None)."""
+    lru = _Lru(n_slots)
+    events = [lru.lookup(key) for key in keys]
+    return events, lru.stats()
+
+
+def station_simulate(M, N, K, T, n_slots, order="row_major", strip=None, depth=1):
+    """The tile lookups of one tiled GEMM when tasks pass through a reservation station (section 3.2
+    of the paper: the buffer between the task queue and the streams, on which the runtime schedules
+    by priority).  The paper does not define the priority; the reading taken is locality: the station
+    holds up to `depth` tasks taken from the queue in issue order, and whenever a stream asks for
+    work the task with the most input tiles (A_ik and B_kj over all k) in the tile cache at that
+    moment leaves first, ties going to the task that entered the station first; the station is then
+    topped up from the queue.  depth = 1 is plain queue order.  The cache is strict LRU over the
+    lookups of the tasks in the order they leave (k ascending, A tile then B tile).
+
+    Returns (task ids in the order they left the station, events as lru_simulate gives them, stats)."""
+    if depth < 1:
+        raise ValueError("station depth")
+    n_i, n_j, n_k = _ceil_div(M, T), _ceil_div(N, T), _ceil_div(K, T)
+    queue = list(task_order(n_i, n_j, order, strip))
+    station, left = [], []
+    lru = _Lru(n_slots)
+    events = []
+    while queue or station:
+        while queue and len(station) < depth:
+            station.append(queue.pop(0))
+        best, best_score = 0, -1
+        for pos, tid in enumerate(station):
+            ti, tj = divmod(tid, n_j)
+            score = sum((("A", ti, k) in lru) + (("B", k, tj) in lru) for k in range(n_k))
+            if score > best_score:          # strictly greater: the earlier entry keeps a tie
+                best, best_score = pos, score
+        tid = station.pop(best)
+        left.append(tid)
+        ti, tj = divmod(tid, n_j)
+        for k in range(n_k):
+            events.append(lru.lookup(("A", ti, k)))
+            events.append(lru.lookup(("B", k, tj)))
+    return left, events, lru.stats()

@@ -142,11 +142,25 @@ def test_mlp_mutant_is_caught(oracle, name, old, new):
 PLAN_LRU_PINS = ([(pins_plan.test_paper_tile_counts, ()), (pins_plan.test_edge_extents_config1, ()),
                   (pins_plan.test_lru_closed_forms, ()), (pins_plan.test_lru_vs_brute_force, ()),
                   (pins_plan.test_access_sequence_structure, ()), (pins_plan.test_row_major_reuse_closed_form, ()),
-                  (pins_plan.test_strips_order_written_out, ()), (pins_plan.test_strips_traffic_closed_form, ())]
+                  (pins_plan.test_strips_order_written_out, ()), (pins_plan.test_strips_traffic_closed_form, ()),
+                  (pins_plan.test_station_of_depth_one_is_queue_order, ()), (pins_plan.test_station_worked_example, ()),
+                  (pins_plan.test_station_leaves_by_priority, ())]
                  + [(pins_plan.test_plan_partitions_output, a) for a in [(1000, 1000, 1000, 256), (7, 13, 5, 3), (5, 5, 5, 8)]])
 
 LRU_MUTANTS = [
     ("hit does not refresh (FIFO)", "            cache.move_to_end(key)\n", "            pass\n"),
+    ("station: ties go to the later entry", "            if score > best_score:", "            if score >= best_score:"),
+    ("station: the least cached task leaves", "        best, best_score = 0, -1\n", "        best, best_score = 0, 10 ** 9\n"),
+    ("station: only A tiles count", 'score = sum((("A", ti, k) in lru) + (("B", k, tj) in lru) for k in range(n_k))',
+     'score = sum((("A", ti, k) in lru) for k in range(n_k))'),
+    ("station: B tile index transposed in the score", 'score = sum((("A", ti, k) in lru) + (("B", k, tj) in lru) for k in range(n_k))',
+     'score = sum((("A", ti, k) in lru) + (("B", tj, k) in lru) for k in range(n_k))'),
+    ("station: depth ignored", "        while queue and len(station) < depth:", "        while queue and len(station) < 1:"),
+    ("station: one task too many", "        while queue and len(station) < depth:", "        while queue and len(station) < depth + 1:"),
+    ("station: B looked up before A", '            events.append(lru.lookup(("A", ti, k)))\n            events.append(lru.lookup(("B", k, tj)))',
+     '            events.append(lru.lookup(("B", k, tj)))\n            events.append(lru.lookup(("A", ti, k)))'),
+    ("station: the score refreshes the tiles it finds", "    def __contains__(self, key):\n        return key in self.cache",
+     "    def __contains__(self, key):\n        if key in self.cache:\n            self.cache.move_to_end(key)\n        return key in self.cache"),
     ("evicts the most recent", "victim, _ = cache.popitem(last=False)", "victim, _ = cache.popitem(last=True)"),
     ("one slot too many", "if len(cache) >= n_slots:", "if len(cache) > n_slots:"),
     ("serpentine parity", 'if order == "serpentine" and i % 2 == 1:', 'if order == "serpentine" and i % 2 == 0:'),

@@ -160,3 +160,69 @@ def test_strips_traffic_closed_form(oracle):
     serp = oracle.tgemm_access_sequence(n_i * T, n_j * T, n_k * T, T, order="serpentine")
     _, st2 = oracle.lru_simulate([s[:3] for s in serp], (w + 2) * n_k)
     assert st2["misses"] > st["misses"]
+
+
+# ---- reservation station with locality priority --------------------------------------------------------
+
+def _keys(oracle, M, N, K, T, order, strip=None):
+    return [(m, a, b) for (m, a, b, _, _) in oracle.tgemm_access_sequence(M, N, K, T, order, strip)]
+
+
+def test_station_of_depth_one_is_queue_order(oracle):
+    for (M, N, K, T, slots, order, strip) in [(12, 12, 8, 4, 5, "row_major", None), (20, 12, 8, 4, 7, "serpentine", None),
+                                              (16, 24, 12, 4, 9, "strips", 2), (7, 13, 5, 3, 4, "row_major", None)]:
+        left, ev, st = oracle.station_simulate(M, N, K, T, slots, order, strip, depth=1)
+        n_i, n_j = -(-M // T), -(-N // T)
+        assert left == oracle.task_order(n_i, n_j, order, strip)
+        ev0, st0 = oracle.lru_simulate(_keys(oracle, M, N, K, T, order, strip), slots)
+        assert ev == ev0 and st == st0
+
+
+def test_station_worked_example(oracle):
+    # 2 x 2 tasks, one k-step, two cache slots, station of two, row-major queue 0 1 2 3
+    # (task t = (i, j) = (t / 2, t % 2) looks up A_i then B_j):
+    #   station {0,1}: nothing cached, 0 leaves (first in).  A0 miss, B0 miss.      cache A0 B0
+    #   station {1,2}: task 1 has A0, task 2 has B0: a tie, 1 leaves.  A0 hit, B1 miss evicts B0.  cache A0 B1
+    #   station {2,3}: task 2 = (1,0) has nothing, task 3 = (1,1) has B1: 3 leaves.  A1 miss evicts A0, B1 hit.  cache B1 A1
+    #   station {2}:   A1 hit, B0 miss.
+    # 5 misses; plain queue order has 6 (task 2 evicts B1 before task 3 wants it).
+    left, ev, st = oracle.station_simulate(8, 8, 4, 4, 2, "row_major", None, depth=2)
+    assert left == [0, 1, 3, 2]
+    assert [e[0] for e in ev] == [False, False, True, False, False, True, True, False]
+    assert [e[1] for e in ev] == [None, None, None, ("B", 0, 0), ("A", 0, 0), None, None, ("B", 0, 1)]
+    assert st == dict(hits=3, misses=5, evictions=3)
+    assert oracle.lru_simulate(_keys(oracle, 8, 8, 4, 4, "row_major"), 2)[1]["misses"] == 6
+
+
+def test_station_leaves_by_priority(oracle):
+    """The defining property, checked with independent machinery: the station is always the earliest
+    `depth` tasks of the queue that have not left; the one that leaves has the most input tiles in the
+    cache as lru_simulate leaves it after the lookups so far, and among equals it is the earliest."""
+    import random
+    rnd = random.Random(5)
+    reordered = 0
+    for case in range(30):
+        n_i, n_j, n_k = rnd.randint(1, 5), rnd.randint(1, 5), rnd.randint(1, 3)
+        T, slots, depth = 4, rnd.randint(2, 12), rnd.randint(1, 6)
+        order = rnd.choice(["row_major", "serpentine"])
+        M, N, K = n_i * T - rnd.randint(0, 3), n_j * T - rnd.randint(0, 3), n_k * T - rnd.randint(0, 3)
+        left, ev, st = oracle.station_simulate(M, N, K, T, slots, order, None, depth)
+        queue = oracle.task_order(n_i, n_j, order)
+        assert sorted(left) == sorted(queue) and len(ev) == 2 * n_k * len(queue)
+        reordered += left != queue
+        done, keys = [], []
+        for tid in left:
+            waiting = [t for t in queue if t not in done][:depth]
+            # cache content now: replay the lookups so far
+            resident = set()
+            for key, (hit, victim) in zip(keys, oracle.lru_simulate(keys, slots)[0]):
+                resident.add(key)
+                resident.discard(victim)
+            score = lambda t: sum((("A", t // n_j, k) in resident) + (("B", k, t % n_j) in resident) for k in range(n_k))
+            best = max(score(t) for t in waiting)
+            assert tid == [t for t in waiting if score(t) == best][0], (case, tid, waiting)
+            done.append(tid)
+            for k in range(n_k):
+                keys += [("A", tid // n_j, k), ("B", k, tid % n_j)]
+        assert ev == oracle.lru_simulate(keys, slots)[0]
+    assert reordered >= 5      # the priority did change the order in a fair share of the cases
