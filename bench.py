@@ -105,7 +105,7 @@ def run_gemm_ooc(args, tg, inputs, torch, n, T, budget):
     inputs.fill(A, 1, "uniform", gen_device="cuda")
     inputs.fill(B, 2, "uniform", gen_device="cuda")
     torch.cuda.synchronize()
-    ctx = tg.tgemm_create(0, order=args.order, strip_width=args.strip)
+    ctx = tg.tgemm_create(0, order=args.order, strip_width=args.strip, rs_depth=args.rs_depth)
     flops = 2.0 * n * n * n
     for _ in range(args.warmup):
         tg.tgemm_run(ctx, A, B, C, n, n, n, T, tg.TGEMM_F32, budget)
@@ -119,7 +119,7 @@ def run_gemm_ooc(args, tg, inputs, torch, n, T, budget):
     tfl = flops / (ms_per_step * 1e-3) / 1e12
     out = base_line(args, tfl, "TFLOP/s", ms_per_step, "f32",
                     "fp32 out-of-core tiled GEMM M=N=K=%d, T=%d, A, B, C in pinned host memory, HBM tile-cache budget %d bytes"
-                    % (n, T, budget), {"tile": T, "slots": st["n_slots"], "order": ("serpentine", "row_major", "strips")[args.order]})
+                    % (n, T, budget), {"tile": T, "slots": st["n_slots"], "order": ("serpentine", "row_major", "strips")[args.order], "rs_depth": args.rs_depth})
     link = (st["h2d_bytes"] / 1e9) / (ms_per_step * 1e-3)
     out["roofline"] = {"bound": "mfma", "achieved": tfl, "peak": PEAK_F32_MFMA_TFLOPS, "unit": "TFLOP/s",
                        "frac": tfl / PEAK_F32_MFMA_TFLOPS, "traffic": None, "kernel": "tile_gemm_f32 (whole run, transfers included)"}
@@ -210,6 +210,8 @@ def main():
     ap.add_argument("--order", type=int, default=2, choices=[0, 1, 2],
                     help="out-of-core task order: 0 serpentine, 1 row-major, 2 strips (default)")
     ap.add_argument("--strip", type=int, default=0, help="strip width for --order 2; 0 = from the slot count")
+    ap.add_argument("--rs-depth", type=int, default=0,
+                    help="out-of-core GEMM: reservation station of this many tasks, the one with the most cached tiles first (0: queue order)")
     ap.add_argument("--sync-writeback", action="store_true",
                     help="out-of-core MLP: every step waits for its weight write-back (default: deferred)")
     ap.add_argument("--stochastic-rounding", action="store_true",

@@ -75,7 +75,11 @@ typedef struct tgemm_opts {
                               the write-back of updated weight tiles run on into the next call; the
                               host weights are complete after tgemm_sync, mlp_forward, mlp_backward
                               or mlp_destroy */
-    int32_t reserved[1];
+    int32_t rs_depth;      /* out-of-core tgemm_run, the reservation station of section 3.2: 0 or 1: tasks go
+                              to the streams in queue order; n > 1 (at most 64): the station holds the next
+                              n tasks of the queue, and whenever a stream is free the one with the most
+                              input tiles (A_ik and B_kj over all k) in the tile cache leaves first, ties
+                              going to the one that entered first */
 } tgemm_opts;
 
 /* One output tile C_ij = one task (section 3.1; Algorithm 1, "decode").
@@ -120,7 +124,7 @@ const char* tgemm_last_error(void);
  *            the context; entries that are NULL are created (and later destroyed) by the library.
  *            All streams must have default priority.
  *   opts     NULL for defaults (no trace, strips order with automatic width, no core binding,
- *            synchronous).
+ *            synchronous, queue order).
  * Errors: TGEMM_EARG (out == NULL, bad device, bad enum), TGEMM_EHIP, TGEMM_ENOMEM. */
 int tgemm_create(tgemm_ctx** out, int device, void* const* streams, const tgemm_opts* opts);
 

@@ -93,6 +93,7 @@ int tgemm_create(tgemm_ctx** out, int device, void* const* streams, const tgemm_
     if (o.strip_width < 0) return fail(TGEMM_EARG, "tgemm_create: strip_width %d", o.strip_width);
     if (o.kernel_config < 0 || o.kernel_config > 4)
         return fail(TGEMM_EARG, "tgemm_create: kernel_config %d", o.kernel_config);
+    if (o.rs_depth < 0 || o.rs_depth > 64) return fail(TGEMM_EARG, "tgemm_create: rs_depth %d (0 .. 64)", o.rs_depth);
     TG_HIP(hipSetDevice(device));
     tgemm_ctx* c = new (std::nothrow) tgemm_ctx();
     if (!c) return fail(TGEMM_ENOMEM, "tgemm_create: host allocation failed");

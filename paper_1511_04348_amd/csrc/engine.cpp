@@ -346,18 +346,39 @@ struct Run {
             CPU_SET(ctx->opts.affinity_core, &set);
             (void)pthread_setaffinity_np(pthread_self(), sizeof set, &set);   // best effort
         }
-        // Algorithm 1 line 5: run until the task queue has drained (and the producer has finished)
-        int64_t id;
+        // Algorithm 1 line 5: run until the task queue has drained (and the producer has finished).
+        // Tasks pass through the reservation station (section 3.2): it is topped up from the queue to
+        // `depth` tasks -- waiting for the producer, so that its content does not depend on thread
+        // timing -- and when a slot is free the task with the most input tiles in the tile cache
+        // leaves first, ties going to the one that entered first.  depth 1 is plain queue order.
+        const size_t depth = (size_t)std::min(std::max(ctx->opts.rs_depth, 1), 64);
+        std::vector<int64_t> station;
+        station.reserve(depth);
+        bool drained = false;
         while (rc == TGEMM_OK) {
-            if (!queue->dequeue(&id)) {
-                if (!producer_done.load(std::memory_order_acquire)) {
-                    std::this_thread::yield();
-                    continue;
-                }
-                if (!queue->dequeue(&id)) break;
+            while (!drained && station.size() < depth) {
+                int64_t id;
+                if (queue->dequeue(&id)) { station.push_back(id); continue; }
+                if (!producer_done.load(std::memory_order_acquire)) { std::this_thread::yield(); continue; }
+                if (queue->dequeue(&id)) station.push_back(id);      // enqueued just before the flag
+                else drained = true;
             }
+            if (station.empty()) break;
             const int s = pick_slot();
             if (s < 0) break;
+            size_t best = 0;
+            if (depth > 1) {
+                int64_t best_score = -1;
+                for (size_t q = 0; q < station.size(); ++q) {
+                    const int64_t i = station[q] / n_j, j = station[q] % n_j;
+                    int64_t score = 0;
+                    for (int64_t k = 0; k < n_k; ++k)
+                        score += (int64_t)eng->dir.count(tile_key(0, i, k)) + (int64_t)eng->dir.count(tile_key(1, k, j));
+                    if (score > best_score) { best_score = score; best = q; }
+                }
+            }
+            const int64_t id = station[best];
+            station.erase(station.begin() + (std::ptrdiff_t)best);
             issue_task(id, s);
         }
         for (int s = 0; s < 4; ++s) check(hipStreamSynchronize(ctx->streams[s]), "hipStreamSynchronize");

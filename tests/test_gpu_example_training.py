@@ -36,3 +36,4 @@ def test_example_out_of_core_gemm():
         assert st["hits"] + st["misses"] == 2 * 512                     # one A and one B lookup per tile product
     # the strip order reuses what the cache holds; row-major order re-fetches B for every task row
     assert res["strips"][0]["misses"] < res["serpentine"][0]["misses"] <= res["row-major"][0]["misses"]
+    assert res["row-major + station"][0]["misses"] < res["row-major"][0]["misses"]

@@ -288,3 +288,49 @@ def test_config3_full_size(oracle):
     lhs = _matvec64(Cn, x)
     rhs = _matvec64(An, _matvec64(Bn, x))
     assert np.array_equal(lhs, rhs)                                  # integers in fp64: exact on both sides
+
+
+@pytest.mark.parametrize("order,order_name", [(tg.TGEMM_ORDER_ROW_MAJOR, "row_major"), (tg.TGEMM_ORDER_SERPENTINE, "serpentine")])
+@pytest.mark.parametrize("M,N,K,T,n_ab,depth", [(1500, 1400, 1300, 256, 20, 4), (640, 640, 640, 128, 8, 8),
+                                                (300, 2000, 700, 256, 11, 3), (1280, 2304, 768, 256, 15, 64)])
+def test_reservation_station_priority(oracle, M, N, K, T, n_ab, depth, order, order_name):
+    """opts.rs_depth: the order in which tasks leave the reservation station, every hit, miss and
+    eviction of the trace, and the statistics equal the oracle's station simulation; the values are
+    those of the plain product (integer inputs: bit for bit); the priority saves host-link traffic."""
+    announce("ooc reservation station", M, N, K, T, n_ab, depth, order_name)
+    A = inputs.int_matrix(11, M, K)
+    B = inputs.int_matrix(12, K, N)
+    C0 = inputs.int_matrix(13, M, N)
+    ref = oracle.gemm(A.numpy(), B.numpy(), c_in=C0.numpy())
+    misses = {}
+    for d in (depth, 1):
+        ctx = tg.tgemm_create(0, trace=1, order=order, rs_depth=d)
+        try:
+            Ap, Bp, Cp = _pinned(A), _pinned(B), _pinned(C0)
+            tg.tgemm_run(ctx, Ap, Bp, Cp, M, N, K, T, tg.TGEMM_F32, _budget(T, n_ab, M, N, K))
+            assert np.array_equal(Cp.numpy().astype(np.float64), ref)
+            stats = tg.tgemm_last_stats(ctx)
+            trace = tg.tgemm_trace(ctx)
+            left, events, st = oracle.station_simulate(M, N, K, T, stats["n_slots"], order_name, None, d)
+            n_j, n_k = -(-N // T), -(-K // T)
+            assert [r["task_id"] for r in trace[::n_k]] == left
+            assert len(trace) * 2 == len(events)
+            for t, rec in enumerate(trace):
+                tid = left[t // n_k]
+                assert (rec["task_id"], rec["i"], rec["j"], rec["k"]) == (tid, tid // n_j, tid % n_j, t % n_k)
+                assert bool(rec["a_hit"]) == events[2 * t][0] and bool(rec["b_hit"]) == events[2 * t + 1][0]
+                assert bool(rec["a_evicted"]) == (events[2 * t][1] is not None)
+                assert bool(rec["b_evicted"]) == (events[2 * t + 1][1] is not None)
+            assert (stats["hits"], stats["misses"], stats["evictions"]) == (st["hits"], st["misses"], st["evictions"])
+            assert stats["d2h_bytes"] == M * N * 4
+            misses[d] = stats["misses"]
+        finally:
+            tg.tgemm_destroy(ctx)
+    assert misses[depth] <= misses[1]
+
+
+def test_reservation_station_depth_is_checked():
+    for bad in (-1, 65):
+        with pytest.raises(tg.TgemmError) as e:
+            tg.tgemm_create(0, rs_depth=bad)
+        assert e.value.code == tg.TGEMM_EARG
