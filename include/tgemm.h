@@ -91,7 +91,9 @@ typedef struct tgemm_task {
 typedef struct tgemm_stats {
     double wall_ms;        /* host wall clock of the last tgemm_run / mlp_* call                  */
     double kernel_ms;      /* HIP-event time on the launch stream around the GEMM kernel(s) of the
-                              last in-core tgemm_run (0 for out-of-core runs)                       */
+                              last in-core tgemm_run, or from the first to the last launch of the
+                              last mlp_step on its compute stream (0 for out-of-core tgemm_run,
+                              mlp_forward and mlp_backward)                                        */
     int64_t in_core;       /* 1 if the last run was in-core                                       */
     int64_t n_tasks;       /* output tiles                                                        */
     int64_t n_tile_gemms;  /* tile products C_ij += A_ik B_kj                                      */
@@ -121,8 +123,10 @@ const char* tgemm_last_error(void);
  * in-core runs and the MLP passes launch on streams[0].
  *   device   HIP device ordinal.
  *   streams  NULL, or 4 hipStream_t values (as void*) borrowed from the caller for the lifetime of
- *            the context; entries that are NULL are created (and later destroyed) by the library.
- *            All streams must have default priority.
+ *            the context; entries that are NULL are taken from the library's own set of four streams
+ *            for that device, which is created at first need and kept until the process ends, so
+ *            contexts on one device that bring no streams share them (work of two such contexts is
+ *            ordered per stream; results never depend on it).  All streams must have default priority.
  *   opts     NULL for defaults (no trace, strips order with automatic width, no core binding,
  *            synchronous, queue order).
  * Errors: TGEMM_EARG (out == NULL, bad device, bad enum), TGEMM_EHIP, TGEMM_ENOMEM. */

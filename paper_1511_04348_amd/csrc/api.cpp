@@ -5,6 +5,7 @@
 
 #include <atomic>
 #include <chrono>
+#include <mutex>
 #include <thread>
 
 #include "common.h"
@@ -38,6 +39,25 @@ PtrKind classify_pointer(const void* p, int device)
     if (at.type == hipMemoryTypeManaged) return PTR_DEVICE;
     (void)device;
     return PTR_PAGEABLE;
+}
+
+// The library's own streams, four per device, created when a context first needs one and kept until
+// the process ends: contexts that bring no streams of their own borrow these.  (Streams that are
+// created and destroyed with every context end up sharing hardware queues after a few contexts --
+// measured: an out-of-core step ran 1.5 times slower in a process that had destroyed a used
+// context before -- because fetch, compute and write-back then queue behind each other.)  Contexts
+// on one device therefore share streams; that adds ordering between them, never removes any.
+static std::mutex g_stream_mu;
+static hipStream_t g_streams[64][4] = {};
+static hipError_t pooled_stream(int device, int s, hipStream_t* out)
+{
+    std::lock_guard<std::mutex> lock(g_stream_mu);
+    if (!g_streams[device][s]) {
+        hipError_t e = hipStreamCreateWithFlags(&g_streams[device][s], hipStreamNonBlocking);
+        if (e != hipSuccess) { g_streams[device][s] = nullptr; return e; }
+    }
+    *out = g_streams[device][s];
+    return hipSuccess;
 }
 
 static double now_ms()
@@ -82,7 +102,7 @@ int tgemm_create(tgemm_ctx** out, int device, void* const* streams, const tgemm_
         (void)hipGetLastError();
         return fail(TGEMM_EHIP, "tgemm_create: no HIP device is visible");
     }
-    if (device < 0 || device >= n_dev) return fail(TGEMM_EARG, "tgemm_create: device %d of %d", device, n_dev);
+    if (device < 0 || device >= n_dev || device >= 64) return fail(TGEMM_EARG, "tgemm_create: device %d of %d", device, n_dev);
     tgemm_opts o;
     memset(&o, 0, sizeof o);
     o.affinity_core = -1;
@@ -103,12 +123,11 @@ int tgemm_create(tgemm_ctx** out, int device, void* const* streams, const tgemm_
         if (streams && streams[s]) {
             c->streams[s] = (hipStream_t)streams[s];
         } else {
-            hipError_t e = hipStreamCreateWithFlags(&c->streams[s], hipStreamNonBlocking);
+            hipError_t e = pooled_stream(device, s, &c->streams[s]);
             if (e != hipSuccess) {
                 tgemm_destroy(c);
                 return fail(TGEMM_EHIP, "hipStreamCreate: %s", hipGetErrorString(e));
             }
-            c->own_stream[s] = true;
         }
     }
     if (hipEventCreate(&c->ev_start) != hipSuccess || hipEventCreate(&c->ev_stop) != hipSuccess) {
@@ -126,8 +145,6 @@ int tgemm_destroy(tgemm_ctx* ctx)
     for (int s = 0; s < 4; ++s)
         if (ctx->streams[s]) (void)hipStreamSynchronize(ctx->streams[s]);
     destroy_engine(ctx);
-    for (int s = 0; s < 4; ++s)
-        if (ctx->own_stream[s] && ctx->streams[s]) (void)hipStreamDestroy(ctx->streams[s]);
     if (ctx->ev_start) (void)hipEventDestroy(ctx->ev_start);
     if (ctx->ev_stop) (void)hipEventDestroy(ctx->ev_stop);
     delete ctx;

@@ -26,12 +26,12 @@ PtrKind classify_pointer(const void* p, int device);
 
 class Engine;   // out-of-core tile engine (engine.cpp)
 
+
 }  // namespace tg
 
 struct tgemm_ctx {
     int device = 0;
     hipStream_t streams[4] = {nullptr, nullptr, nullptr, nullptr};
-    bool own_stream[4] = {false, false, false, false};
     tgemm_opts opts{};
     tgemm_stats stats{};
     hipEvent_t ev_start = nullptr, ev_stop = nullptr;

@@ -642,8 +642,9 @@ int launch(tgemm_mlp* m, GemmDesc& d, hipStream_t st)
 
 hipStream_t compute_stream(tgemm_mlp* m) { return m->ctx->streams[m->ooc ? 1 : 0]; }
 
-// equation 1 for layer l: out = epilogue(A_{l-1} W_l)
-int forward_layer(tgemm_mlp* m, int l, const char* in, int64_t batch)
+// equation 1 for layer l: out = epilogue(A_{l-1} W_l); out: batch x n_l (the layer's activation
+// matrix in the network's element type, or the float logits for the last layer)
+int forward_layer(tgemm_mlp* m, int l, const char* in, int64_t batch, char* out)
 {
     const int L = m->n_layers;
     const bool bf = m->dtype == TGEMM_BF16;
@@ -656,7 +657,6 @@ int forward_layer(tgemm_mlp* m, int l, const char* in, int64_t batch)
     d.act = m->act_kind;
     d.alpha = 1.f; d.beta = 0.f;
     d.out_bf16 = (bf && l < L) ? 1 : 0;                                  // logits stay float
-    char* out = (l < L) ? m->act[l] : (char*)m->logits;
     const size_t out_es = (l < L) ? m->es : 4;
     d.ldc = m->dims[l];
     const float* b = m->bias.empty() ? nullptr : m->bias[(size_t)l - 1];
@@ -691,7 +691,7 @@ int forward(tgemm_mlp* m, const char* X, int64_t batch)
 {
     const char* in = X;
     for (int l = 1; l <= m->n_layers; ++l) {
-        const int rc = forward_layer(m, l, in, batch);
+        const int rc = forward_layer(m, l, in, batch, (l < m->n_layers) ? m->act[l] : (char*)m->logits);
         if (rc != TGEMM_OK) return rc;
         in = (l < m->n_layers) ? m->act[l] : nullptr;
     }
@@ -701,23 +701,30 @@ int forward(tgemm_mlp* m, const char* X, int64_t batch)
     return TGEMM_OK;
 }
 
-int softmax(tgemm_mlp* m, const int32_t* labels, float* probs, bool want_delta)
+// Row-wise softmax of `logits` (batch x n_L floats, 16-byte aligned): probabilities to `probs`, and
+// with labels the error matrix to `delta` and the row losses to `row_loss` (any of them may be NULL).
+int softmax_rows(tgemm_mlp* m, const float* logits, int64_t batch, const int32_t* labels, float* probs, void* delta,
+                 float* row_loss)
 {
     const int L = m->n_layers;
     const int64_t n = m->dims[L];
-    void* delta = want_delta ? (void*)m->delta[L] : nullptr;
     const bool vec = (n % 4 == 0) && ((reinterpret_cast<uintptr_t>(probs) & 15) == 0);   // the workspaces are aligned
-    const dim3 grid((unsigned)m->batch), block(256);
-    const float inv_batch = 1.f / (float)m->batch;
+    const dim3 grid((unsigned)batch), block(256);
+    const float inv_batch = 1.f / (float)batch;
     hipStream_t st = compute_stream(m);
 #define TG_SOFTMAX(BF, V) \
-    hipLaunchKernelGGL((softmax_xent_rows<BF, V>), grid, block, 0, st, m->logits, n, (int)n, labels, inv_batch, delta, probs, m->row_loss)
+    hipLaunchKernelGGL((softmax_xent_rows<BF, V>), grid, block, 0, st, logits, n, (int)n, labels, inv_batch, delta, probs, row_loss)
     if (m->dtype == TGEMM_BF16) { if (vec) TG_SOFTMAX(true, true); else TG_SOFTMAX(true, false); }
     else { if (vec) TG_SOFTMAX(false, true); else TG_SOFTMAX(false, false); }
 #undef TG_SOFTMAX
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(TGEMM_EHIP, "mlp: softmax launch failed: %s", hipGetErrorString(e));
     return TGEMM_OK;
+}
+
+int softmax(tgemm_mlp* m, const int32_t* labels, float* probs, bool want_delta)
+{
+    return softmax_rows(m, m->logits, m->batch, labels, probs, want_delta ? (void*)m->delta[m->n_layers] : nullptr, m->row_loss);
 }
 
 int sync_all(tgemm_mlp* m)
@@ -1185,11 +1192,19 @@ int mlp_step(tgemm_mlp* m, const void* X, const int32_t* labels, int64_t batch, 
     TG_HIP(hipSetDevice(m->ctx->device));
     if ((rc = ensure_workspaces(m, batch)) != TGEMM_OK) return rc;
     begin_call(m);
+    m->ctx->kernel_timing_pending = false;     // the two events now belong to this step
+    TG_HIP(hipEventRecord(m->ctx->ev_start, compute_stream(m)));
     if ((rc = forward(m, (const char*)X, batch)) != TGEMM_OK) return rc;
     if ((rc = softmax(m, labels, nullptr, true)) != TGEMM_OK) return rc;
     if ((rc = backward(m, nullptr, true, lr)) != TGEMM_OK) return rc;
+    TG_HIP(hipEventRecord(m->ctx->ev_stop, compute_stream(m)));
     if ((rc = read_loss(m, loss)) != TGEMM_OK) return rc;
     if ((rc = (m->ooc && m->ctx->opts.deferred_writeback) ? sync_compute(m) : sync_all(m)) != TGEMM_OK) return rc;
+    {   // time on the compute stream from the step's first launch to its last
+        float ms = 0.f;
+        TG_HIP(hipEventElapsedTime(&ms, m->ctx->ev_start, m->ctx->ev_stop));
+        m->ctx->stats.kernel_ms = ms;
+    }
     m->have_delta = true;
     ++m->sr_step;
     m->ctx->stats.wall_ms = now_ms() - t0;
