@@ -305,6 +305,26 @@ int mlp_set_master_weights(tgemm_mlp* mlp, void* const* Wm);
  *   probs  NULL, or device pointer to batch x dims[n_layers] floats receiving softmax(logits). */
 int mlp_forward(tgemm_mlp* mlp, const void* X, int64_t batch, float* probs);
 
+/* mlp_forward for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same computation, same kernels and same results as
+ * mlp_forward, but the hidden activations and the logits live in a static device array of
+ * TGEMM_STATIC_SCRATCH_BYTES that every GPU running the library holds from load time to process end
+ * (its address on the context's device is looked up once, in tgemm_create).  The call allocates and
+ * frees nothing, on the device or through any library.
+ *   mlp    a network with device-resident weights (TGEMM_EARG for out-of-core weights).  Its own
+ *          workspaces and pass state are left alone: a pending mlp_forward stays pending, and
+ *          mlp_backward / mlp_read never see this call's activations.
+ *   X      device pointer, batch x dims[0], dtype elements.
+ *   probs  device pointer to batch x dims[n_layers] floats (16-byte aligned) receiving
+ *          softmax(logits); required.
+ * The activations (batch x dims[l] elements for l = 1..n_layers-1, each rounded up to 256 bytes)
+ * plus batch x dims[n_layers] floats of logits must fit the array: TGEMM_EBUDGET otherwise, before
+ * any work.  Nothing in the array has to start at zero (every product overwrites its destination),
+ * so it keeps the previous call's contents.  All calls on one GPU share that GPU's array: calls
+ * that overlap in time on one GPU (from several contexts or threads) race. */
+#define TGEMM_STATIC_SCRATCH_BYTES (32u << 20)
+int mlp_forward_static(tgemm_mlp* mlp, const void* X, int64_t batch, float* probs);
+
 /* Equations 3 and 4 for every layer, from the activations of the preceding mlp_forward:
  *   D_L = (softmax(Z_L) - onehot(labels)) / batch;  dW_l = A_{l-1}^T D_l;
  *   D_{l-1} = (D_l W_l^T) * A_{l-1} * (1 - A_{l-1}).

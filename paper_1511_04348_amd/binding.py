@@ -19,7 +19,7 @@ TGEMM_ROUND_NEAREST, TGEMM_ROUND_STOCHASTIC = 0, 1
 EXPORTS = [
     "tgemm_strerror", "tgemm_last_error", "tgemm_create", "tgemm_destroy", "tgemm_run", "tgemm_sync", "tgemm_invalidate",
     "tgemm_plan", "tgemm_task_order", "tgemm_last_stats", "tgemm_trace", "tgemm_queue_selftest",
-    "mlp_create", "mlp_destroy", "mlp_set_activation", "mlp_set_rounding", "mlp_set_bias", "mlp_set_momentum", "mlp_set_master_weights", "mlp_forward", "mlp_backward", "mlp_step", "mlp_read",
+    "mlp_create", "mlp_destroy", "mlp_set_activation", "mlp_set_rounding", "mlp_set_bias", "mlp_set_momentum", "mlp_set_master_weights", "mlp_forward", "mlp_forward_static", "mlp_backward", "mlp_step", "mlp_read",
 ]
 
 
@@ -89,6 +89,7 @@ def load():
     lib.mlp_set_momentum.argtypes = [vp, ctypes.c_float, P(vp), P(vp)]
     lib.mlp_set_master_weights.argtypes = [vp, P(vp)]
     lib.mlp_forward.argtypes = [vp, vp, i64, vp]
+    lib.mlp_forward_static.argtypes = [vp, vp, i64, vp]
     lib.mlp_backward.argtypes = [vp, vp, P(vp), P(ctypes.c_float)]
     lib.mlp_step.argtypes = [vp, vp, vp, i64, ctypes.c_float, P(ctypes.c_float)]
     lib.mlp_read.argtypes = [vp, i32, i32, vp, sz, sz]
@@ -235,6 +236,10 @@ def mlp_set_master_weights(mlp, Wm):
 
 def mlp_forward(mlp, X, batch, probs=None):
     _check(load().mlp_forward(mlp, _p(X), batch, _p(probs)))
+
+
+def mlp_forward_static(mlp, X, batch, probs):
+    _check(load().mlp_forward_static(mlp, _p(X), batch, _p(probs)))
 
 
 def mlp_backward(mlp, labels, dW=None):

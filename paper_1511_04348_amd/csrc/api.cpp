@@ -115,6 +115,10 @@ int tgemm_create(tgemm_ctx** out, int device, void* const* streams, const tgemm_
         return fail(TGEMM_EARG, "tgemm_create: kernel_config %d", o.kernel_config);
     if (o.rs_depth < 0 || o.rs_depth > 64) return fail(TGEMM_EARG, "tgemm_create: rs_depth %d (0 .. 64)", o.rs_depth);
     TG_HIP(hipSetDevice(device));
+    {   // the static scratch array's address on this device, for the entry points that allocate nothing
+        const int rc = static_scratch_resolve(device, nullptr);
+        if (rc != TGEMM_OK) return rc;
+    }
     tgemm_ctx* c = new (std::nothrow) tgemm_ctx();
     if (!c) return fail(TGEMM_ENOMEM, "tgemm_create: host allocation failed");
     c->device = device;

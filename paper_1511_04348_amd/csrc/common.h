@@ -26,6 +26,9 @@ PtrKind classify_pointer(const void* p, int device);
 
 class Engine;   // out-of-core tile engine (engine.cpp)
 
+// Address of the current device's copy of the static scratch array of mlp_forward_static (mlp.hip);
+// looked up once per device.  `device` must be current.  out may be NULL.
+int static_scratch_resolve(int device, void** out);
 
 }  // namespace tg
 

@@ -22,13 +22,47 @@
 #include <algorithm>
 #include <chrono>
 #include <deque>
+#include <mutex>
 #include <unordered_map>
 #include <vector>
 
 #include "common.h"
 #include "gemm_kernel.h"
 
+// ---- static scratch for mlp_forward_static ------------------------------------------------------
+// Device memory that exists from the moment the code object is loaded: the hidden activations and
+// the logits of a forward pass for callers that must not allocate.  Every GPU that loads the library
+// holds its own copy at its own address; host code never uses the array's name as an address (it is
+// only a host-side stand-in for the symbol) but the per-device address that hipGetSymbolAddress
+// returned for it.
+static __device__ __align__(256) unsigned char tgemm_static_scratch[TGEMM_STATIC_SCRATCH_BYTES];
+
 namespace tg {
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+void* g_static_scratch[MAX_DEVICES] = {};     // per device: address of that device's copy of the array
+std::mutex g_static_scratch_mu;
+}  // namespace
+
+// Looks the array's address up on `device` (which must be the current device); once per device.
+int static_scratch_resolve(int device, void** out)
+{
+    if (device < 0 || device >= MAX_DEVICES) return fail(TGEMM_EARG, "static scratch: device %d", device);
+    std::lock_guard<std::mutex> lock(g_static_scratch_mu);
+    if (!g_static_scratch[device]) {
+        void* p = nullptr;
+        hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(tgemm_static_scratch));
+        if (e != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return fail(TGEMM_EHIP, "static scratch: hipGetSymbolAddress failed on device %d: %s", device, hipGetErrorString(e));
+        }
+        g_static_scratch[device] = p;
+    }
+    if (out) *out = g_static_scratch[device];
+    return TGEMM_OK;
+}
+
 namespace {
 
 // ---- weight tile cache (out-of-core mode) -------------------------------------------------------
@@ -1162,6 +1196,44 @@ int mlp_forward(tgemm_mlp* m, const void* X, int64_t batch, float* probs)
     if ((rc = forward(m, (const char*)X, batch)) != TGEMM_OK) return rc;
     if (probs && (rc = softmax(m, nullptr, probs, false)) != TGEMM_OK) return rc;
     if ((rc = sync_all(m)) != TGEMM_OK) return rc;
+    m->ctx->stats.wall_ms = now_ms() - t0;
+    return TGEMM_OK;
+}
+
+int mlp_forward_static(tgemm_mlp* m, const void* X, int64_t batch, float* probs)
+{
+    int rc = check_batch(m, X, batch);
+    if (rc != TGEMM_OK) return rc;
+    if (!probs) return fail(TGEMM_EARG, "mlp_forward_static: probs is NULL (the logits do not outlive the call)");
+    if (m->ooc) return fail(TGEMM_EARG, "mlp_forward_static: the weights must be device-resident");
+    const int L = m->n_layers;
+    // layout of the scratch array: A_1 .. A_{L-1}, then the logits, each rounded up to 256 bytes
+    size_t need = 0;
+    for (int l = 1; l < L; ++l) need += ((size_t)batch * m->dims[l] * m->es + 255) / 256 * 256;
+    const size_t logits_at = need;
+    need += (size_t)batch * m->dims[L] * 4;
+    if (need > (size_t)TGEMM_STATIC_SCRATCH_BYTES)
+        return fail(TGEMM_EBUDGET, "mlp_forward_static: batch %lld needs %zu bytes of activations and logits, the static "
+                    "scratch holds %zu; use mlp_forward", (long long)batch, need, (size_t)TGEMM_STATIC_SCRATCH_BYTES);
+    const double t0 = now_ms();
+    TG_HIP(hipSetDevice(m->ctx->device));
+    void* base = nullptr;
+    if ((rc = static_scratch_resolve(m->ctx->device, &base)) != TGEMM_OK) return rc;
+    begin_call(m);
+    char* at = (char*)base;
+    const char* in = (const char*)X;
+    for (int l = 1; l <= L; ++l) {
+        char* out = (l < L) ? at : (char*)base + logits_at;
+        if ((rc = forward_layer(m, l, in, batch, out)) != TGEMM_OK) break;
+        in = out;
+        if (l < L) at += ((size_t)batch * m->dims[l] * m->es + 255) / 256 * 256;
+    }
+    if (rc == TGEMM_OK)
+        rc = softmax_rows(m, (const float*)((char*)base + logits_at), batch, nullptr, probs, nullptr, nullptr);
+    // whatever was launched has finished before the call returns, also after an error
+    const hipError_t e = hipStreamSynchronize(compute_stream(m));
+    if (rc != TGEMM_OK) return rc;
+    if (e != hipSuccess) return fail(TGEMM_EHIP, "mlp_forward_static: %s", hipGetErrorString(e));
     m->ctx->stats.wall_ms = now_ms() - t0;
     return TGEMM_OK;
 }
