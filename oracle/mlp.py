@@ -21,6 +21,12 @@ The equations themselves are not printed, so the textbook forms are taken:
                     every product of the two passes taken with the bf16 W_l
 
 numpy's fp64 matmul is the library primitive used for the products.
+
+mlp_rows evaluates the per-sample quantities (activations, logits, probabilities, errors) for a
+subset of the batch rows: each of them depends on that sample's row alone, apart from the 1 / batch
+in D_L, which is passed in.  It exists for networks whose weight matrices are too large to widen to
+fp64 whole (a 17 GB bf16 matrix would become 69 GB): its products walk the weight matrix in blocks of
+the OUTPUT index, so every output entry is still one fp64 dot product over the whole inner dimension.
 """
 import numpy as np
 
@@ -175,3 +181,51 @@ def mlp_step_master(X, Ws, y, lr, masters, act="sigmoid", mu=None, Vs=None):
     if Vs is None:
         return loss, bits, new_M, exact
     return loss, bits, new_M, exact, vel
+
+
+def _rows_times(R, W, transpose=False, block=4096):
+    """R @ W (or R @ W^T with transpose) in fp64 without ever holding the fp64 image of all of W: the
+    output index (columns of W; rows of W with transpose) is walked in blocks, the inner dimension
+    is never split."""
+    W = np.asarray(W)
+    n_out = W.shape[0] if transpose else W.shape[1]
+    out = np.empty((R.shape[0], n_out), dtype=np.float64)
+    for o0 in range(0, n_out, block):
+        o1 = min(n_out, o0 + block)
+        if transpose:
+            out[:, o0:o1] = R @ _f64(W[o0:o1, :]).T
+        else:
+            out[:, o0:o1] = R @ _f64(np.ascontiguousarray(W[:, o0:o1]))
+    return out
+
+
+def mlp_rows(X_rows, Ws, y_rows, batch, act="sigmoid", block=4096):
+    """Forward and backward quantities of the batch rows given (X_rows: r x n_0, y_rows: r labels) of a
+    step whose whole batch has `batch` samples.  Returns (acts, logits, probs, loss_rows, deltas):
+    acts[l] the input of layer l+1 (acts[0] = X_rows), loss_rows[b] = -log P[b, y_b], deltas[l] the
+    error at the output of layer l+1, with D_L = (P - onehot(y)) / batch."""
+    a = _f64(X_rows)
+    acts, pre = [a], [None]
+    L = len(Ws)
+    z = None
+    for l, W in enumerate(Ws):
+        z = _rows_times(a, W, block=block)
+        if l < L - 1:
+            a = _act(z, act)
+            acts.append(a)
+            pre.append(z)
+    zmax = z.max(axis=1, keepdims=True)
+    e = np.exp(z - zmax)
+    probs = e / e.sum(axis=1)[:, None]
+    y = np.asarray(y_rows, dtype=np.int64)
+    r = np.arange(z.shape[0])
+    loss_rows = zmax[:, 0] + np.log(e.sum(axis=1)) - z[r, y]
+    d = probs.copy()
+    d[r, y] -= 1.0
+    d /= batch
+    deltas = [None] * L
+    for l in range(L - 1, -1, -1):
+        deltas[l] = d
+        if l > 0:
+            d = _rows_times(d, Ws[l], transpose=True, block=block) * _act_slope(pre[l], acts[l], act)
+    return acts, z, probs, loss_rows, deltas

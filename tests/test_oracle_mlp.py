@@ -334,3 +334,63 @@ def test_momentum_with_bias_rows(oracle):
     _, W2, V2, b2, none = oracle.mlp_step_momentum(X, Ws, y, lr, mu, V0, bs=b)
     assert none is None and all(np.array_equal(a, c) for a, c in zip(W2, W1))
     assert all(np.allclose(b2[l], b[l] - lr * gb[l], atol=1e-16) for l in range(2))
+
+
+def test_rows_equal_the_whole_batch_pass(oracle):
+    """mlp_rows on a subset of the batch rows = those rows of the whole-batch passes, for block sizes
+    that split the output index raggedly, one by one, or not at all; fp32 and bf16 bit patterns."""
+    dims, B = [9, 13, 11, 7], 10
+    X, Ws, y = _net(21, dims, B)
+    rows = [0, 3, 4, 9]
+    for conv in (lambda a: a.astype(np.float32), lambda a: (a.astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)):
+        Xc, Wc = conv(X), [conv(w) for w in Ws]
+        for act in ("sigmoid", "tanh", "relu"):
+            acts, z, P = oracle.mlp_forward(Xc, Wc, act)
+            _, _, deltas = oracle.mlp_backward(Xc, Wc, y, act)
+            for block in (1, 4, 5, 64):
+                a_r, z_r, P_r, loss_r, d_r = oracle.mlp_rows(Xc[rows], Wc, y[rows], B, act, block=block)
+                for l in range(len(dims) - 1):
+                    assert np.allclose(a_r[l], acts[l][rows], rtol=1e-13, atol=1e-15), ("act", l, block)
+                    assert np.allclose(d_r[l], deltas[l][rows], rtol=1e-12, atol=1e-18), ("delta", l, block)
+                assert np.allclose(z_r, z[rows], rtol=1e-13, atol=1e-15) and np.allclose(P_r, P[rows], rtol=1e-13)
+    # the row losses average to the loss when every row is given
+    _, _, _, loss_r, _ = oracle.mlp_rows(X.astype(np.float32), [w.astype(np.float32) for w in Ws], y, B)
+    assert abs(loss_r.mean() - oracle.mlp_loss(X.astype(np.float32), [w.astype(np.float32) for w in Ws], y)) < 1e-13
+
+
+def test_rows_closed_forms_and_input_gradient(oracle):
+    """Independent of the whole-batch functions: zero weights (P = 1/C, row loss = ln C, hidden 0.5,
+    D_L = (1/C - onehot) / batch, earlier errors vanish), and the first error times W_1^T is the
+    gradient of sum(row losses) / batch with respect to the rows' inputs (central differences)."""
+    dims, B = [6, 8, 5, 4], 7
+    X, Ws, y = _net(22, dims, B)
+    rows = [1, 2, 6]
+    Z = [np.zeros_like(w, dtype=np.float32) for w in Ws]
+    a_r, z_r, P_r, loss_r, d_r = oracle.mlp_rows(X[rows].astype(np.float32), Z, y[rows], B)
+    C = dims[-1]
+    assert np.all(P_r == 1.0 / C) and np.allclose(loss_r, np.log(C), rtol=1e-15) and np.all(a_r[1] == 0.5) and np.all(a_r[2] == 0.5)
+    want = np.full((len(rows), C), 1.0 / C)
+    want[np.arange(len(rows)), y[rows]] -= 1.0
+    assert np.allclose(d_r[-1], want / B, rtol=1e-15) and np.all(d_r[0] == 0.0) and np.all(d_r[1] == 0.0)
+    Wf = [w.astype(np.float32) for w in Ws]
+    Xr = X[rows].astype(np.float32).astype(np.float64)
+    for act in ("sigmoid", "tanh"):
+        _, _, _, _, d_r = oracle.mlp_rows(Xr.astype(np.float32), Wf, y[rows], B, act, block=3)
+        grad = d_r[0] @ Wf[0].astype(np.float64).T
+        h = 1e-5
+        for r in range(len(rows)):
+            for c in range(dims[0]):
+                def total(v):
+                    Xp = Xr.copy()
+                    Xp[r, c] = v
+                    # inputs stay fp64 here: the check is on the mathematics, not on storage rounding
+                    a = Xp
+                    for l, W in enumerate(Wf):
+                        zz = a @ W.astype(np.float64)
+                        if l < len(Wf) - 1:
+                            a = 1.0 / (1.0 + np.exp(-zz)) if act == "sigmoid" else np.tanh(zz)
+                    m = zz.max(axis=1)
+                    lse = m + np.log(np.exp(zz - m[:, None]).sum(axis=1))
+                    return float((lse - zz[np.arange(len(rows)), y[rows]]).sum() / B)
+                fd = (total(Xr[r, c] + h) - total(Xr[r, c] - h)) / (2 * h)
+                assert abs(fd - grad[r, c]) <= 1e-6 * max(1e-3, abs(grad[r, c])), (act, r, c, fd, grad[r, c])

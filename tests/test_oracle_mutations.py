@@ -61,7 +61,8 @@ MLP_PINS = [(pins_mlp.test_finite_differences_every_weight, ()), (pins_mlp.test_
             (pins_mlp.test_bias_finite_differences, ()), (pins_mlp.test_bias_is_a_constant_one_input_column, ()),
             (pins_mlp.test_bias_closed_forms, ()), (pins_mlp.test_bias_step, ()),
             (pins_mlp.test_momentum_reduces_to_sgd_and_heavy_ball_identity, ()), (pins_mlp.test_momentum_with_bias_rows, ()),
-            (pins_round.test_master_step_written_out, ()), (pins_round.test_master_copies_keep_the_steps_that_bf16_storage_loses, ())]
+            (pins_round.test_master_step_written_out, ()), (pins_round.test_master_copies_keep_the_steps_that_bf16_storage_loses, ()),
+            (pins_mlp.test_rows_equal_the_whole_batch_pass, ()), (pins_mlp.test_rows_closed_forms_and_input_gradient, ())]
 
 MLP_MUTANTS = [
     ("sigmoid sign", "        return 1.0 / (1.0 + np.exp(-z))", "        return 1.0 / (1.0 + np.exp(z))"),
@@ -128,6 +129,19 @@ MLP_MUTANTS = [
      "[g + np.asarray(V, dtype=np.float64) for g, V in zip(dWs, Vs)]"),
     ("bias update without lr", "new_bs = [np.asarray(b, dtype=np.float64) - lr * g for b, g in zip(bs, dbs)]",
      "new_bs = [np.asarray(b, dtype=np.float64) - g for b, g in zip(bs, dbs)]"),
+    ("rows: block product drops the transposition", "            out[:, o0:o1] = R @ _f64(W[o0:o1, :]).T", "            out[:, o0:o1] = R @ _f64(W[:, o0:o1])"),
+    ("rows: blocks land one block late", "            out[:, o0:o1] = R @ _f64(np.ascontiguousarray(W[:, o0:o1]))",
+     "            out[:, o0:o1] = R @ _f64(np.ascontiguousarray(W[:, max(0, o0 - (o1 - o0)):max(0, o0 - (o1 - o0)) + o1 - o0]))"),
+    ("rows: last block dropped", "    for o0 in range(0, n_out, block):\n        o1 = min(n_out, o0 + block)\n        if transpose:",
+     "    for o0 in range(0, n_out - block + 1, block):\n        o1 = min(n_out, o0 + block)\n        if transpose:"),
+    ("rows: softmax without the row sum", "    probs = e / e.sum(axis=1)[:, None]", "    probs = e / e.sum()"),
+    ("rows: one-hot sign", "    d[r, y] -= 1.0", "    d[r, y] += 1.0"),
+    ("rows: divided by the number of rows given", "    d /= batch\n", "    d /= z.shape[0]\n"),
+    ("rows: loss without the label's logit", "    loss_rows = zmax[:, 0] + np.log(e.sum(axis=1)) - z[r, y]", "    loss_rows = zmax[:, 0] + np.log(e.sum(axis=1))"),
+    ("rows: slope dropped", "            d = _rows_times(d, Ws[l], transpose=True, block=block) * _act_slope(pre[l], acts[l], act)",
+     "            d = _rows_times(d, Ws[l], transpose=True, block=block)"),
+    ("rows: error through the wrong layer's weights", "            d = _rows_times(d, Ws[l], transpose=True, block=block) * _act_slope(pre[l], acts[l], act)",
+     "            d = _rows_times(d, Ws[l], transpose=True, block=block) * _act_slope(pre[l - 1] if l > 1 else pre[l], acts[l - 1] if l > 1 else acts[l], act)"),
 ]
 
 
