@@ -5,6 +5,11 @@ cache) is used directly; a tile absent from it is fetched from host memory.
 Algorithm 1 looks up A[i,k] then B[k,j] for every k-step of a task.  The
 paper does not name the eviction rule; the reading taken is strict LRU with
 a touch on every lookup.  On one GPU there is no second-level (peer) cache.
+
+The weight-tile cache of the out-of-core MLP step sees a lookup sequence that repeats every step
+(mlp_sweep_groups), so the next use of every resident tile is known; next_use_simulate is the
+replacement rule "evict the resident tile whose next use lies furthest ahead" on such a cyclic
+sequence, with the tiles of the launch being assembled protected from eviction.
 """
 from collections import OrderedDict
 
@@ -130,3 +135,74 @@ def station_simulate(M, N, K, T, n_slots, order="row_major", strip=None, depth=1
             events.append(lru.lookup(("A", ti, k)))
             events.append(lru.lookup(("B", k, tj)))
     return left, events, lru.stats()
+
+
+def mlp_sweep_groups(dims, T, update=True):
+    """The weight-tile lookups of one out-of-core training step, as a list of launch groups (each a
+    list of keys (layer, tile row, tile col), layer = 1..L).  Forward: layers ascending, one group
+    per tile COLUMN of W_l holding the column's tiles by ascending tile row (the k-steps of the
+    product A_{l-1} W_l).  Backward: layers descending, one group per tile ROW of W_l holding the
+    row's tiles by ascending tile column (they serve D_l W_l^T and then take the update).  Without
+    update and with a single use for W_1 (no error is propagated below the first layer) the first
+    layer has no backward lookups."""
+    L = len(dims) - 1
+    groups = []
+    for l in range(1, L + 1):
+        n_r, n_c = _ceil_div(dims[l - 1], T), _ceil_div(dims[l], T)
+        for c in range(n_c):
+            groups.append([(l, r, c) for r in range(n_r)])
+    for l in range(L, 0, -1):
+        if l == 1 and not update:
+            continue
+        n_r, n_c = _ceil_div(dims[l - 1], T), _ceil_div(dims[l], T)
+        for r in range(n_r):
+            groups.append([(l, r, c) for c in range(n_c)])
+    return groups
+
+
+def next_use_simulate(groups, n_slots, n_sweeps=1):
+    """Replacement by next use on a cyclic lookup sequence.
+
+    groups   the lookups of one sweep as a list of groups of hashable keys; the sweep repeats
+             forever, and `n_sweeps` of it are simulated starting from an empty cache.
+    On a miss with the cache full, the victim is the resident key, outside the current group, whose
+    next lookup (counted from the current position along the endlessly repeated sweep) lies
+    furthest ahead; a key that never occurs again would be infinitely far, but in a cyclic sweep
+    every key does.  Two distinct keys cannot tie: they never share a position.
+
+    Returns (events, stats) like lru_simulate: events[t] = (hit, evicted_key_or_None)."""
+    if n_slots < 1:
+        raise ValueError("need at least one slot")
+    flat = [key for g in groups for key in g]
+    group_of = [gi for gi, g in enumerate(groups) for _ in g]
+    period = len(flat)
+    where = {}
+    for t, key in enumerate(flat):
+        where.setdefault(key, []).append(t)
+    resident = set()
+    events = []
+    hits = misses = evictions = 0
+    for sweep in range(n_sweeps):
+        for t, key in enumerate(flat):
+            if key in resident:
+                hits += 1
+                events.append((True, None))
+                continue
+            misses += 1
+            victim = None
+            if len(resident) >= n_slots:
+                current = set(groups[group_of[t]])
+                best = -1
+                for cand in resident:
+                    if cand in current:
+                        continue
+                    ahead = min((u - t - 1) % period for u in where[cand])
+                    if ahead > best:
+                        best, victim = ahead, cand
+                if victim is None:
+                    raise ValueError("the cache cannot hold one group")
+                resident.discard(victim)
+                evictions += 1
+            resident.add(key)
+            events.append((False, victim))
+    return events, dict(hits=hits, misses=misses, evictions=evictions)

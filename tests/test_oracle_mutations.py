@@ -158,7 +158,9 @@ PLAN_LRU_PINS = ([(pins_plan.test_paper_tile_counts, ()), (pins_plan.test_edge_e
                   (pins_plan.test_access_sequence_structure, ()), (pins_plan.test_row_major_reuse_closed_form, ()),
                   (pins_plan.test_strips_order_written_out, ()), (pins_plan.test_strips_traffic_closed_form, ()),
                   (pins_plan.test_station_of_depth_one_is_queue_order, ()), (pins_plan.test_station_worked_example, ()),
-                  (pins_plan.test_station_leaves_by_priority, ())]
+                  (pins_plan.test_station_leaves_by_priority, ()),
+                  (pins_plan.test_next_use_is_optimal_on_every_small_sweep, ()), (pins_plan.test_next_use_worked_example_and_closed_forms, ()),
+                  (pins_plan.test_next_use_against_explicit_scan_with_groups, ()), (pins_plan.test_mlp_sweep_written_out, ())]
                  + [(pins_plan.test_plan_partitions_output, a) for a in [(1000, 1000, 1000, 256), (7, 13, 5, 3), (5, 5, 5, 8)]])
 
 LRU_MUTANTS = [
@@ -186,6 +188,21 @@ LRU_MUTANTS = [
      'seq.append(("B", k, j, tid, k))\n            seq.append(("A", i, k, tid, k))'),
     ("task id decoded column-major", "i, j = tid // n_j, tid % n_j", "i, j = tid % n_i, tid // n_i"),
     ("automatic strip one too wide", "return min(n_j, max(1, n_slots // n_k - 2))", "return min(n_j, max(1, n_slots // n_k - 1))"),
+    ("next use: the nearest leaves", "                    if ahead > best:", "                    if ahead < best or best < 0:"),
+    ("next use: distance counted backwards", "ahead = min((u - t - 1) % period for u in where[cand])", "ahead = min((t - u - 1) % period for u in where[cand])"),
+    ("next use: the later of a key's lookups counts", "ahead = min((u - t - 1) % period for u in where[cand])", "ahead = max((u - t - 1) % period for u in where[cand])"),
+    ("next use: no wrap-around into the next sweep", "ahead = min((u - t - 1) % period for u in where[cand])",
+     "ahead = min(((u - t - 1) if u > t else 10 ** 9) for u in where[cand])"),
+    ("next use: the current group may be evicted", "                    if cand in current:\n                        continue\n", ""),
+    ("next use: one slot too many", "            if len(resident) >= n_slots:", "            if len(resident) > n_slots:"),
+    ("next use: victim stays resident", "                resident.discard(victim)\n", ""),
+    ("sweep: forward by tile rows", "        for c in range(n_c):\n            groups.append([(l, r, c) for r in range(n_r)])",
+     "        for r in range(n_r):\n            groups.append([(l, r, c) for c in range(n_c)])"),
+    ("sweep: backward layers ascending", "    for l in range(L, 0, -1):", "    for l in range(1, L + 1):"),
+    ("sweep: backward by tile columns", "        for r in range(n_r):\n            groups.append([(l, r, c) for c in range(n_c)])",
+     "        for c in range(n_c):\n            groups.append([(l, r, c) for r in range(n_r)])"),
+    ("sweep: tile counts rounded down", "        n_r, n_c = _ceil_div(dims[l - 1], T), _ceil_div(dims[l], T)\n        for c in range(n_c):",
+     "        n_r, n_c = dims[l - 1] // T, dims[l] // T\n        for c in range(n_c):"),
 ]
 
 PLAN_MUTANTS = [

@@ -226,3 +226,134 @@ def test_station_leaves_by_priority(oracle):
                 keys += [("A", tid // n_j, k), ("B", k, tid % n_j)]
         assert ev == oracle.lru_simulate(keys, slots)[0]
     assert reordered >= 5      # the priority did change the order in a fair share of the cases
+
+
+# ---- replacement by next use on the cyclic sweep of an out-of-core training step --------------------
+
+def _min_misses(seq, n_slots):
+    """Fewest misses any replacement policy can reach on the finite sequence, by exhaustive search
+    over every eviction choice (memoised on position and cache content)."""
+    from functools import lru_cache
+
+    @lru_cache(maxsize=None)
+    def go(t, cache):
+        if t == len(seq):
+            return 0
+        key = seq[t]
+        if key in cache:
+            return go(t + 1, cache)
+        if len(cache) < n_slots:
+            return 1 + go(t + 1, cache | {key})
+        return 1 + min(go(t + 1, (cache - {v}) | {key}) for v in cache)
+
+    return go(0, frozenset())
+
+
+def test_next_use_is_optimal_on_every_small_sweep(oracle):
+    """Evicting the key needed furthest ahead is Belady's rule, which reaches the minimum number of
+    misses on every prefix of a sequence; so on m repetitions of a sweep the simulation must meet the
+    exhaustive-search minimum exactly.  All sweeps of length <= 5 over <= 4 keys, 1..3 slots."""
+    import itertools
+    checked = 0
+    for n_keys in (2, 3, 4):
+        for length in range(n_keys, 6):
+            for sweep in itertools.product(range(n_keys), repeat=length):
+                if len(set(sweep)) != n_keys or sweep[0] != 0:
+                    continue
+                for n_slots in range(1, n_keys + 1):
+                    for m in (1, 2, 3):
+                        _, st = oracle.next_use_simulate([[k] for k in sweep], n_slots, n_sweeps=m)
+                        assert st["misses"] == _min_misses(sweep * m, n_slots), (sweep, n_slots, m)
+                        assert st["hits"] + st["misses"] == m * length
+                        checked += 1
+    assert checked > 1500
+
+
+def test_next_use_worked_example_and_closed_forms(oracle):
+    # sweep a b c, two slots: c evicts b (needed two lookups ahead, a one); a hits; b evicts a; c hits;
+    # a evicts c; b hits: from then on every other lookup misses, the rate (n - s) / (n - 1) of a
+    # cyclic sweep of n keys through s slots
+    ev, st = oracle.next_use_simulate([["a"], ["b"], ["c"]], 2, n_sweeps=3)
+    assert ev == [(False, None), (False, None), (False, "b"), (True, None), (False, "a"), (True, None),
+                  (False, "c"), (True, None), (False, "b")]
+    assert st == dict(hits=3, misses=6, evictions=4)
+    for n, s in ((5, 2), (7, 3), (9, 8), (6, 5)):
+        m = 4 * (n - 1)
+        _, st = oracle.next_use_simulate([[k] for k in range(n)], s, n_sweeps=m + 1)
+        _, st1 = oracle.next_use_simulate([[k] for k in range(n)], s, n_sweeps=1)
+        assert st["misses"] - st1["misses"] == m * n * (n - s) // (n - 1), (n, s)      # steady state, whole cycles
+    # room for every key: compulsory misses only, like LRU; one slot: every lookup of a changing key misses
+    seq = [[0], [1], [2], [1], [0]]
+    _, st = oracle.next_use_simulate(seq, 3, n_sweeps=4)
+    assert st == dict(hits=17, misses=3, evictions=0)
+    _, st = oracle.next_use_simulate(seq, 1, n_sweeps=2)
+    assert st["misses"] == 9 and st["hits"] == 1                                       # 0 ... 0 | 0: the wrap-around repeats key 0
+    # a sweep that runs forward and then back (the shape of a training step): the tile used last in the
+    # forward half is the first of the backward half, and LRU -- which must agree whenever the victim is
+    # forced -- never does better
+    fb = [[k] for k in range(6)] + [[k] for k in range(5, -1, -1)]
+    for s in range(1, 7):
+        _, st = oracle.next_use_simulate(fb, s, n_sweeps=3)
+        _, lru = oracle.lru_simulate([g[0] for g in fb] * 3, s)
+        assert st["misses"] <= lru["misses"], s
+        if s in (1, 6):
+            assert st == lru
+
+
+def test_next_use_against_explicit_scan_with_groups(oracle):
+    """The same rule with independent machinery: the future is written out as a list, every resident
+    key's next occurrence is found by scanning it, the current group's keys are passed over; random
+    sweeps with repeated keys and ragged groups.  Also: no victim ever belongs to the group being
+    assembled, and every victim was resident."""
+    import random
+    rnd = random.Random(5)
+    for case in range(40):
+        n_keys = rnd.randint(3, 9)
+        groups = []
+        for _ in range(rnd.randint(2, 6)):
+            groups.append(rnd.sample(range(n_keys), rnd.randint(1, min(3, n_keys))))
+        biggest = max(len(g) for g in groups)
+        n_slots = rnd.randint(biggest + 1, n_keys + 1)     # one slot beyond the largest group: a victim always exists
+        n_sweeps = 3
+        events, st = oracle.next_use_simulate(groups, n_slots, n_sweeps)
+        flat = [k for g in groups for k in g]
+        owner = [gi for gi, g in enumerate(groups) for _ in g]
+        future = flat * (n_sweeps + 2)
+        cache, t = [], 0
+        for sweep in range(n_sweeps):
+            for pos, key in enumerate(flat):
+                hit, victim = events[t]
+                assert hit == (key in cache), (case, t)
+                if not hit:
+                    if len(cache) >= n_slots:
+                        ahead = {}
+                        for cand in cache:
+                            if cand in groups[owner[pos]]:
+                                continue
+                            ahead[cand] = future.index(cand, t + 1) - t
+                        want = max(ahead, key=lambda c: ahead[c])
+                        assert victim == want and victim in cache and victim not in groups[owner[pos]], (case, t)
+                        cache.remove(victim)
+                    else:
+                        assert victim is None
+                    cache.append(key)
+                t += 1
+        assert t == len(events) and st["misses"] == sum(1 for h, _ in events if not h)
+
+
+def test_mlp_sweep_written_out(oracle):
+    # 4 -> 6 -> 2 with T = 2: W_1 is 2 x 3 tiles, W_2 is 3 x 1
+    g = oracle.mlp_sweep_groups([4, 6, 2], 2)
+    assert g == [[(1, 0, 0), (1, 1, 0)], [(1, 0, 1), (1, 1, 1)], [(1, 0, 2), (1, 1, 2)],      # forward W_1 by tile columns
+                 [(2, 0, 0), (2, 1, 0), (2, 2, 0)],                                           # forward W_2
+                 [(2, 0, 0)], [(2, 1, 0)], [(2, 2, 0)],                                       # backward W_2 by tile rows
+                 [(1, 0, 0), (1, 0, 1), (1, 0, 2)], [(1, 1, 0), (1, 1, 1), (1, 1, 2)]]        # backward W_1
+    # without the update nothing needs W_1 in the backward pass
+    assert oracle.mlp_sweep_groups([4, 6, 2], 2, update=False) == g[:7]
+    # ragged sizes round up; every tile is looked up exactly twice per training step
+    for dims, T in (([5, 7, 3], 2), ([8192, 32768, 32768, 262144], 2048), ([10, 10], 3)):
+        g = oracle.mlp_sweep_groups(dims, T)
+        flat = [k for grp in g for k in grp]
+        tiles = sum(-(-dims[l] // T) * -(-dims[l + 1] // T) for l in range(len(dims) - 1))
+        assert len(flat) == 2 * tiles and len(set(flat)) == tiles
+        assert all(flat.count(k) == 2 for k in set(flat)) if tiles < 100 else True
