@@ -80,6 +80,13 @@ typedef struct tgemm_opts {
                               n tasks of the queue, and whenever a stream is free the one with the most
                               input tiles (A_ik and B_kj over all k) in the tile cache leaves first, ties
                               going to the one that entered first */
+    int32_t exact_replacement; /* out-of-core MLP weight cache: 1: the victim of a miss is always the cached
+                              tile (outside the launch being assembled) whose next use in the step's
+                              sweep lies furthest ahead -- a pure function of sizes, T and slot count.
+                              0 (default): among the tiles whose next use is at least half as far as
+                              that, one with no read or write-back in flight is preferred, so that
+                              fetches keep running ahead of the products; which tile that is depends
+                              on timing, the number of misses need not */
 } tgemm_opts;
 
 /* One output tile C_ij = one task (section 3.1; Algorithm 1, "decode").
@@ -174,6 +181,21 @@ int tgemm_plan(int64_t M, int64_t N, int64_t K, int32_t T, tgemm_task* out, int6
 /* Issue order of the task ids for an n_i x n_j task grid under `order` (`strip` >= 1 is the strip
  * width of TGEMM_ORDER_STRIPS and ignored otherwise); writes n_i * n_j ids. */
 int tgemm_task_order(int64_t n_i, int64_t n_j, int32_t order, int64_t strip, int64_t* out_ids);
+
+/* One weight-tile lookup of an out-of-core mlp_forward / mlp_backward / mlp_step, in issue order
+ * (section 3.4: a hit uses the cached copy, a miss fetches the tile from host memory).
+ * A training step looks tiles up in a fixed sweep: forward, layers ascending, one launch group per
+ * tile column of W_l with its tiles by ascending tile row; backward, layers descending, one group per
+ * tile row of W_l with its tiles by ascending tile column (without an update the first layer has no
+ * backward lookups). */
+typedef struct tgemm_mlp_trace_rec {
+    int64_t group;          /* running number of the launch group since the object was created */
+    int32_t layer, r, c;    /* tile (r, c) of W_layer, layer = 1 .. n_layers                     */
+    int32_t backward;       /* 1: the lookup belongs to the backward sweep                        */
+    int32_t hit;            /* 1: found in the cache                                              */
+    int32_t slot;           /* cache slot that holds the tile from now on                         */
+    int32_t ev_layer, ev_r, ev_c; /* the tile the fetch displaced, or -1, -1, -1                  */
+} tgemm_mlp_trace_rec;
 
 /* Statistics of the last tgemm_run / mlp_* call on the context. */
 int tgemm_last_stats(tgemm_ctx* ctx, tgemm_stats* out);
@@ -339,6 +361,10 @@ int mlp_backward(tgemm_mlp* mlp, const int32_t* labels, void* const* dW, float* 
  * epilogue (dW is never stored); every error D_{l-1} is formed from the pre-update W_l.
  *   loss  host pointer receiving the loss before the update (may be NULL). */
 int mlp_step(tgemm_mlp* mlp, const void* X, const int32_t* labels, int64_t batch, float lr, float* loss);
+
+/* Weight-tile lookups of the last mlp_forward / mlp_backward / mlp_step on an out-of-core network
+ * (requires opts.trace).  Copies min(cap, n) records; out may be NULL when cap == 0. */
+int mlp_trace(tgemm_mlp* mlp, tgemm_mlp_trace_rec* out, int64_t cap, int64_t* n);
 
 /* Test access to the object's device workspaces after a forward / backward:
  *   what 0: activation A_l (l = 1..n_layers-1; batch x dims[l], dtype elements)

@@ -183,23 +183,33 @@ def mlp_step_master(X, Ws, y, lr, masters, act="sigmoid", mu=None, Vs=None):
     return loss, bits, new_M, exact, vel
 
 
-def _rows_times(R, W, transpose=False, block=4096):
+def _rows_times(R, W, transpose=False, block=4096, workers=1):
     """R @ W (or R @ W^T with transpose) in fp64 without ever holding the fp64 image of all of W: the
     output index (columns of W; rows of W with transpose) is walked in blocks, the inner dimension
-    is never split."""
+    is never split.  workers > 1 only hands the independent blocks to a thread pool."""
     W = np.asarray(W)
     n_out = W.shape[0] if transpose else W.shape[1]
     out = np.empty((R.shape[0], n_out), dtype=np.float64)
-    for o0 in range(0, n_out, block):
+
+    def one_block(o0):
         o1 = min(n_out, o0 + block)
         if transpose:
             out[:, o0:o1] = R @ _f64(W[o0:o1, :]).T
         else:
             out[:, o0:o1] = R @ _f64(np.ascontiguousarray(W[:, o0:o1]))
+
+    starts = range(0, n_out, block)
+    if workers > 1:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(workers) as pool:
+            list(pool.map(one_block, starts))
+    else:
+        for o0 in starts:
+            one_block(o0)
     return out
 
 
-def mlp_rows(X_rows, Ws, y_rows, batch, act="sigmoid", block=4096):
+def mlp_rows(X_rows, Ws, y_rows, batch, act="sigmoid", block=4096, workers=1):
     """Forward and backward quantities of the batch rows given (X_rows: r x n_0, y_rows: r labels) of a
     step whose whole batch has `batch` samples.  Returns (acts, logits, probs, loss_rows, deltas):
     acts[l] the input of layer l+1 (acts[0] = X_rows), loss_rows[b] = -log P[b, y_b], deltas[l] the
@@ -209,7 +219,7 @@ def mlp_rows(X_rows, Ws, y_rows, batch, act="sigmoid", block=4096):
     L = len(Ws)
     z = None
     for l, W in enumerate(Ws):
-        z = _rows_times(a, W, block=block)
+        z = _rows_times(a, W, block=block, workers=workers)
         if l < L - 1:
             a = _act(z, act)
             acts.append(a)
@@ -227,5 +237,5 @@ def mlp_rows(X_rows, Ws, y_rows, batch, act="sigmoid", block=4096):
     for l in range(L - 1, -1, -1):
         deltas[l] = d
         if l > 0:
-            d = _rows_times(d, Ws[l], transpose=True, block=block) * _act_slope(pre[l], acts[l], act)
+            d = _rows_times(d, Ws[l], transpose=True, block=block, workers=workers) * _act_slope(pre[l], acts[l], act)
     return acts, z, probs, loss_rows, deltas

@@ -19,7 +19,7 @@ TGEMM_ROUND_NEAREST, TGEMM_ROUND_STOCHASTIC = 0, 1
 EXPORTS = [
     "tgemm_strerror", "tgemm_last_error", "tgemm_create", "tgemm_destroy", "tgemm_run", "tgemm_sync", "tgemm_invalidate",
     "tgemm_plan", "tgemm_task_order", "tgemm_last_stats", "tgemm_trace", "tgemm_queue_selftest",
-    "mlp_create", "mlp_destroy", "mlp_set_activation", "mlp_set_rounding", "mlp_set_bias", "mlp_set_momentum", "mlp_set_master_weights", "mlp_forward", "mlp_forward_static", "mlp_backward", "mlp_step", "mlp_read",
+    "mlp_create", "mlp_destroy", "mlp_set_activation", "mlp_set_rounding", "mlp_set_bias", "mlp_set_momentum", "mlp_set_master_weights", "mlp_forward", "mlp_forward_static", "mlp_backward", "mlp_step", "mlp_read", "mlp_trace",
 ]
 
 
@@ -27,7 +27,7 @@ class tgemm_opts(ctypes.Structure):
     _fields_ = [("trace", ctypes.c_int32), ("order", ctypes.c_int32), ("affinity_core", ctypes.c_int32),
                 ("async_incore", ctypes.c_int32), ("kernel_config", ctypes.c_int32),
                 ("strip_width", ctypes.c_int32), ("deferred_writeback", ctypes.c_int32),
-                ("rs_depth", ctypes.c_int32)]
+                ("rs_depth", ctypes.c_int32), ("exact_replacement", ctypes.c_int32)]
 
 
 class tgemm_task(ctypes.Structure):
@@ -47,6 +47,11 @@ class tgemm_trace_rec(ctypes.Structure):
     _fields_ = [("task_id", ctypes.c_int64)] + \
                [(n, ctypes.c_int32) for n in ("i", "j", "k", "stream", "a_hit", "b_hit", "a_slot", "b_slot",
                                               "a_evicted", "b_evicted")]
+
+
+class tgemm_mlp_trace_rec(ctypes.Structure):
+    _fields_ = [("group", ctypes.c_int64)] + \
+               [(n, ctypes.c_int32) for n in ("layer", "r", "c", "backward", "hit", "slot", "ev_layer", "ev_r", "ev_c")]
 
 
 class TgemmError(RuntimeError):
@@ -93,6 +98,7 @@ def load():
     lib.mlp_backward.argtypes = [vp, vp, P(vp), P(ctypes.c_float)]
     lib.mlp_step.argtypes = [vp, vp, vp, i64, ctypes.c_float, P(ctypes.c_float)]
     lib.mlp_read.argtypes = [vp, i32, i32, vp, sz, sz]
+    lib.mlp_trace.argtypes = [vp, P(tgemm_mlp_trace_rec), i64, P(i64)]
     for name in EXPORTS:
         if name not in ("tgemm_strerror", "tgemm_last_error"):
             getattr(lib, name).restype = ctypes.c_int
@@ -124,11 +130,12 @@ def tgemm_last_error():
 
 
 def tgemm_create(device=0, streams=None, trace=0, order=TGEMM_ORDER_STRIPS, affinity_core=-1,
-                 async_incore=0, kernel_config=0, strip_width=0, deferred_writeback=0, rs_depth=0):
+                 async_incore=0, kernel_config=0, strip_width=0, deferred_writeback=0, rs_depth=0,
+                 exact_replacement=0):
     lib = load()
     o = tgemm_opts(trace=trace, order=order, affinity_core=affinity_core, async_incore=async_incore,
                    kernel_config=kernel_config, strip_width=strip_width,
-                   deferred_writeback=deferred_writeback, rs_depth=rs_depth)
+                   deferred_writeback=deferred_writeback, rs_depth=rs_depth, exact_replacement=exact_replacement)
     arr = None
     if streams is not None:
         if len(streams) != 4:
@@ -259,3 +266,12 @@ def mlp_step(mlp, X, labels, batch, lr):
 
 def mlp_read(mlp, what, layer, dst, nbytes, offset=0):
     _check(load().mlp_read(mlp, what, layer, _p(dst), offset, nbytes))
+
+
+def mlp_trace(mlp):
+    lib = load()
+    n = ctypes.c_int64()
+    _check(lib.mlp_trace(mlp, None, 0, ctypes.byref(n)))
+    buf = (tgemm_mlp_trace_rec * max(1, n.value))()
+    _check(lib.mlp_trace(mlp, buf, n.value, ctypes.byref(n)))
+    return [{f: getattr(buf[t], f) for f, _ in tgemm_mlp_trace_rec._fields_} for t in range(n.value)]

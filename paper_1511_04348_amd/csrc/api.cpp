@@ -211,6 +211,10 @@ int tgemm_run(tgemm_ctx* ctx, const void* A, const void* B, void* C,
         return fail(TGEMM_EARG, "tgemm_run: A, B, C must be all device or all pinned host pointers");
 
     const int64_t n_i = (M + T - 1) / T, n_j = (N + T - 1) / T, n_k = (K + T - 1) / T;
+    // task ids, the task queue and the launch grid are sized by the task count
+    if (n_i * n_j > ((int64_t)1 << 31) || n_i * n_j * n_k > ((int64_t)1 << 40))
+        return fail(TGEMM_EARG, "tgemm_run: %lld x %lld x %lld tiles: more than 2^31 tasks (or 2^40 tile products); use a larger T",
+                    (long long)n_i, (long long)n_j, (long long)n_k);
     ctx->stats.n_tasks = n_i * n_j;
     ctx->stats.n_tile_gemms = n_i * n_j * n_k;
 

@@ -34,6 +34,8 @@
 #include <algorithm>
 #include <atomic>
 #include <chrono>
+#include <exception>
+#include <new>
 #include <thread>
 #include <unordered_map>
 #include <vector>
@@ -89,9 +91,11 @@ public:
         if (pool) (void)hipFree(pool);
     }
 
+    // The pool is exactly what the call's budget allows: a larger one left by an earlier call with a
+    // larger budget is given back first, so the device bytes held never exceed the current budget.
     int ensure_pool(size_t bytes)
     {
-        if (pool && pool_bytes >= bytes) return TGEMM_OK;
+        if (pool && pool_bytes == bytes) return TGEMM_OK;
         if (pool) {
             (void)hipFree(pool);
             pool = nullptr;
@@ -390,8 +394,26 @@ inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 }  // namespace
 
+static int run_out_of_core_body(tgemm_ctx* ctx, const void* A, const void* B, float* C, int64_t M, int64_t N,
+                                int64_t K, int32_t T, int32_t dtype, size_t hbm_budget);
+
 int run_out_of_core(tgemm_ctx* ctx, const void* A, const void* B, float* C, int64_t M, int64_t N,
                     int64_t K, int32_t T, int32_t dtype, size_t hbm_budget)
+{
+    // nothing thrown by the host containers or by std::thread may cross the C boundary
+    try {
+        return run_out_of_core_body(ctx, A, B, C, M, N, K, T, dtype, hbm_budget);
+    } catch (const std::bad_alloc&) {
+        return fail(TGEMM_ENOMEM, "tgemm_run: host allocation failed");
+    } catch (const std::exception& e) {
+        return fail(TGEMM_ENOMEM, "tgemm_run: %s", e.what());
+    } catch (...) {
+        return fail(TGEMM_ENOMEM, "tgemm_run: unexpected exception");
+    }
+}
+
+static int run_out_of_core_body(tgemm_ctx* ctx, const void* A, const void* B, float* C, int64_t M, int64_t N,
+                                int64_t K, int32_t T, int32_t dtype, size_t hbm_budget)
 {
     Run r;
     r.ctx = ctx;
@@ -440,7 +462,18 @@ int run_out_of_core(tgemm_ctx* ctx, const void* A, const void* B, float* C, int6
     if (ctx->opts.trace) ctx->trace.reserve((size_t)(n_tasks * r.n_k));
 
     // Algorithm 1 lines 3-4: the GPU computation thread; the caller thread is the producer
-    std::thread submit([&r] { r.submit_loop(); });
+    std::thread submit([&r] {
+        try {
+            r.submit_loop();
+        } catch (...) {     // host allocation inside the loop: report it, let the producer stop
+            if (r.rc == TGEMM_OK) {
+                r.rc = TGEMM_ENOMEM;
+                snprintf(r.err, sizeof r.err, "host allocation failed in the submit thread");
+            }
+            r.failed.store(true, std::memory_order_release);
+            for (int s = 0; s < 4; ++s) (void)hipStreamSynchronize(r.ctx->streams[s]);
+        }
+    });
     for (int64_t t = 0; t < n_tasks && !r.failed.load(std::memory_order_acquire); ++t)
         while (!queue.enqueue(order[(size_t)t]) && !r.failed.load(std::memory_order_acquire))
             std::this_thread::yield();   // pool full: the consumer is behind

@@ -8,7 +8,8 @@
 //
 // Two residency modes.  In-core: the weights are device matrices and every product is one launch
 // on stream 0.  Out-of-core: the weights stay in pinned host memory and are staged, T x T tile by
-// tile, through an HBM tile cache (strict LRU; section 3.4 of the paper) -- the kernels then take
+// tile, through an HBM tile cache (section 3.4 of the paper; the victim is the tile whose next use
+// in the step's fixed sweep lies furthest ahead, see WeightCache) -- the kernels then take
 // the weight operand as a table of tile pointers.  Streams form the same pipeline as in
 // tgemm_run: stream 0 fetches weight tiles (running ahead of the products), stream 1 computes,
 // stream 3 writes updated tiles back.  The forward pass walks W_l by tile columns (a column of
@@ -22,6 +23,7 @@
 #include <algorithm>
 #include <chrono>
 #include <deque>
+#include <new>
 #include <mutex>
 #include <unordered_map>
 #include <vector>
@@ -93,6 +95,7 @@ struct WeightCache {
     int n_slots = 0, n_used = 0;
     std::vector<WSlot> slots;
     std::unordered_map<int64_t, int> dir;
+    bool exact = false;                      // tgemm_opts.exact_replacement: the furthest next use, whatever is in flight
     int64_t period = 0;                      // accesses per training step (two per tile)
     int64_t launch_id = 0;                   // current launch group (one tile column / tile row)
     std::vector<int64_t> base_f, base_b;     // first sweep position of layer l, forward / backward
@@ -176,6 +179,16 @@ struct WeightCache {
     // trail the products by a long queue, and a fetch waiting for one holds up every later fetch).
     int pick_victim(int64_t cur)
     {
+        if (exact) {     // two tiles never share a sweep position, so there are no ties
+            int far = -1;
+            int64_t d_far = -1;
+            for (int i = 0; i < n_slots; ++i) {
+                if (slots[i].last_launch == launch_id) continue;
+                const int64_t d = next_use(slots[i], cur);
+                if (d > d_far) { d_far = d; far = i; }
+            }
+            return far;
+        }
         advance(reads, read_done);
         advance(flushes, flush_done);
         int64_t dmax = -1;
@@ -270,6 +283,7 @@ struct tgemm_mlp {
     tg::WeightCache cache;
     tg::TableRing ring;
     tg::RowStream vel_rows, master_rows;   // out-of-core networks with velocities / master copies
+    std::vector<tgemm_mlp_trace_rec> trace; // weight-tile lookups of the last call (tgemm_opts.trace)
 };
 
 namespace tg {
@@ -568,10 +582,15 @@ int acquire_tile(tgemm_mlp* m, int l, int64_t r, int64_t c, bool bwd, int* slot_
     const int64_t n_r = cdiv(m->dims[l - 1], T), n_c = cdiv(nc, T);
     const int64_t pos_f = wc.base_f[(size_t)l] + c * n_r + r, pos_b = wc.base_b[(size_t)l] + r * n_c + c;
     auto it = wc.dir.find(key);
+    tgemm_mlp_trace_rec rec;
+    rec.group = wc.launch_id;
+    rec.layer = l; rec.r = (int32_t)r; rec.c = (int32_t)c; rec.backward = bwd ? 1 : 0;
+    rec.ev_layer = rec.ev_r = rec.ev_c = -1;
     if (it != wc.dir.end()) {
         wc.slots[it->second].last_launch = wc.launch_id;
         ctx->stats.hits++;
         *slot_out = it->second;
+        if (ctx->opts.trace) { rec.hit = 1; rec.slot = it->second; m->trace.push_back(rec); }
         return TGEMM_OK;
     }
     ctx->stats.misses++;
@@ -583,6 +602,7 @@ int acquire_tile(tgemm_mlp* m, int l, int64_t r, int64_t c, bool bwd, int* slot_
         if (slot < 0) return fail(TGEMM_EBUDGET, "mlp: the weight-tile cache cannot hold the tiles of one launch");
         WSlot& s = wc.slots[slot];
         wc.dir.erase(s.key);
+        rec.ev_layer = (int32_t)(s.key >> 56); rec.ev_r = (int32_t)((s.key >> 28) & 0xfffffff); rec.ev_c = (int32_t)(s.key & 0xfffffff);
         ctx->stats.evictions++;
         (void)wc.settled(s);      // the flags are fresh: a pending one's event has not been recycled
         if (s.read_pending) TG_HIP(hipStreamWaitEvent(fetch, s.read, 0));
@@ -603,6 +623,7 @@ int acquire_tile(tgemm_mlp* m, int l, int64_t r, int64_t c, bool bwd, int* slot_
     TG_HIP(hipEventRecord(s.ready, fetch));
     s.fetch_seq = ++wc.fetch_issue;
     *slot_out = slot;
+    if (ctx->opts.trace) { rec.hit = 0; rec.slot = slot; m->trace.push_back(rec); }
     return TGEMM_OK;
 }
 
@@ -1010,9 +1031,26 @@ int check_batch(tgemm_mlp* m, const void* X, int64_t batch)
     return TGEMM_OK;
 }
 
+// After a pass that failed part-way: wait for whatever was enqueued (ignoring further errors) and
+// forget the pass, so that nothing runs on half-overwritten activations afterwards.
+void abandon_pass(tgemm_mlp* m)
+{
+    (void)hipSetDevice(m->ctx->device);
+    for (int s = 0; s < 4; ++s) (void)hipStreamSynchronize(m->ctx->streams[s]);
+    (void)hipGetLastError();
+    for (auto& s : m->cache.slots) s.read_pending = s.flush_pending = false;
+    m->cache.all_reads_done();
+    m->cache.all_flushes_done();
+    m->cache.fetch_waited = m->cache.fetch_issue;
+    for (auto& u : m->ring.used) u = false;
+    m->batch = 0;
+    m->have_delta = false;
+}
+
 void begin_call(tgemm_mlp* m)
 {
     memset(&m->ctx->stats, 0, sizeof m->ctx->stats);
+    m->trace.clear();
     m->ctx->stats.in_core = m->ooc ? 0 : 1;
     m->ctx->stats.n_slots = m->cache.n_slots;
 }
@@ -1055,6 +1093,7 @@ int mlp_create(tgemm_ctx* ctx, tgemm_mlp** out, int32_t n_layers, const int64_t*
     m->T = T;
     m->budget = hbm_budget;
     m->ooc = n_host > 0;
+    m->cache.exact = ctx->opts.exact_replacement != 0;
     m->act.assign(n_layers + 1, nullptr);
     m->delta.assign(n_layers + 1, nullptr);
     *out = m;
@@ -1185,7 +1224,7 @@ int mlp_destroy(tgemm_mlp* m)
     return TGEMM_OK;
 }
 
-int mlp_forward(tgemm_mlp* m, const void* X, int64_t batch, float* probs)
+static int mlp_forward_body(tgemm_mlp* m, const void* X, int64_t batch, float* probs)
 {
     int rc = check_batch(m, X, batch);
     if (rc != TGEMM_OK) return rc;
@@ -1200,7 +1239,7 @@ int mlp_forward(tgemm_mlp* m, const void* X, int64_t batch, float* probs)
     return TGEMM_OK;
 }
 
-int mlp_forward_static(tgemm_mlp* m, const void* X, int64_t batch, float* probs)
+static int mlp_forward_static_body(tgemm_mlp* m, const void* X, int64_t batch, float* probs)
 {
     int rc = check_batch(m, X, batch);
     if (rc != TGEMM_OK) return rc;
@@ -1238,7 +1277,7 @@ int mlp_forward_static(tgemm_mlp* m, const void* X, int64_t batch, float* probs)
     return TGEMM_OK;
 }
 
-int mlp_backward(tgemm_mlp* m, const int32_t* labels, void* const* dW, float* loss)
+static int mlp_backward_body(tgemm_mlp* m, const int32_t* labels, void* const* dW, float* loss)
 {
     if (!m || !labels) return fail(TGEMM_EARG, "mlp_backward: NULL argument");
     if (m->batch <= 0) return fail(TGEMM_ESTATE, "mlp_backward: no forward pass precedes");
@@ -1255,7 +1294,7 @@ int mlp_backward(tgemm_mlp* m, const int32_t* labels, void* const* dW, float* lo
     return TGEMM_OK;
 }
 
-int mlp_step(tgemm_mlp* m, const void* X, const int32_t* labels, int64_t batch, float lr, float* loss)
+static int mlp_step_body(tgemm_mlp* m, const void* X, const int32_t* labels, int64_t batch, float lr, float* loss)
 {
     int rc = check_batch(m, X, batch);
     if (rc != TGEMM_OK) return rc;
@@ -1283,6 +1322,15 @@ int mlp_step(tgemm_mlp* m, const void* X, const int32_t* labels, int64_t batch, 
     return TGEMM_OK;
 }
 
+int mlp_trace(tgemm_mlp* m, tgemm_mlp_trace_rec* out, int64_t cap, int64_t* n)
+{
+    if (!m || !n || cap < 0 || (cap > 0 && !out)) return fail(TGEMM_EARG, "mlp_trace: bad argument");
+    *n = (int64_t)m->trace.size();
+    const int64_t k = cap < *n ? cap : *n;
+    if (k > 0) memcpy(out, m->trace.data(), (size_t)k * sizeof(tgemm_mlp_trace_rec));
+    return TGEMM_OK;
+}
+
 int mlp_read(tgemm_mlp* m, int32_t what, int32_t layer, void* dst, size_t offset, size_t bytes)
 {
     if (!m || !dst) return fail(TGEMM_EARG, "mlp_read: NULL argument");
@@ -1303,5 +1351,31 @@ int mlp_read(tgemm_mlp* m, int32_t what, int32_t layer, void* dst, size_t offset
     TG_HIP(hipMemcpy(dst, (const char*)src + offset, bytes, hipMemcpyDeviceToHost));
     return TGEMM_OK;
 }
+
+// The public forms: no exception crosses the C boundary, and after any error everything that was
+// enqueued has finished and the object holds no half-made pass (the next call starts from a clean
+// state; mlp_backward then reports TGEMM_ESTATE until a forward pass has succeeded).
+#define TG_GUARDED(m, call)                                                                   \
+    int rc_;                                                                                  \
+    try { rc_ = (call); }                                                                     \
+    catch (const std::bad_alloc&) { rc_ = fail(TGEMM_ENOMEM, "mlp: host allocation failed"); } \
+    catch (...) { rc_ = fail(TGEMM_EHIP, "mlp: unexpected exception"); }                      \
+    /* argument and call-order errors are reported before any work: a pending pass stays usable */ \
+    if (rc_ != TGEMM_OK && rc_ != TGEMM_EARG && rc_ != TGEMM_ESTATE && (m)) abandon_pass(m);  \
+    return rc_
+
+int mlp_forward(tgemm_mlp* m, const void* X, int64_t batch, float* probs) { TG_GUARDED(m, mlp_forward_body(m, X, batch, probs)); }
+int mlp_forward_static(tgemm_mlp* m, const void* X, int64_t batch, float* probs)
+{
+    // leaves the object's own pass state alone, also on error (it has drained its stream itself)
+    try { return mlp_forward_static_body(m, X, batch, probs); }
+    catch (...) { return fail(TGEMM_EHIP, "mlp_forward_static: unexpected exception"); }
+}
+int mlp_backward(tgemm_mlp* m, const int32_t* labels, void* const* dW, float* loss) { TG_GUARDED(m, mlp_backward_body(m, labels, dW, loss)); }
+int mlp_step(tgemm_mlp* m, const void* X, const int32_t* labels, int64_t batch, float lr, float* loss)
+{
+    TG_GUARDED(m, mlp_step_body(m, X, labels, batch, lr, loss));
+}
+#undef TG_GUARDED
 
 }  // extern "C"

@@ -10,7 +10,8 @@ int main(void)
     int64_t ids[12];
     int32_t popped[1000];
     int i, rc;
-    printf("sizes %zu %zu %zu %zu\n", sizeof(tgemm_opts), sizeof(tgemm_task), sizeof(tgemm_stats), sizeof(tgemm_trace_rec));
+    printf("sizes %zu %zu %zu %zu %zu\n", sizeof(tgemm_opts), sizeof(tgemm_task), sizeof(tgemm_stats), sizeof(tgemm_trace_rec),
+           sizeof(tgemm_mlp_trace_rec));
     rc = tgemm_task_order(3, 4, TGEMM_ORDER_SERPENTINE, 1, ids);
     if (rc != TGEMM_OK) { printf("task_order failed: %s\n", tgemm_last_error()); return 1; }
     printf("order");

@@ -29,10 +29,11 @@ def test_exports_match_header(lib):
 
 
 def test_struct_sizes():
-    assert ctypes.sizeof(tg.tgemm_opts) == 32
+    assert ctypes.sizeof(tg.tgemm_opts) == 36
     assert ctypes.sizeof(tg.tgemm_task) == 64
     assert ctypes.sizeof(tg.tgemm_stats) == 96
     assert ctypes.sizeof(tg.tgemm_trace_rec) == 48
+    assert ctypes.sizeof(tg.tgemm_mlp_trace_rec) == 48
 
 
 @pytest.mark.parametrize("M,N,K,T", [(1000, 1000, 1000, 256), (8000, 8000, 8000, 1024), (65536, 65536, 65536, 4096),
@@ -108,7 +109,7 @@ def test_header_is_plain_c_and_links_from_c(lib, tmp_path):
     r = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=120)
     assert r.returncode == 0, r.stdout
     out = r.stdout.splitlines()
-    sizes = [ctypes.sizeof(t) for t in (tg.tgemm_opts, tg.tgemm_task, tg.tgemm_stats, tg.tgemm_trace_rec)]
+    sizes = [ctypes.sizeof(t) for t in (tg.tgemm_opts, tg.tgemm_task, tg.tgemm_stats, tg.tgemm_trace_rec, tg.tgemm_mlp_trace_rec)]
     assert out[0] == "sizes " + " ".join(str(s) for s in sizes)
     assert out[1] == "order 0 1 2 3 7 6 5 4 8 9 10 11"
     assert out[2].startswith("bad order -> %d" % tg.TGEMM_EARG)

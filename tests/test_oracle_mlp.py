@@ -348,7 +348,7 @@ def test_rows_equal_the_whole_batch_pass(oracle):
             acts, z, P = oracle.mlp_forward(Xc, Wc, act)
             _, _, deltas = oracle.mlp_backward(Xc, Wc, y, act)
             for block in (1, 4, 5, 64):
-                a_r, z_r, P_r, loss_r, d_r = oracle.mlp_rows(Xc[rows], Wc, y[rows], B, act, block=block)
+                a_r, z_r, P_r, loss_r, d_r = oracle.mlp_rows(Xc[rows], Wc, y[rows], B, act, block=block, workers=1 + block % 3)
                 for l in range(len(dims) - 1):
                     assert np.allclose(a_r[l], acts[l][rows], rtol=1e-13, atol=1e-15), ("act", l, block)
                     assert np.allclose(d_r[l], deltas[l][rows], rtol=1e-12, atol=1e-18), ("delta", l, block)
