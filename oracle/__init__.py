@@ -20,6 +20,6 @@ and the tile counts the paper prints; nothing is "parity unpinned".
 from .build import build_oracle, lib_path  # noqa: F401
 from .gemm import gemm, gemm_tiled, gemm_samples, num_threads, bf16_to_f64  # noqa: F401
 from .plan import plan_tiles, tile_counts, decode_task, kstep_ranges  # noqa: F401
-from .lru import lru_simulate, tgemm_access_sequence, task_order, auto_strip, station_simulate, next_use_simulate, mlp_sweep_groups  # noqa: F401
+from .lru import Invalidate, lru_simulate, tgemm_access_sequence, task_order, auto_strip, station_simulate, next_use_simulate, mlp_sweep_groups  # noqa: F401
 from .mlp import mlp_forward, mlp_backward, mlp_step, mlp_step_stochastic, mlp_step_momentum, mlp_step_master, mlp_loss, mlp_rows  # noqa: F401
 from .rounding import mix32, step_key, rounding_bits, stochastic_round_bf16, stochastic_round_matrix, round_bf16_nearest  # noqa: F401

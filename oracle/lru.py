@@ -61,6 +61,16 @@ def tgemm_access_sequence(M, N, K, T, order="serpentine", strip=None):
     return seq
 
 
+class Invalidate:
+    """Marker inside a lookup sequence: the caller has changed host matrix `name`, so every cached tile
+    of it (every key whose first component equals `name`) is dropped and its slot is free again.
+    Section 3.4 keeps tiles cached for reuse; a cached copy of a matrix that has since changed must not
+    be used.  The marker is no lookup: it produces no event and counts in no statistic."""
+
+    def __init__(self, name):
+        self.name = name
+
+
 class _Lru:
     """Strict LRU over hashable keys with `n_slots` entries; a lookup touches the key."""
 
@@ -89,15 +99,25 @@ class _Lru:
         cache[key] = True
         return (False, victim)
 
+    def drop(self, name):
+        for key in [k for k in self.cache if k[0] == name]:
+            del self.cache[key]
+
     def stats(self):
         return dict(hits=self.hits, misses=self.misses, evictions=self.evictions)
 
 
 def lru_simulate(keys, n_slots):
     """Runs strict LRU over hashable keys.  Returns (events, stats); events[t] =
-    (hit, evicted_key_or_None)."""
+    (hit, evicted_key_or_None) for the t-th lookup.  Invalidate markers among the keys drop a
+    matrix's tiles and produce no event."""
     lru = _Lru(n_slots)
-    events = [lru.lookup(key) for key in keys]
+    events = []
+    for key in keys:
+        if isinstance(key, Invalidate):
+            lru.drop(key.name)
+        else:
+            events.append(lru.lookup(key))
     return events, lru.stats()
 
 

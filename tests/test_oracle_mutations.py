@@ -129,19 +129,18 @@ MLP_MUTANTS = [
      "[g + np.asarray(V, dtype=np.float64) for g, V in zip(dWs, Vs)]"),
     ("bias update without lr", "new_bs = [np.asarray(b, dtype=np.float64) - lr * g for b, g in zip(bs, dbs)]",
      "new_bs = [np.asarray(b, dtype=np.float64) - g for b, g in zip(bs, dbs)]"),
-    ("rows: block product drops the transposition", "            out[:, o0:o1] = R @ _f64(W[o0:o1, :]).T", "            out[:, o0:o1] = R @ _f64(W[:, o0:o1])"),
+    ("rows: block product drops the transposition", "            out[:, o0:o1] = R @ _f64(W[o0:o1, :]).T\n", "            out[:, o0:o1] = R @ _f64(W[:, o0:o1])\n"),
     ("rows: blocks land one block late", "            out[:, o0:o1] = R @ _f64(np.ascontiguousarray(W[:, o0:o1]))",
      "            out[:, o0:o1] = R @ _f64(np.ascontiguousarray(W[:, max(0, o0 - (o1 - o0)):max(0, o0 - (o1 - o0)) + o1 - o0]))"),
-    ("rows: last block dropped", "    for o0 in range(0, n_out, block):\n        o1 = min(n_out, o0 + block)\n        if transpose:",
-     "    for o0 in range(0, n_out - block + 1, block):\n        o1 = min(n_out, o0 + block)\n        if transpose:"),
+    ("rows: last block dropped", "    starts = range(0, n_out, block)\n", "    starts = range(0, n_out - block + 1, block)\n"),
     ("rows: softmax without the row sum", "    probs = e / e.sum(axis=1)[:, None]", "    probs = e / e.sum()"),
     ("rows: one-hot sign", "    d[r, y] -= 1.0", "    d[r, y] += 1.0"),
     ("rows: divided by the number of rows given", "    d /= batch\n", "    d /= z.shape[0]\n"),
     ("rows: loss without the label's logit", "    loss_rows = zmax[:, 0] + np.log(e.sum(axis=1)) - z[r, y]", "    loss_rows = zmax[:, 0] + np.log(e.sum(axis=1))"),
-    ("rows: slope dropped", "            d = _rows_times(d, Ws[l], transpose=True, block=block) * _act_slope(pre[l], acts[l], act)",
-     "            d = _rows_times(d, Ws[l], transpose=True, block=block)"),
-    ("rows: error through the wrong layer's weights", "            d = _rows_times(d, Ws[l], transpose=True, block=block) * _act_slope(pre[l], acts[l], act)",
-     "            d = _rows_times(d, Ws[l], transpose=True, block=block) * _act_slope(pre[l - 1] if l > 1 else pre[l], acts[l - 1] if l > 1 else acts[l], act)"),
+    ("rows: slope dropped", "            d = _rows_times(d, Ws[l], transpose=True, block=block, workers=workers) * _act_slope(pre[l], acts[l], act)",
+     "            d = _rows_times(d, Ws[l], transpose=True, block=block, workers=workers)"),
+    ("rows: error through the wrong layer's weights", "            d = _rows_times(d, Ws[l], transpose=True, block=block, workers=workers) * _act_slope(pre[l], acts[l], act)",
+     "            d = _rows_times(d, Ws[l], transpose=True, block=block, workers=workers) * _act_slope(pre[l - 1] if l > 1 else pre[l], acts[l - 1] if l > 1 else acts[l], act)"),
 ]
 
 
@@ -154,7 +153,7 @@ def test_mlp_mutant_is_caught(oracle, name, old, new):
 
 
 PLAN_LRU_PINS = ([(pins_plan.test_paper_tile_counts, ()), (pins_plan.test_edge_extents_config1, ()),
-                  (pins_plan.test_lru_closed_forms, ()), (pins_plan.test_lru_vs_brute_force, ()),
+                  (pins_plan.test_lru_closed_forms, ()), (pins_plan.test_lru_vs_brute_force, ()), (pins_plan.test_lru_invalidate, ()),
                   (pins_plan.test_access_sequence_structure, ()), (pins_plan.test_row_major_reuse_closed_form, ()),
                   (pins_plan.test_strips_order_written_out, ()), (pins_plan.test_strips_traffic_closed_form, ()),
                   (pins_plan.test_station_of_depth_one_is_queue_order, ()), (pins_plan.test_station_worked_example, ()),
@@ -188,6 +187,10 @@ LRU_MUTANTS = [
      'seq.append(("B", k, j, tid, k))\n            seq.append(("A", i, k, tid, k))'),
     ("task id decoded column-major", "i, j = tid // n_j, tid % n_j", "i, j = tid % n_i, tid // n_i"),
     ("automatic strip one too wide", "return min(n_j, max(1, n_slots // n_k - 2))", "return min(n_j, max(1, n_slots // n_k - 1))"),
+    ("invalidate: drops the other matrices", "        for key in [k for k in self.cache if k[0] == name]:", "        for key in [k for k in self.cache if k[0] != name]:"),
+    ("invalidate: drops everything", "        for key in [k for k in self.cache if k[0] == name]:", "        for key in list(self.cache):"),
+    ("invalidate: ignored", "            lru.drop(key.name)\n", "            pass\n"),
+    ("invalidate: counted as a lookup", "            lru.drop(key.name)\n", "            lru.drop(key.name)\n            events.append((False, None))\n"),
     ("next use: the nearest leaves", "                    if ahead > best:", "                    if ahead < best or best < 0:"),
     ("next use: distance counted backwards", "ahead = min((u - t - 1) % period for u in where[cand])", "ahead = min((t - u - 1) % period for u in where[cand])"),
     ("next use: the later of a key's lookups counts", "ahead = min((u - t - 1) % period for u in where[cand])", "ahead = max((u - t - 1) % period for u in where[cand])"),

@@ -98,6 +98,39 @@ def test_lru_vs_brute_force(oracle):
         assert st["hits"] + st["misses"] == len(keys)
 
 
+def test_lru_invalidate(oracle):
+    """Dropping a changed matrix's tiles: they miss at their next lookup, into the slots they freed (no
+    eviction); the other matrices' tiles stay and keep their recency; the marker itself is no event.
+    Then random sequences against an independent list-based LRU that handles the marker itself."""
+    keys = [("A", 0), ("B", 0), ("A", 1), ("B", 1), oracle.Invalidate("A"), ("B", 0), ("A", 0), ("A", 1), ("C", 0), ("B", 1)]
+    ev, st = oracle.lru_simulate(keys, 4)
+    assert ev == [(False, None)] * 4 + [(True, None), (False, None), (False, None), (False, ("B", 1)), (False, ("B", 0))]
+    assert st == dict(hits=1, misses=8, evictions=2)
+    # nothing cached of that matrix: the marker changes nothing
+    assert oracle.lru_simulate([("B", 0), oracle.Invalidate("A"), ("B", 0)], 2)[1] == dict(hits=1, misses=1, evictions=0)
+    import random
+    rnd = random.Random(3)
+    for n in (2, 3, 6):
+        keys = []
+        for _ in range(500):
+            keys.append(oracle.Invalidate(rnd.choice("AB")) if rnd.random() < 0.05 else (rnd.choice("AB"), rnd.randrange(5)))
+        order, want = [], []
+        for k in keys:
+            if isinstance(k, oracle.Invalidate):
+                order = [c for c in order if c[0] != k.name]
+                continue
+            if k in order:
+                order.remove(k)
+                order.append(k)
+                want.append((True, None))
+            else:
+                victim = order.pop(0) if len(order) == n else None
+                order.append(k)
+                want.append((False, victim))
+        ev, st = oracle.lru_simulate(keys, n)
+        assert ev == want and st["hits"] + st["misses"] == len(want)
+
+
 def test_access_sequence_structure(oracle):
     seq = oracle.tgemm_access_sequence(5, 7, 9, 2, order="row_major")
     n_i, n_j, n_k = 3, 4, 5
