@@ -87,6 +87,15 @@ typedef struct tgemm_opts {
                               that, one with no read or write-back in flight is preferred, so that
                               fetches keep running ahead of the products; which tile that is depends
                               on timing, the number of misses need not */
+    int32_t keep_tiles;    /* out-of-core tgemm_run: 1: A/B tiles stay in the tile cache from one call on the
+                              context to the next (section 3.4: tiles are cached for reuse), with their
+                              recency order, as long as tile size, slot sizes and slot count of the calls
+                              agree (a call with another geometry starts with an empty cache).  A cached
+                              tile is recognised by its host matrix (base pointer, shape, element size,
+                              T) and its tile indices.  The caller then owns coherence: after changing a
+                              host matrix that earlier calls have read (or reusing its memory for
+                              another matrix), call tgemm_invalidate before the next tgemm_run, or stale
+                              tiles are used.  0 (default): every call starts with an empty cache */
 } tgemm_opts;
 
 /* One output tile C_ij = one task (section 3.1; Algorithm 1, "decode").
@@ -154,19 +163,23 @@ int tgemm_destroy(tgemm_ctx* ctx);
  *      harvest overlap on the 4 streams with 4 tasks in flight.  Every
  *      device byte allocated for the call (A/B slots + 4 C slots) stays within hbm_budget bytes;
  *      the minimum is 4 C slots + 8 A/B slots (TGEMM_EBUDGET otherwise, before any work).
- *      The cache directory starts empty at every call (the pool of slots is kept): no tile survives
- *      from one call to the next, so the caller may change A and B between calls and no call to
- *      invalidate cached tiles is needed; on return no tile of C remains on the device only.
+ *      Unless tgemm_opts.keep_tiles is set, the cache directory starts empty at every call: no tile
+ *      survives from one call to the next, so the caller may change A and B between calls freely.
+ *      With keep_tiles see tgemm_invalidate.  C tiles are never kept: on return no tile of C remains
+ *      on the device only.  The slot pool is exactly what the call's budget allows (a larger one left
+ *      by an earlier call is given back first).
+ *   At most 2^31 tasks and 2^40 tile products (TGEMM_EARG above that: use a larger T).
  *   M, N or K == 0 is legal (C unchanged).
  * Errors: TGEMM_EARG, TGEMM_EUNPINNED, TGEMM_EBUDGET, TGEMM_ENOMEM, TGEMM_EHIP. */
 int tgemm_run(tgemm_ctx* ctx, const void* A, const void* B, void* C,
               int64_t M, int64_t N, int64_t K, int32_t T, int32_t dtype, size_t hbm_budget);
 
-/* Section 3.4 keeps tiles in the cache for later reuse; a caller who changes a host matrix would have
- * to have its cached tiles dropped.  In this library tgemm_run starts every call with an empty cache
- * directory, so no copy outlives a call and this function has nothing to drop: it checks its
- * arguments and returns TGEMM_OK.  It exists so that callers written for a cache that survives
- * calls need no change.  (Out-of-core MLP weights are different: see mlp_create.)
+/* Section 3.4 keeps tiles in GPU memory for later reuse.  With tgemm_opts.keep_tiles that holds across
+ * calls, and a caller who has changed a host matrix (or reused its memory) must have its cached tiles
+ * dropped: this call waits for the context's streams, then removes every cached tile of every matrix
+ * whose base pointer is host_base; their slots are free for the next fetches.  Without keep_tiles no
+ * tile outlives a call and there is nothing to drop (the call still succeeds).  Out-of-core MLP
+ * weights are not touched (see mlp_create).
  * TGEMM_EARG if ctx or host_base is NULL. */
 int tgemm_invalidate(tgemm_ctx* ctx, const void* host_base);
 

@@ -159,8 +159,10 @@ int tgemm_invalidate(tgemm_ctx* ctx, const void* host_base)
 {
     if (!ctx) return fail(TGEMM_EARG, "tgemm_invalidate: ctx is NULL");
     if (!host_base) return fail(TGEMM_EARG, "tgemm_invalidate: host_base is NULL");
-    // tgemm_run empties the tile cache directory at every call, so no copy of the caller's matrix
-    // outlives a call: there is never anything to drop
+    // only tgemm_opts.keep_tiles lets tiles outlive a call; without it there is never anything to drop
+    TG_HIP(hipSetDevice(ctx->device));
+    for (int s = 0; s < 4; ++s) TG_HIP(hipStreamSynchronize(ctx->streams[s]));
+    (void)invalidate_tiles(ctx, host_base);
     return TGEMM_OK;
 }
 

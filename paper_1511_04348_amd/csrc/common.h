@@ -48,4 +48,6 @@ namespace tg {
 int run_out_of_core(tgemm_ctx* ctx, const void* A, const void* B, float* C, int64_t M, int64_t N,
                     int64_t K, int32_t T, int32_t dtype, size_t hbm_budget);
 void destroy_engine(tgemm_ctx* ctx);
+// Drops the cached tiles of every matrix that starts at host_base; returns how many there were.
+int64_t invalidate_tiles(tgemm_ctx* ctx, const void* host_base);
 }  // namespace tg

@@ -49,15 +49,45 @@ namespace tg {
 
 namespace {
 
+// Identity of a cached tile: which host matrix (index into Engine::mats) and which tile of it.
+struct TileKey {
+    int32_t mat = -1;
+    int32_t ti = 0, tj = 0;
+    bool operator==(const TileKey& o) const { return mat == o.mat && ti == o.ti && tj == o.tj; }
+};
+struct TileKeyHash {
+    size_t operator()(const TileKey& k) const
+    {
+        uint64_t h = ((uint64_t)(uint32_t)k.ti << 32) | (uint32_t)k.tj;
+        h ^= (uint64_t)(uint32_t)k.mat * 0x9E3779B97F4A7C15ull;
+        h ^= h >> 29; h *= 0xBF58476D1CE4E5B9ull; h ^= h >> 32;
+        return (size_t)h;
+    }
+};
+// A host matrix as the cache knows it.  Two calls mean the same matrix when base pointer, shape,
+// element size and tile size agree (the same matrix may be the left operand of one product and the
+// right operand of another: a tile's layout in its slot depends on the matrix alone).
+struct HostMatrix {
+    const void* base;
+    int64_t rows, cols;
+    size_t es;
+    int64_t T;
+};
+
 struct Slot {
-    int64_t key = -1;
+    TileKey key;
     hipEvent_t ready = nullptr;
     hipEvent_t read_ev[2] = {nullptr, nullptr};     // last product on compute stream 0 / 1 that read the slot
     bool read_pending[2] = {false, false};
     int prev = -1, next = -1;
 };
 
-inline int64_t tile_key(int mat, int64_t ti, int64_t tj) { return ((int64_t)mat << 62) | (ti << 31) | tj; }
+inline TileKey tile_key(int mat, int64_t ti, int64_t tj)
+{
+    TileKey k;
+    k.mat = mat; k.ti = (int32_t)ti; k.tj = (int32_t)tj;
+    return k;
+}
 
 }  // namespace
 
@@ -72,9 +102,13 @@ public:
     hipEvent_t task_done[4] = {nullptr, nullptr, nullptr, nullptr};     // C_ij harvested
     bool task_pending[4] = {false, false, false, false};
     // directory + LRU list (head = least recently used)
-    std::unordered_map<int64_t, int> dir;
+    std::unordered_map<TileKey, int, TileKeyHash> dir;
     int lru_head = -1, lru_tail = -1;
-    int n_used = 0;
+    int n_used = 0;                 // slots handed out so far (slots below it are in use or on the free list)
+    std::vector<int> free_slots;    // slots emptied by tgemm_invalidate
+    std::vector<HostMatrix> mats;   // the matrices whose tiles the directory may hold
+    size_t geom_slot_ab = 0, geom_slot_c = 0;   // slot geometry the cached tiles were laid out for
+    int geom_n_ab = 0;
 
     ~Engine()
     {
@@ -130,14 +164,42 @@ public:
     void reset_directory()
     {
         dir.clear();
+        mats.clear();
+        free_slots.clear();
         lru_head = lru_tail = -1;
         n_used = 0;
         for (auto& s : slots) {
-            s.key = -1;
+            s.key = TileKey();
             s.prev = s.next = -1;
             for (auto& p : s.read_pending) p = false;
         }
         for (auto& p : task_pending) p = false;
+    }
+
+    int matrix_id(const void* base, int64_t rows, int64_t cols, size_t es, int64_t T)
+    {
+        for (size_t i = 0; i < mats.size(); ++i)
+            if (mats[i].base == base && mats[i].rows == rows && mats[i].cols == cols && mats[i].es == es && mats[i].T == T)
+                return (int)i;
+        mats.push_back(HostMatrix{base, rows, cols, es, T});
+        return (int)mats.size() - 1;
+    }
+
+    // Drops every cached tile of the matrices that start at `base`; their slots become free.
+    // Called between runs only (all streams idle), so nothing reads the slots any more.
+    int64_t invalidate(const void* base)
+    {
+        int64_t dropped = 0;
+        for (int i = 0; i < n_used; ++i) {
+            Slot& s = slots[i];
+            if (s.key.mat < 0 || mats[(size_t)s.key.mat].base != base) continue;
+            dir.erase(s.key);
+            lru_unlink(i);
+            s.key = TileKey();
+            free_slots.push_back(i);
+            ++dropped;
+        }
+        return dropped;
     }
 
     void lru_unlink(int i)
@@ -156,6 +218,11 @@ public:
         lru_tail = i;
     }
 };
+
+int64_t invalidate_tiles(tgemm_ctx* ctx, const void* host_base)
+{
+    return ctx->engine ? ctx->engine->invalidate(host_base) : 0;
+}
 
 void destroy_engine(tgemm_ctx* ctx)
 {
@@ -186,6 +253,7 @@ struct Run {
     int64_t n_issued = 0;      // tasks issued so far (alternates the compute stream)
     int copy_mode = 1;
     bool bf16 = false;
+    int mat_a = 0, mat_b = 1;  // directory ids of the two operand matrices
 
     char* ab_slot_ptr(int slot) const { return eng->pool + 4 * slot_c + (size_t)slot * slot_ab; }
     float* c_slot_ptr(int s) const { return (float*)(eng->pool + (size_t)s * slot_c); }
@@ -243,7 +311,7 @@ struct Run {
     {
         Engine& e = *eng;
         hipStream_t fetch = ctx->streams[0];
-        const int64_t key = tile_key(mat, ti, tj);
+        const TileKey key = tile_key(mat, ti, tj);
         auto it = e.dir.find(key);
         *evicted = 0;
         if (it != e.dir.end()) {
@@ -257,7 +325,10 @@ struct Run {
         *hit = 0;
         ctx->stats.misses++;
         int slot;
-        if (e.n_used < n_ab) {
+        if (!e.free_slots.empty()) {
+            slot = e.free_slots.back();
+            e.free_slots.pop_back();
+        } else if (e.n_used < n_ab) {
             slot = e.n_used++;
         } else {
             slot = e.lru_head;
@@ -303,8 +374,8 @@ struct Run {
         for (int64_t k = 0; k < n_k && rc == TGEMM_OK; ++k) {
             const int64_t k0 = k * T, klen = std::min(T, K - k0);
             int a_hit, b_hit, a_ev, b_ev;
-            const int sa = acquire(0, i, k, A + (r0 * K + k0) * es, K * es, klen * es, rows, tk * es, &a_hit, &a_ev);
-            const int sb = acquire(1, k, j, B + (k0 * N + c0) * es, N * es, cols * es, klen, tn * es, &b_hit, &b_ev);
+            const int sa = acquire(mat_a, i, k, A + (r0 * K + k0) * es, K * es, klen * es, rows, tk * es, &a_hit, &a_ev);
+            const int sb = acquire(mat_b, k, j, B + (k0 * N + c0) * es, N * es, cols * es, klen, tn * es, &b_hit, &b_ev);
             Slot& la = eng->slots[sa];
             Slot& lb = eng->slots[sb];
             check(hipStreamWaitEvent(comp, la.ready, 0), "hipStreamWaitEvent(A ready)");
@@ -377,7 +448,7 @@ struct Run {
                     const int64_t i = station[q] / n_j, j = station[q] % n_j;
                     int64_t score = 0;
                     for (int64_t k = 0; k < n_k; ++k)
-                        score += (int64_t)eng->dir.count(tile_key(0, i, k)) + (int64_t)eng->dir.count(tile_key(1, k, j));
+                        score += (int64_t)eng->dir.count(tile_key(mat_a, i, k)) + (int64_t)eng->dir.count(tile_key(mat_b, k, j));
                     if (score > best_score) { best_score = score; best = q; }
                 }
             }
@@ -444,7 +515,19 @@ static int run_out_of_core_body(tgemm_ctx* ctx, const void* A, const void* B, fl
     if (rc != TGEMM_OK) return rc;
     rc = r.eng->ensure_events(r.n_ab);
     if (rc != TGEMM_OK) return rc;
-    r.eng->reset_directory();
+    // Section 3.4 keeps tiles in GPU memory for reuse.  Across calls that is opt-in (tgemm_opts.keep_tiles):
+    // the directory, the recency order and the tiles survive as long as the slot geometry does; otherwise
+    // every call starts with an empty directory and a changed host matrix can never be seen stale.
+    Engine& e = *r.eng;
+    if (!ctx->opts.keep_tiles || e.geom_slot_ab != r.slot_ab || e.geom_slot_c != r.slot_c || e.geom_n_ab != r.n_ab ||
+        e.mats.size() > 4096)
+        e.reset_directory();
+    for (auto& sl : e.slots)          // the previous run ended with every stream idle
+        for (auto& p : sl.read_pending) p = false;
+    for (auto& p : e.task_pending) p = false;
+    e.geom_slot_ab = r.slot_ab; e.geom_slot_c = r.slot_c; e.geom_n_ab = r.n_ab;
+    r.mat_a = e.matrix_id(A, M, K, r.es, T);
+    r.mat_b = e.matrix_id(B, K, N, r.es, T);
     ctx->stats.n_slots = r.n_ab;
 
     // Algorithm 1 line 1: the task queue receives every task id in issue order

@@ -128,8 +128,11 @@ def test_error_paths(ctxs):
 
 
 def test_config2_sampled_parity_full_size(ctxs, oracle):
-    """fp32 8000^3, T = 1024 (832-wide edge tiles): every tile-corner entry and 4096 random
-    entries against fp64 dot products; an integer-valued run checked the same way, bit-exact."""
+    """fp32 8000^3, T = 1024 (832-wide edge tiles): the whole matrix against the oracle's untiled
+    fp64 triple loop (relative Frobenius and the largest entry error), every tile-corner entry and
+    4096 random entries against fp64 dot products, Freivalds' identity C x = A (B x) for random
+    +-1 vectors; an integer-valued run checked bit-exact on the samples and, through the same
+    identity, on every entry."""
     n, T = 8000, 1024
     A = inputs.uniform_matrix(1, n, n, device="cuda")
     B = inputs.uniform_matrix(2, n, n, device="cuda")
@@ -147,10 +150,22 @@ def test_config2_sampled_parity_full_size(ctxs, oracle):
     err = rel_fro(got, ref)
     print("config2 sampled rel fro", err, "kernel ms", tg.tgemm_last_stats(ctxs[0])["kernel_ms"])
     assert err <= TOL_F32
-    # column / row sums: C 1 = A (B 1) and 1^T C = (1^T A) B touch every entry of C
+    # the whole matrix: the oracle's definition, every one of the 6.4e7 entries (5.1e11 multiply-adds in fp64)
+    announce("config2 full oracle")
+    Cn = C.cpu().numpy()
+    full = oracle.gemm(An, Bn)
+    err_full = rel_fro(Cn, full)
+    worst = float(np.max(np.abs(Cn - full)))
+    print("config2 full-matrix rel fro", err_full, "largest entry error", worst, flush=True)
+    assert err_full <= TOL_F32
+    assert worst <= 64 * 2.0 ** -24 * float(np.max(np.abs(full)))      # no single entry is off by more than rounding
+    del full
+    # Freivalds: C x = A (B x) for random +-1 vectors; an error anywhere in C survives with probability 1/2 per vector
+    A64, B64 = An.astype(np.float64), Bn.astype(np.float64)
+    for trial in range(3):
+        x = rnd.choice([-1.0, 1.0], n)
+        assert rel_fro(Cn.astype(np.float64) @ x, A64 @ (B64 @ x)) <= TOL_F32, trial
     ones = np.ones(n)
-    assert rel_fro(C.double().sum(1).cpu().numpy(), An.astype(np.float64) @ (Bn.astype(np.float64) @ ones)) <= TOL_F32
-    assert rel_fro(C.double().sum(0).cpu().numpy(), (ones @ An.astype(np.float64)) @ Bn.astype(np.float64)) <= TOL_F32
     announce("config2 integer")
     Ai = inputs.int_matrix(31, n, n, device="cuda")
     Bi = inputs.int_matrix(32, n, n, device="cuda")
@@ -160,6 +175,10 @@ def test_config2_sampled_parity_full_size(ctxs, oracle):
     refi = oracle.gemm_samples(Ain, Bin, rows, cols)
     assert np.array_equal(Ci.cpu().numpy()[rows, cols].astype(np.float64), refi)
     assert np.array_equal(Ci.double().sum(1).cpu().numpy(), Ain.astype(np.float64) @ (Bin.astype(np.float64) @ ones))
+    Cin = Ci.cpu().numpy().astype(np.float64)
+    for trial in range(3):                        # integers in fp64: both sides exact
+        x = rnd.choice([-1.0, 1.0], n)
+        assert np.array_equal(Cin @ x, Ain.astype(np.float64) @ (Bin.astype(np.float64) @ x)), trial
 
 
 def test_seeded_random_shapes_integer_exact(ctxs, oracle):

@@ -188,6 +188,132 @@ def test_changed_host_matrix_is_seen_by_the_next_call(oracle):
         tg.tgemm_destroy(ctx)
 
 
+def _names_sequence(oracle, M, N, K, T, order_name, name_a, name_b, strip=None):
+    seq = oracle.tgemm_access_sequence(M, N, K, T, order=order_name, strip=strip)
+    return [((name_a if s[0] == "A" else name_b), s[1], s[2]) for s in seq]
+
+
+def test_tiles_survive_between_calls_and_invalidate_drops_them(oracle):
+    """tgemm_opts.keep_tiles (section 3.4: cached tiles are reused): a later call on the context finds
+    the tiles an earlier call left, recency order included; a matrix seen as the left operand is the
+    same matrix when it comes back as the right operand; tgemm_invalidate drops one matrix's tiles.
+    Hits, misses and evictions of every call equal the oracle's strict LRU run over the calls' lookups
+    put end to end (keys = matrix, tile row, tile column), with the invalidation marked; results are
+    bit-exact (integer inputs); without the invalidation a changed matrix is seen stale, which is the
+    caller's error in this mode and shows that the copy really was reused."""
+    n, T, n_ab = 640, 128, 30
+    announce("out-of-core GEMM: tiles kept across calls", n, T, n_ab)
+    X = inputs.int_matrix(1, n, n).pin_memory()
+    Y = inputs.int_matrix(2, n, n).pin_memory()
+    Z = inputs.int_matrix(3, n, n).pin_memory()
+    budget = _budget(T, n_ab, n, n, n)
+    ctx = tg.tgemm_create(0, trace=1, keep_tiles=1, order=tg.TGEMM_ORDER_SERPENTINE)
+    keys, calls = [], []
+
+    def run(A, name_a, B, name_b):
+        C = torch.zeros(n, n).pin_memory()
+        tg.tgemm_run(ctx, A, B, C, n, n, n, T, tg.TGEMM_F32, budget)
+        ks = _names_sequence(oracle, n, n, n, T, "serpentine", name_a, name_b)
+        keys.extend(ks)
+        calls.append((tg.tgemm_trace(ctx), tg.tgemm_last_stats(ctx), len(ks)))
+        return C
+
+    try:
+        C1 = run(X, "X", Y, "Y")
+        assert np.array_equal(C1.numpy().astype(np.float64), oracle.gemm(X.numpy(), Y.numpy()))
+        C2 = run(X, "X", Z, "Z")                     # X's tiles are still there
+        assert np.array_equal(C2.numpy().astype(np.float64), oracle.gemm(X.numpy(), Z.numpy()))
+        C3 = run(Z, "Z", X, "X")                     # the same matrices in the other roles
+        assert np.array_equal(C3.numpy().astype(np.float64), oracle.gemm(Z.numpy(), X.numpy()))
+        X_old = X.clone()
+        X.mul_(-2.0)                                 # the caller changes X ...
+        tg.tgemm_invalidate(ctx, X)                  # ... and says so
+        keys.append(oracle.Invalidate("X"))
+        C4 = run(Z, "Z", X, "X")
+        assert np.array_equal(C4.numpy().astype(np.float64), oracle.gemm(Z.numpy(), X.numpy()))
+        assert not torch.equal(X, X_old)
+    finally:
+        tg.tgemm_destroy(ctx)
+    events, _ = oracle.lru_simulate(keys, n_ab)
+    at = 0
+    reused = 0
+    for c, (trace, st, n_lookups) in enumerate(calls):
+        assert len(trace) * 2 == n_lookups and st["n_slots"] == n_ab
+        ev = events[at:at + n_lookups]
+        at += n_lookups
+        for t, rec in enumerate(trace):
+            assert bool(rec["a_hit"]) == ev[2 * t][0] and bool(rec["b_hit"]) == ev[2 * t + 1][0], (c, t)
+            assert bool(rec["a_evicted"]) == (ev[2 * t][1] is not None) and bool(rec["b_evicted"]) == (ev[2 * t + 1][1] is not None)
+        hits = sum(1 for e in ev if e[0])
+        assert (st["hits"], st["misses"], st["evictions"]) == (hits, len(ev) - hits, sum(1 for e in ev if e[1] is not None)), c
+        assert st["h2d_bytes"] == (len(ev) - hits) * T * T * 4 + n * n * 4
+        if c > 0:
+            alone, _ = oracle.lru_simulate(keys_of_call(keys, calls, c), n_ab)
+            reused += hits - sum(1 for e in alone if e[0])
+    assert at == len(events) and reused > 0            # later calls hit tiles that earlier calls fetched
+
+
+def keys_of_call(keys, calls, c):
+    """The lookups of call c alone (markers left out)."""
+    plain = [k for k in keys if not hasattr(k, "name")]
+    start = sum(n for _, _, n in calls[:c])
+    return plain[start:start + calls[c][2]]
+
+
+def test_kept_tiles_go_stale_without_invalidate_and_not_at_all_by_default(oracle):
+    n, T = 256, 64
+    announce("out-of-core GEMM: stale tiles are the caller's error only with keep_tiles")
+    budget = _budget(T, 40, n, n, n)                 # room for every tile of A and B: nothing is evicted
+    for keep in (1, 0):
+        A = inputs.int_matrix(1, n, n).pin_memory()
+        B = inputs.int_matrix(2, n, n).pin_memory()
+        ctx = tg.tgemm_create(0, keep_tiles=keep)
+        try:
+            C = torch.zeros(n, n).pin_memory()
+            tg.tgemm_run(ctx, A, B, C, n, n, n, T, tg.TGEMM_F32, budget)
+            old = oracle.gemm(A.numpy(), B.numpy())
+            assert np.array_equal(C.numpy().astype(np.float64), old)
+            A.mul_(-2.0)
+            new = oracle.gemm(A.numpy(), B.numpy())
+            C.zero_()
+            tg.tgemm_run(ctx, A, B, C, n, n, n, T, tg.TGEMM_F32, budget)
+            st = tg.tgemm_last_stats(ctx)
+            if keep:
+                assert st["misses"] == 0 and st["h2d_bytes"] == n * n * 4      # only C travelled
+                assert np.array_equal(C.numpy().astype(np.float64), old)       # the cached copy of the old A
+                tg.tgemm_invalidate(ctx, A)
+                C.zero_()
+                tg.tgemm_run(ctx, A, B, C, n, n, n, T, tg.TGEMM_F32, budget)
+                st = tg.tgemm_last_stats(ctx)
+                assert st["misses"] == 16 and st["hits"] == 2 * 64 - 16         # A fetched again, B still cached
+            assert np.array_equal(C.numpy().astype(np.float64), new)
+        finally:
+            tg.tgemm_destroy(ctx)
+
+
+def test_tile_pool_follows_the_budget_down():
+    """A context that has run with a large budget gives the memory back when a later call allows less."""
+    n, T = 4096, 512
+    announce("out-of-core GEMM: the slot pool shrinks with the budget")
+    A = inputs.int_matrix(1, n, n).pin_memory()
+    B = inputs.int_matrix(2, n, n).pin_memory()
+    ctx = tg.tgemm_create(0)
+    try:
+        frees = []
+        for n_ab in (128, 16, 64):
+            C = torch.zeros(n, n).pin_memory()
+            tg.tgemm_run(ctx, A, B, C, n, n, n, T, tg.TGEMM_F32, _budget(T, n_ab, n, n, n))
+            assert tg.tgemm_last_stats(ctx)["n_slots"] == n_ab
+            if n_ab == 16:
+                assert torch.equal(C, A @ B)
+            frees.append(torch.cuda.mem_get_info()[0])
+        slot = T * T * 4
+        assert frees[1] - frees[0] >= (128 - 16) * slot // 2, frees        # memory came back
+        assert frees[1] - frees[2] >= (64 - 16) * slot // 2, frees         # and is taken again when allowed
+    finally:
+        tg.tgemm_destroy(ctx)
+
+
 def test_error_paths():
     ctx = tg.tgemm_create(0)
     try:
