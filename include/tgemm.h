@@ -25,6 +25,8 @@
  *   - The library's streams do not synchronise with any other stream: work that produces an input
  *     on another stream (including the null stream) must have completed before a call.
  *   - A context is used by one caller thread at a time.
+ *   - TGEMM_LOG=1 in the environment prints one line per tgemm_run / mlp_* call on stderr (status,
+ *     wall and kernel time, tasks, launches, cache hits / misses / evictions, host-link bytes).
  */
 #ifndef TGEMM_H
 #define TGEMM_H

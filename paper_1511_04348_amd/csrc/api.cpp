@@ -1,6 +1,7 @@
 // C-ABI entry points: argument checks, pointer classification, dispatch to the in-core launch or
 // the out-of-core tile engine.  See include/tgemm.h for the contract of every function.
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <atomic>
@@ -58,6 +59,19 @@ static hipError_t pooled_stream(int device, int s, hipStream_t* out)
     }
     *out = g_streams[device][s];
     return hipSuccess;
+}
+
+// TGEMM_LOG=1 in the environment: one line per tgemm_run / mlp_* call on stderr.
+void log_call(const char* what, const tgemm_ctx* ctx, int rc)
+{
+    static const bool on = [] { const char* v = getenv("TGEMM_LOG"); return v && *v && *v != '0'; }();
+    if (!on) return;
+    const tgemm_stats& s = ctx->stats;
+    fprintf(stderr, "[tgemm] %s rc=%d %s wall %.3f ms kernel %.3f ms tasks %lld tile products %lld launches %lld slots %lld "
+            "hits %lld misses %lld evictions %lld h2d %lld B d2h %lld B\n", what, rc, s.in_core ? "in-core" : "out-of-core",
+            s.wall_ms, s.kernel_ms, (long long)s.n_tasks, (long long)s.n_tile_gemms, (long long)s.kernel_launches,
+            (long long)s.n_slots, (long long)s.hits, (long long)s.misses, (long long)s.evictions, (long long)s.h2d_bytes,
+            (long long)s.d2h_bytes);
 }
 
 static double now_ms()
@@ -223,6 +237,7 @@ int tgemm_run(tgemm_ctx* ctx, const void* A, const void* B, void* C,
     if (ka == PTR_PINNED) {
         const int rc = run_out_of_core(ctx, A, B, (float*)C, M, N, K, T, dtype, hbm_budget);
         ctx->stats.wall_ms = now_ms() - t0;
+        log_call("tgemm_run", ctx, rc);
         return rc;
     }
 
@@ -251,6 +266,7 @@ int tgemm_run(tgemm_ctx* ctx, const void* A, const void* B, void* C,
         ctx->kernel_timing_pending = false;
     }
     ctx->stats.wall_ms = now_ms() - t0;
+    log_call("tgemm_run", ctx, TGEMM_OK);
     return TGEMM_OK;
 }
 

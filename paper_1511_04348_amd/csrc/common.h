@@ -8,6 +8,8 @@
 
 #include "../../include/tgemm.h"
 
+struct tgemm_ctx;
+
 namespace tg {
 
 // Records the message for tgemm_last_error() on this thread and returns `code`.
@@ -25,6 +27,8 @@ enum PtrKind { PTR_DEVICE = 0, PTR_PINNED = 1, PTR_PAGEABLE = 2 };
 PtrKind classify_pointer(const void* p, int device);
 
 class Engine;   // out-of-core tile engine (engine.cpp)
+// With TGEMM_LOG=1 in the environment: one line on stderr with the call's statistics.
+void log_call(const char* what, const tgemm_ctx* ctx, int rc);
 
 // Address of the current device's copy of the static scratch array of mlp_forward_static (mlp.hip);
 // looked up once per device.  `device` must be current.  out may be NULL.

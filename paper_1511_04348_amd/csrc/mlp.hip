@@ -1362,6 +1362,7 @@ int mlp_read(tgemm_mlp* m, int32_t what, int32_t layer, void* dst, size_t offset
     catch (...) { rc_ = fail(TGEMM_EHIP, "mlp: unexpected exception"); }                      \
     /* argument and call-order errors are reported before any work: a pending pass stays usable */ \
     if (rc_ != TGEMM_OK && rc_ != TGEMM_EARG && rc_ != TGEMM_ESTATE && (m)) abandon_pass(m);  \
+    if (m) log_call(__func__, (m)->ctx, rc_);                                                 \
     return rc_
 
 int mlp_forward(tgemm_mlp* m, const void* X, int64_t batch, float* probs) { TG_GUARDED(m, mlp_forward_body(m, X, batch, probs)); }

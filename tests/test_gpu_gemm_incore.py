@@ -158,7 +158,10 @@ def test_config2_sampled_parity_full_size(ctxs, oracle):
     worst = float(np.max(np.abs(Cn - full)))
     print("config2 full-matrix rel fro", err_full, "largest entry error", worst, flush=True)
     assert err_full <= TOL_F32
-    assert worst <= 64 * 2.0 ** -24 * float(np.max(np.abs(full)))      # no single entry is off by more than rounding
+    # no single entry is off by more than rounding: an fp32 chain of n terms wanders by about
+    # 2^-24 sqrt(n) rms(C) (measured: 1.4e-4 rms, 7.6e-4 at worst over 6.4e7 entries); one dropped
+    # or doubled product would be off by 0.1 or more
+    assert worst <= 16 * 2.0 ** -24 * np.sqrt(n) * float(np.sqrt(np.mean(full * full))), worst
     del full
     # Freivalds: C x = A (B x) for random +-1 vectors; an error anywhere in C survives with probability 1/2 per vector
     A64, B64 = An.astype(np.float64), Bn.astype(np.float64)
