@@ -295,6 +295,26 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
     const int a_off = wm * WTM + RA * li;
     const int b_off = wn * WTN + RB * li;
 
+    // C: the dense matrix, or this task's tile from the tile table (tile-local coordinates)
+    float* __restrict__ C = p.c_tiles ? reinterpret_cast<float*>(p.c_tiles[(int64_t)ti * p.n_j + tj]) -
+                                            ((int64_t)(ti * p.T) * p.ldc + tj * p.T)
+                                      : p.C;
+    // The small shape (one 32 x 32 block per wave, one wave per SIMD) asks for its C values now: its
+    // products are short, and 16 dependent load -> multiply-add -> store round trips at the end of the
+    // kernel, with nothing else on the SIMD to fill them, cost more than the k loop's last chunks.
+    constexpr bool C_EARLY = (RA * RB == 1) && (EPI == EPI_AXPBY);
+    float c_early[16];
+    if constexpr (C_EARLY) {
+        const int colb = col0 + wn * WTN + li;
+        if (p.beta != 0.f) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = row0 + wm * WTM + 8 * (v >> 2) + 4 * lh + (v & 3);
+                c_early[v] = (row < row_end && colb < col_end) ? gload<float>(C + (int64_t)row * p.ldc + colb) : 0.f;
+            }
+        }
+    }
+
     // one 16-k chunk from LDS stage st
     auto compute = [&](int st) {
         const float* as = As + st * STAGE_A + lh * LDA_S + a_off;
@@ -667,10 +687,6 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
 
     // -- epilogue.  acc[r][cc][v] is element (row, col) of the wave tile with
     //    row = RA * (8*(v/4) + 4*lh + v%4) + r,  col = RB * li + cc.
-    // C: the dense matrix, or this task's tile from the tile table (tile-local coordinates)
-    float* __restrict__ C = p.c_tiles ? reinterpret_cast<float*>(p.c_tiles[(int64_t)ti * p.n_j + tj]) -
-                                            ((int64_t)(ti * p.T) * p.ldc + tj * p.T)
-                                      : p.C;
     const float* __restrict__ aux = reinterpret_cast<const float*>(p.aux);
     const float alpha = p.alpha, beta = p.beta;
     const int colb = col0 + wn * WTN + RB * li;
@@ -678,10 +694,45 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
     float bv[RB];   // this lane's columns of the bias row
 #pragma unroll
     for (int cc = 0; cc < RB; ++cc) bv[cc] = (p.bias && colb + cc < col_end) ? gload<float>(p.bias + colb + cc) : 0.f;
+    // Two passes per row block: first every value the epilogue reads (C, or the stored activations, or
+    // the velocities), then the arithmetic and the stores.  Written as one pass, each of the 16 rows
+    // waits for its own loads before its stores go out and the next row's loads cannot pass those
+    // stores (they may alias as far as the compiler knows): 16 memory round trips in a row per block.
 #pragma unroll
     for (int r = 0; r < RA; ++r) {
+        constexpr bool READS_C = (EPI == EPI_AXPBY && !C_EARLY) || EPI == EPI_MOMENTUM;
+        constexpr bool READS_X = EPI == EPI_DACT || EPI == EPI_MOMENTUM;      // aux, or the velocity
+        // rows per pass: all 16 of the block, or 4 where two operands are read and registers are short
+        constexpr int G = (READS_C && READS_X && RA * RB >= 8) ? 4 : 16;
+        const bool need_c = (EPI == EPI_MOMENTUM) || (EPI == EPI_AXPBY && !C_EARLY && beta != 0.f);
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
+        for (int g = 0; g < 16; g += G) {
+        float cin[READS_C ? G : 1][RB], xin[READS_X ? G : 1][RB];
+#pragma unroll
+        for (int vv = 0; vv < G; ++vv) {
+            const int v = g + vv;
+            const int row = row0 + wm * WTM + RA * (8 * (v >> 2) + 4 * lh + (v & 3)) + r;
+            const bool live = row < row_end;
+            if constexpr (READS_C) {
+                const float* src = C + (int64_t)row * p.ldc + colb;
+                if (live && need_c && cvec) {
+                    const f32x4 q = gload<f32x4>(src);
+#pragma unroll
+                    for (int cc = 0; cc < RB; ++cc) cin[vv][cc] = q[cc & 3];
+                } else {
+#pragma unroll
+                    for (int cc = 0; cc < RB; ++cc) cin[vv][cc] = (live && need_c && colb + cc < col_end) ? gload<float>(src + cc) : 0.f;
+                }
+            }
+            if constexpr (READS_X) {
+                const float* src = (EPI == EPI_DACT) ? aux + (int64_t)row * p.ldaux + colb : p.state + (int64_t)row * p.ldstate + colb;
+#pragma unroll
+                for (int cc = 0; cc < RB; ++cc) xin[vv][cc] = (live && colb + cc < col_end) ? gload<float>(src + cc) : 0.f;
+            }
+        }
+#pragma unroll
+        for (int vv = 0; vv < G; ++vv) {
+            const int v = g + vv;
             const int row = row0 + wm * WTM + RA * (8 * (v >> 2) + 4 * lh + (v & 3)) + r;
             if (row >= row_end) continue;
             float o[RB];
@@ -689,16 +740,12 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
             for (int cc = 0; cc < RB; ++cc) o[cc] = acc[r][cc][v] + bv[cc];
             float* dst = C + (int64_t)row * p.ldc + colb;
             if (EPI == EPI_AXPBY) {
-                if (beta != 0.f) {
-                    if (cvec) {
-                        const f32x4 cin = gload<f32x4>(dst);
+                if (C_EARLY) {
+                    if (beta != 0.f) o[0] = fmaf(alpha, o[0], beta * c_early[v]);
+                    else o[0] = alpha * o[0];
+                } else if (beta != 0.f) {
 #pragma unroll
-                        for (int cc = 0; cc < RB; ++cc) o[cc] = fmaf(alpha, o[cc], beta * cin[cc]);
-                    } else {
-#pragma unroll
-                        for (int cc = 0; cc < RB; ++cc)
-                            if (colb + cc < col_end) o[cc] = fmaf(alpha, o[cc], beta * gload<float>(dst + cc));
-                    }
+                    for (int cc = 0; cc < RB; ++cc) o[cc] = fmaf(alpha, o[cc], beta * cin[READS_C ? vv : 0][cc]);
                 } else {
 #pragma unroll
                     for (int cc = 0; cc < RB; ++cc) o[cc] = alpha * o[cc];
@@ -708,20 +755,16 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
 #pragma unroll
                 for (int cc = 0; cc < RB; ++cc)
                     if (colb + cc < col_end) {
-                        const float v = fmaf(p.mu, gload<float>(st + cc), o[cc]);
-                        gstore<float>(st + cc, v);
-                        o[cc] = fmaf(alpha, v, gload<float>(dst + cc));
+                        const float vel = fmaf(p.mu, xin[READS_X ? vv : 0][cc], o[cc]);
+                        gstore<float>(st + cc, vel);
+                        o[cc] = fmaf(alpha, vel, cin[READS_C ? vv : 0][cc]);
                     }
             } else if (EPI == EPI_ACT) {
 #pragma unroll
                 for (int cc = 0; cc < RB; ++cc) o[cc] = act_apply(p.act, o[cc]);
             } else if (EPI == EPI_DACT) {
-                const float* ax = aux + (int64_t)row * p.ldaux + colb;
 #pragma unroll
-                for (int cc = 0; cc < RB; ++cc)
-                    if (colb + cc < col_end) {
-                        o[cc] = o[cc] * act_slope(p.act, gload<float>(ax + cc));
-                    }
+                for (int cc = 0; cc < RB; ++cc) o[cc] = o[cc] * act_slope(p.act, xin[READS_X ? vv : 0][cc]);
             }
             if (cvec) {
                 f32x4 ov;
@@ -733,6 +776,7 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
                 for (int cc = 0; cc < RB; ++cc)
                     if (colb + cc < col_end) gstore<float>(dst + cc, o[cc]);
             }
+        }
         }
     }
 }
