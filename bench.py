@@ -35,7 +35,7 @@ PEAK_BF16_MFMA_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
 # summary under profiles/ that holds the figure.  None where no counter run exists.
 MEASURED_TRAFFIC_BYTES = {("c2", 8000, 1024): (3.584e9, "profiles/tile_gemm_f32_incore_8000_T1024.md"),
                           ("bf16", 8192, 2048): (2.148e9, "profiles/tile_gemm_bf16_incore_8192_T2048.md")}
-DEFAULT_STEPS = {"c1": (200, 20), "c2": (50, 5), "c3": (3, 1), "c4": (10, 3), "c5": (10, 2), "bf16": (50, 5)}
+DEFAULT_STEPS = {"c1": (200, 20), "c2": (50, 5), "c3": (3, 1), "c4": (10, 3), "c5": (20, 2), "bf16": (50, 5)}
 C4_DIMS, C4_BATCH = [4096, 16384, 16384, 16384, 10000], 4096
 C5_DIMS, C5_BATCH = [8192, 32768, 32768, 262144], 8192
 
