@@ -394,3 +394,18 @@ def test_rows_closed_forms_and_input_gradient(oracle):
                     return float((lse - zz[np.arange(len(rows)), y[rows]]).sum() / B)
                 fd = (total(Xr[r, c] + h) - total(Xr[r, c] - h)) / (2 * h)
                 assert abs(fd - grad[r, c]) <= 1e-6 * max(1e-3, abs(grad[r, c])), (act, r, c, fd, grad[r, c])
+
+
+def test_products_equal_the_triple_loop(oracle):
+    """The MLP oracle takes its products from numpy's fp64 matmul; the GEMM oracle is a triple loop in
+    C.  On fp32 inputs (which both widen exactly) the first layer's pre-activations, the last layer's
+    dW = A^T D and the error D W^T must agree between the two to fp64 rounding."""
+    dims, B = [6, 9, 5], 8
+    X, Ws, y = _net(31, dims, B)
+    acts, z, P, pre = oracle.mlp_forward(X, Ws, return_pre=True)
+    _, dWs, deltas = oracle.mlp_backward(X, Ws, y)
+    assert np.allclose(pre[1], oracle.gemm(X, Ws[0]), rtol=1e-13, atol=1e-15)
+    a1 = acts[1].astype(np.float32)                       # what a device would hold; both sides get the same bits
+    d2 = deltas[1].astype(np.float32)
+    assert np.allclose(a1.astype(np.float64).T @ d2.astype(np.float64), oracle.gemm(a1, d2, trans_a=True), rtol=1e-13, atol=1e-18)
+    assert np.allclose(d2.astype(np.float64) @ Ws[1].astype(np.float64).T, oracle.gemm(d2, Ws[1], trans_b=True), rtol=1e-13, atol=1e-18)
