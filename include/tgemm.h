@@ -64,6 +64,8 @@ enum {
  *               A once per strip; that is the automatic width. */
 enum { TGEMM_ORDER_SERPENTINE = 0, TGEMM_ORDER_ROW_MAJOR = 1, TGEMM_ORDER_STRIPS = 2 };
 
+enum { TGEMM_SCHEDULE_AUTO = 0, TGEMM_SCHEDULE_ONE_LAUNCH = 1, TGEMM_SCHEDULE_BALANCED = 2 };
+
 typedef struct tgemm_opts {
     int32_t trace;         /* 1: record one tgemm_trace_rec per tile product of out-of-core runs */
     int32_t order;         /* TGEMM_ORDER_* */
@@ -98,6 +100,21 @@ typedef struct tgemm_opts {
                               host matrix that earlier calls have read (or reusing its memory for
                               another matrix), call tgemm_invalidate before the next tgemm_run, or stale
                               tiles are used.  0 (default): every call starts with an empty cache */
+    int32_t incore_schedule; /* in-core fp32 tgemm_run with the automatic kernel shape.
+                              TGEMM_SCHEDULE_AUTO (0, default): where the 256 x 256 macro tiles do not fill
+                              whole rounds of one tile per compute unit (and T is a multiple of 256, K of
+                              32, rows 16-byte aligned) and a cost estimate promises a gain, the tiles of
+                              the last, partial round are cut along k into segments that run on all units
+                              and leave partial sums in a 128 MiB device workspace (allocated by the
+                              context at the first such call); a second kernel adds a tile's sums in
+                              ascending order of k, and then C.  Rows and columns beyond the last
+                              multiple of 256 run as a launch of their own.  Elements of those tiles are
+                              then sums of up to three chains over consecutive parts of the k range
+                              instead of one chain; which parts depends on the sizes and the number of
+                              compute units only.
+                              TGEMM_SCHEDULE_ONE_LAUNCH (1): always one launch, one chain per element.
+                              TGEMM_SCHEDULE_BALANCED (2): the balanced schedule wherever it applies,
+                              whatever the estimate says */
 } tgemm_opts;
 
 /* One output tile C_ij = one task (section 3.1; Algorithm 1, "decode").
@@ -159,7 +176,7 @@ int tgemm_destroy(tgemm_ctx* ctx);
  *   T  tile size (> 0).  Output tile (i,j) is one task; it accumulates A_ik B_kj for k ascending;
  *      edge tiles are clamped to the matrix.
  *   All three pointers device pointers  -> in-core: one kernel launch covers every task, hbm_budget
- *      is ignored.
+ *      is ignored (fp32: possibly a few launches with a workspace, see tgemm_opts.incore_schedule).
  *   All three pointers pinned host      -> out-of-core: A/B tiles are staged into an HBM tile cache
  *      (LRU, section 3.4); C tiles are uploaded, accumulated and harvested; fetch, products and
  *      harvest overlap on the 4 streams with 4 tasks in flight.  Every

@@ -13,6 +13,7 @@ LIB_PATH = os.path.join(_HERE, "libtgemm.so")
 TGEMM_F32, TGEMM_BF16 = 0, 1
 TGEMM_OK, TGEMM_EARG, TGEMM_ENOMEM, TGEMM_EUNPINNED, TGEMM_EBUDGET, TGEMM_EHIP, TGEMM_ESTATE = 0, -1, -2, -3, -4, -5, -6
 TGEMM_ORDER_SERPENTINE, TGEMM_ORDER_ROW_MAJOR, TGEMM_ORDER_STRIPS = 0, 1, 2
+TGEMM_SCHEDULE_AUTO, TGEMM_SCHEDULE_ONE_LAUNCH, TGEMM_SCHEDULE_BALANCED = 0, 1, 2
 TGEMM_ACT_SIGMOID, TGEMM_ACT_TANH, TGEMM_ACT_RELU = 0, 1, 2
 TGEMM_ROUND_NEAREST, TGEMM_ROUND_STOCHASTIC = 0, 1
 
@@ -27,7 +28,8 @@ class tgemm_opts(ctypes.Structure):
     _fields_ = [("trace", ctypes.c_int32), ("order", ctypes.c_int32), ("affinity_core", ctypes.c_int32),
                 ("async_incore", ctypes.c_int32), ("kernel_config", ctypes.c_int32),
                 ("strip_width", ctypes.c_int32), ("deferred_writeback", ctypes.c_int32),
-                ("rs_depth", ctypes.c_int32), ("exact_replacement", ctypes.c_int32), ("keep_tiles", ctypes.c_int32)]
+                ("rs_depth", ctypes.c_int32), ("exact_replacement", ctypes.c_int32), ("keep_tiles", ctypes.c_int32),
+                ("incore_schedule", ctypes.c_int32)]
 
 
 class tgemm_task(ctypes.Structure):
@@ -131,11 +133,12 @@ def tgemm_last_error():
 
 def tgemm_create(device=0, streams=None, trace=0, order=TGEMM_ORDER_STRIPS, affinity_core=-1,
                  async_incore=0, kernel_config=0, strip_width=0, deferred_writeback=0, rs_depth=0,
-                 exact_replacement=0, keep_tiles=0):
+                 exact_replacement=0, keep_tiles=0, incore_schedule=0):
     lib = load()
     o = tgemm_opts(trace=trace, order=order, affinity_core=affinity_core, async_incore=async_incore,
                    kernel_config=kernel_config, strip_width=strip_width,
-                   deferred_writeback=deferred_writeback, rs_depth=rs_depth, exact_replacement=exact_replacement, keep_tiles=keep_tiles)
+                   deferred_writeback=deferred_writeback, rs_depth=rs_depth, exact_replacement=exact_replacement, keep_tiles=keep_tiles,
+                   incore_schedule=incore_schedule)
     arr = None
     if streams is not None:
         if len(streams) != 4:

@@ -127,6 +127,8 @@ int tgemm_create(tgemm_ctx** out, int device, void* const* streams, const tgemm_
     if (o.strip_width < 0) return fail(TGEMM_EARG, "tgemm_create: strip_width %d", o.strip_width);
     if (o.kernel_config < 0 || o.kernel_config > 4)
         return fail(TGEMM_EARG, "tgemm_create: kernel_config %d", o.kernel_config);
+    if (o.incore_schedule < 0 || o.incore_schedule > 2)
+        return fail(TGEMM_EARG, "tgemm_create: incore_schedule %d", o.incore_schedule);
     if (o.rs_depth < 0 || o.rs_depth > 64) return fail(TGEMM_EARG, "tgemm_create: rs_depth %d (0 .. 64)", o.rs_depth);
     TG_HIP(hipSetDevice(device));
     {   // the static scratch array's address on this device, for the entry points that allocate nothing
@@ -148,10 +150,13 @@ int tgemm_create(tgemm_ctx** out, int device, void* const* streams, const tgemm_
             }
         }
     }
-    if (hipEventCreate(&c->ev_start) != hipSuccess || hipEventCreate(&c->ev_stop) != hipSuccess) {
+    if (hipEventCreate(&c->ev_start) != hipSuccess || hipEventCreate(&c->ev_stop) != hipSuccess ||
+        hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming) != hipSuccess) {
         tgemm_destroy(c);
         return fail(TGEMM_EHIP, "hipEventCreate failed");
     }
+    if (hipDeviceGetAttribute(&c->n_cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess) c->n_cus = 0;
     *out = c;
     return TGEMM_OK;
 }
@@ -165,6 +170,9 @@ int tgemm_destroy(tgemm_ctx* ctx)
     destroy_engine(ctx);
     if (ctx->ev_start) (void)hipEventDestroy(ctx->ev_start);
     if (ctx->ev_stop) (void)hipEventDestroy(ctx->ev_stop);
+    if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
+    if (ctx->ev_join) (void)hipEventDestroy(ctx->ev_join);
+    sk_destroy(ctx->sk);
     delete ctx;
     return TGEMM_OK;
 }
@@ -252,12 +260,23 @@ int tgemm_run(tgemm_ctx* ctx, const void* A, const void* B, void* C,
     d.config = ctx->opts.kernel_config;
     hipStream_t st = ctx->streams[0];
     TG_HIP(hipEventRecord(ctx->ev_start, st));
-    hipError_t e = launch_tile_gemm(d, dtype == TGEMM_BF16, st);
+    // fp32 with the automatic shape: the balanced schedule where the macro tiles leave a partial round
+    // (it declines, having launched nothing, wherever it does not apply or would not gain)
+    hipError_t e = hipErrorNotSupported;
+    int launches = 1;
+    if (dtype == TGEMM_F32 && ctx->opts.incore_schedule != TGEMM_SCHEDULE_ONE_LAUNCH) {
+        e = launch_gemm_f32_balanced(d, &ctx->sk, ctx->n_cus, ctx->opts.incore_schedule == TGEMM_SCHEDULE_BALANCED, st,
+                                     ctx->streams[1], ctx->ev_fork, ctx->ev_join, &launches);
+    }
+    if (e == hipErrorNotSupported) {
+        launches = 1;
+        e = launch_tile_gemm(d, dtype == TGEMM_BF16, st);
+    }
     if (e != hipSuccess) return fail(TGEMM_EHIP, "tile GEMM launch failed: %s", hipGetErrorString(e));
     TG_HIP(hipEventRecord(ctx->ev_stop, st));
     ctx->kernel_timing_pending = true;
     ctx->stats.in_core = 1;
-    ctx->stats.kernel_launches = 1;
+    ctx->stats.kernel_launches = launches;
     if (!ctx->opts.async_incore) {
         TG_HIP(hipStreamSynchronize(st));
         float ms = 0.f;

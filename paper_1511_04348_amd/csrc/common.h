@@ -27,6 +27,7 @@ enum PtrKind { PTR_DEVICE = 0, PTR_PINNED = 1, PTR_PAGEABLE = 2 };
 PtrKind classify_pointer(const void* p, int device);
 
 class Engine;   // out-of-core tile engine (engine.cpp)
+struct SkWorkspace;   // plan and workspace of the balanced in-core fp32 product (gemm_f32.hip)
 // With TGEMM_LOG=1 in the environment: one line on stderr with the call's statistics.
 void log_call(const char* what, const tgemm_ctx* ctx, int rc);
 
@@ -45,6 +46,10 @@ struct tgemm_ctx {
     bool kernel_timing_pending = false;
     std::vector<tgemm_trace_rec> trace;
     tg::Engine* engine = nullptr;
+    // in-core fp32 tgemm_run: the balanced schedule's state, the device's compute units, fork / join events
+    tg::SkWorkspace* sk = nullptr;
+    int n_cus = 0;
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
 };
 
 namespace tg {

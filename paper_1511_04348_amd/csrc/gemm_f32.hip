@@ -19,8 +19,11 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <algorithm>
+#include <new>
 #include <type_traits>
 #include <utility>
+#include <vector>
 
 #include "gemm_kernel.h"
 
@@ -228,7 +231,10 @@ __device__ __attribute__((always_inline)) inline void sched_mix()
 // TAIL: the instance for products whose last k chunk is ragged (K % BK != 0); its loop over full chunks
 // ends with one predicated, zero-filling chunk.  A separate kernel so that the plain instance's loop
 // is compiled exactly as if the tail did not exist.
-template <int RA, int RB, int WM, int WN, int BK, bool A_KC, bool B_KC, int EPI, bool TAIL>
+// LSH: the launch covers the strips right of column p.l_col0 (all rows) and below row p.l_row0 (the
+// columns left of l_col0) of the product instead of the whole of it: macro tiles 0 .. l_split - 1
+// cover the right strip (l_rcols to a row), the others the bottom strip (l_bcols to a row).
+template <int RA, int RB, int WM, int WN, int BK, bool A_KC, bool B_KC, int EPI, bool TAIL, bool LSH = false>
 __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p)
 {
     constexpr int WTM = 32 * RA, WTN = 32 * RB;
@@ -263,6 +269,13 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
         const int q = n >> 3, r = n & 7, xcd = b & 7, local = b >> 3;
         lid = xcd * q + (xcd < r ? xcd : r) + local;
     }
+    // EPI_PARTIAL: this workgroup's segment (macro tile, first chunk, chunks, workspace slot) comes from
+    // a table, longest segments first: the dispatcher hands them to compute units as those fall free
+    int c_begin = 0, c_count = p.n_chunks, ws_slot = 0;
+    if constexpr (EPI == EPI_PARTIAL) {
+        const SkSegment sg = p.segments[blockIdx.x];
+        lid = sg.tile; c_begin = sg.first_chunk; c_count = sg.n_chunks; ws_slot = sg.slot;
+    }
     const int band = p.tpm * p.macro_cols;            // macro tiles in a full band of tasks
     int ti = lid / band;
     const int in_band = lid - ti * band;
@@ -273,10 +286,18 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
     const int wcols = (tj == p.n_j - 1) ? p.tpn_last : p.tpn;
     const int si = in_task / wcols, sj = in_task - si * wcols;
 
-    const int row0 = ti * p.T + si * BM;
-    const int col0 = tj * p.T + sj * BN;
-    const int row_end = min(p.M, (ti + 1) * p.T);
-    const int col_end = min(p.N, (tj + 1) * p.T);
+    int row0 = ti * p.T + si * BM;
+    int col0 = tj * p.T + sj * BN;
+    int row_end = min(p.M, (ti + 1) * p.T);
+    int col_end = min(p.N, (tj + 1) * p.T);
+    if constexpr (LSH) {     // dense operands; ti, tj are not used then
+        if (lid < p.l_split) {
+            row0 = (lid / p.l_rcols) * BM; col0 = p.l_col0 + (lid % p.l_rcols) * BN; row_end = p.M; col_end = p.N;
+        } else {
+            const int b = lid - p.l_split;
+            row0 = p.l_row0 + (b / p.l_bcols) * BM; col0 = (b % p.l_bcols) * BN; row_end = p.M; col_end = p.l_col0;
+        }
+    }
 
     const float* __restrict__ A = reinterpret_cast<const float*>(p.A);
     const float* __restrict__ B = reinterpret_cast<const float*>(p.B);
@@ -290,7 +311,7 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
             for (int v = 0; v < 16; ++v) acc[r][c][v] = 0.f;
 
     f32x4 ra[LA::UP], rb[LB::UP];
-    const int n_chunks = p.n_chunks;
+    const int n_chunks = c_count;                 // this workgroup's chunks of the k range
     const int cps = p.chunks_per_step;
     const int a_off = wm * WTM + RA * li;
     const int b_off = wn * WTN + RB * li;
@@ -373,6 +394,10 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
         const float* b_org = B + (B_KC ? (int64_t)col0 * p.ldb : (int64_t)col0);
         const int64_t a_adv = A_KC ? (int64_t)BK : (int64_t)BK * p.lda;
         const int64_t b_adv = B_KC ? (int64_t)BK : (int64_t)BK * p.ldb;
+        if constexpr (EPI == EPI_PARTIAL) {     // dense operands only: the part starts c_begin chunks in
+            a_org += (int64_t)c_begin * a_adv;
+            b_org += (int64_t)c_begin * b_adv;
+        }
         // The origin of the next B chunk changes tile at a k-step boundary when B is a tile table;
         // that (uniform) branch is kept apart from the loads so that loads, MFMAs and LDS traffic
         // of one iteration form a single scheduling region.
@@ -687,6 +712,26 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
 
     // -- epilogue.  acc[r][cc][v] is element (row, col) of the wave tile with
     //    row = RA * (8*(v/4) + 4*lh + v%4) + r,  col = RB * li + cc.
+    if constexpr (EPI == EPI_PARTIAL) {
+        // the raw sum over this segment of the k range: BM x BN floats in its slot of the workspace
+        float* __restrict__ W = p.partial + (int64_t)ws_slot * (int64_t)(BM * BN);
+#pragma unroll
+        for (int r = 0; r < RA; ++r)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                float* dst = W + (wm * WTM + RA * (8 * (v >> 2) + 4 * lh + (v & 3)) + r) * BN + wn * WTN + RB * li;
+#pragma unroll
+                for (int cc = 0; cc < RB; cc += 4) {
+                    if constexpr (RB % 4 == 0) {
+                        gstore<f32x4>(dst + cc, f32x4{acc[r][cc][v], acc[r][cc + 1][v], acc[r][cc + 2][v], acc[r][cc + 3][v]});
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < RB; ++e) gstore<float>(dst + e, acc[r][e][v]);
+                    }
+                }
+            }
+        return;
+    }
     const float* __restrict__ aux = reinterpret_cast<const float*>(p.aux);
     const float alpha = p.alpha, beta = p.beta;
     const int colb = col0 + wn * WTN + RB * li;
@@ -788,11 +833,11 @@ struct Cfg {
     static constexpr size_t LDS = 2 * (size_t)BK * ((BM + PAD) + (BN + PAD)) * sizeof(float);
 };
 
-template <int RA, int RB, int WM, int WN, int BK, bool A_KC, bool B_KC, int EPI, bool TAIL>
+template <int RA, int RB, int WM, int WN, int BK, bool A_KC, bool B_KC, int EPI, bool TAIL, bool LSH = false>
 static hipError_t launch_one(const GemmParams& p, int grid, hipStream_t stream)
 {
     typedef Cfg<RA, RB, WM, WN, BK> C;
-    auto kern = tile_gemm_f32<RA, RB, WM, WN, BK, A_KC, B_KC, EPI, TAIL>;
+    auto kern = tile_gemm_f32<RA, RB, WM, WN, BK, A_KC, B_KC, EPI, TAIL, LSH>;
     static bool attr_set = false;   // per instantiation; the attribute is per function, idempotent
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -804,7 +849,7 @@ static hipError_t launch_one(const GemmParams& p, int grid, hipStream_t stream)
     return hipGetLastError();
 }
 
-template <int RA, int RB, int WM, int WN, int BK>
+template <int RA, int RB, int WM, int WN, int BK, bool STRIPS_ONLY = false>
 static hipError_t launch_cfg(GemmParams& p, const GemmDesc& d, hipStream_t stream)
 {
     typedef Cfg<RA, RB, WM, WN, BK> C;
@@ -822,14 +867,48 @@ static hipError_t launch_cfg(GemmParams& p, const GemmDesc& d, hipStream_t strea
     p.tpn_last = (int)((last_n + C::BN - 1) / C::BN);
     p.macro_cols = (p.n_j - 1) * p.tpn + p.tpn_last;
     const int64_t macro_rows = (int64_t)(p.n_i - 1) * p.tpm + p.tpm_last;
-    const int64_t grid = macro_rows * p.macro_cols;
+    int64_t grid = macro_rows * p.macro_cols;
     if (grid <= 0 || grid > 0x7fffffff) return hipErrorInvalidValue;
+    if (d.sk_grid_limit > 0 && d.sk_grid_limit < grid) grid = d.sk_grid_limit;   // the first macro tiles only
     const int64_t full_k = n_k > 1 ? T : d.K;
     p.chunks_per_step = (int)((full_k + BK - 1) / BK);
     const int64_t last_k = d.K - (n_k - 1) * T;
     p.n_chunks = (int)((n_k - 1) * p.chunks_per_step + (last_k + BK - 1) / BK);
 
     const bool tail = p.fast_k && (d.K % BK != 0);   // ragged last chunk inside the unpredicated loop
+    if (d.l_shape) {
+        // the two strips beyond (l_row0, l_col0) of a dense NN product, small shape
+        if constexpr (RA * RB == 1) {
+            if (!d.a_kcontig || d.b_kcontig || d.epilogue != EPI_AXPBY || d.b_tiles || d.c_tiles || d.l_row0 < 0 || d.l_col0 < 0 ||
+                d.l_row0 > d.M || d.l_col0 > d.N)
+                return hipErrorInvalidValue;
+            const int64_t rcols = (d.N - d.l_col0 + C::BN - 1) / C::BN, bcols = (d.l_col0 + C::BN - 1) / C::BN;
+            const int64_t n_right = ((d.M + C::BM - 1) / C::BM) * rcols;
+            const int64_t n_bottom = ((d.M - d.l_row0 + C::BM - 1) / C::BM) * bcols;
+            if (n_right + n_bottom <= 0 || n_right + n_bottom > 0x7fffffff) return hipErrorInvalidValue;
+            p.l_split = (int)n_right; p.l_row0 = (int)d.l_row0; p.l_col0 = (int)d.l_col0;
+            p.l_rcols = (int)(rcols > 0 ? rcols : 1); p.l_bcols = (int)(bcols > 0 ? bcols : 1);
+            return tail ? launch_one<RA, RB, WM, WN, BK, true, false, EPI_AXPBY, true, true>(p, (int)(n_right + n_bottom), stream)
+                        : launch_one<RA, RB, WM, WN, BK, true, false, EPI_AXPBY, false, true>(p, (int)(n_right + n_bottom), stream);
+        } else {
+            return hipErrorInvalidValue;
+        }
+    }
+    if constexpr (STRIPS_ONLY) return hipErrorInvalidValue;
+    else {
+    if (d.epilogue == EPI_PARTIAL) {
+        // segments of full interior tiles of a dense NN product on the unpredicated path (large shape)
+        if constexpr (RA == 2 && RB == 4 && WM == 4 && WN == 2) {
+            if (!d.a_kcontig || d.b_kcontig || tail || !p.fast_k || !p.fast_a || !p.fast_b || !p.vec_c || d.b_tiles ||
+                d.c_tiles || d.sk_n_segments <= 0 || !d.sk_segments || !d.sk_partial || d.M % C::BM || d.N % C::BN || T % C::BM)
+                return hipErrorInvalidValue;
+            p.segments = d.sk_segments;
+            p.partial = d.sk_partial;
+            return launch_one<RA, RB, WM, WN, BK, true, false, EPI_PARTIAL, false>(p, d.sk_n_segments, stream);
+        } else {
+            return hipErrorInvalidValue;
+        }
+    }
 #define TG_LAUNCH(AK, BKC, E)                                                                        \
     return tail ? launch_one<RA, RB, WM, WN, BK, AK, BKC, E, true>(p, (int)grid, stream)              \
                 : launch_one<RA, RB, WM, WN, BK, AK, BKC, E, false>(p, (int)grid, stream)
@@ -847,12 +926,15 @@ static hipError_t launch_cfg(GemmParams& p, const GemmDesc& d, hipStream_t strea
     }
     if (d.a_kcontig && d.b_kcontig) { TG_EPI(true, true) }
     return hipErrorInvalidValue;   // (m-contiguous A) x (k-contiguous B) is not used by any pass
+    }
 #undef TG_EPI
 #undef TG_LAUNCH
 }
 
-int pick_config(const GemmDesc& d)
+// *est_us_per_k (optional): the model's time of the chosen shape in microseconds per unit of K
+static int pick_config_est(const GemmDesc& d, double* est_us_per_k)
 {
+    if (est_us_per_k) *est_us_per_k = 0.0;
     if (d.config >= 1 && d.config <= 3) return d.config;
     // Large macro tiles are the most efficient per flop; smaller ones spread small products over
     // the 256 CUs.  Pick the shape with the least estimated time.
@@ -876,9 +958,12 @@ int pick_config(const GemmDesc& d)
     const double c3 = 0.230 * t3;
     const double c2 = t2 <= 1.0 ? 0.081 : t2 <= 2.0 ? 0.134 : 0.061 * t2;
     const double c1 = 0.0155 * (t1 + 1.2);
+    if (est_us_per_k) *est_us_per_k = c3 <= c2 && c3 <= c1 ? c3 : (c2 <= c1 ? c2 : c1);
     if (c3 <= c2 && c3 <= c1) return 3;
     return c2 <= c1 ? 2 : 1;
 }
+
+int pick_config(const GemmDesc& d) { return pick_config_est(d, nullptr); }
 
 hipError_t launch_tile_gemm_f32(const GemmDesc& d, hipStream_t stream)
 {
@@ -901,6 +986,8 @@ hipError_t launch_tile_gemm_f32(const GemmDesc& d, hipStream_t stream)
     if (d.master) return hipErrorInvalidValue;   // fp32 C is its own master copy
     if (d.epilogue == EPI_MOMENTUM && !d.state) return hipErrorInvalidValue;
     p.b_tiles = d.b_tiles; p.c_tiles = d.c_tiles;
+    p.segments = nullptr; p.partial = nullptr;
+    p.l_split = 0; p.l_row0 = 0; p.l_col0 = 0; p.l_rcols = 1; p.l_bcols = 1;
     const bool t4 = (T % 4 == 0);
     auto al16 = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15) == 0; };
     p.vec_a = t4 && al16(d.A) && (d.lda % 4 == 0);
@@ -912,6 +999,9 @@ hipError_t launch_tile_gemm_f32(const GemmDesc& d, hipStream_t stream)
     p.fast_b = p.vec_b && off32(d.ldb);
     GemmDesc dd = d;
     dd.T = (int32_t)T;
+    // the strips stream whole rows of A and columns of B from HBM, 64-k stages fetch them in 256-byte pieces
+    if (d.l_shape) return (d.K % 64 == 0 && T % 64 == 0) ? launch_cfg<1, 1, 2, 2, 64, true>(p, dd, stream)
+                                                         : launch_cfg<1, 1, 2, 2, SMALL_BK>(p, dd, stream);
     switch (pick_config(dd)) {
         case 3: return launch_cfg<2, 4, 4, 2, 32>(p, dd, stream);   // 256 x 256, 512 threads
         case 2: return launch_cfg<2, 2, 2, 2, 32>(p, dd, stream);   // 128 x 128, 256 threads
@@ -920,6 +1010,226 @@ hipError_t launch_tile_gemm_f32(const GemmDesc& d, hipStream_t stream)
         // in flight (see the kernel)
         default: return launch_cfg<1, 1, 2, 2, SMALL_BK>(p, dd, stream);
     }
+}
+
+// ---- balanced schedule of the in-core product (see gemm_kernel.h) --------------------------------
+struct SkTile {
+    int32_t row0, col0, first_slot, n_slots;   // a tile of the partial round and its slots of the workspace
+};
+constexpr int SK_MAX_SLOTS = 512;              // segments <= units + tiles of the partial round < 2 * 256
+constexpr size_t SK_SLOT_FLOATS = 256 * 256;
+constexpr size_t SK_TABLE_BYTES = 16384;       // segment table, then tile table (8 KiB each)
+
+struct SkWorkspace {
+    int64_t M = 0, N = 0, K = 0, ldc = 0;      // the product the tables were made for
+    int32_t T = 0, n_cus = 0;
+    bool forced = false;
+    bool use = false;
+    int64_t Mi = 0, Ni = 0;
+    int grid_full = 0;                          // macro tiles of the whole rounds
+    std::vector<SkSegment> segments;            // longest first
+    std::vector<SkTile> tiles;
+    bool uploaded = false;
+    char* dev = nullptr;                        // SK_TABLE_BYTES of tables, then SK_MAX_SLOTS slots
+};
+
+void sk_destroy(SkWorkspace* ws)
+{
+    if (!ws) return;
+    if (ws->dev) (void)hipFree(ws->dev);
+    delete ws;
+}
+
+// Adds a tile's segment sums (ascending k) and then C: 16 workgroups per tile, 16 rows each.
+__global__ __launch_bounds__(256) void sk_fixup(float* __restrict__ C, int64_t ldc, const float* __restrict__ partial,
+                                                 const SkTile* __restrict__ tiles)
+{
+    const SkTile t = tiles[blockIdx.x >> 4];
+    const int rg = blockIdx.x & 15;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int u = threadIdx.x + 256 * i;            // 16-byte unit of the row group: 16 rows x 64 units
+        const int r = rg * 16 + (u >> 6), c4 = (u & 63) << 2;
+        const float* src = partial + (size_t)t.first_slot * SK_SLOT_FLOATS + r * 256 + c4;
+        f32x4 sum = gload<f32x4>(src);
+        for (int s = 1; s < t.n_slots; ++s) {
+            const f32x4 q = gload<f32x4>(src + (size_t)s * SK_SLOT_FLOATS);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) sum[e] += q[e];
+        }
+        float* dst = C + (int64_t)(t.row0 + r) * ldc + t.col0 + c4;
+        const f32x4 c = gload<f32x4>(dst);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) sum[e] += c[e];
+        gstore<f32x4>(dst, sum);
+    }
+}
+
+// The plan for one product: whether the balanced schedule applies and is expected to win, and its tables.
+static void sk_make_plan(SkWorkspace& w, const GemmDesc& d, int n_cus, bool forced)
+{
+    w.M = d.M; w.N = d.N; w.K = d.K; w.T = d.T; w.ldc = d.ldc; w.n_cus = n_cus; w.forced = forced;
+    w.use = false; w.uploaded = false;
+    w.segments.clear(); w.tiles.clear();
+    constexpr int64_t B = 256, BK = 32;
+    if (n_cus < 8 || n_cus > 256 || d.K % BK != 0 || d.K < 16 * BK || d.M < B || d.N < B) return;
+    if (d.M > 0x7fffffff || d.N > 0x7fffffff || d.K > 0x7fffffff) return;
+    const int64_t Mi = d.M / B * B, Ni = d.N / B * B;
+    // the tile size as the launcher clamps it for the interior product; tasks must be whole macro tiles
+    int64_t T = d.T;
+    const int64_t big = (Mi > Ni ? Mi : Ni) > d.K ? (Mi > Ni ? Mi : Ni) : d.K;
+    if (T > big) T = big;
+    if (T % B != 0) return;
+    const int64_t n_tiles = (Mi / B) * (Ni / B), n_ch = d.K / BK;
+    const int64_t rounds = n_tiles / n_cus, n_tail = n_tiles % n_cus;
+    if (n_tail == 0 || n_tiles > 0x7fffffff) return;
+    // estimate (the cost model of pick_config, microseconds): whole rounds + the busiest unit of the
+    // partial round (its share, about 8 chunks of segment starts and imbalance) + fix-up + strips
+    double plain = 0.0, strips = 0.0, e = 0.0;
+    pick_config_est(d, &plain);
+    plain *= (double)d.K;
+    GemmDesc s = d;
+    if (d.N > Ni) { s.M = d.M; s.N = d.N - Ni; pick_config_est(s, &e); strips += e * (double)d.K; }
+    if (d.M > Mi) { s.M = d.M - Mi; s.N = Ni; pick_config_est(s, &e); strips += e * (double)d.K; }
+    // (strips of at most one 64 x 64 tile per unit between them: one chain of K / 2 MFMAs per SIMD)
+    const int64_t small = ((d.M + 63) / 64) * ((d.N - Ni + 63) / 64) + ((d.M - Mi + 63) / 64) * (Ni / 64);
+    if (small <= n_cus) strips = small > 0 ? 0.0166 * (double)d.K + 12.0 : 0.0;
+    const double balanced = 0.230 * (double)d.K * ((double)rounds + (double)n_tail / n_cus) + 0.230 * BK * 8 + 50.0 + strips;
+    if (balanced > 0.985 * plain && !forced) return;
+
+    // macro tile number (task by task, as the kernel numbers them) -> origin, for the interior product
+    const int64_t n_i = (Mi + T - 1) / T, n_j = (Ni + T - 1) / T;
+    const int64_t tpm = (n_i > 1 ? T : Mi) / B, tpn = (n_j > 1 ? T : Ni) / B;
+    const int64_t tpm_last = (Mi - (n_i - 1) * T) / B, tpn_last = (Ni - (n_j - 1) * T) / B;
+    const int64_t macro_cols = (n_j - 1) * tpn + tpn_last, band = tpm * macro_cols;
+    auto origin = [&](int64_t lid, int32_t* row0, int32_t* col0) {
+        const int64_t ti = lid / band, in_band = lid - ti * band;
+        const int64_t h = (ti == n_i - 1) ? tpm_last : tpm;
+        int64_t tj = in_band / (h * tpn);
+        if (tj > n_j - 1) tj = n_j - 1;
+        const int64_t in_task = in_band - tj * h * tpn;
+        const int64_t wcols = (tj == n_j - 1) ? tpn_last : tpn;
+        const int64_t si = in_task / wcols, sj = in_task - si * wcols;
+        *row0 = (int32_t)(ti * T + si * B);
+        *col0 = (int32_t)(tj * T + sj * B);
+    };
+    // the (tile, chunk) pairs of the partial round laid end to end, cut into n_cus equal ranges, each
+    // range cut again where it crosses into the next tile; slots are numbered in that order, so a
+    // tile's slots are consecutive and ascend with k
+    const int64_t U = n_tail * n_ch;
+    w.tiles.resize((size_t)n_tail);
+    for (int64_t t = 0; t < n_tail; ++t) {
+        origin(rounds * n_cus + t, &w.tiles[t].row0, &w.tiles[t].col0);
+        w.tiles[t].first_slot = -1;
+        w.tiles[t].n_slots = 0;
+    }
+    for (int64_t g = 0; g < n_cus; ++g) {
+        int64_t b = g * U / n_cus;
+        const int64_t e2 = (g + 1) * U / n_cus;
+        while (b < e2) {
+            const int64_t t = b / n_ch, te = (t + 1) * n_ch;
+            const int64_t n = (e2 < te ? e2 : te) - b;
+            const int32_t slot = (int32_t)w.segments.size();
+            w.segments.push_back(SkSegment{(int32_t)(rounds * n_cus + t), (int32_t)(b - t * n_ch), (int32_t)n, slot});
+            if (w.tiles[t].first_slot < 0) w.tiles[t].first_slot = slot;
+            w.tiles[t].n_slots += 1;
+            b += n;
+        }
+    }
+    if (w.segments.size() > (size_t)SK_MAX_SLOTS || w.segments.size() * sizeof(SkSegment) > SK_TABLE_BYTES / 2 ||
+        w.tiles.size() * sizeof(SkTile) > SK_TABLE_BYTES / 2) {
+        w.segments.clear(); w.tiles.clear();
+        return;
+    }
+    std::stable_sort(w.segments.begin(), w.segments.end(),
+                     [](const SkSegment& a, const SkSegment& b2) { return a.n_chunks > b2.n_chunks; });
+    w.Mi = Mi; w.Ni = Ni;
+    w.grid_full = (int)(rounds * n_cus);
+    w.use = true;
+}
+
+hipError_t launch_gemm_f32_balanced(const GemmDesc& d, SkWorkspace** wsp, int n_cus, bool forced, hipStream_t stream,
+                                    hipStream_t side, hipEvent_t fork, hipEvent_t join, int* launches)
+{
+    if (launches) *launches = 0;
+    if (!wsp || d.config != 0 || d.epilogue != EPI_AXPBY || d.alpha != 1.f || d.beta != 1.f || !d.a_kcontig || d.b_kcontig ||
+        d.bias || d.b_tiles || d.c_tiles || d.M <= 0 || d.N <= 0 || d.K <= 0 || d.T <= 0)
+        return hipErrorNotSupported;
+    // what the unpredicated, vector paths of the kernels ask of the operands
+    auto al16 = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15) == 0; };
+    auto off32 = [](int64_t ld) { return 256 * ld * 4 + 4096 < ((int64_t)1 << 31); };
+    if (!al16(d.A) || !al16(d.B) || !al16(d.C) || d.lda % 4 || d.ldb % 4 || d.ldc % 4 || !off32(d.lda) || !off32(d.ldb))
+        return hipErrorNotSupported;
+    SkWorkspace* w = *wsp;
+    if (!w) {
+        w = new (std::nothrow) SkWorkspace();
+        if (!w) return hipErrorNotSupported;
+        *wsp = w;
+    }
+    if (w->M != d.M || w->N != d.N || w->K != d.K || w->T != d.T || w->ldc != d.ldc || w->n_cus != n_cus || w->forced != forced) {
+        try {
+            sk_make_plan(*w, d, n_cus, forced);
+        } catch (...) {
+            w->use = false;
+            w->M = 0;
+        }
+    }
+    if (!w->use) return hipErrorNotSupported;
+    if (!w->dev) {
+        if (hipMalloc((void**)&w->dev, SK_TABLE_BYTES + SK_MAX_SLOTS * SK_SLOT_FLOATS * sizeof(float)) != hipSuccess) {
+            (void)hipGetLastError();
+            w->dev = nullptr;
+            return hipErrorNotSupported;
+        }
+    }
+    hipError_t e;
+    if (!w->uploaded) {     // the vectors live as long as the plan: the copies may read them any time
+        e = hipMemcpyAsync(w->dev, w->segments.data(), w->segments.size() * sizeof(SkSegment), hipMemcpyHostToDevice, stream);
+        if (e != hipSuccess) return e;
+        e = hipMemcpyAsync(w->dev + SK_TABLE_BYTES / 2, w->tiles.data(), w->tiles.size() * sizeof(SkTile), hipMemcpyHostToDevice, stream);
+        if (e != hipSuccess) return e;
+        w->uploaded = true;
+    }
+    int n = 0;
+    GemmDesc in = d;
+    in.M = w->Mi; in.N = w->Ni; in.config = 3;
+    if (w->grid_full > 0) {
+        in.sk_grid_limit = w->grid_full;
+        if ((e = launch_tile_gemm_f32(in, stream)) != hipSuccess) return e;
+        ++n;
+    }
+    in.sk_grid_limit = 0;
+    in.epilogue = EPI_PARTIAL;
+    in.sk_segments = reinterpret_cast<const SkSegment*>(w->dev);
+    in.sk_n_segments = (int32_t)w->segments.size();
+    in.sk_partial = reinterpret_cast<float*>(w->dev + SK_TABLE_BYTES);
+    if ((e = launch_tile_gemm_f32(in, stream)) != hipSuccess) return e;
+    ++n;
+    // The strips start when the segments are done, next to the fix-up, as one launch.  (Started with the
+    // whole rounds they took compute units from them -- a large workgroup and a small one do not fit a
+    // unit together; as two launches side by side their workgroups landed two to a unit, on half of
+    // the units, and took twice their time.)
+    const bool right = d.N > w->Ni, bottom = d.M > w->Mi;
+    if (right || bottom) {
+        e = hipEventRecord(fork, stream);
+        if (e != hipSuccess) return e;
+    }
+    if (right || bottom) {  // both strips in one launch (see GemmDesc::l_shape)
+        GemmDesc s = d;
+        s.l_shape = 1; s.l_row0 = w->Mi; s.l_col0 = w->Ni;
+        if ((e = hipStreamWaitEvent(side, fork, 0)) != hipSuccess) return e;
+        if ((e = launch_tile_gemm_f32(s, side)) != hipSuccess) return e;
+        if ((e = hipEventRecord(join, side)) != hipSuccess) return e;
+        ++n;
+    }
+    hipLaunchKernelGGL(sk_fixup, dim3((unsigned)w->tiles.size() * 16), dim3(256), 0, stream, d.C, d.ldc,
+                       reinterpret_cast<const float*>(w->dev + SK_TABLE_BYTES),
+                       reinterpret_cast<const SkTile*>(w->dev + SK_TABLE_BYTES / 2));
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    ++n;
+    if ((right || bottom) && (e = hipStreamWaitEvent(stream, join, 0)) != hipSuccess) return e;
+    if (launches) *launches = n;
+    return hipSuccess;
 }
 
 }  // namespace tg

@@ -5,14 +5,23 @@
 
 namespace tg {
 
-enum { EPI_AXPBY = 0, EPI_ACT = 1, EPI_DACT = 2, EPI_MOMENTUM = 3 };
+enum { EPI_AXPBY = 0, EPI_ACT = 1, EPI_DACT = 2, EPI_MOMENTUM = 3, EPI_PARTIAL = 4 };
 enum { ACT_SIGMOID = 0, ACT_TANH = 1, ACT_RELU = 2 };   // same values as TGEMM_ACT_* of the C ABI
+
+// A segment of the balanced schedule (launch_gemm_f32_balanced): n_chunks chunks of the k range of
+// macro tile `tile` (its number in the launch's task-by-task order) from chunk first_chunk on; the sum
+// goes to slot `slot` of the workspace.
+struct SkSegment {
+    int32_t tile, first_chunk, n_chunks, slot;
+};
 
 // What a caller asks for: out = epilogue(op(A) op(B)), tiled by T (section 3.1 of the paper).
 //   EPI_AXPBY    C = alpha * (A B) + beta * C       (beta == 0: C is not read)
 //   EPI_ACT      C = act(A B)                        act: sigmoid, tanh or max(0, .)
 //   EPI_DACT     C = (A B) * act'(z) with act' written in terms of the stored activation aux = act(z)
 //                (aux: M x N, leading dimension ldaux): aux (1 - aux), 1 - aux^2, or [aux > 0]
+//   EPI_PARTIAL  (fp32 launcher's own use, see launch_gemm_f32_balanced) the raw sum over a part of
+//                the k range of one macro tile, stored to a workspace
 //   EPI_MOMENTUM S = mu * S + (A B);  C = C + alpha * S   (S: M x N floats, leading dimension ldstate;
 //                the update with a velocity matrix; S is dense also when C is a tile table).  Offered for the layout of the
 //                dW product (both operands m/n-contiguous).
@@ -56,6 +65,17 @@ struct GemmDesc {
     // tile of task (ti, tj).  Inside a tile the pitch is ldb / ldc.  NULL = dense operand.
     const void* const* b_tiles;
     void* const* c_tiles;
+    // Set only by launch_gemm_f32_balanced (zero otherwise): launch the first sk_grid_limit macro tiles
+    // of the product only; or, with EPI_PARTIAL, one workgroup per entry of the segment table
+    // sk_segments (device memory, sk_n_segments entries), which store their sums to sk_partial.
+    int32_t sk_grid_limit, sk_n_segments;
+    const SkSegment* sk_segments;
+    float* sk_partial;
+    // fp32, EPI_AXPBY, dense NN operands, small shape: with l_shape set the launch computes only the
+    // entries of C in columns >= l_col0 (all rows) and in rows >= l_row0 (columns < l_col0): the two
+    // strips that a product leaves beyond a block of whole macro tiles.
+    int32_t l_shape;
+    int64_t l_row0, l_col0;
 };
 
 // Kernel argument block (filled by the launcher).
@@ -90,10 +110,32 @@ struct GemmParams {
     bool fast_k;                // every k chunk is full (fp32 kernel: except a ragged last chunk of the product)
     const void* const* b_tiles; // see GemmDesc
     void* const* c_tiles;
+    int l_split, l_row0, l_col0; // strips launch (see the kernel's LSH parameter):
+    int l_rcols, l_bcols;        // macro-tile columns of the right strip and of the bottom strip
+    const SkSegment* segments;  // EPI_PARTIAL: one entry per workgroup
+    float* partial;             // EPI_PARTIAL: workspace, 256 x 256 floats per segment
 };
 
 int pick_config(const GemmDesc& d);
 hipError_t launch_tile_gemm_f32(const GemmDesc& d, hipStream_t stream);
+// C += A B (fp32, A row-major M x K, B row-major K x N: the in-core tgemm_run) with the work spread
+// evenly over the compute units when the 256 x 256 macro tiles do not come out as whole rounds of
+// one tile per unit.  The interior (the multiples of 256 in M and N) runs its whole rounds as usual;
+// the tiles of the last, partial round are cut along k into segments -- the (tile, chunk) pairs laid
+// end to end and divided into as many equal ranges as there are units -- which run as workgroups of
+// their own, longest first, and leave their sums in a workspace; a fix-up kernel then adds each
+// tile's segment sums in ascending order of k, and that sum to C.  The remainder strips (fewer than
+// 256 rows / columns) run as one launch of small macro tiles on a side stream.
+// An element's summation order is still a function of the sizes and the unit count alone.
+// Returns hipErrorNotSupported -- having launched nothing -- when the product does not qualify or the
+// estimate promises no gain, unless whatever_the_estimate (the caller then uses launch_tile_gemm_f32).  The main work is enqueued
+// on `stream`; the strips on `side` behind `fork` (recorded on stream when the segments are
+// enqueued), and stream waits for `join` (recorded on side) at the end.  *ws: plan and device workspace
+// (128 MiB, allocated at the first qualifying call), kept across calls; released by sk_destroy.
+struct SkWorkspace;
+void sk_destroy(SkWorkspace* ws);
+hipError_t launch_gemm_f32_balanced(const GemmDesc& d, SkWorkspace** ws, int n_cus, bool whatever_the_estimate, hipStream_t stream,
+                                    hipStream_t side, hipEvent_t fork, hipEvent_t join, int* launches);
 // A, B are bf16 bit patterns; accumulation is fp32.  With out_bf16 the result is rounded to nearest
 // even into bf16 and aux is read as bf16; otherwise C is float (aux unused).
 hipError_t launch_tile_gemm_bf16(const GemmDesc& d, hipStream_t stream);

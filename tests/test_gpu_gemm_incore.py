@@ -217,3 +217,83 @@ def test_seeded_random_shapes_integer_exact(ctxs, oracle):
             C = C0.cuda()
             run_incore(ctxs[cfg], Ad, Bd, C, T)
             assert np.array_equal(C.cpu().numpy().astype(np.float64), ref), (M, N, K, T, cfg)
+
+
+# Products for the balanced schedule (tgemm_opts.incore_schedule): interior tiles of 256 x 256 in whole
+# rounds or not, a right strip, a bottom strip, both, neither; strips narrower than a small macro tile;
+# K a multiple of 32 only (the strips then keep 32-k stages); a tile size that covers the whole interior.
+BALANCED_CASES = [
+    # M, N, K, T, launches expected in TGEMM_SCHEDULE_BALANCED mode
+    (1600, 1576, 512, 256, 3),      # 36 interior tiles (no whole round): segments + fix-up + strips
+    (1536, 1536, 1024, 512, 2),     # no strips
+    (4376, 4352, 512, 256, 4),      # 289 interior tiles: one whole round, 33 tiles cut up; bottom strip of 24 rows
+    (4352, 4452, 544, 256, 4),      # right strip of 100 columns, K = 17 chunks
+    (4482, 4352, 512, 256, 4),      # bottom strip of 130 rows: three rows of small macro tiles
+    (1700, 1736, 512, 256, 3),      # both strips several small macro tiles wide
+    (800, 800, 1024, 1024, 3),      # one task
+    (2600, 2100, 768, 512, 3),      # 5 x 4 tasks, the last ones 512 x 512 of whole tiles
+    (512, 512, 800, 1024, 1),       # T is clamped to 800, no multiple of 256: one launch
+    (300, 200, 512, 256, 1),        # fewer than 256 columns: one launch
+]
+
+
+@pytest.mark.parametrize("M,N,K,T,launches", BALANCED_CASES)
+def test_balanced_schedule(oracle, M, N, K, T, launches):
+    """The balanced in-core schedule (whole rounds, k segments of the partial round with their fix-up,
+    strips) against the oracle: integer-valued operands bit-exact on the whole matrix, and equal to the
+    one-launch schedule's result; uniform operands within the fp32 bar."""
+    announce("balanced", M, N, K, T)
+    cb = tg.tgemm_create(0, incore_schedule=tg.TGEMM_SCHEDULE_BALANCED)
+    c1 = tg.tgemm_create(0, incore_schedule=tg.TGEMM_SCHEDULE_ONE_LAUNCH)
+    try:
+        A = inputs.int_matrix(41, M, K)
+        B = inputs.int_matrix(42, K, N)
+        C0 = inputs.int_matrix(43, M, N, lo=-7, hi=7)
+        ref = oracle.gemm(A.numpy(), B.numpy(), c_in=C0.numpy())
+        Ad, Bd = A.cuda(), B.cuda()
+        for rep in range(2):              # the second call reuses the plan and the workspace
+            Cb = C0.cuda()
+            run_incore(cb, Ad, Bd, Cb, T)
+            assert tg.tgemm_last_stats(cb)["kernel_launches"] == launches
+            assert np.array_equal(Cb.cpu().numpy().astype(np.float64), ref), rep
+        C1 = C0.cuda()
+        run_incore(c1, Ad, Bd, C1, T)
+        assert tg.tgemm_last_stats(c1)["kernel_launches"] == 1
+        assert torch.equal(C1, Cb)
+        Au = inputs.uniform_matrix(44, M, K)
+        Bu = inputs.uniform_matrix(45, K, N)
+        Cu0 = inputs.uniform_matrix(46, M, N)
+        refu = oracle.gemm(Au.numpy(), Bu.numpy(), c_in=Cu0.numpy())
+        Cu = Cu0.cuda()
+        run_incore(cb, Au.cuda(), Bu.cuda(), Cu, T)
+        assert rel_fro(Cu.cpu().numpy(), refu) <= TOL_F32
+        # another product on the same context: the plan follows the sizes
+        M2, N2 = M + 256, N
+        A2 = inputs.int_matrix(47, M2, K)
+        C2 = torch.zeros(M2, N2, device="cuda")
+        run_incore(cb, A2.cuda(), Bd, C2, T)
+        assert np.array_equal(C2.cpu().numpy().astype(np.float64), oracle.gemm(A2.numpy(), B.numpy()))
+    finally:
+        tg.tgemm_destroy(cb)
+        tg.tgemm_destroy(c1)
+
+
+def test_balanced_schedule_is_the_automatic_choice_where_it_gains(oracle):
+    """7168^2 x 4096 (784 macro tiles: three whole rounds and 16 tiles more) takes the balanced schedule
+    by itself, 8192^2 x 4096 (four whole rounds) one launch; sampled entries against the oracle."""
+    ctx = tg.tgemm_create(0)
+    try:
+        for n, K, launches in ((7168, 4096, 3), (8192, 4096, 1)):
+            announce("automatic schedule", n, K)
+            A = inputs.uniform_matrix(51, n, K, device="cuda")
+            B = inputs.uniform_matrix(52, K, n, device="cuda")
+            C = torch.zeros(n, n, device="cuda")
+            run_incore(ctx, A, B, C, 1024)
+            assert tg.tgemm_last_stats(ctx)["kernel_launches"] == launches
+            rnd = np.random.default_rng(n)
+            rows = np.concatenate([rnd.integers(0, n, 2048), rnd.integers(n - 256, n, 2048)])
+            cols = np.concatenate([rnd.integers(0, n, 2048), rnd.integers(n - 512, n, 2048)])
+            ref = oracle.gemm_samples(A.cpu().numpy(), B.cpu().numpy(), rows, cols)
+            assert rel_fro(C.cpu().numpy()[rows, cols], ref) <= TOL_F32
+    finally:
+        tg.tgemm_destroy(ctx)

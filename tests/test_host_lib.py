@@ -29,7 +29,7 @@ def test_exports_match_header(lib):
 
 
 def test_struct_sizes():
-    assert ctypes.sizeof(tg.tgemm_opts) == 40
+    assert ctypes.sizeof(tg.tgemm_opts) == 44
     assert ctypes.sizeof(tg.tgemm_task) == 64
     assert ctypes.sizeof(tg.tgemm_stats) == 96
     assert ctypes.sizeof(tg.tgemm_trace_rec) == 48
