@@ -33,7 +33,7 @@ PEAK_BF16_MFMA_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE in separate counter runs
 # (a counter run perturbs timing, so it cannot be this run); keyed by (workload, size, tile), with the
 # summary under profiles/ that holds the figure.  None where no counter run exists.
-MEASURED_TRAFFIC_BYTES = {("c2", 8000, 1024): (3.584e9, "profiles/tile_gemm_f32_incore_8000_T1024.md"),
+MEASURED_TRAFFIC_BYTES = {("c2", 8000, 1024): (7.007e9, "profiles/tile_gemm_f32_incore_8000_T1024.md"),
                           ("bf16", 8192, 2048): (2.148e9, "profiles/tile_gemm_bf16_incore_8192_T2048.md")}
 DEFAULT_STEPS = {"c1": (200, 20), "c2": (50, 5), "c3": (3, 1), "c4": (10, 3), "c5": (20, 2), "bf16": (50, 5)}
 C4_DIMS, C4_BATCH = [4096, 16384, 16384, 16384, 10000], 4096
@@ -139,7 +139,7 @@ def run_gemm_incore(args, env, name, steps, warmup, n, T, bf16):
     if bf16:
         A, B = A.to(torch.bfloat16), B.to(torch.bfloat16)
     C = torch.zeros(n, n, device="cuda")
-    ctx = tg.tgemm_create(0, kernel_config=args.kernel_config)
+    ctx = tg.tgemm_create(0, kernel_config=args.kernel_config, incore_schedule=args.incore_schedule)
     dt = tg.TGEMM_BF16 if bf16 else tg.TGEMM_F32
     flops = 2.0 * n * n * n
     torch.cuda.synchronize()      # inputs complete before the library's own streams read them
@@ -152,6 +152,7 @@ def run_gemm_incore(args, env, name, steps, warmup, n, T, bf16):
     for _ in range(steps):
         tg.tgemm_run(ctx, A, B, C, n, n, n, T, dt)          # synchronous: returns when C is complete
         kernel_ms += tg.tgemm_last_stats(ctx)["kernel_ms"]  # HIP events on the launch stream
+    launches = tg.tgemm_last_stats(ctx)["kernel_launches"]
     tg.tgemm_sync(ctx)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
@@ -170,10 +171,13 @@ def run_gemm_incore(args, env, name, steps, warmup, n, T, bf16):
                  "%s tiled GEMM M=N=K=%d, T=%d, in-core (A, B, C resident in HBM), C += A B"
                  % ("bf16-input fp32-accumulate" if bf16 else "fp32", n, T),
                  {"tile": T, "tasks": ((n + T - 1) // T) ** 2})
-    traffic = MEASURED_TRAFFIC_BYTES.get((name, n, T)) if args.kernel_config == 0 else None
+    traffic = MEASURED_TRAFFIC_BYTES.get((name, n, T)) if args.kernel_config == 0 and args.incore_schedule == 0 else None
+    kernel = "tile_gemm_bf16" if bf16 else "tile_gemm_f32"
+    if launches > 1:     # the balanced schedule: whole rounds, k segments of the partial round, strips, fix-up
+        kernel += " (balanced schedule: the %d launches of a step, first to last on the launch stream)" % launches
     out["roofline"] = {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
                        "traffic": traffic[0] if traffic else None, "traffic_source": traffic[1] if traffic else None,
-                       "kernel": "tile_gemm_bf16" if bf16 else "tile_gemm_f32", "avg_kernel_ms": avg_kernel_ms,
+                       "kernel": kernel, "avg_kernel_ms": avg_kernel_ms, "launches_per_step": launches,
                        "flops_per_launch": flops}
     if not args.no_cpu_baseline:
         Ah = A.float().cpu().numpy() if bf16 else A.cpu().numpy()
@@ -344,6 +348,8 @@ def main():
     ap.add_argument("--size", type=int, default=None, help="override the matrix size of a GEMM workload (with --workload)")
     ap.add_argument("--tile", type=int, default=None)
     ap.add_argument("--kernel-config", type=int, default=0)
+    ap.add_argument("--incore-schedule", type=int, default=0, choices=[0, 1, 2],
+                    help="fp32 in-core products: 0 automatic, 1 always one launch, 2 balanced wherever it applies (tgemm_opts.incore_schedule)")
     ap.add_argument("--order", type=int, default=2, choices=[0, 1, 2],
                     help="out-of-core task order: 0 serpentine, 1 row-major, 2 strips (default)")
     ap.add_argument("--strip", type=int, default=0, help="strip width for --order 2; 0 = from the slot count")
