@@ -100,7 +100,8 @@ typedef struct tgemm_opts {
                               host matrix that earlier calls have read (or reusing its memory for
                               another matrix), call tgemm_invalidate before the next tgemm_run, or stale
                               tiles are used.  0 (default): every call starts with an empty cache */
-    int32_t incore_schedule; /* in-core fp32 tgemm_run with the automatic kernel shape.
+    int32_t incore_schedule; /* in-core tgemm_run with the automatic kernel shape (bf16: only products whose M
+                              and N are multiples of 256, so there is no remainder launch).
                               TGEMM_SCHEDULE_AUTO (0, default): where the 256 x 256 macro tiles do not fill
                               whole rounds of one tile per compute unit (and T is a multiple of 256, K of
                               32, rows 16-byte aligned) and a cost estimate promises a gain, the tiles of
@@ -176,7 +177,7 @@ int tgemm_destroy(tgemm_ctx* ctx);
  *   T  tile size (> 0).  Output tile (i,j) is one task; it accumulates A_ik B_kj for k ascending;
  *      edge tiles are clamped to the matrix.
  *   All three pointers device pointers  -> in-core: one kernel launch covers every task, hbm_budget
- *      is ignored (fp32: possibly a few launches with a workspace, see tgemm_opts.incore_schedule).
+ *      is ignored (possibly a few launches with a workspace, see tgemm_opts.incore_schedule).
  *   All three pointers pinned host      -> out-of-core: A/B tiles are staged into an HBM tile cache
  *      (LRU, section 3.4); C tiles are uploaded, accumulated and harvested; fetch, products and
  *      harvest overlap on the 4 streams with 4 tasks in flight.  Every

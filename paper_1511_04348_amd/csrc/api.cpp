@@ -264,9 +264,9 @@ int tgemm_run(tgemm_ctx* ctx, const void* A, const void* B, void* C,
     // (it declines, having launched nothing, wherever it does not apply or would not gain)
     hipError_t e = hipErrorNotSupported;
     int launches = 1;
-    if (dtype == TGEMM_F32 && ctx->opts.incore_schedule != TGEMM_SCHEDULE_ONE_LAUNCH) {
-        e = launch_gemm_f32_balanced(d, &ctx->sk, ctx->n_cus, ctx->opts.incore_schedule == TGEMM_SCHEDULE_BALANCED, st,
-                                     ctx->streams[1], ctx->ev_fork, ctx->ev_join, &launches);
+    if (ctx->opts.incore_schedule != TGEMM_SCHEDULE_ONE_LAUNCH) {
+        e = launch_gemm_balanced(d, dtype == TGEMM_BF16, &ctx->sk, ctx->n_cus, ctx->opts.incore_schedule == TGEMM_SCHEDULE_BALANCED, st,
+                                 ctx->streams[1], ctx->ev_fork, ctx->ev_join, &launches);
     }
     if (e == hipErrorNotSupported) {
         launches = 1;

@@ -459,6 +459,8 @@ hipError_t launch_tile_gemm_bf16(const GemmDesc& d, hipStream_t stream)
     p.bias = d.bias;
     p.vec_bias = d.bias && ((reinterpret_cast<uintptr_t>(d.bias) & 15) == 0) && (T % 4 == 0);
     p.b_tiles = d.b_tiles; p.c_tiles = d.c_tiles;
+    p.segments = nullptr; p.partial = nullptr;
+    p.l_split = 0; p.l_row0 = 0; p.l_col0 = 0; p.l_rcols = 1; p.l_bcols = 1;
     // k-contiguous operands use 16-byte loads (8 elements), m/n-contiguous ones 8-byte loads (4)
     auto ok = [&](const void* q, int64_t ld, bool kc) {
         const int e = kc ? 8 : 4;
@@ -502,6 +504,9 @@ hipError_t launch_tile_gemm_bf16(const GemmDesc& d, hipStream_t stream)
         const double c2 = cost(tiles(128, 128), 512, dl_ok ? 0.95 : 0.6);
         cfg = c3 <= c2 ? 3 : 2;
     }
+    // the balanced schedule's launches exist in the direct-to-LDS kernel only
+    if (d.epilogue == EPI_PARTIAL || d.sk_grid_limit > 0) return dl_ok ? bf::launch_tile_gemm_bf16_dl(p, dd, stream) : hipErrorInvalidValue;
+    if (d.l_shape) return hipErrorInvalidValue;
     if (cfg == 3 && dl_ok) return bf::launch_tile_gemm_bf16_dl(p, dd, stream);
     if (d.master) cfg = 2;   // of the register-staged shapes only the smaller one carries a master copy
     if (cfg >= 3) return bf::launch_cfg<2, 4, 4, 2, 1>(p, dd, stream);   // 256 x 256, 8 waves of 64 x 128

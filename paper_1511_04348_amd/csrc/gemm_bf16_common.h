@@ -43,11 +43,12 @@ struct TileCoord {
     int row_end, col_end;   // end of the task's rows / columns (clamped to the matrix)
 };
 
+// macro_tile >= 0: that macro tile (its number in the task-by-task order) instead of the workgroup's own.
 template <int BM, int BN>
-__device__ inline TileCoord decode_tile(const GemmParams& p)
+__device__ inline TileCoord decode_tile(const GemmParams& p, int macro_tile = -1)
 {
-    int lid;
-    {
+    int lid = macro_tile;
+    if (macro_tile < 0) {
         const int n = gridDim.x, b = blockIdx.x;
         const int q = n >> 3, r = n & 7, xcd = b & 7, local = b >> 3;
         lid = xcd * q + (xcd < r ? xcd : r) + local;

@@ -190,7 +190,17 @@ __global__ __launch_bounds__(DL_NW * 64) void tile_gemm_bf16_dl(const GemmParams
     // the tile coordinates are the same in every lane; kept in scalar registers they make the tile
     // table lookups scalar loads (a vector load there would have to be waited for with vmcnt(0),
     // draining the direct loads in flight)
-    TileCoord tc = decode_tile<BM, BN>(p);
+    // EPI_PARTIAL (the balanced schedule of the in-core product, see gemm_kernel.h): this workgroup's
+    // segment of a macro tile's k range comes from a table; its sum goes to a slot of the workspace
+    int seg_tile = -1, seg_first = 0, seg_chunks = p.n_chunks, seg_slot = 0;
+    if constexpr (EPI == EPI_PARTIAL) {
+        const SkSegment sg = p.segments[blockIdx.x];
+        seg_tile = __builtin_amdgcn_readfirstlane(sg.tile);
+        seg_first = __builtin_amdgcn_readfirstlane(sg.first_chunk);
+        seg_chunks = __builtin_amdgcn_readfirstlane(sg.n_chunks);
+        seg_slot = __builtin_amdgcn_readfirstlane(sg.slot);
+    }
+    TileCoord tc = decode_tile<BM, BN>(p, seg_tile);
     tc.ti = __builtin_amdgcn_readfirstlane(tc.ti);
     tc.tj = __builtin_amdgcn_readfirstlane(tc.tj);
     tc.row0 = __builtin_amdgcn_readfirstlane(tc.row0);
@@ -214,7 +224,7 @@ __global__ __launch_bounds__(DL_NW * 64) void tile_gemm_bf16_dl(const GemmParams
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[r][c][v] = 0.f;
 
-    const int n_chunks = p.n_chunks;
+    const int n_chunks = seg_chunks;
     const int cps = p.chunks_per_step;
     const int bcol = col0 - tj * p.T;          // column inside the task's tile column (tile tables)
 
@@ -224,6 +234,10 @@ __global__ __launch_bounds__(DL_NW * 64) void tile_gemm_bf16_dl(const GemmParams
     const uint16_t* b_org = LB::chunk_origin(B, p.ldb, col0, 0);
     const int64_t a_adv = A_KC ? (int64_t)DL_BK : (int64_t)DL_BK * p.lda;
     const int64_t b_adv = B_KC ? (int64_t)DL_BK : (int64_t)DL_BK * p.ldb;
+    if constexpr (EPI == EPI_PARTIAL) {      // dense operands only
+        a_org += seg_first * a_adv;
+        b_org += seg_first * b_adv;
+    }
     auto issue = [&]() {
         if (p.b_tiles && ld_within == 0) {
             const uint16_t* t = reinterpret_cast<const uint16_t*>(table_entry(p.b_tiles, (int64_t)ld_step * p.n_j + tj));
@@ -285,8 +299,19 @@ __global__ __launch_bounds__(DL_NW * 64) void tile_gemm_bf16_dl(const GemmParams
 
     // every wave has passed its last LDS read and all direct loads have landed: the stages are free, and
     // each wave takes 32 x 68 floats of them for the transposition of its accumulators
-    epilogue_rows<RA, RB, EPI, OUT_BF16>(p, tc, acc, row0 + wm * WTM, col0 + wn * WTN, lane,
-                                         reinterpret_cast<float*>(smem) + wave * (32 * (32 * RB + 4)));
+    float* area = reinterpret_cast<float*>(smem) + wave * (32 * (32 * RB + 4));
+    if constexpr (EPI == EPI_PARTIAL) {
+        // the raw sums, as a plain store into a "matrix" of pitch BN whose entry (row0, col0) is the slot's first float
+        GemmParams q = p;
+        q.C = p.partial + (int64_t)seg_slot * (BM * BN) - ((int64_t)row0 * BN + col0);
+        q.ldc = BN;
+        q.alpha = 1.f; q.beta = 0.f;
+        q.bias = nullptr; q.c_tiles = nullptr; q.master = nullptr; q.sr = 0;
+        q.vec_c = true;
+        epilogue_rows<RA, RB, EPI_AXPBY, false>(q, tc, acc, row0 + wm * WTM, col0 + wn * WTN, lane, area);
+    } else {
+        epilogue_rows<RA, RB, EPI, OUT_BF16>(p, tc, acc, row0 + wm * WTM, col0 + wn * WTN, lane, area);
+    }
 }
 
 template <bool A_KC, bool B_KC, int EPI, bool OB>
@@ -323,15 +348,25 @@ bool bf16_dl_applicable(const GemmDesc& d)
     if (!fits(d.lda, d.a_kcontig != 0) || !fits(d.ldb, d.b_kcontig != 0)) return false;
     // layouts and epilogues the kernel is instantiated for
     if (!d.a_kcontig && d.b_kcontig) return false;
-    if (d.epilogue != EPI_AXPBY && !d.out_bf16) return false;
+    if (d.epilogue != EPI_AXPBY && d.epilogue != EPI_PARTIAL && !d.out_bf16) return false;
     return true;
 }
 
 hipError_t launch_tile_gemm_bf16_dl(GemmParams p, const GemmDesc& d, hipStream_t stream)
 {
     if (!bf16_dl_applicable(d)) return hipErrorNotSupported;
-    const int64_t grid = fill_grid(p, d, DL_BM, DL_BN, DL_BK);
+    int64_t grid = fill_grid(p, d, DL_BM, DL_BN, DL_BK);
     if (grid == 0) return hipErrorInvalidValue;
+    if (d.sk_grid_limit > 0 && d.sk_grid_limit < grid) grid = d.sk_grid_limit;     // the first macro tiles only
+    if (d.epilogue == EPI_PARTIAL) {
+        // segments of whole interior tiles of a dense NN product with a float result
+        if (!d.a_kcontig || d.b_kcontig || d.out_bf16 || d.b_tiles || d.c_tiles || d.sk_n_segments <= 0 || !d.sk_segments ||
+            !d.sk_partial || d.M % DL_BM || d.N % DL_BN || d.T % DL_BM)
+            return hipErrorInvalidValue;
+        p.segments = d.sk_segments;
+        p.partial = d.sk_partial;
+        return launch_dl<true, false, EPI_PARTIAL, false>(p, d.sk_n_segments, stream);
+    }
 
 #define TGD_LAUNCH(AK, BKC, E, OB) return launch_dl<AK, BKC, E, OB>(p, (int)grid, stream)
 #define TGD_EPI(AK, BKC)                                                            \

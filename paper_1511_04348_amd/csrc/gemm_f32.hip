@@ -1023,7 +1023,7 @@ constexpr size_t SK_TABLE_BYTES = 16384;       // segment table, then tile table
 struct SkWorkspace {
     int64_t M = 0, N = 0, K = 0, ldc = 0;      // the product the tables were made for
     int32_t T = 0, n_cus = 0;
-    bool forced = false;
+    bool forced = false, bf16 = false;
     bool use = false;
     int64_t Mi = 0, Ni = 0;
     int grid_full = 0;                          // macro tiles of the whole rounds
@@ -1066,9 +1066,9 @@ __global__ __launch_bounds__(256) void sk_fixup(float* __restrict__ C, int64_t l
 }
 
 // The plan for one product: whether the balanced schedule applies and is expected to win, and its tables.
-static void sk_make_plan(SkWorkspace& w, const GemmDesc& d, int n_cus, bool forced)
+static void sk_make_plan(SkWorkspace& w, const GemmDesc& d, bool bf16, int n_cus, bool forced)
 {
-    w.M = d.M; w.N = d.N; w.K = d.K; w.T = d.T; w.ldc = d.ldc; w.n_cus = n_cus; w.forced = forced;
+    w.M = d.M; w.N = d.N; w.K = d.K; w.T = d.T; w.ldc = d.ldc; w.n_cus = n_cus; w.forced = forced; w.bf16 = bf16;
     w.use = false; w.uploaded = false;
     w.segments.clear(); w.tiles.clear();
     constexpr int64_t B = 256, BK = 32;
@@ -1083,7 +1083,34 @@ static void sk_make_plan(SkWorkspace& w, const GemmDesc& d, int n_cus, bool forc
     const int64_t n_tiles = (Mi / B) * (Ni / B), n_ch = d.K / BK;
     const int64_t rounds = n_tiles / n_cus, n_tail = n_tiles % n_cus;
     if (n_tail == 0 || n_tiles > 0x7fffffff) return;
-    // estimate (the cost model of pick_config, microseconds): whole rounds + the busiest unit of the
+    int uniform_parts = 0;      // > 0: every tile of the partial round in this many even pieces (bf16)
+    if (bf16) {
+        // the direct-to-LDS kernel alone has the segment epilogue; strips are not offered
+        if (Mi != d.M || Ni != d.N) return;
+        GemmDesc in = d;
+        in.T = (int32_t)T;
+        if (!bf::bf16_dl_applicable(in)) return;
+        // estimate in rounds of 256 x 256 tiles (0.0284 us per unit of K), as the bf16 launcher compares
+        // its shapes: one launch takes whole rounds of the large shape, or of the 128 x 128 one (512 to a
+        // round, 0.95 of a large round); balanced, the partial round costs its share plus 8 chunks of
+        // segment starts and imbalance plus the fix-up
+        // The bf16 loop takes a chunk in under a microsecond: segments at different depths of k, which
+        // share no panel piece in the L2 at any moment, ask for more than HBM delivers and run at about
+        // half pace.  So the tiles are cut evenly instead, each into `parts` = units / tiles pieces at the
+        // same depths, in one wave of workgroups that walk k together like a round of whole tiles;
+        // with more than half as many tiles as units that is no cut at all, and the ranges of the fp32
+        // schedule are used at their measured pace.
+        uniform_parts = (int)(n_cus / n_tail);
+        if (uniform_parts > n_ch / 4) uniform_parts = (int)(n_ch / 4);
+        const double round_us = 0.0284 * (double)d.K;
+        const double c3 = (double)((n_tiles + n_cus - 1) / n_cus), c2 = 0.95 * (double)((4 * n_tiles + 2 * n_cus - 1) / (2 * n_cus));
+        const double plain_rounds = c3 < c2 ? c3 : c2;
+        const double tail_rounds = uniform_parts >= 2 ? (double)((n_ch + uniform_parts - 1) / uniform_parts) / (double)n_ch
+                                                      : 2.0 * (double)n_tail / n_cus;
+        const double bal_rounds = (double)rounds + tail_rounds + (0.0284 * BK * 8 + 45.0) / round_us;
+        if (bal_rounds > 0.985 * plain_rounds && !forced) return;
+        if (uniform_parts < 2) uniform_parts = 0;
+    } else {    // estimate (the cost model of pick_config, microseconds): whole rounds + the busiest unit of the
     // partial round (its share, about 8 chunks of segment starts and imbalance) + fix-up + strips
     double plain = 0.0, strips = 0.0, e = 0.0;
     pick_config_est(d, &plain);
@@ -1096,6 +1123,7 @@ static void sk_make_plan(SkWorkspace& w, const GemmDesc& d, int n_cus, bool forc
     if (small <= n_cus) strips = small > 0 ? 0.0166 * (double)d.K + 12.0 : 0.0;
     const double balanced = 0.230 * (double)d.K * ((double)rounds + (double)n_tail / n_cus) + 0.230 * BK * 8 + 50.0 + strips;
     if (balanced > 0.985 * plain && !forced) return;
+    }
 
     // macro tile number (task by task, as the kernel numbers them) -> origin, for the interior product
     const int64_t n_i = (Mi + T - 1) / T, n_j = (Ni + T - 1) / T;
@@ -1123,6 +1151,28 @@ static void sk_make_plan(SkWorkspace& w, const GemmDesc& d, int n_cus, bool forc
         w.tiles[t].first_slot = -1;
         w.tiles[t].n_slots = 0;
     }
+    if (uniform_parts > 0) {
+        // slot = tile * parts + part; workgroups by part, then by tile (neighbours in the task order share
+        // panels), numbered so that consecutive ones land on the same XCD like the whole rounds' workgroups
+        const int64_t n = n_tail * uniform_parts;
+        std::vector<SkSegment> list((size_t)n);
+        for (int64_t j = 0; j < uniform_parts; ++j)
+            for (int64_t t = 0; t < n_tail; ++t) {
+                const int64_t b = j * n_ch / uniform_parts, e2 = (j + 1) * n_ch / uniform_parts;
+                list[(size_t)(j * n_tail + t)] = SkSegment{(int32_t)(rounds * n_cus + t), (int32_t)b, (int32_t)(e2 - b),
+                                                           (int32_t)(t * uniform_parts + j)};
+            }
+        for (int64_t t = 0; t < n_tail; ++t) {
+            w.tiles[t].first_slot = (int32_t)(t * uniform_parts);
+            w.tiles[t].n_slots = uniform_parts;
+        }
+        w.segments.resize((size_t)n);
+        const int64_t q = n >> 3, r = n & 7;
+        for (int64_t blk = 0; blk < n; ++blk) {
+            const int64_t xcd = blk & 7, local = blk >> 3;
+            w.segments[(size_t)blk] = list[(size_t)(xcd * q + (xcd < r ? xcd : r) + local)];
+        }
+    } else
     for (int64_t g = 0; g < n_cus; ++g) {
         int64_t b = g * U / n_cus;
         const int64_t e2 = (g + 1) * U / n_cus;
@@ -1141,15 +1191,16 @@ static void sk_make_plan(SkWorkspace& w, const GemmDesc& d, int n_cus, bool forc
         w.segments.clear(); w.tiles.clear();
         return;
     }
-    std::stable_sort(w.segments.begin(), w.segments.end(),
-                     [](const SkSegment& a, const SkSegment& b2) { return a.n_chunks > b2.n_chunks; });
+    if (uniform_parts == 0)
+        std::stable_sort(w.segments.begin(), w.segments.end(),
+                         [](const SkSegment& a, const SkSegment& b2) { return a.n_chunks > b2.n_chunks; });
     w.Mi = Mi; w.Ni = Ni;
     w.grid_full = (int)(rounds * n_cus);
     w.use = true;
 }
 
-hipError_t launch_gemm_f32_balanced(const GemmDesc& d, SkWorkspace** wsp, int n_cus, bool forced, hipStream_t stream,
-                                    hipStream_t side, hipEvent_t fork, hipEvent_t join, int* launches)
+hipError_t launch_gemm_balanced(const GemmDesc& d, bool bf16, SkWorkspace** wsp, int n_cus, bool forced, hipStream_t stream,
+                                hipStream_t side, hipEvent_t fork, hipEvent_t join, int* launches)
 {
     if (launches) *launches = 0;
     if (!wsp || d.config != 0 || d.epilogue != EPI_AXPBY || d.alpha != 1.f || d.beta != 1.f || !d.a_kcontig || d.b_kcontig ||
@@ -1158,7 +1209,8 @@ hipError_t launch_gemm_f32_balanced(const GemmDesc& d, SkWorkspace** wsp, int n_
     // what the unpredicated, vector paths of the kernels ask of the operands
     auto al16 = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15) == 0; };
     auto off32 = [](int64_t ld) { return 256 * ld * 4 + 4096 < ((int64_t)1 << 31); };
-    if (!al16(d.A) || !al16(d.B) || !al16(d.C) || d.lda % 4 || d.ldb % 4 || d.ldc % 4 || !off32(d.lda) || !off32(d.ldb))
+    const int row_unit = bf16 ? 8 : 4;       // elements of A and B in 16 bytes
+    if (!al16(d.A) || !al16(d.B) || !al16(d.C) || d.lda % row_unit || d.ldb % row_unit || d.ldc % 4 || !off32(d.lda) || !off32(d.ldb))
         return hipErrorNotSupported;
     SkWorkspace* w = *wsp;
     if (!w) {
@@ -1166,9 +1218,10 @@ hipError_t launch_gemm_f32_balanced(const GemmDesc& d, SkWorkspace** wsp, int n_
         if (!w) return hipErrorNotSupported;
         *wsp = w;
     }
-    if (w->M != d.M || w->N != d.N || w->K != d.K || w->T != d.T || w->ldc != d.ldc || w->n_cus != n_cus || w->forced != forced) {
+    if (w->M != d.M || w->N != d.N || w->K != d.K || w->T != d.T || w->ldc != d.ldc || w->n_cus != n_cus || w->forced != forced ||
+        w->bf16 != bf16) {
         try {
-            sk_make_plan(*w, d, n_cus, forced);
+            sk_make_plan(*w, d, bf16, n_cus, forced);
         } catch (...) {
             w->use = false;
             w->M = 0;
@@ -1195,7 +1248,7 @@ hipError_t launch_gemm_f32_balanced(const GemmDesc& d, SkWorkspace** wsp, int n_
     in.M = w->Mi; in.N = w->Ni; in.config = 3;
     if (w->grid_full > 0) {
         in.sk_grid_limit = w->grid_full;
-        if ((e = launch_tile_gemm_f32(in, stream)) != hipSuccess) return e;
+        if ((e = launch_tile_gemm(in, bf16, stream)) != hipSuccess) return e;
         ++n;
     }
     in.sk_grid_limit = 0;
@@ -1203,13 +1256,13 @@ hipError_t launch_gemm_f32_balanced(const GemmDesc& d, SkWorkspace** wsp, int n_
     in.sk_segments = reinterpret_cast<const SkSegment*>(w->dev);
     in.sk_n_segments = (int32_t)w->segments.size();
     in.sk_partial = reinterpret_cast<float*>(w->dev + SK_TABLE_BYTES);
-    if ((e = launch_tile_gemm_f32(in, stream)) != hipSuccess) return e;
+    if ((e = launch_tile_gemm(in, bf16, stream)) != hipSuccess) return e;
     ++n;
     // The strips start when the segments are done, next to the fix-up, as one launch.  (Started with the
     // whole rounds they took compute units from them -- a large workgroup and a small one do not fit a
     // unit together; as two launches side by side their workgroups landed two to a unit, on half of
     // the units, and took twice their time.)
-    const bool right = d.N > w->Ni, bottom = d.M > w->Mi;
+    const bool right = d.N > w->Ni, bottom = d.M > w->Mi;      // (fp32 only)
     if (right || bottom) {
         e = hipEventRecord(fork, stream);
         if (e != hipSuccess) return e;

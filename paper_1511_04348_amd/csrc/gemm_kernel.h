@@ -8,7 +8,7 @@ namespace tg {
 enum { EPI_AXPBY = 0, EPI_ACT = 1, EPI_DACT = 2, EPI_MOMENTUM = 3, EPI_PARTIAL = 4 };
 enum { ACT_SIGMOID = 0, ACT_TANH = 1, ACT_RELU = 2 };   // same values as TGEMM_ACT_* of the C ABI
 
-// A segment of the balanced schedule (launch_gemm_f32_balanced): n_chunks chunks of the k range of
+// A segment of the balanced schedule (launch_gemm_balanced): n_chunks chunks of the k range of
 // macro tile `tile` (its number in the launch's task-by-task order) from chunk first_chunk on; the sum
 // goes to slot `slot` of the workspace.
 struct SkSegment {
@@ -20,7 +20,7 @@ struct SkSegment {
 //   EPI_ACT      C = act(A B)                        act: sigmoid, tanh or max(0, .)
 //   EPI_DACT     C = (A B) * act'(z) with act' written in terms of the stored activation aux = act(z)
 //                (aux: M x N, leading dimension ldaux): aux (1 - aux), 1 - aux^2, or [aux > 0]
-//   EPI_PARTIAL  (fp32 launcher's own use, see launch_gemm_f32_balanced) the raw sum over a part of
+//   EPI_PARTIAL  (launch_gemm_balanced's own use) the raw sum over a part of
 //                the k range of one macro tile, stored to a workspace
 //   EPI_MOMENTUM S = mu * S + (A B);  C = C + alpha * S   (S: M x N floats, leading dimension ldstate;
 //                the update with a velocity matrix; S is dense also when C is a tile table).  Offered for the layout of the
@@ -65,7 +65,7 @@ struct GemmDesc {
     // tile of task (ti, tj).  Inside a tile the pitch is ldb / ldc.  NULL = dense operand.
     const void* const* b_tiles;
     void* const* c_tiles;
-    // Set only by launch_gemm_f32_balanced (zero otherwise): launch the first sk_grid_limit macro tiles
+    // Set only by launch_gemm_balanced (zero otherwise): launch the first sk_grid_limit macro tiles
     // of the product only; or, with EPI_PARTIAL, one workgroup per entry of the segment table
     // sk_segments (device memory, sk_n_segments entries), which store their sums to sk_partial.
     int32_t sk_grid_limit, sk_n_segments;
@@ -118,7 +118,7 @@ struct GemmParams {
 
 int pick_config(const GemmDesc& d);
 hipError_t launch_tile_gemm_f32(const GemmDesc& d, hipStream_t stream);
-// C += A B (fp32, A row-major M x K, B row-major K x N: the in-core tgemm_run) with the work spread
+// C += A B (A row-major M x K, B row-major K x N, C float: the in-core tgemm_run) with the work spread
 // evenly over the compute units when the 256 x 256 macro tiles do not come out as whole rounds of
 // one tile per unit.  The interior (the multiples of 256 in M and N) runs its whole rounds as usual;
 // the tiles of the last, partial round are cut along k into segments -- the (tile, chunk) pairs laid
@@ -134,11 +134,17 @@ hipError_t launch_tile_gemm_f32(const GemmDesc& d, hipStream_t stream);
 // (128 MiB, allocated at the first qualifying call), kept across calls; released by sk_destroy.
 struct SkWorkspace;
 void sk_destroy(SkWorkspace* ws);
-hipError_t launch_gemm_f32_balanced(const GemmDesc& d, SkWorkspace** ws, int n_cus, bool whatever_the_estimate, hipStream_t stream,
-                                    hipStream_t side, hipEvent_t fork, hipEvent_t join, int* launches);
+// With bf16 (A, B bf16 bit patterns, C float) the direct-to-LDS kernel runs the whole rounds and the
+// segments; products with strips (M or N no multiple of 256) are declined.
+hipError_t launch_gemm_balanced(const GemmDesc& d, bool bf16, SkWorkspace** ws, int n_cus, bool whatever_the_estimate,
+                                hipStream_t stream, hipStream_t side, hipEvent_t fork, hipEvent_t join, int* launches);
 // A, B are bf16 bit patterns; accumulation is fp32.  With out_bf16 the result is rounded to nearest
 // even into bf16 and aux is read as bf16; otherwise C is float (aux unused).
 hipError_t launch_tile_gemm_bf16(const GemmDesc& d, hipStream_t stream);
+namespace bf {
+// whether the direct-to-LDS bf16 kernel takes the product (d.T already clamped to the largest dimension)
+bool bf16_dl_applicable(const GemmDesc& d);
+}
 inline hipError_t launch_tile_gemm(const GemmDesc& d, int dtype_bf16, hipStream_t stream)
 {
     return dtype_bf16 ? launch_tile_gemm_bf16(d, stream) : launch_tile_gemm_f32(d, stream);

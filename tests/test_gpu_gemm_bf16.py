@@ -150,3 +150,54 @@ def test_direct_to_lds_kernel_equals_register_staged_kernel_bitwise(ctxs, oracle
             ref = oracle.gemm(inputs.bf16_bits(A.cpu()), inputs.bf16_bits(B.cpu()), c_in=C0.numpy())
             err = rel_fro(outs[0].numpy(), ref)
             assert err <= BAR and err <= SANITY, (M, N, K, T, err)
+
+
+# M, N, K, T, launches expected under TGEMM_SCHEDULE_BALANCED: the partial round's tiles cut evenly (at
+# most half as many tiles as compute units) or by equal ranges (more); with whole rounds before it or not
+BALANCED_CASES = [
+    (1536, 1536, 1024, 512, 2),     # 36 tiles, 7 pieces each
+    (4352, 4352, 512, 256, 3),      # a whole round + 33 tiles, in 4 pieces each (a piece is at least 4 chunks)
+    (2560, 2048, 768, 512, 2),      # 80 tiles, 3 pieces each
+    (3328, 3328, 640, 256, 2),      # 169 tiles: more than half the units, equal ranges
+    (1536, 1528, 1024, 512, 1),     # N no multiple of 256: declined, one launch
+]
+
+
+@pytest.mark.parametrize("M,N,K,T,launches", BALANCED_CASES)
+def test_balanced_schedule(oracle, M, N, K, T, launches):
+    """The balanced in-core schedule with the direct-to-LDS kernel (whole rounds, k pieces of the partial
+    round's tiles into a workspace, fix-up): integer-valued operands bit-exact on the whole matrix and
+    equal to the one launch; uniform operands within the bars."""
+    announce("bf16 balanced", M, N, K, T)
+    cb = tg.tgemm_create(0, incore_schedule=tg.TGEMM_SCHEDULE_BALANCED)
+    c1 = tg.tgemm_create(0, incore_schedule=tg.TGEMM_SCHEDULE_ONE_LAUNCH)
+    try:
+        A = _bf16(inputs.int_matrix(41, M, K))
+        B = _bf16(inputs.int_matrix(42, K, N))
+        C0 = inputs.int_matrix(43, M, N, lo=-7, hi=7)
+        ref = oracle.gemm(inputs.bf16_bits(A), inputs.bf16_bits(B), c_in=C0.numpy())
+        Ad, Bd = A.cuda(), B.cuda()
+        for rep in range(2):
+            Cb = C0.cuda()
+            torch.cuda.synchronize()
+            tg.tgemm_run(cb, Ad, Bd, Cb, M, N, K, T, tg.TGEMM_BF16, 0)
+            assert tg.tgemm_last_stats(cb)["kernel_launches"] == launches
+            assert np.array_equal(Cb.cpu().numpy().astype(np.float64), ref), rep
+        C1 = C0.cuda()
+        torch.cuda.synchronize()
+        tg.tgemm_run(c1, Ad, Bd, C1, M, N, K, T, tg.TGEMM_BF16, 0)
+        assert tg.tgemm_last_stats(c1)["kernel_launches"] == 1
+        assert torch.equal(C1, Cb)
+        Au = _bf16(inputs.uniform_matrix(44, M, K))
+        Bu = _bf16(inputs.uniform_matrix(45, K, N))
+        Cu0 = inputs.uniform_matrix(46, M, N)
+        refu = oracle.gemm(inputs.bf16_bits(Au), inputs.bf16_bits(Bu), c_in=Cu0.numpy())
+        Cu = Cu0.cuda()
+        Aud, Bud = Au.cuda(), Bu.cuda()
+        torch.cuda.synchronize()
+        tg.tgemm_run(cb, Aud, Bud, Cu, M, N, K, T, tg.TGEMM_BF16, 0)
+        err = rel_fro(Cu.cpu().numpy(), refu)
+        assert err <= BAR and err <= SANITY, err
+    finally:
+        tg.tgemm_destroy(cb)
+        tg.tgemm_destroy(c1)
