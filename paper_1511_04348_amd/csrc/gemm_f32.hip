@@ -1220,6 +1220,8 @@ hipError_t launch_gemm_balanced(const GemmDesc& d, bool bf16, SkWorkspace** wsp,
     }
     if (w->M != d.M || w->N != d.N || w->K != d.K || w->T != d.T || w->ldc != d.ldc || w->n_cus != n_cus || w->forced != forced ||
         w->bf16 != bf16) {
+        // an earlier call's table copies may still be reading the vectors that the new plan rewrites
+        if (w->uploaded && hipStreamSynchronize(stream) != hipSuccess) return hipErrorNotSupported;
         try {
             sk_make_plan(*w, d, bf16, n_cus, forced);
         } catch (...) {
