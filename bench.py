@@ -34,7 +34,11 @@ PEAK_BF16_MFMA_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
 # (a counter run perturbs timing, so it cannot be this run); keyed by (workload, size, tile), with the
 # summary under profiles/ that holds the figure.  None where no counter run exists.
 MEASURED_TRAFFIC_BYTES = {("c2", 8000, 1024): (7.007e9, "profiles/tile_gemm_f32_incore_8000_T1024.md"),
-                          ("bf16", 8192, 2048): (2.148e9, "profiles/tile_gemm_bf16_incore_8192_T2048.md")}
+                          ("c1", 1000, 256): (3.32e7, "profiles/tile_gemm_f32_incore_1000_T256.md"),
+                          ("bf16", 8192, 2048): (2.148e9, "profiles/tile_gemm_bf16_incore_8192_T2048.md"),
+                          # per training step, every kernel of the step summed
+                          ("c4",): (6.88e10, "profiles/mlp_steps_config4_config5.md"),
+                          ("c5",): (7.99e11, "profiles/mlp_steps_config4_config5.md")}
 DEFAULT_STEPS = {"c1": (200, 20), "c2": (50, 5), "c3": (3, 1), "c4": (10, 3), "c5": (20, 2), "bf16": (50, 5)}
 C4_DIMS, C4_BATCH = [4096, 16384, 16384, 16384, 10000], 4096
 C5_DIMS, C5_BATCH = [8192, 32768, 32768, 262144], 8192
@@ -297,8 +301,12 @@ def run_mlp(args, env, name, steps, warmup, dims, batch, T, bf16, budget):
                  {"tile": T, "loss": loss, "rounding": "stochastic" if bf16 and args.stochastic_rounding else "nearest",
                   "bias": bool(args.bias), "momentum": args.momentum, "master_weights": bool(args.master_weights and bf16),
                   "step_TFLOPs": flops / (ms_per_step * 1e-3) / 1e12})
+    plain = not (args.bias or args.momentum is not None or args.master_weights or args.stochastic_rounding or args.sync_writeback
+                 or args.kernel_config or (name == "c4" and bf16))
+    traffic = MEASURED_TRAFFIC_BYTES.get((name,)) if plain else None
     out["roofline"] = {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
-                       "traffic": None, "kernel": "tile_gemm_%s (all %d launches of a step, first to last on the compute stream; "
+                       "traffic": traffic[0] if traffic else None, "traffic_source": traffic[1] if traffic else None,
+                       "kernel": "tile_gemm_%s (all %d launches of a step, first to last on the compute stream; "
                        "the softmax launch included)" % ("bf16" if bf16 else "f32", st["kernel_launches"]),
                        "avg_kernel_ms": avg_kernel_ms, "flops_per_step": flops}
     if budget:
