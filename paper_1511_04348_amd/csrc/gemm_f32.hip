@@ -1110,8 +1110,10 @@ static void sk_make_plan(SkWorkspace& w, const GemmDesc& d, bool bf16, int n_cus
         const double bal_rounds = (double)rounds + tail_rounds + (0.0284 * BK * 8 + 45.0) / round_us;
         if (bal_rounds > 0.985 * plain_rounds && !forced) return;
         if (uniform_parts < 2) uniform_parts = 0;
-    } else {    // estimate (the cost model of pick_config, microseconds): whole rounds + the busiest unit of the
-    // partial round (its share, about 8 chunks of segment starts and imbalance) + fix-up + strips
+    } else {    // estimate in microseconds, fitted to square products of 2048 .. 10240: whole rounds at 0.227 per tile
+    // and unit of K; the partial round's share 7 % slower (its segments share no panel pieces in L2) plus
+    // 10 for their starts; the fix-up 8 + 0.19 per tile; strips.  Against the one launch's best shape by
+    // the cost model of pick_config, which is rough for small products: below 140 tiles they are left alone.
     double plain = 0.0, strips = 0.0, e = 0.0;
     pick_config_est(d, &plain);
     plain *= (double)d.K;
@@ -1121,8 +1123,8 @@ static void sk_make_plan(SkWorkspace& w, const GemmDesc& d, bool bf16, int n_cus
     // (strips of at most one 64 x 64 tile per unit between them: one chain of K / 2 MFMAs per SIMD)
     const int64_t small = ((d.M + 63) / 64) * ((d.N - Ni + 63) / 64) + ((d.M - Mi + 63) / 64) * (Ni / 64);
     if (small <= n_cus) strips = small > 0 ? 0.0166 * (double)d.K + 12.0 : 0.0;
-    const double balanced = 0.230 * (double)d.K * ((double)rounds + (double)n_tail / n_cus) + 0.230 * BK * 8 + 50.0 + strips;
-    if (balanced > 0.985 * plain && !forced) return;
+    const double balanced = 0.227 * (double)d.K * ((double)rounds + 1.07 * (double)n_tail / n_cus) + 10.0 + (8.0 + 0.19 * (double)n_tail) + strips;
+    if ((balanced > 0.975 * plain || n_tiles < 140) && !forced) return;
     }
 
     // macro tile number (task by task, as the kernel numbers them) -> origin, for the interior product
