@@ -241,6 +241,34 @@ int tgemm_trace(tgemm_ctx* ctx, tgemm_trace_rec* out, int64_t cap, int64_t* n);
  * times each id came out.  Host-only self test used by the CPU test-suite. */
 int tgemm_queue_selftest(int64_t n, int32_t producers, int32_t consumers, int32_t* popped_count);
 
+/* The balanced schedule of an in-core product (tgemm_opts.incore_schedule), for inspection and for the
+ * CPU test-suite; host only, no GPU needed.  For C (M x N) += A (M x K) B (K x N) with tile size T on a
+ * device of n_cus compute units (at most 256), operands assumed 16-byte aligned with rows of M, N, K
+ * elements: whether the schedule applies (whatever_the_estimate != 0: wherever it can run, else only where
+ * its cost estimate promises a gain), the interior it covers with 256 x 256 macro tiles, how many of
+ * them run as whole rounds, and the k segments of the others in launch order.
+ *   segment.tile         macro tile, numbered task by task over the interior (tiles below
+ *                        whole_round_tiles belong to the whole rounds)
+ *   segment.first_chunk  first 32-k chunk of the segment, n_chunks of them
+ *   segment.slot         where its partial sum goes; the slots of one tile are consecutive and ascend with k
+ * Copies min(cap, n_segments) segments; segments may be NULL when cap is 0.  dtype as in tgemm_run. */
+typedef struct tgemm_segment {
+    int32_t tile, first_chunk, n_chunks, slot;
+} tgemm_segment;
+typedef struct tgemm_balance {
+    int32_t applies;            /* 0: tgemm_run takes one launch for this product; the other fields are 0 */
+    int32_t whole_round_tiles;  /* macro tiles of the whole rounds (a multiple of n_cus)              */
+    int32_t tail_tiles;         /* macro tiles of the partial round, cut into segments                */
+    int32_t n_segments;
+    int32_t chunks_per_tile;    /* K / 32                                                             */
+    int32_t even_parts;         /* > 0: every tile of the partial round is cut into this many pieces at the
+                                   same depths (bf16); 0: equal ranges of the (tile, chunk) pairs laid end
+                                   to end, longest segment first                                      */
+    int64_t interior_rows, interior_cols; /* multiples of 256; the rest of C is computed by a launch of its own */
+} tgemm_balance;
+int tgemm_balance_plan(int64_t M, int64_t N, int64_t K, int32_t T, int32_t dtype, int32_t n_cus,
+                       int32_t whatever_the_estimate, tgemm_balance* out, tgemm_segment* segments, int64_t cap);
+
 /* ---- MLP passes (section 2: forward pass = equation 1, backward pass = equations 3 and 4) ----
  *
  * Network: n_layers weight matrices W_l of shape dims[l] x dims[l+1], no bias; sigmoid after every

@@ -19,7 +19,7 @@ TGEMM_ROUND_NEAREST, TGEMM_ROUND_STOCHASTIC = 0, 1
 
 EXPORTS = [
     "tgemm_strerror", "tgemm_last_error", "tgemm_create", "tgemm_destroy", "tgemm_run", "tgemm_sync", "tgemm_invalidate",
-    "tgemm_plan", "tgemm_task_order", "tgemm_last_stats", "tgemm_trace", "tgemm_queue_selftest",
+    "tgemm_plan", "tgemm_task_order", "tgemm_last_stats", "tgemm_trace", "tgemm_queue_selftest", "tgemm_balance_plan",
     "mlp_create", "mlp_destroy", "mlp_set_activation", "mlp_set_rounding", "mlp_set_bias", "mlp_set_momentum", "mlp_set_master_weights", "mlp_forward", "mlp_forward_static", "mlp_backward", "mlp_step", "mlp_read", "mlp_trace",
 ]
 
@@ -30,6 +30,16 @@ class tgemm_opts(ctypes.Structure):
                 ("strip_width", ctypes.c_int32), ("deferred_writeback", ctypes.c_int32),
                 ("rs_depth", ctypes.c_int32), ("exact_replacement", ctypes.c_int32), ("keep_tiles", ctypes.c_int32),
                 ("incore_schedule", ctypes.c_int32)]
+
+
+class tgemm_segment(ctypes.Structure):
+    _fields_ = [("tile", ctypes.c_int32), ("first_chunk", ctypes.c_int32), ("n_chunks", ctypes.c_int32), ("slot", ctypes.c_int32)]
+
+
+class tgemm_balance(ctypes.Structure):
+    _fields_ = [("applies", ctypes.c_int32), ("whole_round_tiles", ctypes.c_int32), ("tail_tiles", ctypes.c_int32),
+                ("n_segments", ctypes.c_int32), ("chunks_per_tile", ctypes.c_int32), ("even_parts", ctypes.c_int32),
+                ("interior_rows", ctypes.c_int64), ("interior_cols", ctypes.c_int64)]
 
 
 class tgemm_task(ctypes.Structure):
@@ -88,6 +98,7 @@ def load():
     lib.tgemm_last_stats.argtypes = [vp, P(tgemm_stats)]
     lib.tgemm_trace.argtypes = [vp, P(tgemm_trace_rec), i64, P(i64)]
     lib.tgemm_queue_selftest.argtypes = [i64, i32, i32, P(i32)]
+    lib.tgemm_balance_plan.argtypes = [i64, i64, i64, i32, i32, i32, i32, P(tgemm_balance), P(tgemm_segment), i64]
     lib.mlp_create.argtypes = [vp, P(vp), i32, P(i64), P(vp), i32, i32, sz]
     lib.mlp_destroy.argtypes = [vp]
     lib.mlp_set_activation.argtypes = [vp, i32]
@@ -193,6 +204,17 @@ def tgemm_trace(ctx):
     buf = (tgemm_trace_rec * max(1, n.value))()
     _check(lib.tgemm_trace(ctx, buf, n.value, ctypes.byref(n)))
     return [{f: getattr(buf[t], f) for f, _ in tgemm_trace_rec._fields_} for t in range(n.value)]
+
+
+def tgemm_balance_plan(M, N, K, T, dtype=0, n_cus=256, whatever_the_estimate=0):
+    """(plan as a dict, segments in launch order as a list of dicts); plan["applies"] == 0: one launch."""
+    lib = load()
+    b = tgemm_balance()
+    _check(lib.tgemm_balance_plan(M, N, K, T, dtype, n_cus, whatever_the_estimate, ctypes.byref(b), None, 0))
+    segs = (tgemm_segment * max(1, b.n_segments))()
+    _check(lib.tgemm_balance_plan(M, N, K, T, dtype, n_cus, whatever_the_estimate, ctypes.byref(b), segs, b.n_segments))
+    plan = {f: getattr(b, f) for f, _ in tgemm_balance._fields_}
+    return plan, [{f: getattr(segs[i], f) for f, _ in tgemm_segment._fields_} for i in range(b.n_segments)]
 
 
 def tgemm_queue_selftest(n, producers, consumers):

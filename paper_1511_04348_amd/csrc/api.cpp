@@ -305,6 +305,19 @@ int tgemm_trace(tgemm_ctx* ctx, tgemm_trace_rec* out, int64_t cap, int64_t* n)
     return TGEMM_OK;
 }
 
+int tgemm_balance_plan(int64_t M, int64_t N, int64_t K, int32_t T, int32_t dtype, int32_t n_cus,
+                       int32_t whatever_the_estimate, tgemm_balance* out, tgemm_segment* segments, int64_t cap)
+{
+    if (!out || cap < 0 || (cap > 0 && !segments)) return fail(TGEMM_EARG, "tgemm_balance_plan: bad argument");
+    if (dtype != TGEMM_F32 && dtype != TGEMM_BF16) return fail(TGEMM_EARG, "tgemm_balance_plan: dtype %d", dtype);
+    if (M < 0 || N < 0 || K < 0 || T <= 0 || n_cus <= 0) return fail(TGEMM_EARG, "tgemm_balance_plan: bad size");
+    try {
+        return sk_inspect(M, N, K, T, dtype == TGEMM_BF16, n_cus, whatever_the_estimate != 0, out, segments, cap);
+    } catch (...) {
+        return fail(TGEMM_ENOMEM, "tgemm_balance_plan: host allocation failed");
+    }
+}
+
 int tgemm_queue_selftest(int64_t n, int32_t producers, int32_t consumers, int32_t* popped_count)
 {
     if (n < 0 || n > 0x7ffffff0 || producers < 1 || consumers < 1 || producers > 64 || consumers > 64 || (n > 0 && !popped_count))

@@ -31,6 +31,11 @@ struct SkWorkspace;   // plan and workspace of the balanced in-core fp32 product
 // With TGEMM_LOG=1 in the environment: one line on stderr with the call's statistics.
 void log_call(const char* what, const tgemm_ctx* ctx, int rc);
 
+// The balanced schedule's plan for a product, without a device (gemm_f32.hip); fills *out (applies = 0 where
+// tgemm_run would take one launch) and copies up to cap segments.  May throw std::bad_alloc.
+int sk_inspect(int64_t M, int64_t N, int64_t K, int32_t T, bool bf16, int n_cus, bool forced, tgemm_balance* out,
+               tgemm_segment* segments, int64_t cap);
+
 // Address of the current device's copy of the static scratch array of mlp_forward_static (mlp.hip);
 // looked up once per device.  `device` must be current.  out may be NULL.
 int static_scratch_resolve(int device, void** out);

@@ -25,6 +25,9 @@
 #include <utility>
 #include <vector>
 
+#include <string.h>
+
+#include "../../include/tgemm.h"
 #include "gemm_kernel.h"
 
 namespace tg {
@@ -1025,6 +1028,7 @@ struct SkWorkspace {
     int32_t T = 0, n_cus = 0;
     bool forced = false, bf16 = false;
     bool use = false;
+    int even_parts = 0;                         // see tgemm_balance
     int64_t Mi = 0, Ni = 0;
     int grid_full = 0;                          // macro tiles of the whole rounds
     std::vector<SkSegment> segments;            // longest first
@@ -1174,18 +1178,62 @@ static void sk_make_plan(SkWorkspace& w, const GemmDesc& d, bool bf16, int n_cus
             const int64_t xcd = blk & 7, local = blk >> 3;
             w.segments[(size_t)blk] = list[(size_t)(xcd * q + (xcd < r ? xcd : r) + local)];
         }
-    } else
-    for (int64_t g = 0; g < n_cus; ++g) {
-        int64_t b = g * U / n_cus;
-        const int64_t e2 = (g + 1) * U / n_cus;
-        while (b < e2) {
-            const int64_t t = b / n_ch, te = (t + 1) * n_ch;
-            const int64_t n = (e2 < te ? e2 : te) - b;
-            const int32_t slot = (int32_t)w.segments.size();
-            w.segments.push_back(SkSegment{(int32_t)(rounds * n_cus + t), (int32_t)(b - t * n_ch), (int32_t)n, slot});
-            if (w.tiles[t].first_slot < 0) w.tiles[t].first_slot = slot;
-            w.tiles[t].n_slots += 1;
-            b += n;
+    } else {
+        std::vector<int> first_of_range((size_t)n_cus + 1);     // a range's pieces: segments first_of_range[g] .. [g + 1]
+        for (int64_t g = 0; g < n_cus; ++g) {
+            first_of_range[(size_t)g] = (int)w.segments.size();
+            int64_t b = g * U / n_cus;
+            const int64_t e2 = (g + 1) * U / n_cus;
+            while (b < e2) {
+                const int64_t t = b / n_ch, te = (t + 1) * n_ch;
+                const int64_t n = (e2 < te ? e2 : te) - b;
+                const int32_t slot = (int32_t)w.segments.size();
+                w.segments.push_back(SkSegment{(int32_t)(rounds * n_cus + t), (int32_t)(b - t * n_ch), (int32_t)n, slot});
+                if (w.tiles[t].first_slot < 0) w.tiles[t].first_slot = slot;
+                w.tiles[t].n_slots += 1;
+                b += n;
+            }
+        }
+        first_of_range[(size_t)n_cus] = (int)w.segments.size();
+        // Launch order.  The hardware deals workgroup b to XCD b % 8, and inside an XCD the next workgroup goes to
+        // the first unit that falls free.  Every range is a unit's fair share, in one piece or two (t < units, so a
+        // range crosses at most one tile boundary).  Each XCD gets as many ranges as it has units, the two-piece
+        // ones dealt round, which is exactly the number of workgroups the hardware will hand it; its list is its
+        // ranges' longer pieces, longest first, then the shorter ones, longest first: the unit with the shortest
+        // long piece falls free first and takes the longest short piece, its own range's other half or one as long.
+        const int64_t n = (int64_t)w.segments.size();
+        if (n_cus % 8 == 0 && n <= SK_MAX_SLOTS) {
+            std::vector<SkSegment> head[8], tail[8];
+            int64_t cut = 0, whole = 0;
+            for (int64_t g = 0; g < n_cus; ++g)
+                if (first_of_range[(size_t)g + 1] - first_of_range[(size_t)g] == 2) {
+                    const SkSegment& a = w.segments[(size_t)first_of_range[(size_t)g]];
+                    const SkSegment& b = w.segments[(size_t)first_of_range[(size_t)g] + 1];
+                    const int x = (int)(cut++ % 8);
+                    head[x].push_back(a.n_chunks >= b.n_chunks ? a : b);
+                    tail[x].push_back(a.n_chunks >= b.n_chunks ? b : a);
+                }
+            for (int64_t g = 0; g < n_cus; ++g)
+                if (first_of_range[(size_t)g + 1] - first_of_range[(size_t)g] == 1) {
+                    int x = (int)(whole++ % 8);
+                    while ((int64_t)head[x].size() >= n_cus / 8) x = (x + 1) % 8;     // the XCD's ranges are complete
+                    head[x].push_back(w.segments[(size_t)first_of_range[(size_t)g]]);
+                }
+            auto longer = [](const SkSegment& a, const SkSegment& b) { return a.n_chunks > b.n_chunks; };
+            std::vector<SkSegment> order((size_t)n);
+            bool ok = true;
+            for (int x = 0; x < 8 && ok; ++x) {
+                std::stable_sort(head[x].begin(), head[x].end(), longer);
+                std::stable_sort(tail[x].begin(), tail[x].end(), longer);
+                head[x].insert(head[x].end(), tail[x].begin(), tail[x].end());
+                ok = (int64_t)head[x].size() == n / 8 + (x < n % 8 ? 1 : 0);
+                for (size_t i = 0; ok && i < head[x].size(); ++i) order[8 * i + (size_t)x] = head[x][i];
+            }
+            if (ok) w.segments.swap(order);
+            else std::stable_sort(w.segments.begin(), w.segments.end(), longer);
+        } else {
+            std::stable_sort(w.segments.begin(), w.segments.end(),
+                             [](const SkSegment& a, const SkSegment& b2) { return a.n_chunks > b2.n_chunks; });
         }
     }
     if (w.segments.size() > (size_t)SK_MAX_SLOTS || w.segments.size() * sizeof(SkSegment) > SK_TABLE_BYTES / 2 ||
@@ -1193,12 +1241,44 @@ static void sk_make_plan(SkWorkspace& w, const GemmDesc& d, bool bf16, int n_cus
         w.segments.clear(); w.tiles.clear();
         return;
     }
-    if (uniform_parts == 0)
-        std::stable_sort(w.segments.begin(), w.segments.end(),
-                         [](const SkSegment& a, const SkSegment& b2) { return a.n_chunks > b2.n_chunks; });
     w.Mi = Mi; w.Ni = Ni;
     w.grid_full = (int)(rounds * n_cus);
+    w.even_parts = uniform_parts;
     w.use = true;
+}
+
+// The plan alone, for tgemm_balance_plan: operands taken as aligned, dense, with rows of M, N, K elements.
+int sk_inspect(int64_t M, int64_t N, int64_t K, int32_t T, bool bf16, int n_cus, bool forced, tgemm_balance* out,
+               tgemm_segment* segments, int64_t cap)
+{
+    static_assert(sizeof(tgemm_segment) == sizeof(SkSegment), "the table is handed out as it is");
+    memset(out, 0, sizeof *out);
+    if (M <= 0 || N <= 0 || K <= 0 || T <= 0) return 0;
+    GemmDesc d;
+    memset(&d, 0, sizeof d);
+    alignas(16) static const char aligned_dummy[16] = {0};
+    d.A = aligned_dummy; d.B = aligned_dummy; d.C = nullptr;      // only their alignment is looked at
+    d.lda = K; d.ldb = N; d.ldc = N;
+    d.M = M; d.N = N; d.K = K; d.T = T;
+    d.a_kcontig = 1; d.b_kcontig = 0;
+    d.epilogue = EPI_AXPBY; d.alpha = 1.f; d.beta = 1.f;
+    const int row_unit = bf16 ? 8 : 4;
+    auto off32 = [](int64_t ld) { return 256 * ld * 4 + 4096 < ((int64_t)1 << 31); };
+    if (d.lda % row_unit || d.ldb % row_unit || d.ldc % 4 || !off32(d.lda) || !off32(d.ldb)) return 0;
+    SkWorkspace w;
+    sk_make_plan(w, d, bf16, n_cus, forced);
+    if (!w.use) return 0;
+    out->applies = 1;
+    out->whole_round_tiles = w.grid_full;
+    out->tail_tiles = (int32_t)w.tiles.size();
+    out->n_segments = (int32_t)w.segments.size();
+    out->chunks_per_tile = (int32_t)(K / 32);
+    out->even_parts = w.even_parts;
+    out->interior_rows = w.Mi;
+    out->interior_cols = w.Ni;
+    const int64_t n = cap < (int64_t)w.segments.size() ? cap : (int64_t)w.segments.size();
+    if (n > 0) memcpy(segments, w.segments.data(), (size_t)n * sizeof(SkSegment));
+    return 0;
 }
 
 hipError_t launch_gemm_balanced(const GemmDesc& d, bool bf16, SkWorkspace** wsp, int n_cus, bool forced, hipStream_t stream,
