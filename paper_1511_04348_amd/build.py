@@ -9,7 +9,7 @@ CSRC = os.path.join(_HERE, "csrc")
 OBJ = os.path.join(_HERE, "_build")
 LIB = os.path.join(_HERE, "libtgemm.so")
 
-SOURCES = ["api.cpp", "plan.cpp", "engine.cpp", "mlp.hip", "gemm_f32.hip", "gemm_bf16.hip", "gemm_bf16_dl.hip", "copy_kernel.hip"]
+SOURCES = ["api.cpp", "plan.cpp", "engine.cpp", "mlp.hip", "gemm_f32.hip", "balance.hip", "gemm_bf16.hip", "gemm_bf16_dl.hip", "copy_kernel.hip"]
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",

@@ -117,6 +117,9 @@ struct GemmParams {
 };
 
 int pick_config(const GemmDesc& d);
+// the same choice; *est_us_per_k (optional) receives the cost model's time of the chosen shape in
+// microseconds per unit of K
+int pick_config_est(const GemmDesc& d, double* est_us_per_k);
 hipError_t launch_tile_gemm_f32(const GemmDesc& d, hipStream_t stream);
 // C += A B (A row-major M x K, B row-major K x N, C float: the in-core tgemm_run) with the work spread
 // evenly over the compute units when the 256 x 256 macro tiles do not come out as whole rounds of
