@@ -37,3 +37,14 @@ def test_example_out_of_core_gemm():
     # the strip order reuses what the cache holds; row-major order re-fetches B for every task row
     assert res["strips"][0]["misses"] < res["serpentine"][0]["misses"] <= res["row-major"][0]["misses"]
     assert res["row-major + station"][0]["misses"] < res["row-major"][0]["misses"]
+
+
+def test_example_size_sweep():
+    import size_sweep
+    print("[case] example size sweep", flush=True)
+    res = size_sweep.run([2048, 4608, 4096], "f32", 512, reps=3, quiet=True)
+    by_n = {n: (launches, rate, rate_one, plan) for n, launches, rate, rate_one, plan in res}
+    assert by_n[2048][0] == 1 and by_n[4096][0] == 1            # too small to gain; whole rounds only
+    launches, rate, rate_one, plan = by_n[4608]                 # 324 macro tiles: one whole round and 68 tiles cut up
+    assert launches == 3 and plan["applies"] == 1 and plan["whole_round_tiles"] == 256 and plan["tail_tiles"] == 68
+    assert rate > rate_one                                      # measured: 137 against 127 TFLOP/s
