@@ -297,3 +297,31 @@ def test_balanced_schedule_is_the_automatic_choice_where_it_gains(oracle):
             assert rel_fro(C.cpu().numpy()[rows, cols], ref) <= TOL_F32
     finally:
         tg.tgemm_destroy(ctx)
+
+
+def test_balanced_schedule_asynchronous_calls_of_changing_sizes(oracle):
+    """tgemm_opts.async_incore with the balanced schedule: calls of different sizes enqueued back to back
+    share one workspace and its tables (a new plan waits for the copies of the old one); results after one
+    tgemm_sync, integer-valued operands bit-exact."""
+    ctx = tg.tgemm_create(0, async_incore=1, incore_schedule=tg.TGEMM_SCHEDULE_BALANCED)
+    try:
+        jobs = []
+        for i, (M, N, K, T) in enumerate([(1600, 1576, 512, 256), (800, 800, 1024, 1024), (1600, 1576, 512, 256), (1536, 1536, 1024, 512)]):
+            A = inputs.int_matrix(61 + i, M, K)
+            B = inputs.int_matrix(71 + i, K, N)
+            C0 = inputs.int_matrix(81 + i, M, N, lo=-7, hi=7)
+            jobs.append((A, B, C0, A.cuda(), B.cuda(), C0.cuda(), T))
+        torch.cuda.synchronize()
+        for rep in range(2):          # every C accumulates twice
+            for A, B, C0, Ad, Bd, Cd, T in jobs:
+                M, K = A.shape
+                announce("async balanced", M, B.shape[1], K, T)
+                tg.tgemm_run(ctx, Ad, Bd, Cd, M, B.shape[1], K, T, tg.TGEMM_F32, 0)
+                assert tg.tgemm_last_stats(ctx)["kernel_launches"] > 1
+        tg.tgemm_sync(ctx)
+        for A, B, C0, Ad, Bd, Cd, T in jobs:
+            ref = oracle.gemm(A.numpy(), B.numpy(), c_in=C0.numpy())
+            ref = oracle.gemm(A.numpy(), B.numpy(), c_in=ref)
+            assert np.array_equal(Cd.cpu().numpy().astype(np.float64), ref)
+    finally:
+        tg.tgemm_destroy(ctx)
