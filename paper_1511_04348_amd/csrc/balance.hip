@@ -33,7 +33,7 @@ struct SkWorkspace {
     int even_parts = 0;                         // see tgemm_balance
     int64_t Mi = 0, Ni = 0;
     int grid_full = 0;                          // macro tiles of the whole rounds
-    std::vector<SkSegment> segments;            // longest first
+    std::vector<SkSegment> segments;            // in launch order
     std::vector<SkTile> tiles;
     bool uploaded = false;
     char* dev = nullptr;                        // SK_TABLE_BYTES of tables, then SK_MAX_SLOTS slots
@@ -96,41 +96,45 @@ static void sk_make_plan(SkWorkspace& w, const GemmDesc& d, bool bf16, int n_cus
         GemmDesc in = d;
         in.T = (int32_t)T;
         if (!bf::bf16_dl_applicable(in)) return;
-        // estimate in rounds of 256 x 256 tiles (0.0284 us per unit of K), as the bf16 launcher compares
-        // its shapes: one launch takes whole rounds of the large shape, or of the 128 x 128 one (512 to a
-        // round, 0.95 of a large round); balanced, the partial round costs its share plus 8 chunks of
-        // segment starts and imbalance plus the fix-up
         // The bf16 loop takes a chunk in under a microsecond: segments at different depths of k, which
         // share no panel piece in the L2 at any moment, ask for more than HBM delivers and run at about
-        // half pace.  So the tiles are cut evenly instead, each into `parts` = units / tiles pieces at the
-        // same depths, in one wave of workgroups that walk k together like a round of whole tiles;
-        // with more than half as many tiles as units that is no cut at all, and the ranges of the fp32
-        // schedule are used at their measured pace.
+        // half pace.  So the tiles are cut evenly instead, each into units / tiles pieces (of at least 4
+        // chunks) at the same depths, in one wave of workgroups that walk k together like a round of
+        // whole tiles; with more than half as many tiles as units that is no cut at all, and the
+        // ranges of the fp32 schedule are used, priced at half pace.
         uniform_parts = (int)(n_cus / n_tail);
         if (uniform_parts > n_ch / 4) uniform_parts = (int)(n_ch / 4);
+        // Estimate in rounds of 256 x 256 tiles (0.0284 us per unit of K), as the bf16 launcher compares
+        // its shapes: one launch takes whole rounds of the large shape, or of the 128 x 128 one (512 to a
+        // round, 0.95 of a large round); balanced, the partial round costs its longest piece, plus 8
+        // chunks of starts and 45 us of fix-up.
         const double round_us = 0.0284 * (double)d.K;
-        const double c3 = (double)((n_tiles + n_cus - 1) / n_cus), c2 = 0.95 * (double)((4 * n_tiles + 2 * n_cus - 1) / (2 * n_cus));
+        const double c3 = (double)((n_tiles + n_cus - 1) / n_cus);
+        const double c2 = 0.95 * (double)((4 * n_tiles + 2 * n_cus - 1) / (2 * n_cus));
         const double plain_rounds = c3 < c2 ? c3 : c2;
         const double tail_rounds = uniform_parts >= 2 ? (double)((n_ch + uniform_parts - 1) / uniform_parts) / (double)n_ch
                                                       : 2.0 * (double)n_tail / n_cus;
         const double bal_rounds = (double)rounds + tail_rounds + (0.0284 * BK * 8 + 45.0) / round_us;
         if (bal_rounds > 0.985 * plain_rounds && !forced) return;
         if (uniform_parts < 2) uniform_parts = 0;
-    } else {    // estimate in microseconds, fitted to square products of 2048 .. 10240: whole rounds at 0.227 per tile
-    // and unit of K; the partial round's share 7 % slower (its segments share no panel pieces in L2) plus
-    // 10 for their starts; the fix-up 8 + 0.19 per tile; strips.  Against the one launch's best shape by
-    // the cost model of pick_config, which is rough for small products: below 140 tiles they are left alone.
-    double plain = 0.0, strips = 0.0, e = 0.0;
-    pick_config_est(d, &plain);
-    plain *= (double)d.K;
-    GemmDesc s = d;
-    if (d.N > Ni) { s.M = d.M; s.N = d.N - Ni; pick_config_est(s, &e); strips += e * (double)d.K; }
-    if (d.M > Mi) { s.M = d.M - Mi; s.N = Ni; pick_config_est(s, &e); strips += e * (double)d.K; }
-    // (strips of at most one 64 x 64 tile per unit between them: one chain of K / 2 MFMAs per SIMD)
-    const int64_t small = ((d.M + 63) / 64) * ((d.N - Ni + 63) / 64) + ((d.M - Mi + 63) / 64) * (Ni / 64);
-    if (small <= n_cus) strips = small > 0 ? 0.0166 * (double)d.K + 12.0 : 0.0;
-    const double balanced = 0.227 * (double)d.K * ((double)rounds + 1.07 * (double)n_tail / n_cus) + 10.0 + (8.0 + 0.19 * (double)n_tail) + strips;
-    if ((balanced > 0.975 * plain || n_tiles < 140) && !forced) return;
+    } else {
+        // Estimate in microseconds, fitted to square products of 2048 .. 10240: whole rounds at 0.227 per
+        // tile and unit of K; the partial round's share 7 % slower (its segments share no panel pieces in
+        // L2) plus 10 for their starts; the fix-up 8 + 0.19 per tile; the strips by the cost model of
+        // pick_config, or, with at most one 64 x 64 tile per unit between them, one chain of K / 2 MFMAs
+        // per SIMD.  Against the one launch's best shape by the same cost model, which is rough for
+        // small products: below 140 tiles they are left alone.
+        double plain = 0.0, strips = 0.0, e = 0.0;
+        pick_config_est(d, &plain);
+        plain *= (double)d.K;
+        GemmDesc s = d;
+        if (d.N > Ni) { s.M = d.M; s.N = d.N - Ni; pick_config_est(s, &e); strips += e * (double)d.K; }
+        if (d.M > Mi) { s.M = d.M - Mi; s.N = Ni; pick_config_est(s, &e); strips += e * (double)d.K; }
+        const int64_t small = ((d.M + 63) / 64) * ((d.N - Ni + 63) / 64) + ((d.M - Mi + 63) / 64) * (Ni / 64);
+        if (small <= n_cus) strips = small > 0 ? 0.0166 * (double)d.K + 12.0 : 0.0;
+        const double balanced = 0.227 * (double)d.K * ((double)rounds + 1.07 * (double)n_tail / n_cus) + 10.0 +
+                                (8.0 + 0.19 * (double)n_tail) + strips;
+        if ((balanced > 0.975 * plain || n_tiles < 140) && !forced) return;
     }
 
     // macro tile number (task by task, as the kernel numbers them) -> origin, for the interior product
