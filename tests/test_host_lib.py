@@ -109,7 +109,9 @@ def test_header_is_plain_c_and_links_from_c(lib, tmp_path):
     r = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=120)
     assert r.returncode == 0, r.stdout
     out = r.stdout.splitlines()
-    sizes = [ctypes.sizeof(t) for t in (tg.tgemm_opts, tg.tgemm_task, tg.tgemm_stats, tg.tgemm_trace_rec, tg.tgemm_mlp_trace_rec)]
+    sizes = [ctypes.sizeof(t) for t in (tg.tgemm_opts, tg.tgemm_task, tg.tgemm_stats, tg.tgemm_trace_rec, tg.tgemm_mlp_trace_rec,
+                                        tg.tgemm_balance, tg.tgemm_segment)]
     assert out[0] == "sizes " + " ".join(str(s) for s in sizes)
     assert out[1] == "order 0 1 2 3 7 6 5 4 8 9 10 11"
-    assert out[2].startswith("bad order -> %d" % tg.TGEMM_EARG)
+    assert out[2] == "balance 1 768 193 447"
+    assert out[3].startswith("bad order -> %d" % tg.TGEMM_EARG)
