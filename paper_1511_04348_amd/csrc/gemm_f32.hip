@@ -267,7 +267,8 @@ __global__ __launch_bounds__(WM * WN * 64) void tile_gemm_f32(const GemmParams p
         lid = xcd * q + (xcd < r ? xcd : r) + local;
     }
     // EPI_PARTIAL: this workgroup's segment (macro tile, first chunk, chunks, workspace slot) comes from
-    // a table, longest segments first: the dispatcher hands them to compute units as those fall free
+    // a table whose order is the plan's: the dispatcher hands workgroups to compute units in that order as
+    // the units fall free
     int c_begin = 0, c_count = p.n_chunks, ws_slot = 0;
     if constexpr (EPI == EPI_PARTIAL) {
         const SkSegment sg = p.segments[blockIdx.x];
