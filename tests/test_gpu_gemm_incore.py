@@ -121,6 +121,9 @@ def test_error_paths(ctxs):
     with pytest.raises(tg.TgemmError) as e:
         tg.tgemm_run(ctx, A, A.clone(), A.clone(), 8, 8, 8, 4, dtype=7)
     assert e.value.code == tg.TGEMM_EARG
+    with pytest.raises(tg.TgemmError) as e:
+        tg.tgemm_create(0, incore_schedule=3)
+    assert e.value.code == tg.TGEMM_EARG
     # the context is still usable
     C = torch.zeros(8, 8, device="cuda")
     tg.tgemm_run(ctx, torch.eye(8, device="cuda"), torch.ones(8, 8, device="cuda"), C, 8, 8, 8, 4)
