@@ -59,9 +59,10 @@ enum {
  *   SERPENTINE  as ROW_MAJOR, but odd tile rows run right to left.
  *   STRIPS      column strips of `strip` tile columns, left to right; inside a strip the tile rows
  *               ascend (even strips) or descend (odd strips), and inside a tile row the strip's
- *               columns ascend.  With strip = slots / k-steps - 2 the strip's B tiles and two row
+ *               columns ascend.  With strip <= slots / k-steps - 2 the strip's B tiles and two row
  *               panels of A fit in the cache together, so under strict LRU B is fetched once and
- *               A once per strip; that is the automatic width. */
+ *               A once per strip; the automatic width shares the tile columns out evenly over the
+ *               fewest strips of at most that width. */
 enum { TGEMM_ORDER_SERPENTINE = 0, TGEMM_ORDER_ROW_MAJOR = 1, TGEMM_ORDER_STRIPS = 2 };
 
 enum { TGEMM_SCHEDULE_AUTO = 0, TGEMM_SCHEDULE_ONE_LAUNCH = 1, TGEMM_SCHEDULE_BALANCED = 2 };

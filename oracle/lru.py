@@ -42,10 +42,15 @@ def task_order(n_i, n_j, order, strip=None):
 
 
 def auto_strip(n_slots, n_k, n_j):
-    """Strip width for the 'strips' order from the slot count: the strip's B tiles and two row
-    panels of A (n_k tiles per tile column / row) fit in the cache together.  Two, because under
-    strict LRU the previous row panel outlives the strip's oldest B column."""
-    return min(n_j, max(1, n_slots // n_k - 2))
+    """Strip width for the 'strips' order from the slot count.  The widest strip is the one whose B
+    tiles and two row panels of A (n_k tiles per tile column / row) fit in the cache together -- two,
+    because under strict LRU the previous row panel outlives the strip's oldest B column.  The tile
+    columns are shared out evenly over the fewest strips of at most that width (the paper leaves the
+    order of the tasks open, section 3.4; a narrow strip left over at the end would fetch a whole row
+    panel of A per task for one column of products)."""
+    widest = min(max(1, n_j), max(1, n_slots // n_k - 2))
+    n_strips = -(-n_j // widest)
+    return max(1, -(-n_j // n_strips)) if n_strips > 0 else 1
 
 
 def tgemm_access_sequence(M, N, K, T, order="serpentine", strip=None):

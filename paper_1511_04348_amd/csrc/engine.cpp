@@ -536,7 +536,15 @@ static int run_out_of_core_body(tgemm_ctx* ctx, const void* A, const void* B, fl
     // strips: as many tile columns of B as fit in the cache beside two row panels of A (under
     // strict LRU the previous row panel is still younger than the strip's first B column when the
     // next one arrives, so it needs room too or the strip's B tiles get evicted in a cascade)
-    int64_t strip = ctx->opts.strip_width > 0 ? ctx->opts.strip_width : std::max<int64_t>(1, r.n_ab / r.n_k - 2);
+    // That is the widest strip; the columns are then shared out evenly over as few strips as that
+    // allows, so that no narrow strip is left over at the end (in a strip of one column every task
+    // fetches a whole row panel of A for a single column of products: more link time than MFMA time).
+    int64_t strip = ctx->opts.strip_width;
+    if (strip <= 0) {
+        const int64_t widest = std::min(std::max<int64_t>(1, r.n_ab / r.n_k - 2), std::max<int64_t>(1, r.n_j));
+        const int64_t n_strips = (r.n_j + widest - 1) / widest;
+        strip = n_strips > 0 ? (r.n_j + n_strips - 1) / n_strips : 1;
+    }
     strip = std::min(strip, r.n_j);
     rc = tgemm_task_order(r.n_i, r.n_j, ctx->opts.order, strip, order.data());
     if (rc != TGEMM_OK) return rc;

@@ -363,10 +363,11 @@ def test_config3_full_size(oracle):
         stats = tg.tgemm_last_stats(ctx)
         print("config3 stats", stats, "TFLOP/s", 2.0 * n ** 3 / stats["wall_ms"] / 1e9, flush=True)
         assert stats["n_slots"] == 115 and stats["n_tasks"] == 256 and stats["n_tile_gemms"] == 4096
-        # default order: strips of 115 / 16 - 2 = 5 tile columns; B comes in once and A once per
-        # strip, less what survives in the cache across a strip boundary
-        assert oracle.auto_strip(115, 16, 16) == 5
-        _check_trace(oracle, ctx, n, n, n, T, "strips", 115, strip=5)
+        # default order: the cache has room for strips of 115 / 16 - 2 = 5 tile columns, so the 16 columns
+        # go into four strips of 4; B comes in once and A once per strip, less what survives in the cache
+        # across a strip boundary
+        assert oracle.auto_strip(115, 16, 16) == 4
+        _check_trace(oracle, ctx, n, n, n, T, "strips", 115, strip=4)
         assert stats["misses"] == 1232
         assert stats["h2d_bytes"] == (stats["misses"] + 256) * T * T * 4 and stats["d2h_bytes"] == n * n * 4
     finally:

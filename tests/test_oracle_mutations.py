@@ -186,7 +186,9 @@ LRU_MUTANTS = [
     ("B looked up before A", 'seq.append(("A", i, k, tid, k))\n            seq.append(("B", k, j, tid, k))',
      'seq.append(("B", k, j, tid, k))\n            seq.append(("A", i, k, tid, k))'),
     ("task id decoded column-major", "i, j = tid // n_j, tid % n_j", "i, j = tid % n_i, tid // n_i"),
-    ("automatic strip one too wide", "return min(n_j, max(1, n_slots // n_k - 2))", "return min(n_j, max(1, n_slots // n_k - 1))"),
+    ("automatic strip one too wide", "widest = min(max(1, n_j), max(1, n_slots // n_k - 2))", "widest = min(max(1, n_j), max(1, n_slots // n_k - 1))"),
+    ("automatic strip: widest, not evened out", "return max(1, -(-n_j // n_strips)) if n_strips > 0 else 1", "return widest"),
+    ("automatic strip: one strip too many", "n_strips = -(-n_j // widest)", "n_strips = -(-n_j // widest) + 1"),
     ("invalidate: drops the other matrices", "        for key in [k for k in self.cache if k[0] == name]:", "        for key in [k for k in self.cache if k[0] != name]:"),
     ("invalidate: drops everything", "        for key in [k for k in self.cache if k[0] == name]:", "        for key in list(self.cache):"),
     ("invalidate: ignored", "            lru.drop(key.name)\n", "            pass\n"),

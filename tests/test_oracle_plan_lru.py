@@ -182,6 +182,20 @@ def test_strips_traffic_closed_form(oracle):
     n_strips = n_j // w
     seq = oracle.tgemm_access_sequence(n_i * T, n_j * T, n_k * T, T, order="strips", strip=w)
     assert oracle.auto_strip((w + 2) * n_k, n_k, n_j) == w
+    # the automatic width: the fewest strips that the cache allows, the columns shared out evenly
+    # (16 columns, room for 5: four strips of 4, not 5 + 5 + 5 + 1; both cost the same 1232 misses)
+    assert oracle.auto_strip(115, 16, 16) == 4
+    for slots, nk, nj in [(115, 16, 16), (40, 8, 8), (64, 4, 9), (200, 16, 16), (8, 16, 16), (1000, 2, 7), (24, 4, 1)]:
+        widest = min(nj, max(1, slots // nk - 2))
+        got = oracle.auto_strip(slots, nk, nj)
+        assert 1 <= got <= widest
+        assert -(-nj // got) == -(-nj // widest)                   # as few strips as the widest would need
+        assert got == 1 or -(-nj // (got - 1)) > -(-nj // widest)    # and no narrower width does that
+    misses = {}
+    for width in (4, 5):
+        big = oracle.tgemm_access_sequence(16, 16, 16, 1, order="strips", strip=width)
+        misses[width] = oracle.lru_simulate([s[:3] for s in big], 115)[1]["misses"]
+    assert misses[4] == misses[5] == 1232
     ev, st = oracle.lru_simulate([s[:3] for s in seq], (w + 2) * n_k)
     a_miss = sum(1 for s, e in zip(seq, ev) if s[0] == "A" and not e[0])
     b_miss = sum(1 for s, e in zip(seq, ev) if s[0] == "B" and not e[0])
