@@ -151,15 +151,20 @@ def run_gemm_incore(args, env, name, steps, warmup, n, T, bf16):
         tg.tgemm_run(ctx, A, B, C, n, n, n, T, dt)
     torch.cuda.synchronize()
     tg.tgemm_sync(ctx)
-    kernel_ms = 0.0
     t0 = time.perf_counter()
     for _ in range(steps):
         tg.tgemm_run(ctx, A, B, C, n, n, n, T, dt)          # synchronous: returns when C is complete
-        kernel_ms += tg.tgemm_last_stats(ctx)["kernel_ms"]  # HIP events on the launch stream
-    launches = tg.tgemm_last_stats(ctx)["kernel_launches"]
     tg.tgemm_sync(ctx)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    # The kernel time of the same call from the library's HIP events on its launch stream, over `steps`
+    # further calls: reading the statistics back after every call costs a 1000^3 product a tenth of its
+    # wall time, so it stays out of the loop above.
+    kernel_ms = 0.0
+    for _ in range(steps):
+        tg.tgemm_run(ctx, A, B, C, n, n, n, T, dt)
+        kernel_ms += tg.tgemm_last_stats(ctx)["kernel_ms"]
+    launches = tg.tgemm_last_stats(ctx)["kernel_launches"]
     tg.tgemm_destroy(ctx)
     pipelined = None
     if name == "c1":
