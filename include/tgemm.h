@@ -111,9 +111,10 @@ typedef struct tgemm_opts {
                               context at the first such call); a second kernel adds a tile's sums in
                               ascending order of k, and then C.  Rows and columns beyond the last
                               multiple of 256 run as a launch of their own.  Elements of those tiles are
-                              then sums of up to three chains over consecutive parts of the k range
-                              instead of one chain; which parts depends on the sizes and the number of
-                              compute units only.
+                              then sums of several chains over consecutive parts of the k range (about
+                              compute units / tiles of the partial round of them, at least two) instead
+                              of one chain; which parts depends on the sizes and the number of compute
+                              units only (tgemm_balance_plan shows them).
                               TGEMM_SCHEDULE_ONE_LAUNCH (1): always one launch, one chain per element.
                               TGEMM_SCHEDULE_BALANCED (2): the balanced schedule wherever it applies,
                               whatever the estimate says */
