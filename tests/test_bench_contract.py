@@ -37,6 +37,9 @@ def test_one_json_line_with_roofline_and_cpu_baseline():
     rf = d["roofline"]
     assert rf["bound"] == "mfma" and rf["unit"] == "TFLOP/s" and rf["peak"] == 157.3
     assert abs(rf["frac"] - rf["achieved"] / rf["peak"]) < 1e-9 and 0 < rf["frac"] < 1
+    assert rf["traffic"] > 0 and rf["traffic_source"].startswith("profiles/") and rf["launches_per_step"] == 1
+    # calls enqueued back to back are not slower than calls that are each waited for
+    assert d["pipelined"]["ms_per_step"] <= 1.05 * d["ms_per_step"]
     cb = d["cpu_baseline"]
     assert cb["kind"] == "oracle" and cb["value"] > 0 and cb["cores"] >= 1 and cb["sample"]
     # the GPU path has to be far ahead of the plain CPU definition it is checked against
