@@ -115,7 +115,10 @@ typedef struct tgemm_opts {
                               compute units / tiles of the partial round of them, at least two) instead
                               of one chain; which parts depends on the sizes and the number of compute
                               units only (tgemm_balance_plan shows them).
-                              TGEMM_SCHEDULE_ONE_LAUNCH (1): always one launch, one chain per element.
+                              TGEMM_SCHEDULE_ONE_LAUNCH (1): always one launch, one chain per element (also
+                              the mode for callers that may not allocate or copy inside tgemm_run: the
+                              balanced schedule allocates its workspace at the first qualifying call and
+                              uploads its tables whenever the sizes change).
                               TGEMM_SCHEDULE_BALANCED (2): the balanced schedule wherever it applies,
                               whatever the estimate says */
 } tgemm_opts;
